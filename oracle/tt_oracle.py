@@ -1,0 +1,201 @@
+"""ctypes wrapper around the CPU oracle (oracle/tt_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product path never imports this module, and
+this module imports nothing from the HIP package.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tt_oracle.c")
+_LIB = os.path.join(_HERE, "libtt_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no intrinsics, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.ora_param_count.restype = C.c_int64
+        _lib.ora_dedup.restype = C.c_int64
+    return _lib
+
+
+def _i64x(values: Sequence[int]):
+    return (C.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+class Shape:
+    """Row / column factorisations and ranks of one table (Section 2, Eq. 2)."""
+
+    def __init__(self, num_rows: int, m, n, r):
+        self.num_rows = int(num_rows)
+        self.m = tuple(int(x) for x in m)
+        self.n = tuple(int(x) for x in n)
+        self.r = tuple(int(x) for x in r)
+        assert len(self.m) == 3 and len(self.n) == 3 and len(self.r) == 4
+        assert self.r[0] == 1 and self.r[3] == 1
+        assert self.m[0] * self.m[1] * self.m[2] >= self.num_rows
+
+    @classmethod
+    def of(cls, s) -> "Shape":
+        return cls(s.num_rows, s.m, s.n, s.r)
+
+    @property
+    def dim(self) -> int:
+        return self.n[0] * self.n[1] * self.n[2]
+
+    def core_size(self, k: int) -> int:
+        return self.m[k] * self.r[k] * self.n[k] * self.r[k + 1]
+
+    def c(self):
+        return _i64x(self.m), _i64x(self.n), _i64x(self.r)
+
+
+def param_count(shape: Shape) -> int:
+    m, n, r = shape.c()
+    return int(_load().ora_param_count(m, n, r))
+
+
+def decode(shape: Shape, indices) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    idx = _i64(indices)
+    out = [np.empty(idx.size, dtype=np.int32) for _ in range(3)]
+    m, _, _ = shape.c()
+    _load().ora_decode(m, _p(idx), C.c_int64(idx.size), _p(out[0]), _p(out[1]), _p(out[2]))
+    return out[0], out[1], out[2]
+
+
+def row(shape: Shape, cores: List[np.ndarray], row_id: int) -> np.ndarray:
+    g = [_f32(c) for c in cores]
+    out = np.empty(shape.dim, dtype=np.float64)
+    m, n, r = shape.c()
+    _load().ora_row(m, n, r, _p(g[0]), _p(g[1]), _p(g[2]), C.c_int64(int(row_id)), _p(out))
+    return out
+
+
+def cache_select(cand_rows, cand_counts, K: int) -> np.ndarray:
+    rows, counts = _i64(cand_rows), _i64(cand_counts)
+    assert rows.size == counts.size and 0 <= K <= rows.size
+    keys = np.empty(K, dtype=np.int64)
+    rc = _load().ora_cache_select(_p(rows), _p(counts), C.c_int64(rows.size), C.c_int64(K), _p(keys))
+    assert rc == 0
+    return keys
+
+
+def cache_fill(shape: Shape, cores, keys) -> np.ndarray:
+    g = [_f32(c) for c in cores]
+    keys = _i64(keys)
+    rows = np.empty((keys.size, shape.dim), dtype=np.float32)
+    m, n, r = shape.c()
+    _load().ora_cache_fill(m, n, r, _p(g[0]), _p(g[1]), _p(g[2]), _p(keys), C.c_int64(keys.size), _p(rows))
+    return rows
+
+
+def cache_lookup(shape: Shape, keys, indices) -> np.ndarray:
+    keys, idx = _i64(keys), _i64(indices)
+    slot = np.empty(idx.size, dtype=np.int32)
+    rc = _load().ora_cache_lookup(C.c_int64(shape.num_rows), _p(keys), C.c_int64(keys.size),
+                                  _p(idx), C.c_int64(idx.size), _p(slot))
+    assert rc == 0
+    return slot
+
+
+def _check_csr(shape: Shape, indices: np.ndarray, offsets: np.ndarray):
+    assert offsets.ndim == 1 and offsets.size >= 1
+    assert offsets[0] == 0 and offsets[-1] == indices.size
+    assert np.all(np.diff(offsets) >= 0)
+    if indices.size:
+        assert indices.min() >= 0 and indices.max() < shape.num_rows, "index out of range"
+
+
+def fwd(shape: Shape, cores, indices, offsets, alpha=None, cache_keys=None, cache_rows=None) -> np.ndarray:
+    g = [_f32(c) for c in cores]
+    idx, off = _i64(indices), _i64(offsets)
+    _check_csr(shape, idx, off)
+    n_bags = off.size - 1
+    a = None if alpha is None else _f32(alpha)
+    K = 0 if cache_keys is None else int(np.asarray(cache_keys).size)
+    ck = None if K == 0 else _i64(cache_keys)
+    cr = None if K == 0 else _f32(cache_rows)
+    out = np.empty((n_bags, shape.dim), dtype=np.float32)
+    m, n, r = shape.c()
+    rc = _load().ora_fwd(m, n, r, C.c_int64(shape.num_rows), _p(g[0]), _p(g[1]), _p(g[2]),
+                         _p(idx), C.c_int64(idx.size), _p(off), C.c_int64(n_bags), _p(a),
+                         _p(ck), _p(cr), C.c_int64(K), _p(out))
+    assert rc == 0
+    return out
+
+
+def bwd(shape: Shape, cores, indices, offsets, grad_output, alpha=None, cache_keys=None):
+    """Returns ([dG1, dG2, dG3] in fp64 with the cores' shapes, dCache fp64 [K][N] or None)."""
+    g = [_f32(c) for c in cores]
+    idx, off = _i64(indices), _i64(offsets)
+    _check_csr(shape, idx, off)
+    n_bags = off.size - 1
+    go = _f32(grad_output)
+    assert go.shape == (n_bags, shape.dim)
+    a = None if alpha is None else _f32(alpha)
+    K = 0 if cache_keys is None else int(np.asarray(cache_keys).size)
+    ck = None if K == 0 else _i64(cache_keys)
+    dG = [np.zeros(g[k].shape, dtype=np.float64) for k in range(3)]
+    dC = None if K == 0 else np.zeros((K, shape.dim), dtype=np.float64)
+    m, n, r = shape.c()
+    rc = _load().ora_bwd(m, n, r, C.c_int64(shape.num_rows), _p(g[0]), _p(g[1]), _p(g[2]),
+                         _p(idx), C.c_int64(idx.size), _p(off), C.c_int64(n_bags), _p(a),
+                         _p(ck), C.c_int64(K), _p(go),
+                         _p(dG[0]), _p(dG[1]), _p(dG[2]), _p(dC))
+    assert rc == 0
+    return dG, dC
+
+
+def sgd(x: np.ndarray, g: np.ndarray, lr: float) -> np.ndarray:
+    """Returns x - lr * g, evaluated in fp64 and rounded to fp32."""
+    out = _f32(x).copy()
+    gg = _f32(g)
+    assert out.shape == gg.shape
+    _load().ora_sgd(_p(out), _p(gg), C.c_int64(out.size), C.c_double(float(lr)))
+    return out
+
+
+def dedup(keys) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(ascending unique keys, counts, grouping permutation); keys < 0 are skipped."""
+    k = _i64(keys)
+    uniq = np.empty(k.size, dtype=np.int64)
+    count = np.empty(k.size, dtype=np.int32)
+    perm = np.empty(k.size, dtype=np.int32)
+    kept = C.c_int64(0)
+    u = int(_load().ora_dedup(_p(k), C.c_int64(k.size), _p(uniq), _p(count), _p(perm), C.byref(kept)))
+    return uniq[:u].copy(), count[:u].copy(), perm[:kept.value].copy()
