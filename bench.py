@@ -1,0 +1,159 @@
+"""Benchmark of the TT-EmbeddingBag hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input:
+forward, backward and the SGD update of the cores, at the Kaggle-shaped R = 32
+configuration (10,131,227 rows as 200x220x250, dimension 16 as 2x2x4, 2048 bags
+of one index, Zipf(1.05) indices).  All inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+POOL = 16                      # distinct batches cycled through, so caches see a stream
+
+
+def algorithmic_bytes(t, L, n_bags, touched_floats):
+    """Bytes the method must move per launch (no re-reads, no intermediates).
+
+    forward : every lookup reads its three slices (S bytes) and its index, every bag
+              writes its output row.
+    backward: the same reads plus the upstream gradient row, and one write of every
+              touched core slice.
+    sgd     : read x, read g, write x for every core element.
+    """
+    S = 4 * (t.n[0] * t.r[1] + t.r[1] * t.n[1] * t.r[2] + t.r[2] * t.n[2])
+    N = t.dim
+    fwd = L * (S + 8) + n_bags * 4 * N
+    bwd = L * (S + 8) + n_bags * 4 * N + 4 * touched_floats
+    total = sum(t.core_size(k) for k in range(3))
+    sgd = 12 * total
+    return {"fwd": fwd, "bwd": bwd, "sgd": sgd}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="kaggle_r32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+                 "(no collectives or sharding are part of it)" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2101_11714_amd import binding as B
+    from paper_2101_11714_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    wl = W.WORKLOADS[args.workload]
+    assert len(wl.tables) == 1, "bench.py times single-table workloads"
+    t = wl.tables[0]
+    shape = B.shape_of(t)
+    cores_h = W.make_cores(t, wl.init, wl.seed)
+    cores = [torch.from_numpy(c).to(dev) for c in cores_h]
+    grads = [torch.zeros_like(c) for c in cores]
+    batches_h = [W.make_batch(wl, 0, step) for step in range(POOL)]
+    idx = [torch.from_numpy(b.indices).to(dev) for b in batches_h]
+    off = [torch.from_numpy(b.offsets).to(dev) for b in batches_h]
+    go = [torch.from_numpy(b.grad_output).to(dev) for b in batches_h]
+    n_bags = wl.n_bags
+    L = int(batches_h[0].indices.size)
+    out = torch.empty((n_bags, t.dim), dtype=torch.float32, device=dev)
+    lr = 1e-3 * wl.lr            # small, so that thousands of steps keep the cores finite
+
+    def step(i):
+        j = i % POOL
+        B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out)
+        B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads)
+        B.tt_emb_sgd_update(shape, cores, grads, lr, zero_grad=True)
+
+    def timed(fn, count):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(count):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count          # ms per call
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_step = timed(step, args.steps)
+    wall = time.perf_counter() - t0
+    value = L / (ms_step * 1e-3)
+
+    # per-kernel durations: each stage launched back to back on the same stream
+    reps = max(200, min(args.steps, 2000))
+    ms_fwd = timed(lambda i: B.tt_emb_fwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out), reps)
+    ms_bwd = timed(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
+    for g in grads:
+        g.zero_()
+    ms_sgd = timed(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
+
+    # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
+    b0 = batches_h[0].indices
+    m1, m2, m3 = t.m
+    touched = (np.unique(b0 // (m2 * m3)).size * t.n[0] * t.r[1]
+               + np.unique((b0 // m3) % m2).size * t.r[1] * t.n[1] * t.r[2]
+               + np.unique(b0 % m3).size * t.r[2] * t.n[2])
+    ab = algorithmic_bytes(t, L, n_bags, touched)
+    stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
+    dominant = max(stage_ms, key=stage_ms.get)
+    achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
+                "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
+                "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import tt_oracle as ora
+        oshape = ora.Shape.of(t)
+        budget, done, spent = 10.0, 0, 0.0
+        oc = [c.copy() for c in cores_h]
+        while done < 3 or (spent < budget and done < POOL):
+            b = batches_h[done % POOL]
+            s0 = time.perf_counter()
+            ora.fwd(oshape, oc, b.indices, b.offsets)
+            dg, _ = ora.bwd(oshape, oc, b.indices, b.offsets, b.grad_output)
+            oc = [ora.sgd(oc[k], dg[k].astype(np.float32), lr) for k in range(3)]
+            spent += time.perf_counter() - s0
+            done += 1
+        cpu = {"value": round(done * L / spent, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+               "sample": "%d whole steps (fwd+bwd+sgd) of the same %d-lookup batches, single thread, fp64" % (done, L)}
+
+    print(json.dumps({
+        "metric": "TT-EmbeddingBag fwd+bwd lookups/sec; % of HBM/fp32 roofline at R=32",
+        "value": round(value, 1), "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
+                               "Zipf(%.2f), fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
+                                                            n_bags, L // n_bags, wl.zipf_alpha),
+                   "lookups_per_step": L, "wall_s_timed_region": round(wall, 3)},
+        "roofline": roofline, "cpu_baseline": cpu}))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,186 @@
+/*
+ * tt_emb.h - C ABI of the TT-EmbeddingBag library for AMD MI355X (gfx950).
+ *
+ * The library computes the forward and backward pass of an embedding bag whose
+ * table W (num_rows x N) is stored in TT-matrix format with d = 3 cores
+ * (paper: Section 2, Eq. 2; Section 3.1, Eq. 3-4; Section 4.1, Eq. 5-6 and
+ * Alg. 1-2), the SGD update of the cores (Section 5), and the uncompressed
+ * cache of the most frequently used rows (Section 4.2).
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ *  - tt_shape_t and tt_cache_t are read from HOST memory.  Every other pointer is
+ *    DEVICE memory owned by the caller, unless a comment says "host".  The
+ *    library allocates nothing and frees nothing; temporary storage comes from a
+ *    caller-provided workspace whose size the *_workspace_bytes queries return.
+ *  - Core k (k = 0,1,2) is a contiguous fp32 array G_k[m_k][r_k][n_k][r_{k+1}]
+ *    with r_0 = r_3 = 1: the paper's G_k in R^{r_{k-1} x m_k x n_k x r_k} with the
+ *    row digit in front, so that the slice selected by one digit is one
+ *    contiguous block.
+ *  - Row index i has digits i = i1*m2*m3 + i2*m3 + i3 (i1 most significant,
+ *    Section 3.1).  Only 0 <= i < num_rows <= m1*m2*m3 may be looked up; this is a
+ *    precondition on `indices` that the library does not check on the device.
+ *  - An embedding row has N = n1*n2*n3 columns; column j = (j1*n2 + j2)*n3 + j3.
+ *  - Bags are given in CSR form: offsets[0..n_bags], offsets[0] = 0,
+ *    non-decreasing, offsets[n_bags] = L; bag b pools positions
+ *    offsets[b] <= k < offsets[b+1] by summation (Section 4.1).  offsets == NULL
+ *    means n_bags == L and one index per bag.  alpha is an optional per-position
+ *    weight (Eq. 5); NULL means 1.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream) and the calls return without waiting for it.
+ *  - Return value: TT_OK or a negative TT_ERR_* code; tt_last_error() gives a
+ *    text for the last failure on the calling thread.  No C++ exception crosses
+ *    the boundary.  On error nothing has been enqueued.
+ *  - Limits: d = 3, num_rows < 2^31, L < 2^31, fp32 data.
+ */
+#ifndef TT_EMB_H
+#define TT_EMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TT_OK = 0,
+    TT_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    TT_ERR_BAD_SHAPE = -2,   /* d != 3, r[0] or r[3] != 1, a factor <= 0, prod(m) < rows  */
+    TT_ERR_BAD_ARG = -3,     /* negative count, K > n_cand, capacity not a power of two.. */
+    TT_ERR_WORKSPACE = -4,   /* workspace missing or smaller than the query's answer     */
+    TT_ERR_HIP = -5,         /* a HIP call or a kernel launch failed                     */
+    TT_ERR_UNSUPPORTED = -6  /* within the interface but beyond this build's limits      */
+};
+
+/* Shape of one TT-compressed table (Section 2, Eq. 2).  Host memory. */
+typedef struct tt_shape_t {
+    int32_t d;          /* number of cores, must be 3                               */
+    int64_t num_rows;   /* rows that may be looked up, <= m[0]*m[1]*m[2]            */
+    int32_t m[3];       /* row factorisation                                        */
+    int32_t n[3];       /* column factorisation, N = n[0]*n[1]*n[2]                 */
+    int32_t r[4];       /* TT ranks, r[0] = r[3] = 1                                */
+} tt_shape_t;
+
+/* The cache of uncompressed rows (Section 4.2).  The struct is host memory; the
+ * three arrays are device memory that the caller allocates and tt_cache_build
+ * fills.  Slot s holds row keys[s]; rows[s][0..N) is its embedding row.  `table`
+ * is an open-addressing hash map row -> slot with `capacity` entries
+ * (tt_cache_table_capacity(K)); its encoding is private to the library. */
+typedef struct tt_cache_t {
+    int64_t K;
+    int64_t capacity;
+    float *rows;          /* [K][N]     */
+    int64_t *keys;        /* [K]        */
+    uint64_t *table;      /* [capacity] */
+} tt_cache_t;
+
+/* Text of the last error on this thread ("" if none).  Host pointer, valid until
+ * the next failing call on the same thread. */
+const char *tt_last_error(void);
+
+/* Smallest table capacity tt_cache_build accepts for K rows (a power of two). */
+int64_t tt_cache_table_capacity(int64_t K);
+
+/* Bytes of device workspace that tt_emb_fwd / tt_emb_bwd need for L positions in
+ * n_bags bags (with_cache != 0 if a cache will be passed).  0 on a bad shape. */
+size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int with_cache);
+
+/* Bytes of device workspace tt_cache_build needs for n_cand candidates. */
+size_t tt_cache_build_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, int64_t K);
+
+/* Bytes of device workspace tt_emb_debug_dedup needs for L keys. */
+size_t tt_emb_dedup_workspace_bytes(int64_t L);
+
+/*
+ * Forward pass (Section 4.1, Eq. 5-6, Alg. 1; cached rows per Section 4.2):
+ *   output[b][:] = sum_{k in bag b} alpha[k] * row(indices[k]),
+ *   row(i) = G1[i1] G2[i2] G3[i3] (Eq. 3), or cache->rows[slot] if i is cached.
+ * cores:   host array of 3 device pointers.
+ * indices: int64 [L].   offsets: int64 [n_bags+1] or NULL.   alpha: fp32 [L] or NULL.
+ * cache:   NULL for no cache.
+ * output:  fp32 [n_bags][N], overwritten; the row of an empty bag is zero.
+ * L == 0 or n_bags == 0 is valid.
+ */
+int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               float *output, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward pass (Section 3.1, Eq. 4; Section 4.1, Alg. 2): gradients of
+ * <output, grad_output> with respect to the cores and, with a cache, the cached
+ * rows.  Positions whose row is cached contribute to grad_cache only, the others
+ * to the cores only (Section 4.2).
+ * grad_output: fp32 [n_bags][N].
+ * grad_cores:  host array of 3 device pointers shaped like the cores.  The
+ *              gradient is ADDED to them (Alg. 2's "+="); slices that no
+ *              position touches are neither read nor written.
+ * grad_cache:  fp32 [K][N], added to; required iff cache != NULL.
+ * Duplicate indices are combined inside the library; no atomics are used, and the
+ * result is bit-identical from run to run.
+ */
+int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               const float *grad_output,
+               float *const grad_cores[3], float *grad_cache,
+               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * SGD step (Section 5; cached rows per Section 4.2): x <- x - lr * g for every
+ * element of the three cores and, if cache != NULL, of cache->rows with
+ * grad_cache.  zero_grad != 0 also clears the gradients afterwards.
+ */
+int tt_emb_sgd_update(const tt_shape_t *shape, float *const cores[3], float *const grad_cores[3],
+                      float lr, const tt_cache_t *cache, float *grad_cache, int zero_grad,
+                      void *stream);
+
+/*
+ * Cache population (Section 4.2): keep the K most frequently used of the
+ * candidate rows, fill their lines from the TT cores, and build the row -> slot
+ * map.  Order: count descending, ties by ascending row id; slot = rank in that
+ * order.
+ * cand_rows / cand_counts: int64 [n_cand], distinct rows with 0 <= count < 2^32.
+ * out: host struct with K, capacity (>= tt_cache_table_capacity(K), power of two)
+ *      and the three device arrays set by the caller; their contents are written.
+ * K == 0 is valid and gives an empty cache.
+ */
+int tt_cache_build(const tt_shape_t *shape, const float *const cores[3],
+                   const int64_t *cand_rows, const int64_t *cand_counts, int64_t n_cand,
+                   const tt_cache_t *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Cache probe (Section 4.2's split into cached and TT indices):
+ * slot[k] = slot of indices[k], or -1 if the row is not cached.  slot: int32 [L]. */
+int tt_cache_lookup(const tt_cache_t *cache, const int64_t *indices, int64_t L,
+                    int32_t *slot, void *stream);
+
+/* ---- exports used by the parity tests ------------------------------------ */
+
+/* Digits of every index (Section 3.1): i1, i2, i3 are int32 [L]. */
+int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                        int32_t *i1, int32_t *i2, int32_t *i3, void *stream);
+
+/*
+ * Canonical duplicate-free form of a key stream derived from `indices`:
+ *   which = 0: the row id itself;  which = 1,2,3: digit i1, i2 or i3.
+ * Positions with slot[k] >= 0 are skipped (slot may be NULL: nothing skipped).
+ * uniq:  int64 [L]  ascending distinct keys        (first *n_uniq entries valid)
+ * count: int32 [L]  occurrences of each            (first *n_uniq entries valid)
+ * perm:  int32 [L]  positions grouped by key, ascending inside a group
+ *                                                  (first *n_kept entries valid)
+ * n_out: int64 [2] on the device: {n_uniq, n_kept}.
+ */
+int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                       const int32_t *slot, int which,
+                       int64_t *uniq, int32_t *count, int32_t *perm, int64_t *n_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* 1 (default): shapes with a specialised kernel use it.  0: every call takes the
+ * shape-generic kernels.  Process-wide; meant for tests.  Returns the old value. */
+int tt_emb_debug_set_fast_path(int enabled);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TT_EMB_H */

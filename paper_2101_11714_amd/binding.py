@@ -1,0 +1,236 @@
+"""Thin ctypes binding of the C-ABI library declared in include/tt_emb.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libtt_emb.so``.  PyTorch supplies device memory (tensors) and the current HIP
+stream; nothing here computes.  There is no CPU fallback: if the library has not
+been built (``python -c "import __graft_entry__ as g; g.build()"``) loading
+raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtt_emb.so")
+
+TT_OK = 0
+ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_BAD_ARG",
+             -4: "TT_ERR_WORKSPACE", -5: "TT_ERR_HIP", -6: "TT_ERR_UNSUPPORTED"}
+
+EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
+           "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
+           "tt_emb_fwd", "tt_emb_bwd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
+           "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
+
+
+class TTShape(C.Structure):
+    _fields_ = [("d", C.c_int32), ("num_rows", C.c_int64),
+                ("m", C.c_int32 * 3), ("n", C.c_int32 * 3), ("r", C.c_int32 * 4)]
+
+
+class TTCache(C.Structure):
+    _fields_ = [("K", C.c_int64), ("capacity", C.c_int64),
+                ("rows", C.c_void_p), ("keys", C.c_void_p), ("table", C.c_void_p)]
+
+
+class TTError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("%s (%d): %s" % (ERR_NAMES.get(code, "?"), code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library %s is missing: run __graft_entry__.build() first" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        l.tt_last_error.restype = C.c_char_p
+        l.tt_cache_table_capacity.restype = C.c_int64
+        l.tt_cache_table_capacity.argtypes = [C.c_int64]
+        for name in ("tt_emb_workspace_bytes", "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes"):
+            getattr(l, name).restype = C.c_size_t
+        l.tt_emb_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int]
+        l.tt_cache_build_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64]
+        l.tt_emb_dedup_workspace_bytes.argtypes = [C.c_int64]
+        vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
+        l.tt_emb_fwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_bwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
+        l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
+        l.tt_cache_lookup.argtypes = [vp, vp, i64, vp, vp]
+        l.tt_emb_debug_decode.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+        l.tt_emb_debug_dedup.argtypes = [vp, vp, i64, vp, C.c_int, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_debug_set_fast_path.argtypes = [C.c_int]
+        _lib = l
+    return _lib
+
+
+def _check(rc: int):
+    if rc != TT_OK:
+        raise TTError(rc, lib().tt_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype, t.is_contiguous())
+    return t
+
+
+def make_shape(num_rows: int, m: Sequence[int], n: Sequence[int], r: Sequence[int]) -> TTShape:
+    s = TTShape()
+    s.d = 3
+    s.num_rows = int(num_rows)
+    for k in range(3):
+        s.m[k] = int(m[k])
+        s.n[k] = int(n[k])
+    for k in range(4):
+        s.r[k] = int(r[k])
+    return s
+
+
+def shape_of(t) -> TTShape:
+    """TTShape from any object with num_rows, m, n, r attributes."""
+    return make_shape(t.num_rows, t.m, t.n, t.r)
+
+
+def _ptr_array(ts: Sequence[torch.Tensor]):
+    arr = (C.c_void_p * 3)()
+    for k in range(3):
+        arr[k] = _dev(ts[k], torch.float32).data_ptr()
+    return arr
+
+
+class Cache:
+    """Device arrays of a cache plus the host struct that points at them."""
+
+    def __init__(self, K: int, dim: int, device="cuda"):
+        self.K = int(K)
+        self.capacity = int(lib().tt_cache_table_capacity(self.K))
+        self.rows = torch.zeros((max(self.K, 1), dim), dtype=torch.float32, device=device)
+        self.keys = torch.zeros(max(self.K, 1), dtype=torch.int64, device=device)
+        self.table = torch.zeros(self.capacity, dtype=torch.int64, device=device)
+        self.c = TTCache(self.K, self.capacity, self.rows.data_ptr(), self.keys.data_ptr(), self.table.data_ptr())
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def workspace_bytes(shape: TTShape, L: int, n_bags: int, with_cache: bool) -> int:
+    return int(lib().tt_emb_workspace_bytes(C.byref(shape), L, n_bags, int(with_cache)))
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def tt_emb_fwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor,
+               offsets: Optional[torch.Tensor], n_bags: int, output: torch.Tensor,
+               alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(output, torch.float32)
+    assert output.numel() == n_bags * shape.n[0] * shape.n[1] * shape.n[2]
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_fwd(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                            _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(workspace), wsb, _stream()))
+    return output
+
+
+def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor,
+               offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
+               grad_cores: Sequence[torch.Tensor], alpha: Optional[torch.Tensor] = None,
+               cache: Optional[Cache] = None, grad_cache: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> None:
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(grad_output, torch.float32)
+    for k in range(3):
+        assert grad_cores[k].numel() == cores[k].numel()
+    if grad_cache is not None:
+        _dev(grad_cache, torch.float32)
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_bwd(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                            _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output), _ptr_array(grad_cores),
+                            _ptr(grad_cache), _ptr(workspace), wsb, _stream()))
+
+
+def tt_emb_sgd_update(shape: TTShape, cores: Sequence[torch.Tensor], grad_cores: Sequence[torch.Tensor], lr: float,
+                      cache: Optional[Cache] = None, grad_cache: Optional[torch.Tensor] = None,
+                      zero_grad: bool = False) -> None:
+    _check(lib().tt_emb_sgd_update(C.byref(shape), _ptr_array(cores), _ptr_array(grad_cores), C.c_float(lr),
+                                   cache.ref() if cache else None, _ptr(grad_cache), int(zero_grad), _stream()))
+
+
+def tt_cache_build(shape: TTShape, cores: Sequence[torch.Tensor], cand_rows: torch.Tensor,
+                   cand_counts: torch.Tensor, cache: Cache, workspace: Optional[torch.Tensor] = None) -> Cache:
+    _dev(cand_rows, torch.int64)
+    _dev(cand_counts, torch.int64)
+    n = cand_rows.numel()
+    assert cand_counts.numel() == n
+    if workspace is None:
+        workspace = _ws(lib().tt_cache_build_workspace_bytes(C.byref(shape), n, cache.K), cand_rows.device)
+    _check(lib().tt_cache_build(C.byref(shape), _ptr_array(cores), _ptr(cand_rows), _ptr(cand_counts), n, cache.ref(),
+                                _ptr(workspace), workspace.numel(), _stream()))
+    return cache
+
+
+def tt_cache_lookup(cache: Cache, indices: torch.Tensor, slot: torch.Tensor) -> torch.Tensor:
+    _dev(indices, torch.int64)
+    _dev(slot, torch.int32)
+    assert slot.numel() == indices.numel()
+    _check(lib().tt_cache_lookup(cache.ref(), _ptr(indices), indices.numel(), _ptr(slot), _stream()))
+    return slot
+
+
+def tt_emb_debug_decode(shape: TTShape, indices: torch.Tensor) -> List[torch.Tensor]:
+    _dev(indices, torch.int64)
+    out = [torch.empty(indices.numel(), dtype=torch.int32, device=indices.device) for _ in range(3)]
+    _check(lib().tt_emb_debug_decode(C.byref(shape), _ptr(indices), indices.numel(), _ptr(out[0]), _ptr(out[1]),
+                                     _ptr(out[2]), _stream()))
+    return out
+
+
+def tt_emb_debug_dedup(shape: TTShape, indices: torch.Tensor, which: int, slot: Optional[torch.Tensor] = None):
+    """Returns (uniq, count, perm) trimmed to their valid lengths (this trims on the host)."""
+    _dev(indices, torch.int64)
+    L = indices.numel()
+    dev = indices.device
+    uniq = torch.empty(max(L, 1), dtype=torch.int64, device=dev)
+    count = torch.empty(max(L, 1), dtype=torch.int32, device=dev)
+    perm = torch.empty(max(L, 1), dtype=torch.int32, device=dev)
+    n_out = torch.zeros(2, dtype=torch.int64, device=dev)
+    ws = _ws(lib().tt_emb_dedup_workspace_bytes(L), dev)
+    _check(lib().tt_emb_debug_dedup(C.byref(shape), _ptr(indices), L, _ptr(slot), int(which), _ptr(uniq), _ptr(count),
+                                    _ptr(perm), _ptr(n_out), _ptr(ws), ws.numel(), _stream()))
+    nu, kept = (int(x) for x in n_out.cpu())
+    return uniq[:nu], count[:nu], perm[:kept]
+
+
+def set_fast_path(enabled: bool) -> bool:
+    return bool(lib().tt_emb_debug_set_fast_path(int(enabled)))

@@ -1,0 +1,393 @@
+// C-ABI entry points of the TT-EmbeddingBag library (declared in include/tt_emb.h):
+// argument checks, workspace layout, kernel selection and launches.  Nothing here
+// allocates device memory or waits for the stream.
+
+#include "../../include/tt_emb.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "tt_common.h"
+#include "tt_sort.h"
+#include "tt_select.h"
+#include "tt_generic.h"
+#include "tt_fast.h"
+
+using namespace tt;
+
+namespace {
+
+thread_local char g_err[512] = "";
+int g_fast_path = 1;
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_shape(const tt_shape_t *s, Params *p)
+{
+    if (!s) return fail(TT_ERR_NULL, "shape is NULL");
+    if (s->d != 3) return fail(TT_ERR_BAD_SHAPE, "d = %d, only d = 3 is supported", s->d);
+    if (s->r[0] != 1 || s->r[3] != 1) return fail(TT_ERR_BAD_SHAPE, "boundary ranks must be 1");
+    for (int k = 0; k < 3; ++k)
+        if (s->m[k] <= 0 || s->n[k] <= 0 || s->r[k + 1] <= 0)
+            return fail(TT_ERR_BAD_SHAPE, "non-positive factor or rank at core %d", k);
+    const __int128 prod = (__int128)s->m[0] * s->m[1] * s->m[2];
+    if (s->num_rows <= 0 || (__int128)s->num_rows > prod)
+        return fail(TT_ERR_BAD_SHAPE, "num_rows must be in [1, m1*m2*m3]");
+    if (s->num_rows >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "num_rows >= 2^31");
+    const int64_t N = (int64_t)s->n[0] * s->n[1] * s->n[2];
+    const int64_t sB = (int64_t)s->r[1] * s->n[1] * s->r[2];
+    if (N > WG) return fail(TT_ERR_UNSUPPORTED, "embedding dimension %lld > %d", (long long)N, WG);
+    if (sB > (1 << 16) || (int64_t)s->n[0] * s->r[1] > (1 << 14) || (int64_t)s->r[2] * s->n[2] > (1 << 14))
+        return fail(TT_ERR_UNSUPPORTED, "core slice too large for the on-chip accumulators");
+    if (p) {
+        p->m1 = s->m[0]; p->m2 = s->m[1]; p->m3 = s->m[2];
+        p->n1 = s->n[0]; p->n2 = s->n[1]; p->n3 = s->n[2];
+        p->R1 = s->r[1]; p->R2 = s->r[2];
+        p->N = (int)N;
+        p->sA = p->n1 * p->R1; p->sB = (int)sB; p->sC = p->R2 * p->n3;
+        p->cols = p->n2 * p->R2;
+        p->mg3 = p->m3 > 1 ? (uint32_t)(((1ull << 32) + p->m3 - 1) / (uint64_t)p->m3) : 0u;
+        p->mg2 = p->m2 > 1 ? (uint32_t)(((1ull << 32) + p->m2 - 1) / (uint64_t)p->m2) : 0u;
+    }
+    return TT_OK;
+}
+
+int check_lookup_args(const int64_t *indices, int64_t L, int64_t n_bags, const int64_t *offsets)
+{
+    if (L < 0 || n_bags < 0) return fail(TT_ERR_BAD_ARG, "negative L or n_bags");
+    if (L >= (1ll << 31) || n_bags >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L or n_bags >= 2^31");
+    if (L > 0 && !indices) return fail(TT_ERR_NULL, "indices is NULL");
+    if (!offsets && n_bags != L) return fail(TT_ERR_BAD_ARG, "offsets == NULL requires n_bags == L");
+    return TT_OK;
+}
+
+int check_cache(const tt_cache_t *c, CacheDev *dev, bool need_rows)
+{
+    dev->rows = nullptr; dev->table = nullptr; dev->mask = 0; dev->K = 0;
+    if (!c) return TT_OK;
+    if (c->K < 0 || c->K > (1 << 24)) return fail(TT_ERR_BAD_ARG, "cache K out of range [0, 2^24]");
+    if (c->K == 0) return TT_OK;
+    if (c->capacity < tt_cache_table_capacity(c->K) || (c->capacity & (c->capacity - 1)) || c->capacity > (1ll << 31))
+        return fail(TT_ERR_BAD_ARG, "cache capacity must be a power of two >= tt_cache_table_capacity(K)");
+    if (!c->table || !c->keys || (need_rows && !c->rows)) return fail(TT_ERR_NULL, "cache array is NULL");
+    dev->rows = c->rows; dev->table = c->table; dev->mask = (uint32_t)(c->capacity - 1); dev->K = (int)c->K;
+    return TT_OK;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(TT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t lds_limit()
+{
+    static size_t lim = 0;
+    if (!lim) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
+            lim = (size_t)v;
+        else
+            lim = 64 * 1024;
+    }
+    return lim;
+}
+
+template <typename K>
+int allow_lds(K kernel, size_t bytes)
+{
+    if (bytes > lds_limit()) return fail(TT_ERR_UNSUPPORTED, "kernel needs %zu bytes of LDS, device offers %zu", bytes, lds_limit());
+    if (bytes > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    }
+    return TT_OK;
+}
+
+inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+size_t fwd_bwd_ws_bytes(int64_t L, int with_cache)
+{
+    return 256 + (with_cache ? align256((size_t)(L > 0 ? L : 1) * 4) : 0);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tt_last_error(void) { return g_err; }
+
+int tt_emb_debug_set_fast_path(int enabled)
+{
+    int old = g_fast_path;
+    g_fast_path = enabled ? 1 : 0;
+    return old;
+}
+
+int64_t tt_cache_table_capacity(int64_t K)
+{
+    int64_t cap = 16;
+    while (cap < 2 * K) cap <<= 1;
+    return cap;
+}
+
+size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int with_cache)
+{
+    (void)n_bags;
+    if (check_shape(shape, nullptr) != TT_OK || L < 0) return 0;
+    return fwd_bwd_ws_bytes(L, with_cache);
+}
+
+size_t tt_emb_dedup_workspace_bytes(int64_t L)
+{
+    if (L < 0) return 0;
+    return sort_ws_layout(nullptr, L > 0 ? L : 1).bytes;
+}
+
+size_t tt_cache_build_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, int64_t K)
+{
+    (void)K;
+    if (check_shape(shape, nullptr) != TT_OK || n_cand < 0) return 0;
+    return sort_ws_layout(nullptr, n_cand > 0 ? n_cand : 1).bytes;
+}
+
+int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               float *output, void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, true))) return rc;
+    if (n_bags == 0) return TT_OK;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (g_fast_path) {
+        int frc = fast_fwd(p, cores[0], cores[1], cores[2], indices, offsets, (int)n_bags, alpha, cd, output, st);
+        if (frc == 0) {
+            hipError_t e = hipGetLastError();
+            return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
+        }
+    }
+    const size_t lds = (size_t)(p.sA + p.sC + p.n1 * p.cols) * sizeof(float);
+    if ((rc = allow_lds(fwd_generic_kernel, lds))) return rc;
+    const int grid = (int)(n_bags < 65536 ? n_bags : 65536);
+    hipLaunchKernelGGL(fwd_generic_kernel, dim3(grid), dim3(WG), lds, st, p, cores[0], cores[1], cores[2],
+                       indices, offsets, (int)n_bags, alpha, cd, output);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
+}
+
+int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               const float *grad_output,
+               float *const grad_cores[3], float *grad_cache,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2])
+        return fail(TT_ERR_NULL, "grad_cores is NULL");
+    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, false))) return rc;
+    if (cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
+    const size_t need = fwd_bwd_ws_bytes(L, cd.K != 0);
+    if (cd.K && (!workspace || workspace_bytes < need))
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    if (L == 0) return TT_OK;
+    hipStream_t st = (hipStream_t)stream;
+
+    // LDS needs of the generic kernels, checked before anything is enqueued
+    const int max_slice = p.sA > p.sB ? (p.sA > p.sC ? p.sA : p.sC) : (p.sB > p.sC ? p.sB : p.sC);
+    const size_t lds_core = sizeof(SelectLds<GEN_CH>) +
+                            (size_t)(max_slice + p.sA + p.sC + p.n1 * p.cols + p.N) * sizeof(float);
+    const int G = WG / p.N > 0 ? WG / p.N : 1;
+    const size_t lds_cache = sizeof(SelectLds<GEN_CH>) + (size_t)G * p.N * sizeof(float);
+    const bool fast = g_fast_path && fast_bwd_supported(p);
+    if (!fast && (rc = allow_lds(bwd_generic_kernel, lds_core))) return rc;
+    if (cd.K && (rc = allow_lds(bwd_cache_kernel, lds_cache))) return rc;
+
+    int32_t *slot = nullptr;
+    if (cd.K) {
+        slot = (int32_t *)workspace;
+        hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
+        hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
+                           offsets, (int)n_bags, alpha, grad_output, grad_cache);
+    }
+    if (fast) {
+        fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
+                 grad_cores[0], grad_cores[1], grad_cores[2], st);
+    } else {
+        hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
+                           cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
+                           grad_output, grad_cores[0], grad_cores[1], grad_cores[2]);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "backward launch");
+}
+
+int tt_emb_sgd_update(const tt_shape_t *shape, float *const cores[3], float *const grad_cores[3],
+                      float lr, const tt_cache_t *cache, float *grad_cache, int zero_grad, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2])
+        return fail(TT_ERR_NULL, "grad_cores is NULL");
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, true))) return rc;
+    if (cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
+    SgdArgs a;
+    const int64_t sizes[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
+    a.start[0] = 0;
+    for (int k = 0; k < 3; ++k) {
+        a.x[k] = cores[k]; a.g[k] = grad_cores[k]; a.count[k] = sizes[k];
+        a.start[k + 1] = a.start[k] + sizes[k];
+    }
+    a.x[3] = cd.K ? cache->rows : nullptr;
+    a.g[3] = cd.K ? grad_cache : nullptr;
+    a.count[3] = cd.K ? (int64_t)cd.K * p.N : 0;
+    a.start[4] = a.start[3] + a.count[3];
+    const int64_t total = a.start[4];
+    int grid = cdiv(total, WG);
+    if (grid > 8192) grid = 8192;
+    hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(WG), 0, (hipStream_t)stream, a, lr, zero_grad);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "sgd launch");
+}
+
+int tt_cache_lookup(const tt_cache_t *cache, const int64_t *indices, int64_t L, int32_t *slot, void *stream)
+{
+    if (!cache) return fail(TT_ERR_NULL, "cache is NULL");
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (L > 0 && (!indices || !slot)) return fail(TT_ERR_NULL, "indices or slot is NULL");
+    CacheDev cd;
+    int rc = check_cache(cache, &cd, false);
+    if (rc) return rc;
+    if (L == 0) return TT_OK;
+    hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, cd, indices, (int)L, slot);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "cache lookup launch");
+}
+
+int tt_cache_build(const tt_shape_t *shape, const float *const cores[3],
+                   const int64_t *cand_rows, const int64_t *cand_counts, int64_t n_cand,
+                   const tt_cache_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (!out) return fail(TT_ERR_NULL, "out is NULL");
+    if (n_cand < 0 || n_cand >= (1ll << 31)) return fail(TT_ERR_BAD_ARG, "n_cand out of range");
+    if (out->K < 0 || out->K > n_cand) return fail(TT_ERR_BAD_ARG, "K must be in [0, n_cand]");
+    CacheDev cd;
+    if ((rc = check_cache(out, &cd, true))) return rc;
+    if (out->K == 0) return TT_OK;
+    if (!cand_rows || !cand_counts) return fail(TT_ERR_NULL, "candidate arrays are NULL");
+    const size_t need = sort_ws_layout(nullptr, n_cand).bytes;
+    if (!workspace || workspace_bytes < need)
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const int K = (int)out->K, n = (int)n_cand;
+    SortWs ws = sort_ws_layout(workspace, n_cand);
+
+    // 1. order the candidates: most used first, ties by row id
+    hipLaunchKernelGGL(cand_keys_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, cand_rows, cand_counts, n, ws.k0);
+    uint64_t *ks; uint32_t *vs;
+    hipError_t e = radix_sort(ws, n, 64, st, &ks, &vs);
+    if (e != hipSuccess) return hip_fail(e, "cache sort");
+    // 2. the first K become slots 0..K-1
+    hipLaunchKernelGGL(take_keys_kernel, dim3(cdiv(K, WG)), dim3(WG), 0, st, ks, K, out->keys);
+    // 3. row -> slot map
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(cdiv(out->capacity, WG)), dim3(WG), 0, st, out->table,
+                       out->capacity, CACHE_EMPTY);
+    hipLaunchKernelGGL(cache_insert_kernel, dim3(cdiv(K, WG)), dim3(WG), 0, st, out->keys, K, out->table,
+                       (uint32_t)(out->capacity - 1));
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "cache build launch");
+    // 4. lines initialised from the cores: one bag per cached row, no cache consulted
+    return tt_emb_fwd(shape, cores, out->keys, K, nullptr, K, nullptr, nullptr, out->rows, nullptr, 0, stream);
+}
+
+int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                        int32_t *i1, int32_t *i2, int32_t *i3, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (L == 0) return TT_OK;
+    if (!indices || !i1 || !i2 || !i3) return fail(TT_ERR_NULL, "NULL array");
+    hipLaunchKernelGGL(decode_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, p, indices, (int)L, i1, i2, i3);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "decode launch");
+}
+
+int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                       const int32_t *slot, int which,
+                       int64_t *uniq, int32_t *count, int32_t *perm, int64_t *n_out,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (which < 0 || which > 3) return fail(TT_ERR_BAD_ARG, "which must be 0..3");
+    if (!n_out) return fail(TT_ERR_NULL, "n_out is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(uq_init_kernel, dim3(1), dim3(64), 0, st, n_out, L);
+    if (L == 0) {
+        hipError_t e0 = hipGetLastError();
+        return e0 == hipSuccess ? TT_OK : hip_fail(e0, "dedup launch");
+    }
+    if (!indices || !uniq || !count || !perm) return fail(TT_ERR_NULL, "NULL array");
+    const size_t need = sort_ws_layout(nullptr, L).bytes;
+    if (!workspace || workspace_bytes < need)
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    SortWs ws = sort_ws_layout(workspace, L);
+    const int n = (int)L;
+    // number of key bits: the sentinel (all ones) must exceed every real key
+    const uint64_t maxkey = which == 0 ? (uint64_t)shape->num_rows - 1
+                                       : (uint64_t)(which == 1 ? p.m1 : (which == 2 ? p.m2 : p.m3)) - 1;
+    int bits = 1;
+    while (((1ull << bits) - 1) <= maxkey) ++bits;
+    const uint64_t sentinel = (1ull << bits) - 1;
+    hipLaunchKernelGGL(dedup_keys_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, p, indices, n, slot, which, sentinel, ws.k0);
+    uint64_t *ks; uint32_t *vs;
+    hipError_t e = radix_sort(ws, n, bits, st, &ks, &vs);
+    if (e != hipSuccess) return hip_fail(e, "dedup sort");
+    const int nblk = rs_blocks(n);
+    hipLaunchKernelGGL(uq_count_kernel, dim3(nblk), dim3(WG), 0, st, ks, n, sentinel, ws.blk);
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, ws.blk, nblk);
+    hipLaunchKernelGGL(uq_write_kernel, dim3(nblk), dim3(WG), 0, st, ks, n, sentinel, ws.blk, nblk, ws.head_pos, uniq, n_out);
+    hipLaunchKernelGGL(uq_counts_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ws.head_pos, n_out, count, n);
+    hipLaunchKernelGGL(copy_perm_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, vs, n, perm);
+    e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "dedup launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,340 @@
+// Shape-generic kernels: correct for any (m, n, r) with d = 3, within the LDS
+// budget.  The specialised kernels in tt_fast.h replace them for the shapes the
+// paper uses; these remain the fallback and the in-library cross-check.
+#pragma once
+
+#include "tt_common.h"
+#include "tt_select.h"
+
+namespace tt {
+
+constexpr int GEN_CH = 1024;     // positions scanned per selection round in the generic backward
+
+// ---- forward (Eq. 3, Eq. 5-6; Alg. 1) -------------------------------------------
+// One workgroup per bag (grid-stride).  LDS: A [sA] | C [sC] | T0 [n1*cols].
+// Thread j < N owns output column j.  Requires N <= 256.
+__global__ __launch_bounds__(WG) void fwd_generic_kernel(Params p, const float *__restrict__ G1,
+                                                         const float *__restrict__ G2, const float *__restrict__ G3,
+                                                         const int64_t *__restrict__ indices,
+                                                         const int64_t *__restrict__ offsets, int n_bags,
+                                                         const float *__restrict__ alpha, CacheDev cache,
+                                                         float *__restrict__ out)
+{
+    extern __shared__ float smem[];
+    float *sA = smem, *sC = sA + p.sA, *sT = sC + p.sC;
+    const int t = threadIdx.x;
+    for (int b = blockIdx.x; b < n_bags; b += gridDim.x) {
+        const int k0 = offsets ? (int)offsets[b] : b;
+        const int k1 = offsets ? (int)offsets[b + 1] : b + 1;
+        float acc = 0.f;
+        for (int k = k0; k < k1; ++k) {
+            const uint32_t row = (uint32_t)indices[k];
+            const float w = alpha ? alpha[k] : 1.f;
+            const int slot = cache.K ? cache_probe(cache, row) : -1;
+            if (slot >= 0) {                                     // uniform over the workgroup
+                if (t < p.N) acc += w * cache.rows[(size_t)slot * p.N + t];
+                continue;
+            }
+            int i1, i2, i3;
+            decode(p, row, i1, i2, i3);
+            const float *A = G1 + (size_t)i1 * p.sA;
+            const float *B = G2 + (size_t)i2 * p.sB;
+            const float *C = G3 + (size_t)i3 * p.sC;
+            for (int e = t; e < p.sA; e += WG) sA[e] = A[e];
+            for (int e = t; e < p.sC; e += WG) sC[e] = C[e];
+            __syncthreads();
+            // T0[j1][c] = sum_a A[j1][a] Bm[a][c]
+            for (int e = t; e < p.n1 * p.cols; e += WG) {
+                const int j1 = e / p.cols, c = e - j1 * p.cols;
+                float s = 0.f;
+                for (int a = 0; a < p.R1; ++a) s = fmaf(sA[j1 * p.R1 + a], B[a * p.cols + c], s);
+                sT[e] = s;
+            }
+            __syncthreads();
+            if (t < p.N) {                                       // y[q][j3] = sum_b T0[q][b] C[b][j3]
+                const int q = t / p.n3, j3 = t - q * p.n3;
+                float s = 0.f;
+                for (int bb = 0; bb < p.R2; ++bb) s = fmaf(sT[q * p.R2 + bb], sC[bb * p.n3 + j3], s);
+                acc += w * s;
+            }
+            __syncthreads();
+        }
+        if (t < p.N) out[(size_t)b * p.N + t] = acc;
+    }
+}
+
+// ---- backward for the cores (Eq. 4; Alg. 2) ---------------------------------------
+// Workgroup g owns one slice: g < m1 -> G1[g]; g < m1+m2 -> G2[g-m1]; else G3[g-m1-m2].
+// It accumulates the slice gradient in LDS (each element has one owner thread) and adds
+// it to grad_cores once.  LDS: SelectLds | acc [max slice] | A | C | T [n1*cols] | dY [N].
+__global__ __launch_bounds__(WG) void bwd_generic_kernel(Params p, const float *__restrict__ G1,
+                                                         const float *__restrict__ G2, const float *__restrict__ G3,
+                                                         const int64_t *__restrict__ indices, int L,
+                                                         const int64_t *__restrict__ offsets, int n_bags,
+                                                         const float *__restrict__ alpha,
+                                                         const int32_t *__restrict__ slot,
+                                                         const float *__restrict__ grad_out,
+                                                         float *__restrict__ dG1, float *__restrict__ dG2,
+                                                         float *__restrict__ dG3)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    SelectLds<GEN_CH> &lds = *reinterpret_cast<SelectLds<GEN_CH> *>(smem_raw);
+    const int max_slice = max(p.sA, max(p.sB, p.sC));
+    float *acc = reinterpret_cast<float *>(smem_raw + sizeof(SelectLds<GEN_CH>));
+    float *sA = acc + max_slice, *sC = sA + p.sA, *sT = sC + p.sC, *sY = sT + p.n1 * p.cols;
+
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    int role, s;
+    {
+        const int g = blockIdx.x;
+        if (g < p.m1) { role = 0; s = g; }
+        else if (g < p.m1 + p.m2) { role = 1; s = g - p.m1; }
+        else { role = 2; s = g - p.m1 - p.m2; }
+    }
+    const int slice = role == 0 ? p.sA : (role == 1 ? p.sB : p.sC);
+    for (int e = t; e < slice; e += WG) acc[e] = 0.f;
+    bool any = false;
+
+    for (int c0 = 0; c0 < L; c0 += GEN_CH) {
+        const int c1 = min(L, c0 + GEN_CH);
+        const int n = select_chunk<GEN_CH>(lds, c0, c1, [&](int k, uint32_t *val) {
+            if (slot && slot[k] >= 0) return false;
+            const uint32_t row = (uint32_t)indices[k];
+            *val = row;
+            return role_digit(p, role, row) == s;
+        });
+        if (n == 0) continue;                                    // uniform
+        any = true;
+        const int nu = sort_dedup<GEN_CH>(lds, n);
+        for (int u = 0; u < nu; ++u) {
+            const int d0 = lds.ustart[u], d1 = lds.ustart[u + 1];
+            int i1, i2, i3;
+            decode(p, lds.sr[d0], i1, i2, i3);
+            const float *A = G1 + (size_t)i1 * p.sA;
+            const float *B = G2 + (size_t)i2 * p.sB;
+            const float *C = G3 + (size_t)i3 * p.sC;
+            // dY = sum over the duplicates of alpha_k * grad_out[bag(k)], in list order
+            if (t < p.N) {
+                float g = 0.f;
+                for (int d = d0; d < d1; ++d) {
+                    const int k = lds.sk[d];
+                    const int bag = bag_of(offsets, n_bags, k);
+                    g += (alpha ? alpha[k] : 1.f) * grad_out[(size_t)bag * p.N + t];
+                }
+                sY[t] = g;
+            }
+            for (int e = t; e < p.sA; e += WG) sA[e] = A[e];
+            for (int e = t; e < p.sC; e += WG) sC[e] = C[e];
+            __syncthreads();
+            if (role == 2) {
+                // T0[j1][c] = sum_a A[j1][a] Bm[a][c];  dG3[b][j3] += sum_q T0[q][b] dY[q][j3]
+                for (int e = t; e < p.n1 * p.cols; e += WG) {
+                    const int j1 = e / p.cols, c = e - j1 * p.cols;
+                    float sum = 0.f;
+                    for (int a = 0; a < p.R1; ++a) sum = fmaf(sA[j1 * p.R1 + a], B[a * p.cols + c], sum);
+                    sT[e] = sum;
+                }
+                __syncthreads();
+                for (int e = t; e < p.sC; e += WG) {
+                    const int bb = e / p.n3, j3 = e - bb * p.n3;
+                    float sum = 0.f;
+                    for (int q = 0; q < p.n1 * p.n2; ++q) sum = fmaf(sT[q * p.R2 + bb], sY[q * p.n3 + j3], sum);
+                    acc[e] += sum;
+                }
+            } else {
+                // dT0[q][b] = sum_j3 dY[q][j3] C[b][j3], stored as dT0'[j1][c]
+                for (int e = t; e < p.n1 * p.cols; e += WG) {
+                    const int q = e / p.R2, bb = e - q * p.R2;
+                    float sum = 0.f;
+                    for (int j3 = 0; j3 < p.n3; ++j3) sum = fmaf(sY[q * p.n3 + j3], sC[bb * p.n3 + j3], sum);
+                    sT[e] = sum;
+                }
+                __syncthreads();
+                if (role == 1) {
+                    // dG2[a][c] += sum_j1 A[j1][a] dT0'[j1][c]
+                    for (int e = t; e < p.sB; e += WG) {
+                        const int a = e / p.cols, c = e - a * p.cols;
+                        float sum = 0.f;
+                        for (int j1 = 0; j1 < p.n1; ++j1) sum = fmaf(sA[j1 * p.R1 + a], sT[j1 * p.cols + c], sum);
+                        acc[e] += sum;
+                    }
+                } else {
+                    // dG1[j1][a] += sum_c dT0'[j1][c] Bm[a][c]: one wave per output, lanes over c
+                    for (int e = w; e < p.sA; e += NWAVE) {
+                        const int j1 = e / p.R1, a = e - j1 * p.R1;
+                        float sum = 0.f;
+                        for (int c = lane; c < p.cols; c += WAVE) sum = fmaf(sT[j1 * p.cols + c], B[a * p.cols + c], sum);
+#pragma unroll
+                        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
+                        if (lane == 0) acc[e] += sum;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (any) {
+        float *dst = role == 0 ? dG1 + (size_t)s * p.sA : (role == 1 ? dG2 + (size_t)s * p.sB : dG3 + (size_t)s * p.sC);
+        __syncthreads();
+        for (int e = t; e < slice; e += WG) dst[e] += acc[e];
+    }
+}
+
+// ---- backward for the cached rows (Section 4.2) ------------------------------------
+// Workgroup g owns the slots [g*G, g*G + G), G = max(1, 256 / N).  It scans the slot of
+// every position, keeps the matches in order and adds alpha_k * grad_out[bag(k)] to the
+// owned line.  LDS: SelectLds | acc [G*N].
+__global__ __launch_bounds__(WG) void bwd_cache_kernel(int N, int K, int G, const int32_t *__restrict__ slot, int L,
+                                                       const int64_t *__restrict__ offsets, int n_bags,
+                                                       const float *__restrict__ alpha,
+                                                       const float *__restrict__ grad_out,
+                                                       float *__restrict__ grad_cache)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    SelectLds<GEN_CH> &lds = *reinterpret_cast<SelectLds<GEN_CH> *>(smem_raw);
+    float *acc = reinterpret_cast<float *>(smem_raw + sizeof(SelectLds<GEN_CH>));
+    const int t = threadIdx.x;
+    const int g0 = blockIdx.x * G;
+    const int g1 = min(K, g0 + G);
+    for (int e = t; e < G * N; e += WG) acc[e] = 0.f;
+    bool any = false;
+    for (int c0 = 0; c0 < L; c0 += GEN_CH) {
+        const int c1 = min(L, c0 + GEN_CH);
+        const int n = select_chunk<GEN_CH>(lds, c0, c1, [&](int k, uint32_t *val) {
+            const int sl = slot[k];
+            *val = (uint32_t)(sl - g0);
+            return sl >= g0 && sl < g1;
+        });
+        if (n == 0) continue;
+        any = true;
+        // lds.sk is free here: keep the bag of every match in it
+        for (int i = t; i < n; i += WG) lds.sk[i] = bag_of(offsets, n_bags, lds.klist[i]);
+        __syncthreads();
+        for (int e = t; e < G * N; e += WG) {
+            const int sl = e / N, j = e - sl * N;
+            float sum = acc[e];
+            for (int i = 0; i < n; ++i) {
+                if ((int)lds.rows[i] == sl) {
+                    const int k = lds.klist[i];
+                    sum += (alpha ? alpha[k] : 1.f) * grad_out[(size_t)lds.sk[i] * N + j];
+                }
+            }
+            acc[e] = sum;
+        }
+        __syncthreads();
+    }
+    if (any) {
+        for (int e = t; e < (g1 - g0) * N; e += WG) grad_cache[(size_t)g0 * N + e] += acc[e];
+    }
+}
+
+// ---- SGD (Section 5) ------------------------------------------------------------------
+// x <- x - lr * g over up to four arrays in one launch (three cores and the cache lines).
+struct SgdArgs {
+    float *x[4];
+    float *g[4];
+    int64_t count[4];
+    int64_t start[5];     // prefix sums of count
+};
+
+__global__ __launch_bounds__(WG) void sgd_kernel(SgdArgs a, float lr, int zero_grad)
+{
+    const int64_t total = a.start[4];
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < total; i += (int64_t)gridDim.x * WG) {
+        int k = 0;
+#pragma unroll
+        for (int q = 1; q < 4; ++q) k += (i >= a.start[q]);
+        const int64_t e = i - a.start[k];
+        float *x = a.x[k];
+        float *g = a.g[k];
+        x[e] = fmaf(-lr, g[e], x[e]);
+        if (zero_grad) g[e] = 0.f;
+    }
+}
+
+// ---- cache map --------------------------------------------------------------------------
+
+__global__ __launch_bounds__(WG) void fill_u64_kernel(uint64_t *__restrict__ p, int64_t n, uint64_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;
+}
+
+// table[h(row)] = (row << 32 | slot) with linear probing; rows are distinct.
+__global__ __launch_bounds__(WG) void cache_insert_kernel(const int64_t *__restrict__ keys, int K,
+                                                          uint64_t *__restrict__ table, uint32_t mask)
+{
+    const int s = blockIdx.x * WG + threadIdx.x;
+    if (s >= K) return;
+    const uint32_t row = (uint32_t)keys[s];
+    const uint64_t entry = ((uint64_t)row << 32) | (uint32_t)s;
+    uint32_t h = cache_hash(row, mask);
+    for (;;) {                                    // ends: capacity >= 2K, so an empty entry exists
+        const unsigned long long old = atomicCAS((unsigned long long *)&table[h], (unsigned long long)CACHE_EMPTY,
+                                                 (unsigned long long)entry);
+        if (old == (unsigned long long)CACHE_EMPTY) return;
+        h = (h + 1) & mask;
+    }
+}
+
+__global__ __launch_bounds__(WG) void cache_lookup_kernel(CacheDev c, const int64_t *__restrict__ indices, int L,
+                                                          int32_t *__restrict__ slot)
+{
+    const int k = blockIdx.x * WG + threadIdx.x;
+    if (k < L) slot[k] = c.K ? cache_probe(c, (uint32_t)indices[k]) : -1;
+}
+
+// ---- integer exports ------------------------------------------------------------------------
+
+__global__ __launch_bounds__(WG) void decode_kernel(Params p, const int64_t *__restrict__ indices, int L,
+                                                    int32_t *__restrict__ o1, int32_t *__restrict__ o2,
+                                                    int32_t *__restrict__ o3)
+{
+    const int k = blockIdx.x * WG + threadIdx.x;
+    if (k >= L) return;
+    int i1, i2, i3;
+    decode(p, (uint32_t)indices[k], i1, i2, i3);
+    o1[k] = i1; o2[k] = i2; o3[k] = i3;
+}
+
+// keys[k] = row id (which = 0) or digit (which = 1..3) of indices[k]; skipped positions get `sentinel`.
+__global__ __launch_bounds__(WG) void dedup_keys_kernel(Params p, const int64_t *__restrict__ indices, int L,
+                                                        const int32_t *__restrict__ slot, int which,
+                                                        uint64_t sentinel, uint64_t *__restrict__ keys)
+{
+    const int k = blockIdx.x * WG + threadIdx.x;
+    if (k >= L) return;
+    const uint32_t row = (uint32_t)indices[k];
+    uint64_t key = row;
+    if (which > 0) {
+        int i1, i2, i3;
+        decode(p, row, i1, i2, i3);
+        key = (uint64_t)(which == 1 ? i1 : (which == 2 ? i2 : i3));
+    }
+    if (slot && slot[k] >= 0) key = sentinel;
+    keys[k] = key;
+}
+
+__global__ __launch_bounds__(WG) void copy_perm_kernel(const uint32_t *__restrict__ v, int n, int32_t *__restrict__ perm)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i < n) perm[i] = (int32_t)v[i];
+}
+
+// Candidate (row, count) -> sort key: most used first, then lower row id (Section 4.2, ties by row).
+__global__ __launch_bounds__(WG) void cand_keys_kernel(const int64_t *__restrict__ rows, const int64_t *__restrict__ counts,
+                                                       int n, uint64_t *__restrict__ keys)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t c = (uint64_t)counts[i];
+    const uint32_t inv = 0xFFFFFFFFu - (uint32_t)(c > 0xFFFFFFFFull ? 0xFFFFFFFFull : c);
+    keys[i] = ((uint64_t)inv << 32) | (uint32_t)rows[i];
+}
+
+__global__ __launch_bounds__(WG) void take_keys_kernel(const uint64_t *__restrict__ sorted, int K, int64_t *__restrict__ keys)
+{
+    const int s = blockIdx.x * WG + threadIdx.x;
+    if (s < K) keys[s] = (int64_t)(uint32_t)sorted[s];
+}
+
+}  // namespace tt

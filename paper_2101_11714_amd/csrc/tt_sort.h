@@ -1,0 +1,237 @@
+// Device-wide stable LSD radix sort (64-bit keys, 32-bit payload) and run-length
+// "unique" on the sorted keys.  Used by the cache population (top-K selection,
+// Section 4.2 of the paper) and by the canonical dedup export.  Integer only.
+#pragma once
+
+#include "tt_common.h"
+
+namespace tt {
+
+constexpr int RS_TILE = 2048;                   // keys per workgroup and pass
+constexpr int RS_SUB = RS_TILE / WG;            // 8 rounds of 256 keys
+constexpr int SCAN_WG = 1024;
+
+static inline int rs_blocks(int64_t n) { return (int)((n + RS_TILE - 1) / RS_TILE); }
+
+// hist[bin * nblk + blk] = number of keys of tile blk whose digit is bin.
+__global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict__ keys, int n, int shift,
+                                                     uint32_t *__restrict__ hist, int nblk)
+{
+    __shared__ uint32_t h[256];
+    const int t = threadIdx.x;
+    h[t] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * RS_TILE;
+#pragma unroll
+    for (int s = 0; s < RS_SUB; ++s) {
+        int i = base + s * WG + t;
+        if (i < n) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[t * nblk + blockIdx.x] = h[t];
+}
+
+// In-place exclusive scan of data[0..total); data[total] receives the sum.  One workgroup.
+__global__ __launch_bounds__(SCAN_WG) void scan_kernel(uint32_t *__restrict__ data, int total)
+{
+    __shared__ uint32_t wsum[SCAN_WG / WAVE];
+    __shared__ uint32_t carry;
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    if (t == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < total; base += SCAN_WG) {
+        int i = base + t;
+        uint32_t v = i < total ? data[i] : 0u;
+        uint32_t inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wsum[w] = inc;
+        __syncthreads();
+        uint32_t pre = carry;
+        for (int j = 0; j < w; ++j) pre += wsum[j];
+        if (i < total) data[i] = pre + inc - v;
+        __syncthreads();
+        if (t == SCAN_WG - 1) carry = pre + inc;
+        __syncthreads();
+    }
+    if (t == 0) data[total] = carry;
+}
+
+// Stable scatter of one pass.  vin == nullptr means payload = position.
+__global__ __launch_bounds__(WG) void rs_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
+                                                        uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
+                                                        int n, int shift, const uint32_t *__restrict__ hist, int nblk)
+{
+    __shared__ uint32_t base[256];
+    __shared__ uint32_t cnt[NWAVE][256];
+    const int t = threadIdx.x, w = t >> 6;
+    base[t] = hist[t * nblk + blockIdx.x];
+    const int tile = blockIdx.x * RS_TILE;
+    for (int s = 0; s < RS_SUB; ++s) {
+        const int i = tile + s * WG + t;
+        const bool valid = i < n;
+        const uint64_t key = valid ? kin[i] : 0ull;
+        const uint32_t dg = (uint32_t)(key >> shift) & 255u;
+#pragma unroll
+        for (int j = 0; j < NWAVE; ++j) cnt[j][t] = 0;
+        __syncthreads();
+        // lanes of this wave that hold the same digit
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (dg >> b) & 1u;
+            const uint64_t bal = __ballot(bit);
+            same &= bit ? bal : ~bal;
+        }
+        const int rank = __popcll(same & lanemask_lt());
+        if (valid && rank == 0) cnt[w][dg] = (uint32_t)__popcll(same);
+        __syncthreads();
+        {   // thread t owns bin t: turn per-wave counts into starting positions
+            uint32_t r = base[t];
+#pragma unroll
+            for (int j = 0; j < NWAVE; ++j) {
+                uint32_t c = cnt[j][t];
+                cnt[j][t] = r;
+                r += c;
+            }
+            base[t] = r;
+        }
+        __syncthreads();
+        if (valid) {
+            const uint32_t dst = cnt[w][dg] + (uint32_t)rank;
+            kout[dst] = key;
+            vout[dst] = vin ? vin[i] : (uint32_t)i;
+        }
+        __syncthreads();
+    }
+}
+
+// ---- unique on sorted keys ------------------------------------------------------
+// Keys equal to `sentinel` (sorted last) are not counted.
+
+__global__ __launch_bounds__(WG) void uq_count_kernel(const uint64_t *__restrict__ keys, int n, uint64_t sentinel,
+                                                      uint32_t *__restrict__ blkcnt)
+{
+    __shared__ int tmp[NWAVE + 1];
+    const int t = threadIdx.x;
+    const int tile = blockIdx.x * RS_TILE;
+    int c = 0;
+#pragma unroll
+    for (int s = 0; s < RS_SUB; ++s) {
+        int i = tile + s * WG + t;
+        if (i < n) {
+            uint64_t k = keys[i];
+            if (k != sentinel && (i == 0 || keys[i - 1] != k)) ++c;
+        }
+    }
+    int total;
+    (void)block_excl_scan(c, tmp, &total);
+    if (t == 0) blkcnt[blockIdx.x] = (uint32_t)total;
+}
+
+// head_pos[u] = position of the first occurrence of the u-th distinct key; uniq[u] = that key.
+// n_out[0] = number of distinct keys, n_out[1] = number of non-sentinel keys.
+__global__ __launch_bounds__(WG) void uq_write_kernel(const uint64_t *__restrict__ keys, int n, uint64_t sentinel,
+                                                      const uint32_t *__restrict__ blkoff, int nblk,
+                                                      uint32_t *__restrict__ head_pos, int64_t *__restrict__ uniq,
+                                                      int64_t *__restrict__ n_out)
+{
+    __shared__ int tmp[NWAVE + 1];
+    const int t = threadIdx.x;
+    const int tile = blockIdx.x * RS_TILE;
+    int running = (int)blkoff[blockIdx.x];
+    for (int s = 0; s < RS_SUB; ++s) {
+        const int i = tile + s * WG + t;
+        uint64_t k = 0;
+        bool head = false;
+        if (i < n) {
+            k = keys[i];
+            const bool first = (i == 0) || keys[i - 1] != k;
+            head = first && k != sentinel;
+            if (first && k == sentinel) n_out[1] = i;          // first skipped key: only one thread can see it
+        }
+        int total;
+        const int ex = block_excl_scan(head ? 1 : 0, tmp, &total);
+        if (head) {
+            head_pos[running + ex] = (uint32_t)i;
+            uniq[running + ex] = (int64_t)k;
+        }
+        running += total;
+    }
+    if (blockIdx.x == 0 && t == 0) n_out[0] = (int64_t)blkoff[nblk];
+}
+
+__global__ void uq_init_kernel(int64_t *n_out, int64_t n)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { n_out[0] = 0; n_out[1] = n; }
+}
+
+__global__ __launch_bounds__(WG) void uq_counts_kernel(const uint32_t *__restrict__ head_pos,
+                                                       const int64_t *__restrict__ n_out,
+                                                       int32_t *__restrict__ count, int n)
+{
+    const int64_t nu = n_out[0], kept = n_out[1];
+    const int64_t u = (int64_t)blockIdx.x * WG + threadIdx.x;
+    if (u < nu && u < n) {
+        const uint32_t next = (u + 1 < nu) ? head_pos[u + 1] : (uint32_t)kept;
+        count[u] = (int32_t)(next - head_pos[u]);
+    }
+}
+
+// Workspace of a sort of n keys: two key buffers, two payload buffers, histogram.
+struct SortWs {
+    uint64_t *k0, *k1;
+    uint32_t *v0, *v1;
+    uint32_t *hist;          // 256*nblk + 1
+    uint32_t *head_pos;      // n + 1
+    uint32_t *blk;           // nblk + 1
+    size_t bytes;
+};
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static inline SortWs sort_ws_layout(void *ws, int64_t n)
+{
+    SortWs s;
+    const int nblk = rs_blocks(n > 0 ? n : 1);
+    char *p = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
+    s.k0 = (uint64_t *)take((size_t)n * 8);
+    s.k1 = (uint64_t *)take((size_t)n * 8);
+    s.v0 = (uint32_t *)take((size_t)n * 4);
+    s.v1 = (uint32_t *)take((size_t)n * 4);
+    s.hist = (uint32_t *)take(((size_t)256 * nblk + 1) * 4);
+    s.head_pos = (uint32_t *)take(((size_t)n + 1) * 4);
+    s.blk = (uint32_t *)take(((size_t)nblk + 1) * 4);
+    s.bytes = off + 256;
+    return s;
+}
+
+// Sort keys in s.k0 (payload = original position) by their low `bits` bits.
+// Returns the buffers that hold the result in *kres / *vres.
+static inline hipError_t radix_sort(const SortWs &s, int n, int bits, hipStream_t st,
+                                    uint64_t **kres, uint32_t **vres)
+{
+    uint64_t *kin = s.k0, *kout = s.k1;
+    uint32_t *vin = nullptr, *vout = s.v0;
+    const int nblk = rs_blocks(n);
+    bool first = true;
+    for (int shift = 0; shift < bits; shift += 8) {
+        hipLaunchKernelGGL(rs_hist_kernel, dim3(nblk), dim3(WG), 0, st, kin, n, shift, s.hist, nblk);
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, s.hist, 256 * nblk);
+        hipLaunchKernelGGL(rs_scatter_kernel, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift,
+                           s.hist, nblk);
+        uint64_t *tk = kin; kin = kout; kout = tk;
+        if (first) { vin = s.v0; vout = s.v1; first = false; }
+        else { uint32_t *tv = vin; vin = vout; vout = tv; }
+    }
+    *kres = kin;
+    *vres = vin;          // nullptr only if bits == 0 (never asked for)
+    return hipGetLastError();
+}
+
+}  // namespace tt

@@ -1,0 +1,111 @@
+"""CPU-only checks of the C-ABI: the library loads, exports every declared symbol,
+and rejects bad arguments on the host before anything touches a device."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2101_11714_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good_shape():
+    return B.make_shape(1000, (10, 10, 10), (2, 2, 4), (1, 8, 8, 1))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "tt_emb.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tt_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    l = B.lib()
+    for name in declared:
+        assert getattr(l, name) is not None
+
+
+def test_struct_layout_matches_header():
+    # int32 d, (pad), int64 num_rows, int32 m[3], n[3], r[4] -> 56 bytes with natural alignment
+    assert C.sizeof(B.TTShape) == 56 and B.TTShape.num_rows.offset == 8 and B.TTShape.m.offset == 16
+    assert C.sizeof(B.TTCache) == 40
+
+
+def test_table_capacity_is_power_of_two_and_at_least_2k():
+    l = B.lib()
+    for K in (0, 1, 7, 1000, 1013, 4000, 4096):
+        cap = l.tt_cache_table_capacity(K)
+        assert cap >= 2 * K and cap & (cap - 1) == 0
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda s: setattr(s, "d", 2), -2),
+    (lambda s: s.r.__setitem__(0, 2), -2),
+    (lambda s: s.r.__setitem__(3, 3), -2),
+    (lambda s: s.m.__setitem__(1, 0), -2),
+    (lambda s: s.n.__setitem__(2, -4), -2),
+    (lambda s: setattr(s, "num_rows", 1001), -2),
+    (lambda s: setattr(s, "num_rows", 0), -2),
+])
+def test_bad_shapes_are_rejected(mutate, code):
+    l = B.lib()
+    s = good_shape()
+    mutate(s)
+    one = C.c_void_p(8)   # never dereferenced: the shape check comes first
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, one, None, 0, None) == code
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, arr, None, None, 0, None) == code
+    assert l.tt_emb_sgd_update(C.byref(s), arr, arr, C.c_float(0.1), None, None, 0, None) == code
+    assert l.tt_emb_workspace_bytes(C.byref(s), 1, 1, 0) == 0
+    assert len(l.tt_last_error()) > 0
+
+
+def test_too_many_rows_is_unsupported():
+    l = B.lib()
+    s = B.make_shape(2 ** 31, (2048, 1024, 1024), (2, 2, 4), (1, 8, 8, 1))
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    one = C.c_void_p(8)
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, one, None, 0, None) == -6
+
+
+def test_null_and_bad_arguments():
+    l = B.lib()
+    s = good_shape()
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    holes = (C.c_void_p * 3)(8, None, 8)
+    one = C.c_void_p(8)
+    assert l.tt_emb_fwd(None, arr, one, 1, None, 1, None, None, one, None, 0, None) == -1
+    assert l.tt_emb_fwd(C.byref(s), None, one, 1, None, 1, None, None, one, None, 0, None) == -1
+    assert l.tt_emb_fwd(C.byref(s), holes, one, 1, None, 1, None, None, one, None, 0, None) == -1
+    assert l.tt_emb_fwd(C.byref(s), arr, None, 1, None, 1, None, None, one, None, 0, None) == -1
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, None, None, 0, None) == -1
+    assert l.tt_emb_fwd(C.byref(s), arr, one, -1, None, 1, None, None, one, None, 0, None) == -3
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 2, None, 1, None, None, one, None, 0, None) == -3   # no offsets, L != n_bags
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, None, arr, None, None, 0, None) == -1
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, holes, None, None, 0, None) == -1
+    # a cache without its gradient buffer, and without workspace
+    cache = B.TTCache(4, 16, 8, 8, 8)
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(cache), one, arr, None, None, 0, None) == -1
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(cache), one, arr, one, None, 0, None) == -4
+    bad_cap = B.TTCache(100, 100, 8, 8, 8)
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(bad_cap), one, None, 0, None) == -3
+    assert l.tt_cache_lookup(None, one, 1, one, None) == -1
+    assert l.tt_cache_build(C.byref(s), arr, one, one, 3, C.byref(cache), None, 0, None) == -3      # K > n_cand
+    assert l.tt_cache_build(C.byref(s), arr, one, one, 10, C.byref(cache), None, 0, None) == -4     # no workspace
+    assert l.tt_emb_debug_decode(C.byref(s), None, 5, one, one, one, None) == -1
+    assert l.tt_emb_debug_dedup(C.byref(s), one, 5, None, 7, one, one, one, one, one, 1 << 20, None) == -3
+
+
+def test_empty_calls_enqueue_nothing_and_succeed():
+    l = B.lib()
+    s = good_shape()
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    assert l.tt_emb_fwd(C.byref(s), arr, None, 0, None, 0, None, None, None, None, 0, None) == 0
+    assert l.tt_emb_bwd(C.byref(s), arr, None, 0, None, 0, None, None, None, arr, None, None, 0, None) == 0
+    assert l.tt_emb_debug_decode(C.byref(s), None, 0, None, None, None, None) == 0
+
+
+def test_binding_has_no_cpu_fallback():
+    src = open(os.path.join(ROOT, "paper_2101_11714_amd", "binding.py")).read()
+    assert "oracle" not in src.replace("no CPU fallback", "")

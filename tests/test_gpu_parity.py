@@ -1,0 +1,287 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the
+same seeded inputs.  Integer work (digits, dedup, cache selection and probe) must be
+bit-exact; floating point must meet max |gpu - ref| / max |ref| <= 1e-4 per tensor."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tt_oracle as ora
+from paper_2101_11714_amd import binding as B
+from paper_2101_11714_amd import workloads as W
+from gpu_util import DeviceTable, assert_close, dev, sample_bags
+
+pytestmark = pytest.mark.gpu
+
+SINGLE = ["tiny", "kaggle_r32", "sweep_r8", "sweep_r16", "sweep_r32", "sweep_r64", "terabyte_r64"]
+
+
+@pytest.fixture(params=[True, False], ids=["fast", "generic"])
+def path(request):
+    old = B.set_fast_path(request.param)
+    yield request.param
+    B.set_fast_path(old)
+
+
+# ------------------------------------------------------------------ integer work
+
+@pytest.mark.parametrize("name", SINGLE + ["multihot_cache"])
+def test_decode_bit_exact(name):
+    wl = W.WORKLOADS[name]
+    for table in (0, len(wl.tables) - 1):
+        t = wl.tables[table]
+        batch = W.make_batch(wl, table)
+        m1, m2, m3 = t.m
+        edge = np.array([0, 1, m3 - 1, m3, m2 * m3 - 1, m2 * m3, t.num_rows - 1, t.num_rows - m3], dtype=np.int64)
+        edge = edge[(edge >= 0) & (edge < t.num_rows)]
+        idx = np.concatenate([edge, batch.indices])
+        got = B.tt_emb_debug_decode(B.shape_of(t), torch.from_numpy(idx).to(dev()))
+        ref = ora.decode(ora.Shape.of(t), idx)
+        for k in range(3):
+            assert np.array_equal(got[k].cpu().numpy(), ref[k])
+
+
+def test_decode_awkward_factors():
+    # divisors 1, 2, powers of two, primes, and a large last factor
+    for m in [(1, 1, 7), (3, 1, 5), (2, 2, 2), (7, 1, 1), (13, 17, 19), (64, 128, 256), (5, 100003, 3), (2, 3, 300000007)]:
+        rows = min(m[0] * m[1] * m[2], 2 ** 31 - 1)
+        shape = B.make_shape(rows, m, (2, 2, 4), (1, 8, 8, 1))
+        rng = np.random.default_rng(1)
+        idx = np.unique(np.concatenate([rng.integers(0, rows, 20000), [0, rows - 1]]))
+        got = B.tt_emb_debug_decode(shape, torch.from_numpy(idx).to(dev()))
+        ref = ora.decode(ora.Shape(rows, m, (2, 2, 4), (1, 8, 8, 1)), idx)
+        for k in range(3):
+            assert np.array_equal(got[k].cpu().numpy(), ref[k]), m
+
+
+@pytest.mark.parametrize("name", ["tiny", "kaggle_r32", "terabyte_r64", "multihot_cache"])
+@pytest.mark.parametrize("which", [0, 1, 2, 3])
+def test_dedup_bit_exact(name, which):
+    wl = W.WORKLOADS[name]
+    t = wl.tables[0]
+    batch = W.make_batch(wl)
+    idx = batch.indices
+    digits = ora.decode(ora.Shape.of(t), idx)
+    keys = idx.copy() if which == 0 else digits[which - 1].astype(np.int64)
+    # skip a pseudo-random 30 % of the positions, as cached lookups would be
+    slot = np.where(np.random.default_rng(3).random(idx.size) < 0.3, 5, -1).astype(np.int32)
+    for use_slot in (False, True):
+        k = keys.copy()
+        if use_slot:
+            k[slot >= 0] = -1
+        ru, rc, rp = ora.dedup(k)
+        gu, gc, gp = B.tt_emb_debug_dedup(B.shape_of(t), torch.from_numpy(idx).to(dev()), which,
+                                          torch.from_numpy(slot).to(dev()) if use_slot else None)
+        assert np.array_equal(gu.cpu().numpy(), ru)
+        assert np.array_equal(gc.cpu().numpy(), rc)
+        assert np.array_equal(gp.cpu().numpy(), rp)
+
+
+def test_dedup_all_equal_and_empty():
+    t = W.WORKLOADS["tiny"].tables[0]
+    idx = np.full(5000, 321, dtype=np.int64)
+    gu, gc, gp = B.tt_emb_debug_dedup(B.shape_of(t), torch.from_numpy(idx).to(dev()), 0)
+    assert gu.cpu().tolist() == [321] and gc.cpu().tolist() == [5000]
+    assert np.array_equal(gp.cpu().numpy(), np.arange(5000))
+    gu, gc, gp = B.tt_emb_debug_dedup(B.shape_of(t), torch.zeros(0, dtype=torch.int64, device=dev()), 0)
+    assert gu.numel() == 0 and gc.numel() == 0 and gp.numel() == 0
+
+
+# ------------------------------------------------------------------ forward
+
+@pytest.mark.parametrize("name", SINGLE)
+def test_forward_matches_oracle(name, path):
+    d = DeviceTable(W.WORKLOADS[name])
+    out = d.fwd()
+    pick, idx, off, alpha = sample_bags(d.batch, 2048)
+    ref = ora.fwd(d.oshape, d.cores, idx, off, alpha=alpha)
+    assert_close(out[pick], ref, name + " forward")
+    if d.L == d.n_bags:                                   # one index per bag: offsets may be omitted
+        assert np.array_equal(d.fwd(use_offsets=False), out)
+
+
+def test_forward_ragged_weighted_and_empty_bags(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(5)
+    lens = np.array([0, 3, 0, 0, 1, 70, 2, 0, 300, 1, 0], dtype=np.int64)
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, t.num_rows, int(off[-1]))
+    idx[10:60] = 77                                        # a long run of one row
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(idx.size)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    out = d.fwd()
+    ref = ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha)
+    assert_close(out, ref, "ragged forward")
+    assert np.all(out[lens == 0] == 0)
+
+
+# ------------------------------------------------------------------ backward + SGD
+
+@pytest.mark.parametrize("name", SINGLE)
+def test_backward_and_sgd_match_oracle(name, path):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl)
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output)
+    dg, _ = d.bwd()
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "%s dG%d" % (name, k + 1))
+    # run-to-run determinism, bit for bit
+    dg2, _ = d.bwd()
+    for k in range(3):
+        assert torch.equal(dg[k], dg2[k])
+    # "+=": a second call on top of the first doubles the gradient
+    d.bwd(grad_cores=dg2)
+    for k in range(3):
+        assert_close(dg2[k].cpu().numpy(), 2 * ref[k], "%s accumulate dG%d" % (name, k + 1))
+    # SGD on the cores, then clear the gradients
+    new_ref = [ora.sgd(d.cores[k], dg[k].cpu().numpy(), wl.lr) for k in range(3)]
+    B.tt_emb_sgd_update(d.shape, d.g, dg, wl.lr, zero_grad=True)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert_close(d.g[k].cpu().numpy(), new_ref[k], "%s sgd core %d" % (name, k + 1))
+        assert float(dg[k].abs().max()) == 0.0
+
+
+def test_backward_leaves_untouched_slices_alone(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(9)
+    idx = np.array([123, 123, 456, 123], dtype=np.int64)      # digits (1,2,3) and (4,5,6)
+    off = np.array([0, 2, 2, 4], dtype=np.int64)
+    batch = W.Batch(idx, off, rng.standard_normal((3, t.dim)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    marker = 7.25
+    grads = [torch.full_like(x, marker) for x in d.g]
+    d.bwd(grad_cores=grads)
+    ref, _ = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output)
+    touched = [{1, 4}, {2, 5}, {3, 6}]
+    for k in range(3):
+        got = grads[k].cpu().numpy()
+        for s in range(10):
+            if s in touched[k]:
+                assert_close(got[s] - marker, ref[k][s], "touched slice")
+            else:
+                assert np.all(got[s] == marker)
+
+
+def test_backward_ragged_weighted(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(15)
+    lens = np.array([0, 3, 0, 1, 700, 2, 0, 1500, 1, 0], dtype=np.int64)   # > one selection round
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, t.num_rows, int(off[-1]))
+    idx[100:400] = 77
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(idx.size)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    dg, _ = d.bwd()
+    ref, _ = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "ragged dG%d" % (k + 1))
+
+
+def test_adversarial_identity_rank_map(path):
+    # all hot rows share i1 and i2: one slice owner gets almost every lookup
+    import dataclasses
+    wl = dataclasses.replace(W.WORKLOADS["kaggle_r32"], identity_rank_map=True, n_bags=1024)
+    d = DeviceTable(wl)
+    out = d.fwd()
+    assert_close(out, ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets), "identity map forward")
+    dg, _ = d.bwd()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "identity map dG%d" % (k + 1))
+
+
+def test_other_shapes_take_the_generic_kernels():
+    # unequal factors and ranks (no specialised kernel exists for them)
+    shape = W.TableShape(2 * 3 * 5 * 7, (6, 5, 7), (3, 2, 5), (1, 4, 7, 1))
+    wl = W.Workload("odd", (shape,), 50, (0, 6), "uniform", 0.0, "normal0.1", 21)
+    d = DeviceTable(wl, with_alpha=True)
+    assert_close(d.fwd(), ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, alpha=d.batch.alpha), "odd fwd")
+    dg, _ = d.bwd()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "odd dG%d" % (k + 1))
+
+
+# ------------------------------------------------------------------ cache
+
+def test_cache_on_tiny(path):
+    wl = W.WORKLOADS["tiny"]
+    d = DeviceTable(wl)
+    rows, counts = np.unique(d.batch.indices, return_counts=True)
+    p = np.random.default_rng(2).permutation(rows.size)
+    rows, counts = rows[p].astype(np.int64), counts[p].astype(np.int64)
+    K = 20
+    cache, _, _ = d.build_cache(K, rows, counts)
+    keys = ora.cache_select(rows, counts, K)
+    assert np.array_equal(cache.keys.cpu().numpy(), keys)
+    assert_close(cache.rows.cpu().numpy(), ora.cache_fill(d.oshape, d.cores, keys), "cache lines")
+    slot = torch.empty(d.L, dtype=torch.int32, device=dev())
+    B.tt_cache_lookup(cache, d.idx, slot)
+    assert np.array_equal(slot.cpu().numpy(), ora.cache_lookup(d.oshape, keys, d.batch.indices))
+    # right after the build the cached forward equals the uncached one
+    assert_close(d.fwd(cache=cache), d.fwd(), "cached vs uncached forward")
+    # lines that differ from the cores are really used
+    crow = cache.rows.cpu().numpy().copy()
+    crow += np.random.default_rng(4).standard_normal(crow.shape).astype(np.float32)
+    cache.rows.copy_(torch.from_numpy(crow))
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, cache_keys=keys, cache_rows=crow)
+    assert_close(d.fwd(cache=cache), ref, "cached forward")
+    dg, dc = d.bwd(cache=cache)
+    rg, rc = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, cache_keys=keys)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), rg[k], "cached dG%d" % (k + 1))
+    assert_close(dc.cpu().numpy()[:K], rc, "dCache")
+    new_rows = ora.sgd(crow, dc.cpu().numpy()[:K], wl.lr)
+    B.tt_emb_sgd_update(d.shape, d.g, dg, wl.lr, cache=cache, grad_cache=dc, zero_grad=True)
+    torch.cuda.synchronize()
+    assert_close(cache.rows.cpu().numpy(), new_rows, "sgd on cache lines")
+    assert float(dc.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("table", [0, 6])
+def test_multihot_with_cache(table, path):
+    wl = W.WORKLOADS["multihot_cache"]
+    d = DeviceTable(wl, table=table)
+    K = W.cache_size(wl, table)
+    cache, rows, counts = d.build_cache(K)
+    keys = ora.cache_select(rows, counts, K)
+    assert np.array_equal(cache.keys.cpu().numpy(), keys)
+    crow = ora.cache_fill(d.oshape, d.cores, keys)
+    assert_close(cache.rows.cpu().numpy(), crow, "cache lines")
+    slot = torch.empty(d.L, dtype=torch.int32, device=dev())
+    B.tt_cache_lookup(cache, d.idx, slot)
+    ref_slot = ora.cache_lookup(d.oshape, keys, d.batch.indices)
+    assert np.array_equal(slot.cpu().numpy(), ref_slot)
+    hit = float((ref_slot >= 0).mean())
+    assert 0.3 < hit < 0.99, hit
+    # perturb the lines so that cached and rebuilt rows differ, then compare a sample of bags
+    crow = (crow * 1.5).astype(np.float32)
+    cache.rows.copy_(torch.from_numpy(crow))
+    out = d.fwd(cache=cache)
+    pick, idx, off, _ = sample_bags(d.batch, 256)
+    assert_close(out[pick], ora.fwd(d.oshape, d.cores, idx, off, cache_keys=keys, cache_rows=crow), "multihot forward")
+    dg, dc = d.bwd(cache=cache)
+    rg, rc = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, cache_keys=keys)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), rg[k], "multihot dG%d" % (k + 1))
+    assert_close(dc.cpu().numpy()[:K], rc, "multihot dCache")
+
+
+def test_cache_selection_with_many_ties():
+    t = W.WORKLOADS["kaggle_r32"].tables[0]
+    rng = np.random.default_rng(33)
+    rows = rng.choice(t.num_rows, 50_000, replace=False).astype(np.int64)
+    counts = rng.integers(1, 4, rows.size).astype(np.int64)
+    counts[:10] = 2 ** 31 + 5                                    # large counts sort first
+    K = 1014
+    d = DeviceTable(W.WORKLOADS["kaggle_r32"])
+    cache, _, _ = d.build_cache(K, rows, counts)
+    assert np.array_equal(cache.keys.cpu().numpy(), ora.cache_select(rows, counts, K))
