@@ -219,7 +219,7 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
 
     // LDS needs of the generic kernels, checked before anything is enqueued
     const int max_slice = p.sA > p.sB ? (p.sA > p.sC ? p.sA : p.sC) : (p.sB > p.sC ? p.sB : p.sC);
-    const size_t lds_core = sizeof(SelectLds<GEN_CH>) +
+    const size_t lds_core = sizeof(SelectLds<GEN_CH>) + (GEN_CH + 4) * sizeof(int) +
                             (size_t)(max_slice + p.sA + p.sC + p.n1 * p.cols + p.N) * sizeof(float);
     const int G = WG / p.N > 0 ? WG / p.N : 1;
     const size_t lds_cache = sizeof(SelectLds<GEN_CH>) + (size_t)G * p.N * sizeof(float);

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(WG) void fwd_generic_kernel(Params p, const float *
 // ---- backward for the cores (Eq. 4; Alg. 2) ---------------------------------------
 // Workgroup g owns one slice: g < m1 -> G1[g]; g < m1+m2 -> G2[g-m1]; else G3[g-m1-m2].
 // It accumulates the slice gradient in LDS (each element has one owner thread) and adds
-// it to grad_cores once.  LDS: SelectLds | acc [max slice] | A | C | T [n1*cols] | dY [N].
+// it to grad_cores once.  LDS: SelectLds | ustart | acc [max slice] | A | C | T [n1*cols] | dY [N].
 __global__ __launch_bounds__(WG) void bwd_generic_kernel(Params p, const float *__restrict__ G1,
                                                          const float *__restrict__ G2, const float *__restrict__ G3,
                                                          const int64_t *__restrict__ indices, int L,
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(WG) void bwd_generic_kernel(Params p, const float *
     extern __shared__ __align__(16) unsigned char smem_raw[];
     SelectLds<GEN_CH> &lds = *reinterpret_cast<SelectLds<GEN_CH> *>(smem_raw);
     const int max_slice = max(p.sA, max(p.sB, p.sC));
-    float *acc = reinterpret_cast<float *>(smem_raw + sizeof(SelectLds<GEN_CH>));
+    int *ustart = reinterpret_cast<int *>(smem_raw + sizeof(SelectLds<GEN_CH>));
+    float *acc = reinterpret_cast<float *>(ustart + GEN_CH + 4);
     float *sA = acc + max_slice, *sC = sA + p.sA, *sT = sC + p.sC, *sY = sT + p.n1 * p.cols;
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -105,9 +106,9 @@ __global__ __launch_bounds__(WG) void bwd_generic_kernel(Params p, const float *
         });
         if (n == 0) continue;                                    // uniform
         any = true;
-        const int nu = sort_dedup<GEN_CH>(lds, n);
+        const int nu = sort_dedup<GEN_CH>(lds, n, ustart);
         for (int u = 0; u < nu; ++u) {
-            const int d0 = lds.ustart[u], d1 = lds.ustart[u + 1];
+            const int d0 = ustart[u], d1 = ustart[u + 1];
             int i1, i2, i3;
             decode(p, lds.sr[d0], i1, i2, i3);
             const float *A = G1 + (size_t)i1 * p.sA;

@@ -19,7 +19,6 @@ struct SelectLds {
     uint32_t rows[CH];        // their row ids (or, for the cache role, their slots)
     int sk[CH];               // positions sorted by (row, k)
     uint32_t sr[CH];          // rows in that order
-    int ustart[CH + 1];       // start of each run of equal rows in sk / sr
     int wcnt[NWAVE];
     int scan_tmp[NWAVE + 1];
 };
@@ -73,12 +72,10 @@ __device__ int select_chunk(SelectLds<CH> &lds, int c0, int c1, KeyFn key_of)
     return off[NWAVE];
 }
 
-// Sort the n selected entries by (row, k) with a rank sort and find the runs of
-// equal rows.  Result: lds.sk / lds.sr sorted, lds.ustart[0..nu] run boundaries.
-// Returns nu, the number of distinct rows.  O(n^2 / 256) per thread: the lists of
-// one slice are short (L / m_k on average).
+// Sort the n selected entries by (row, k) with a rank sort.  Result in lds.sk / lds.sr.
+// O(n^2 / 256) per thread: the lists of one slice are short (L / m_k on average).
 template <int CH>
-__device__ int sort_dedup(SelectLds<CH> &lds, int n)
+__device__ void sort_by_row(SelectLds<CH> &lds, int n)
 {
     const int t = threadIdx.x;
     for (int i = t; i < n; i += WG) {
@@ -92,6 +89,15 @@ __device__ int sort_dedup(SelectLds<CH> &lds, int n)
         lds.sr[rank] = my;
     }
     __syncthreads();
+}
+
+// Sort as above, then find the runs of equal rows: ustart[0..nu] are the run boundaries
+// in lds.sk / lds.sr (ustart: CH + 1 ints of LDS).  Returns nu, the number of distinct rows.
+template <int CH>
+__device__ int sort_dedup(SelectLds<CH> &lds, int n, int *ustart)
+{
+    const int t = threadIdx.x;
+    sort_by_row(lds, n);
     // run heads -> ustart, via a block scan over CH / 256 consecutive entries per thread
     constexpr int PER = CH / WG;
     int heads = 0;
@@ -105,8 +111,8 @@ __device__ int sort_dedup(SelectLds<CH> &lds, int n)
     int u = block_excl_scan(heads, lds.scan_tmp, &total);
 #pragma unroll
     for (int q = 0; q < PER; ++q)
-        if (flags & (1u << q)) lds.ustart[u++] = t * PER + q;
-    if (t == 0) lds.ustart[total] = n;
+        if (flags & (1u << q)) ustart[u++] = t * PER + q;
+    if (t == 0) ustart[total] = n;
     __syncthreads();
     return total;
 }
