@@ -19,6 +19,11 @@ struct Params {
     int sA, sB, sC;       // floats per slice of core 1, 2, 3
     int cols;             // n2*R2: columns of the unfolded G2 slice (R1 x n2 R2)
     uint32_t mg3, mg2;    // ceil(2^32 / m3), ceil(2^32 / m2)
+    // Set per call, not per shape: fixed bag length P = L / n_bags when every bag may have that
+    // length (L divisible by n_bags), else 0; mgP = ceil(2^32 / P).  Only a guess that is checked.
+    uint32_t bagP, mgP;
+    // 1/m3, 0.5/m3, 1/m2, 0.5/m2 and m3, m2 as doubles, for the multiply-free decode below
+    double inv3, half3, inv2, half2, m3d, m2d;
 };
 
 // floor(n / d) for n < 2^31 and 1 <= d < 2^31, with mg = ceil(2^32 / d).
@@ -38,6 +43,20 @@ __device__ __forceinline__ void decode(const Params &p, uint32_t row, int &i1, i
     i3 = (int)(row - q * (uint32_t)p.m3);
     uint32_t q2 = fast_div(q, (uint32_t)p.m2, p.mg2);
     i2 = (int)(q - q2 * (uint32_t)p.m2);
+    i1 = (int)q2;
+}
+
+// The same digits without integer multiplies (which run at a quarter of the fp64 FMA rate on
+// CDNA): q = floor((row + 0.5) / m3) is exact in fp64 for row < 2^31 because (row + 0.5) / m3 is
+// at least 0.5 / m3 away from an integer while the rounding error is below 2^-21 / m3; the
+// remainders are exact integer arithmetic in fp64.
+__device__ __forceinline__ void decode_f64(const Params &p, uint32_t row, int &i1, int &i2, int &i3)
+{
+    const double rd = (double)row;
+    const double q = floor(fma(rd, p.inv3, p.half3));
+    i3 = (int)fma(-q, p.m3d, rd);
+    const double q2 = floor(fma(q, p.inv2, p.half2));
+    i2 = (int)fma(-q2, p.m2d, q);
     i1 = (int)q2;
 }
 
@@ -103,7 +122,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int *tmp, int *total)
 }
 
 // Largest b with offsets[b] <= k (offsets non-decreasing, offsets[0] = 0 <= k < offsets[n_bags]).
-__device__ __forceinline__ int bag_of(const int64_t *offsets, int n_bags, int k)
+__device__ __attribute__((noinline)) int bag_of(const int64_t *offsets, int n_bags, int k)
 {
     if (!offsets) return k;
     int lo = 0, hi = n_bags;                     // answer in [lo, hi)

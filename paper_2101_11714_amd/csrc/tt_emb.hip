@@ -13,6 +13,7 @@
 #include "tt_select.h"
 #include "tt_generic.h"
 #include "tt_fast.h"
+#include "tt_fast_bwd.h"
 
 using namespace tt;
 
@@ -56,6 +57,10 @@ int check_shape(const tt_shape_t *s, Params *p)
         p->cols = p->n2 * p->R2;
         p->mg3 = p->m3 > 1 ? (uint32_t)(((1ull << 32) + p->m3 - 1) / (uint64_t)p->m3) : 0u;
         p->mg2 = p->m2 > 1 ? (uint32_t)(((1ull << 32) + p->m2 - 1) / (uint64_t)p->m2) : 0u;
+        p->bagP = 0; p->mgP = 0;
+        p->m3d = (double)p->m3; p->m2d = (double)p->m2;
+        p->inv3 = 1.0 / p->m3d; p->half3 = 0.5 * p->inv3;
+        p->inv2 = 1.0 / p->m2d; p->half2 = 0.5 * p->inv2;
     }
     return TT_OK;
 }
@@ -235,6 +240,10 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                            offsets, (int)n_bags, alpha, grad_output, grad_cache);
     }
     if (fast) {
+        if (offsets && n_bags > 0 && L % n_bags == 0) {
+            p.bagP = (uint32_t)(L / n_bags);
+            p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
+        }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
                  grad_cores[0], grad_cores[1], grad_cores[2], st);
     } else {
@@ -389,5 +398,14 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
     e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "dedup launch");
 }
+
+#ifdef TT_PROFILE
+// debug builds only: device buffer of [workgroups][16] cycle stamps written by the backward kernel
+int tt_debug_set_prof(void *buf)
+{
+    unsigned long long *pbuf = (unsigned long long *)buf;
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(tt::g_tt_prof), &pbuf, sizeof(pbuf));
+}
+#endif
 
 }  // extern "C"

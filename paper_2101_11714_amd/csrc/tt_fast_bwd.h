@@ -1,0 +1,553 @@
+// Specialised backward kernel (Eq. 4 / Alg. 2 of the paper) for the shapes of tt_fast.h.
+//
+// One workgroup owns one core slice: workgroups [0, m1) own G1[s], the next m2 own G2[s],
+// the last m3 own G3[s].  The owner
+//   1. scans the index array and keeps, in order, the positions whose digit selects its
+//      slice (ballot compaction, no atomics),
+//   2. sorts that short list by row id in pieces of 64 entries, each piece by one wave with a
+//      rank sort, so that equal rows become adjacent,
+//   3. stages alpha_k * grad_out[bag(k)] of every entry in LDS and sums each run of equal rows
+//      into its first entry: one dY per distinct row (a row that shows up in two pieces is
+//      simply handled twice: the gradient is linear in dY),
+//   4. stages the small operands of every distinct row (its G1 and/or G3 slice) in LDS, all
+//      loads in flight together, and streams the large one (the G2 slice, for the G1 and G3
+//      owners) through registers several rows at a time,
+//   5. accumulates its slice gradient in registers and adds it to grad_cores once.
+// All four waves walk over the same rows; wave w owns rows a in [w RQ, (w+1) RQ) of the
+// unfolded G2 slice (R x n2 R), lane l owns columns c0 .. c0+V-1:
+//   G2 owner: dG2[a][c]  += sum_j1 A[j1][a] dT0'[j1][c]              (reads no G2 at all)
+//   G1 owner: dG1[j1][a] += sum_c dT0'[j1][c] Bm[a][c]              (lane partials, reduced once at the end)
+//   G3 owner: dG3[b][j3] += sum_{j1,j2} T0[(j1,j2)][b] dY[(j1,j2)][j3], T0 partial over the wave's rows a
+// with dT0'[j1][c] = sum_j3 dY[(j1,j2)][j3] C[b][j3].  Everything is summed in a fixed order.
+//
+// The kernel is bound by instruction and memory latency, not by bandwidth: the code keeps the
+// dependent chain short (kernel arguments -> indices -> operands -> result), issues the loads
+// of a phase together, avoids integer multiplies, and keeps the role a run-time value so that
+// the three owners share one copy of the code in the instruction cache.
+#pragma once
+
+#include <stddef.h>
+
+#include "tt_fast.h"
+
+namespace tt {
+
+constexpr int FB_CAP = 512;                 // list entries a workgroup handles at once
+constexpr int FB_SCAN = 2048;               // positions scanned per round
+constexpr int FB_ITER = FB_SCAN / WG;       // positions per lane and round
+constexpr int FB_PIECE = WAVE;              // entries sorted together
+constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
+#ifndef TT_BWD_WAVES
+#define TT_BWD_WAVES 3                      // waves per SIMD the register allocation must allow
+#endif
+
+#if defined(TT_PROFILE)
+__device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], debug builds only
+#endif
+
+template <typename C>
+struct FbCfg {
+    static constexpr int W = 4096 / C::N;                   // sorted entries per window
+    static constexpr int NB = (W + WAVE - 1) / WAVE;        // ballots that cover a window
+    static constexpr int SB = 16;                           // distinct rows whose small operands sit in LDS
+    static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
+    static constexpr int BMR = C::RQ * C::V;                // registers per row for the wave's part of G2[i2]
+    static constexpr int UBMAX = 4;
+    static constexpr int UB = BMR >= 8 * UBMAX ? 1 : (8 * UBMAX / BMR > UBMAX ? UBMAX : 8 * UBMAX / BMR);   // rows in flight per wave
+    static_assert(W <= FB_CAP && (W % FB_PIECE == 0 || W < FB_PIECE), "windows hold whole pieces");
+    static_assert(SB % UB == 0, "register batches must not straddle LDS batches");
+};
+
+template <typename C>
+struct __align__(16) FbLds {
+    float stage[FbCfg<C>::W * C::N];                        // alpha_k * grad_out[bag(k)] of the window's entries (16 KB)
+    float small[FbCfg<C>::SB * FbCfg<C>::SMALL];            // must follow stage[]: both are written through one index
+    uint32_t rows[FB_CAP + 16];                             // selected row ids (+ padding read by the sort)
+    uint32_t sr[FB_CAP];                                    // sorted by (row, k) inside each piece
+    uint16_t klist[FB_CAP];                                 // positions k - base of the selected entries
+    uint16_t sk[FB_CAP];
+    int seg_start[FbCfg<C>::W + 1];                         // first entry of each run of equal rows
+    int seg_i1[FbCfg<C>::W], seg_i2[FbCfg<C>::W], seg_i3[FbCfg<C>::W];   // its digits
+    int wcnt[NWAVE];
+};
+
+// Stable compaction of the positions in [lo, hi), hi - lo <= FB_SCAN, that select slice s of
+// the role's core.  Returns the number of matches; the lists are written only if that number
+// is <= FB_CAP.
+template <typename C>
+__device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
+                                         const int64_t *__restrict__ indices, const int32_t *__restrict__ slot,
+                                         int lo, int hi)
+{
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int span = ((hi - lo + WG - 1) / WG) * WAVE;      // positions per wave
+    const int wlo = lo + w * span;
+    uint32_t rowv[FB_ITER];
+#pragma unroll
+    for (int it = 0; it < FB_ITER; ++it) {
+        const int k = wlo + it * WAVE + lane;
+        const bool ok = (it * WAVE < span) && (k < hi);
+        uint32_t r = ok ? (uint32_t)indices[k] : FB_NONE;
+        if (ok && slot && slot[k] >= 0) r = FB_NONE;
+        rowv[it] = r;
+    }
+    // Which rows select slice s?  Role 0 (digit i1): a contiguous range of rows, clamped to the
+    // 31-bit row space.  Role 2 (i3) and role 1 (i2): the digit from the multiply-free fp64 decode.
+    uint64_t masks[FB_ITER];
+    int cnt = 0;
+    if (role == 0) {
+        uint32_t r0lo = 0, r0len = 0;
+        const uint64_t m23 = (uint64_t)p.m2 * (uint64_t)p.m3;
+        const uint64_t lo64 = (uint64_t)s * m23;
+        if (lo64 < (1ull << 31)) {
+            r0lo = (uint32_t)lo64;
+            const uint64_t hi64 = lo64 + m23 < (1ull << 31) ? lo64 + m23 : (1ull << 31);
+            r0len = (uint32_t)(hi64 - lo64);
+        }
+#pragma unroll
+        for (int it = 0; it < FB_ITER; ++it) {
+            const bool hit = rowv[it] != FB_NONE && (rowv[it] - r0lo) < r0len;
+            masks[it] = __ballot(hit);
+            cnt += __popcll(masks[it]);
+        }
+    } else {
+        const double sd = (double)s;
+#pragma unroll
+        for (int it = 0; it < FB_ITER; ++it) {
+            const double rd = (double)rowv[it];
+            const double q = floor(fma(rd, p.inv3, p.half3));
+            double d = fma(-q, p.m3d, rd);                                  // i3
+            if (role == 1) {
+                const double q2 = floor(fma(q, p.inv2, p.half2));
+                d = fma(-q2, p.m2d, q);                                     // i2
+            }
+            const bool hit = rowv[it] != FB_NONE && d == sd;
+            masks[it] = __ballot(hit);
+            cnt += __popcll(masks[it]);
+        }
+    }
+    if (lane == 0) lds.wcnt[w] = cnt;
+    __syncthreads();
+    int off = 0, total = 0;
+#pragma unroll
+    for (int j = 0; j < NWAVE; ++j) {
+        const int c = lds.wcnt[j];
+        if (j < w) off += c;
+        total += c;
+    }
+    if (total > 0 && total <= FB_CAP) {
+        const uint64_t lt = lanemask_lt();
+#pragma unroll
+        for (int it = 0; it < FB_ITER; ++it) {
+            if ((masks[it] >> lane) & 1ull) {
+                const int pos = off + __popcll(masks[it] & lt);
+                lds.klist[pos] = (uint16_t)(wlo + it * WAVE + lane - lo);
+                lds.rows[pos] = rowv[it];
+            }
+            off += __popcll(masks[it]);
+        }
+        if (t < 16) lds.rows[total + t] = FB_NONE;          // padding read by the sort
+    }
+    __syncthreads();
+    return total;
+}
+
+// Sort one piece [p0, p0 + cnt), cnt <= 64, of the selected entries by (row, position) into
+// lds.sr / lds.sk at the same positions: lane i ranks entry p0 + i among the piece.  Only the
+// last piece can be shorter than 64; what is read past its end is the FB_NONE padding, which is
+// greater than any row.
+template <typename C>
+__device__ __forceinline__ void fb_sort_piece(FbLds<C> &lds, int p0, int cnt)
+{
+    const int lane = threadIdx.x & 63;
+    if (lane < cnt) {
+        const uint32_t my = lds.rows[p0 + lane];
+        int lt = 0, eq = 0;
+        for (int j = 0; j < cnt; j += 16) {
+            uint4 r[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(&lds.rows[p0 + j + 4 * q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int jj = j + 4 * q;
+                lt += (r[q].x < my) + (r[q].y < my) + (r[q].z < my) + (r[q].w < my);
+                eq += (r[q].x == my && jj + 0 < lane) + (r[q].y == my && jj + 1 < lane) + (r[q].z == my && jj + 2 < lane) +
+                      (r[q].w == my && jj + 3 < lane);
+            }
+        }
+        lds.sk[p0 + lt + eq] = lds.klist[p0 + lane];
+        lds.sr[p0 + lt + eq] = my;
+    }
+}
+
+template <typename C>
+__device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const int ROLE, int s,
+                                        const float *__restrict__ G1, const float *__restrict__ G2,
+                                        const float *__restrict__ G3, const int64_t *__restrict__ indices, int L,
+                                        const int64_t *__restrict__ offsets, int n_bags,
+                                        const float *__restrict__ alpha, const int32_t *__restrict__ slot,
+                                        const float *__restrict__ grad_out, float *__restrict__ dG1,
+                                        float *__restrict__ dG2, float *__restrict__ dG3)
+{
+    using F = FbCfg<C>;
+    constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
+    constexpr int W = F::W, NB = F::NB, NQ = N / 4, SB = F::SB, UB = F::UB, SMALL = F::SMALL;
+    // float4 of small operands per row: G1 slice (needed by the G2 and G3 owners) and G3 slice (G1, G2 owners)
+    constexpr int PA = C::sA / 4, PC = C::sC / 4;
+    static_assert((PA & (PA - 1)) == 0 && (PC & (PC - 1)) == 0 && (NQ & (NQ - 1)) == 0, "item counts must be powers of two");
+    static_assert(offsetof(FbLds<C>, small) == sizeof(float) * W * N, "small[] must follow stage[]");
+
+    float *stage = lds.stage;
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int a0 = w * RQ;
+    const bool active = lane < C::LANES;
+    const int c0 = active ? lane * V : 0;
+    const int j2 = c0 / R, b0 = c0 % R;
+
+    // accumulators: G1 owner N1*RQ lane partials, G2 owner RQ*V elements, G3 owner V*N3 partials
+    constexpr int NACC1 = N1 * RQ, NACC2 = RQ * V, NACC3 = V * N3;
+    constexpr int NACC = NACC1 > NACC2 ? (NACC1 > NACC3 ? NACC1 : NACC3) : (NACC2 > NACC3 ? NACC2 : NACC3);
+    float acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
+    bool any = false;
+
+    // ---- staging: gather float4 items from global memory into LDS, two per thread and pass ----
+    // Item list of a pass: the window's gradients [0, n_g), then the G1 slices of rows
+    // [sb0, sb0 + nb) (unless the G1 owner), then their G3 slices (unless the G3 owner).
+    auto stage_items = [&](int base, int i0, int n_g, int sb0, int nb) __attribute__((always_inline)) {
+        const int n_a = ROLE != 0 ? nb * PA : 0;
+        const int n_c = ROLE != 2 ? nb * PC : 0;
+        const int total = n_g + n_a + n_c;
+        for (int it0 = 0; it0 < total; it0 += 2 * WG) {                   // uniform
+            float4 val[2];
+            float scale[2];
+            int dst[2], chk_k[2], chk_f[2];
+            int64_t o0[2], o1[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int item = min(it0 + q * WG + t, total - 1);        // past the end: repeat the last item
+                const float *src;
+                scale[q] = 1.f;
+                chk_k[q] = -1;
+                chk_f[q] = 0;
+                o0[q] = 0;
+                o1[q] = 0;
+                if (item < n_g) {
+                    const int e = item / NQ, f = item % NQ;
+                    const int k = base + (int)lds.sk[i0 + e];
+                    if (alpha) scale[q] = alpha[k];
+                    int row = k;
+                    if (offsets) {
+                        // guess the bag (exact for fixed-length bags); its row is loaded while the two
+                        // offsets that confirm the guess are in flight
+                        int gs = p.bagP ? (int)fast_div((uint32_t)k, p.bagP, p.mgP)
+                                        : (int)((float)k * ((float)n_bags / (float)L));
+                        gs = gs < n_bags ? gs : n_bags - 1;
+                        o0[q] = offsets[gs];
+                        o1[q] = offsets[gs + 1];
+                        chk_k[q] = k;
+                        chk_f[q] = f;
+                        row = gs;
+                    }
+                    src = grad_out + (uint32_t)row * (uint32_t)N + 4u * (uint32_t)f;
+                    dst[q] = 4 * item;                                    // = stage[e * N + 4 f]
+                } else if (item < n_g + n_a) {
+                    const int x = item - n_g, u = x / PA, f = x % PA;
+                    src = G1 + (uint32_t)lds.seg_i1[sb0 + u] * (uint32_t)C::sA + 4u * (uint32_t)f;
+                    dst[q] = W * N + u * SMALL + 4 * f;                   // small[] follows stage[] in LDS
+                } else {
+                    const int x = item - n_g - n_a, u = x / PC, f = x % PC;
+                    src = G3 + (uint32_t)lds.seg_i3[sb0 + u] * (uint32_t)C::sC + 4u * (uint32_t)f;
+                    dst[q] = W * N + u * SMALL + C::sA + 4 * f;
+                }
+                val[q] = *reinterpret_cast<const float4 *>(src);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                float4 g = val[q];
+                if (chk_k[q] >= 0 && !(o0[q] <= (int64_t)chk_k[q] && (int64_t)chk_k[q] < o1[q])) {   // ragged bags
+                    const int bag = bag_of(offsets, n_bags, chk_k[q]);
+                    g = *reinterpret_cast<const float4 *>(grad_out + (size_t)bag * N + 4 * chk_f[q]);
+                }
+                g.x *= scale[q]; g.y *= scale[q]; g.z *= scale[q]; g.w *= scale[q];
+                if (it0 + q * WG + t < total) *reinterpret_cast<float4 *>(&stage[dst[q]]) = g;
+            }
+        }
+    };
+
+    // this wave's rows of G2[i2] for rows [ub0, ub0 + UB) of the window -> registers
+    auto bm_load = [&](int ub0, int nsegs, float (&bm)[UB][RQ][V]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int sg = min(ub0 + u, nsegs - 1);
+            const int i2 = __builtin_amdgcn_readfirstlane(lds.seg_i2[sg]);
+            const float *B = G2 + (size_t)i2 * C::sB + (size_t)a0 * C::COLS + c0;
+#pragma unroll
+            for (int aa = 0; aa < RQ; ++aa) load_vec<V>(B + aa * C::COLS, bm[u][aa]);
+        }
+    };
+
+    // Rows [ub0, ub0 + UB) of the window.  Every run has been summed into its first staged entry,
+    // so each row reads exactly one dY.  No branches on the row count: rows past the end repeat
+    // the last one with a zero weight, so the LDS reads of the batch can be in flight together.
+    auto consume = [&](int ub0, int sb0, int nsegs, const float (&bm)[UB][RQ][V]) __attribute__((always_inline)) {
+        const float *sm[UB];
+        const float *dyp[UB];
+        float keep[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int sg = min(ub0 + u, nsegs - 1);
+            keep[u] = ub0 + u < nsegs ? 1.f : 0.f;
+            sm[u] = lds.small + (sg - sb0) * SMALL;
+            dyp[u] = stage + lds.seg_start[sg] * N + j2 * N3;
+        }
+        if (ROLE == 2) {
+            // T0 partial over this wave's rows a, then dG3 partial
+            float t0[UB][N1][V];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) t0[u][j1][v] = 0.f;
+#pragma unroll
+                for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                    for (int j1 = 0; j1 < N1; ++j1) {
+                        const float av = sm[u][j1 * R + a0 + aa];
+#pragma unroll
+                        for (int v = 0; v < V; ++v) t0[u][j1][v] = fmaf(av, bm[u][aa][v], t0[u][j1][v]);
+                    }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const float tk = t0[u][j1][v] * keep[u];
+                        acc[v * N3 + 0] = fmaf(tk, q.x, acc[v * N3 + 0]);
+                        acc[v * N3 + 1] = fmaf(tk, q.y, acc[v * N3 + 1]);
+                        acc[v * N3 + 2] = fmaf(tk, q.z, acc[v * N3 + 2]);
+                        acc[v * N3 + 3] = fmaf(tk, q.w, acc[v * N3 + 3]);
+                    }
+                }
+        } else {
+            // dT0'[j1][c0+v] = sum_j3 dY[(j1,j2)][j3] C[b0+v][j3]
+            float dt[UB][N1][V];
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const float4 cv = *reinterpret_cast<const float4 *>(&sm[u][C::sA + (b0 + v) * N3]);
+                        dt[u][j1][v] = keep[u] * fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
+                    }
+                }
+            if (ROLE == 1) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+#pragma unroll
+                    for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                        for (int j1 = 0; j1 < N1; ++j1) {
+                            const float av = sm[u][j1 * R + a0 + aa];
+#pragma unroll
+                            for (int v = 0; v < V; ++v) acc[aa * V + v] = fmaf(av, dt[u][j1][v], acc[aa * V + v]);
+                        }
+            } else {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+#pragma unroll
+                    for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                        for (int j1 = 0; j1 < N1; ++j1)
+#pragma unroll
+                            for (int v = 0; v < V; ++v)
+                                acc[j1 * RQ + aa] = fmaf(dt[u][j1][v], bm[u][aa][v], acc[j1 * RQ + aa]);
+            }
+        }
+    };
+
+    // one round: entries lds.klist / lds.rows [0, n), positions relative to `base`
+    auto process = [&](int n, int base) __attribute__((always_inline)) {
+        if (n <= FB_PIECE) {
+            fb_sort_piece(lds, 0, n);                                      // every wave, same result: no barrier
+        } else {
+            for (int p0 = w * FB_PIECE; p0 < n; p0 += NWAVE * FB_PIECE) fb_sort_piece(lds, p0, min(FB_PIECE, n - p0));
+            __syncthreads();
+        }
+        for (int i0 = 0; i0 < n; i0 += W) {
+            const int nw = min(W, n - i0);
+            // Runs of equal rows inside the window.  Every wave finds them with ballots and writes
+            // the same values (start, digits of the row), so no barrier is needed before it reads them.
+            int nsegs = 0;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int e = b * WAVE + lane;
+                const bool in = e < nw;
+                const uint32_t r = in ? lds.sr[i0 + e] : 0u;
+                bool head = in;
+                if (in && e > 0) head = r != lds.sr[i0 + e - 1];
+                const uint64_t hm = __ballot(head);
+                if (head) {
+                    const int sg = nsegs + __popcll(hm & lanemask_lt());
+                    int i1, i2, i3;
+                    decode_f64(p, r, i1, i2, i3);
+                    lds.seg_start[sg] = e;
+                    lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
+                }
+                nsegs += __popcll(hm);
+            }
+            if (lane == 0) lds.seg_start[nsegs] = nw;
+            // All global loads of the window's first phase are issued together: first G2 rows,
+            // upstream gradients, small operands of the first rows.
+            float bm[UB][RQ][V];
+            if (ROLE != 1) bm_load(0, nsegs, bm);
+            stage_items(base, i0, nw * NQ, 0, min(SB, nsegs));
+            __syncthreads();
+            if (nsegs < nw) {                                              // uniform: some row occurs more than once
+                // sum each run into its first entry, in list order (a run has at most 64 entries)
+                for (int item = t; item < nsegs * N; item += WG) {
+                    const int sg = item / N, j = item % N;
+                    const int e0 = lds.seg_start[sg], e1 = lds.seg_start[sg + 1];
+                    if (e1 - e0 > 1) {
+                        float sum = stage[e0 * N + j];
+                        for (int e = e0 + 1; e < e1; ++e) sum += stage[e * N + j];
+                        stage[e0 * N + j] = sum;
+                    }
+                }
+                __syncthreads();
+            }
+            consume(0, 0, nsegs, bm);
+            for (int ub0 = UB; ub0 < nsegs; ub0 += UB) {
+                const int sb0 = (ub0 / SB) * SB;
+                if (ROLE != 1) bm_load(ub0, nsegs, bm);
+                if (ub0 == sb0) {                                        // next batch of small operands
+                    __syncthreads();
+                    stage_items(base, i0, 0, sb0, min(SB, nsegs - sb0));
+                    __syncthreads();
+                }
+                consume(ub0, sb0, nsegs, bm);
+            }
+            __syncthreads();                                             // before the LDS lists are reused
+        }
+    };
+
+    // Scan FB_SCAN positions per round; if a round selects more than FB_CAP entries (an adversarial
+    // index stream), redo it in pieces of FB_CAP positions, which always fit.
+    int span = FB_SCAN;
+    for (int lo = 0; lo < L;) {
+        const int hi = min(L, lo + span);
+        const int n = fb_select<C>(lds, p, ROLE, s, indices, slot, lo, hi);
+        if (n > FB_CAP) { span = FB_CAP; continue; }
+        if (n) { any = true; process(n, lo); }
+        lo = hi;
+        if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+    }
+    if (!any) return;
+
+    if (ROLE == 1) {
+        if (active) {
+            float *dst = dG2 + (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
+#pragma unroll
+            for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                for (int v = 0; v < V; ++v) dst[aa * C::COLS + v] += acc[aa * V + v];
+        }
+    } else if (ROLE == 0) {
+        float red[NACC1];
+#pragma unroll
+        for (int i = 0; i < NACC1; ++i) red[i] = active ? acc[i] : 0.f;
+        group_reduce<NACC1, WAVE>(red, lane);
+        if (lane < ReduceKeep<NACC1, WAVE>::writers) {
+            const int base = reduce_base<NACC1, WAVE>(lane);
+            float *dst = dG1 + (size_t)s * C::sA;
+#pragma unroll
+            for (int i = 0; i < ReduceKeep<NACC1, WAVE>::value; ++i) {
+                const int idx = base + i;                                  // = j1 * RQ + aa
+                const int j1 = idx / RQ, aa = idx % RQ;
+                dst[j1 * R + a0 + aa] += red[i];
+            }
+        }
+    } else {
+        // partials [wave][column][j3] -> LDS, then a fixed-order sum over (wave, j2)
+        float *part = lds.stage;
+        static_assert(NWAVE * C::COLS * N3 <= W * N, "partials do not fit");
+        if (active) {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int j3 = 0; j3 < N3; ++j3) part[(w * C::COLS + c0 + v) * N3 + j3] = acc[v * N3 + j3];
+        }
+        __syncthreads();
+        float *dst = dG3 + (size_t)s * C::sC;
+        for (int e = t; e < C::sC; e += WG) {
+            const int b = e / N3, j3 = e - b * N3;
+            float sum = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NWAVE; ++ww)
+#pragma unroll
+                for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
+            dst[e] += sum;
+        }
+    }
+}
+
+template <typename C>
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(TT_BWD_WAVES))) void bwd_fast_kernel(
+    Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3,
+    const int64_t *__restrict__ indices, int L, const int64_t *__restrict__ offsets, int n_bags,
+    const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
+    float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3)
+{
+    __shared__ FbLds<C> lds;
+#if defined(TT_PROFILE)
+    const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
+#endif
+    // role and slice of this workgroup, without branches so that all kernel arguments load together
+    const int g = blockIdx.x;
+    const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
+    const int role = ge1 + ge2;
+    const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
+    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3);
+#if defined(TT_PROFILE)
+    if (g_tt_prof && threadIdx.x == 0) {
+        g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
+        g_tt_prof[blockIdx.x * 16 + 10] = __builtin_amdgcn_s_memrealtime();
+    }
+#endif
+}
+
+template <typename C>
+static inline void launch_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
+                              int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
+                              const float *go, float *dG1, float *dG2, float *dG3, hipStream_t st)
+{
+    hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(p.m1 + p.m2 + p.m3), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+                       n_bags, alpha, slot, go, dG1, dG2, dG3);
+}
+
+static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >= 0; }
+
+static inline void fast_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx, int L,
+                            const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
+                            float *dG1, float *dG2, float *dG3, hipStream_t st)
+{
+    switch (fast_config(p)) {
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    default: break;
+    }
+}
+
+}  // namespace tt
