@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="kaggle_r32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
+                    help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
+                         "stream: every kernel is launched from Python")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus %d is not supported "
@@ -85,6 +88,7 @@ def main():
         B.tt_emb_sgd_update(shape, cores, grads, lr, zero_grad=True)
 
     def timed(fn, count):
+        """ms per call of fn(i), count calls enqueued back to back between two events on the current stream."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -92,23 +96,41 @@ def main():
             fn(i)
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / count          # ms per call
+        return e0.elapsed_time(e1) / count
 
+    def captured(fn):
+        """A HIP graph of POOL consecutive calls fn(0..POOL-1); replay() launches all of them."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(POOL):
+                fn(i)
+        return g
+
+    def timed_any(fn, count):
+        """ms per call of fn, either launched call by call or as replays of a POOL-call graph."""
+        if args.launch == "stream":
+            return timed(fn, count)
+        g = captured(fn)
+        g.replay()
+        reps = max(1, count // POOL)
+        return timed(lambda i: g.replay(), reps) / POOL
+
+    steps = max(POOL, (args.steps // POOL) * POOL)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_step = timed(step, args.steps)
+    ms_step = timed_any(step, steps)
     wall = time.perf_counter() - t0
     value = L / (ms_step * 1e-3)
 
-    # per-kernel durations: each stage launched back to back on the same stream
-    reps = max(200, min(args.steps, 2000))
-    ms_fwd = timed(lambda i: B.tt_emb_fwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out), reps)
-    ms_bwd = timed(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
+    # per-kernel durations: each stage alone, launched back to back on the same stream
+    reps = max(POOL * 16, min(steps, 4096))
+    ms_fwd = timed_any(lambda i: B.tt_emb_fwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out), reps)
+    ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
     for g in grads:
         g.zero_()
-    ms_sgd = timed(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
+    ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
 
     # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
     b0 = batches_h[0].indices
@@ -145,13 +167,13 @@ def main():
 
     print(json.dumps({
         "metric": "TT-EmbeddingBag fwd+bwd lookups/sec; % of HBM/fp32 roofline at R=32",
-        "value": round(value, 1), "unit": "lookups/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 1), "unit": "lookups/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
                                "Zipf(%.2f), fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
                                                             n_bags, L // n_bags, wl.zipf_alpha),
-                   "lookups_per_step": L, "wall_s_timed_region": round(wall, 3)},
+                   "lookups_per_step": L, "launch": args.launch, "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

@@ -268,19 +268,24 @@ int tt_emb_sgd_update(const tt_shape_t *shape, float *const cores[3], float *con
     if ((rc = check_cache(cache, &cd, true))) return rc;
     if (cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
     SgdArgs a;
-    const int64_t sizes[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
-    a.start[0] = 0;
-    for (int k = 0; k < 3; ++k) {
-        a.x[k] = cores[k]; a.g[k] = grad_cores[k]; a.count[k] = sizes[k];
-        a.start[k + 1] = a.start[k] + sizes[k];
+    const int64_t sizes[4] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC,
+                              cd.K ? (int64_t)cd.K * p.N : 0};
+    a.start4[0] = 0;
+    a.tail[0] = 0;
+    for (int k = 0; k < 4; ++k) {
+        a.x[k] = k < 3 ? cores[k] : (cd.K ? cache->rows : nullptr);
+        a.g[k] = k < 3 ? grad_cores[k] : (cd.K ? grad_cache : nullptr);
+        a.count[k] = sizes[k];
+        a.start4[k + 1] = a.start4[k] + sizes[k] / 4;
+        a.tail[k + 1] = a.tail[k] + sizes[k] % 4;
     }
-    a.x[3] = cd.K ? cache->rows : nullptr;
-    a.g[3] = cd.K ? grad_cache : nullptr;
-    a.count[3] = cd.K ? (int64_t)cd.K * p.N : 0;
-    a.start[4] = a.start[3] + a.count[3];
-    const int64_t total = a.start[4];
+    for (int k = 0; k < 4; ++k)
+        if (sizes[k] && ((((uintptr_t)a.x[k]) | ((uintptr_t)a.g[k])) & 15))
+            return fail(TT_ERR_BAD_ARG, "cores and gradients must be 16-byte aligned");
+    const int64_t total = a.start4[4] + a.tail[4];
     int grid = cdiv(total, WG);
-    if (grid > 8192) grid = 8192;
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
     hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(WG), 0, (hipStream_t)stream, a, lr, zero_grad);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "sgd launch");

@@ -44,6 +44,13 @@ constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
 #if defined(TT_PROFILE)
 __device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], debug builds only
 #endif
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+#define TT_STAMP(i) ts[(i)] = __builtin_readcyclecounter()
+#define TT_NOTE(i, v) ts[(i)] = (unsigned long long)(v)
+#else
+#define TT_STAMP(i) do { } while (0)
+#define TT_NOTE(i, v) do { } while (0)
+#endif
 
 template <typename C>
 struct FbCfg {
@@ -71,26 +78,40 @@ struct __align__(16) FbLds {
     int wcnt[NWAVE];
 };
 
-// Stable compaction of the positions in [lo, hi), hi - lo <= FB_SCAN, that select slice s of
-// the role's core.  Returns the number of matches; the lists are written only if that number
-// is <= FB_CAP.
-template <typename C>
-__device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
-                                         const int64_t *__restrict__ indices, const int32_t *__restrict__ slot,
-                                         int lo, int hi)
+// Row ids of the positions [lo, hi), hi - lo <= FB_SCAN, FB_ITER per lane: wave w covers a
+// contiguous quarter.  Positions past hi, and cached positions (slot >= 0), give FB_NONE.
+__device__ __forceinline__ void fb_load_rows(const int64_t *__restrict__ indices, const int32_t *__restrict__ slot,
+                                             int lo, int hi, uint32_t (&rowv)[FB_ITER])
 {
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int span = ((hi - lo + WG - 1) / WG) * WAVE;      // positions per wave
     const int wlo = lo + w * span;
-    uint32_t rowv[FB_ITER];
 #pragma unroll
     for (int it = 0; it < FB_ITER; ++it) {
         const int k = wlo + it * WAVE + lane;
         const bool ok = (it * WAVE < span) && (k < hi);
-        uint32_t r = ok ? (uint32_t)indices[k] : FB_NONE;
-        if (ok && slot && slot[k] >= 0) r = FB_NONE;
-        rowv[it] = r;
+        rowv[it] = ok ? (uint32_t)indices[k] : FB_NONE;
     }
+    if (slot) {
+#pragma unroll
+        for (int it = 0; it < FB_ITER; ++it) {
+            const int k = wlo + it * WAVE + lane;
+            const bool ok = (it * WAVE < span) && (k < hi);
+            if (ok && slot[k] >= 0) rowv[it] = FB_NONE;
+        }
+    }
+}
+
+// Stable compaction of the positions in [lo, hi) (rows in rowv, see fb_load_rows) that select
+// slice s of the role's core.  Returns the number of matches; the lists are written only if
+// that number is <= FB_CAP.
+template <typename C>
+__device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
+                                         const uint32_t (&rowv)[FB_ITER], int lo, int hi)
+{
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int span = ((hi - lo + WG - 1) / WG) * WAVE;      // positions per wave
+    const int wlo = lo + w * span;
     // Which rows select slice s?  Role 0 (digit i1): a contiguous range of rows, clamped to the
     // 31-bit row space.  Role 2 (i3) and role 1 (i2): the digit from the multiply-free fp64 decode.
     uint64_t masks[FB_ITER];
@@ -187,7 +208,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         const int64_t *__restrict__ offsets, int n_bags,
                                         const float *__restrict__ alpha, const int32_t *__restrict__ slot,
                                         const float *__restrict__ grad_out, float *__restrict__ dG1,
-                                        float *__restrict__ dG2, float *__restrict__ dG3)
+                                        float *__restrict__ dG2, float *__restrict__ dG3,
+                                        uint32_t (&rowv)[FB_ITER])
 {
     using F = FbCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
@@ -212,6 +234,10 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
     bool any = false;
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+    unsigned long long ts[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    TT_STAMP(0);
+#endif
 
     // ---- staging: gather float4 items from global memory into LDS, two per thread and pass ----
     // Item list of a pass: the window's gradients [0, n_g), then the G1 slices of rows
@@ -279,10 +305,12 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 
     // this wave's rows of G2[i2] for rows [ub0, ub0 + UB) of the window -> registers
     auto bm_load = [&](int ub0, int nsegs, float (&bm)[UB][RQ][V]) __attribute__((always_inline)) {
+        int i2v[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) i2v[u] = lds.seg_i2[min(ub0 + u, nsegs - 1)];
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
-            const int sg = min(ub0 + u, nsegs - 1);
-            const int i2 = __builtin_amdgcn_readfirstlane(lds.seg_i2[sg]);
+            const int i2 = __builtin_amdgcn_readfirstlane(i2v[u]);
             const float *B = G2 + (size_t)i2 * C::sB + (size_t)a0 * C::COLS + c0;
 #pragma unroll
             for (int aa = 0; aa < RQ; ++aa) load_vec<V>(B + aa * C::COLS, bm[u][aa]);
@@ -376,41 +404,82 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 
     // one round: entries lds.klist / lds.rows [0, n), positions relative to `base`
     auto process = [&](int n, int base) __attribute__((always_inline)) {
+        TT_STAMP(1); TT_NOTE(8, n);
+        int nsegs_small = 0;
         if (n <= FB_PIECE) {
-            fb_sort_piece(lds, 0, n);                                      // every wave, same result: no barrier
+            // One piece: every wave sorts it by itself (same result everywhere, no barrier) and finds
+            // the runs in rank space.  An entry is the head of its run iff no equal row precedes it
+            // in the list; its run starts at sorted position lt, and the run's index is the number
+            // of heads with a smaller row.
+            const bool in = lane < n;
+            const uint32_t my = in ? lds.rows[lane] : FB_NONE;
+            int lt = 0, eq = 0;
+            for (int j = 0; j < n; j += 16) {
+                uint4 r[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(&lds.rows[j + 4 * q]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int jj = j + 4 * q;
+                    lt += (r[q].x < my) + (r[q].y < my) + (r[q].z < my) + (r[q].w < my);
+                    eq += (r[q].x == my && jj + 0 < lane) + (r[q].y == my && jj + 1 < lane) + (r[q].z == my && jj + 2 < lane) +
+                          (r[q].w == my && jj + 3 < lane);
+                }
+            }
+            if (in) lds.sk[lt + eq] = lds.klist[lane];
+            const bool head = in && eq == 0;
+            uint64_t hm = __ballot(head);
+            nsegs_small = __popcll(hm);
+            int sg = 0;
+            while (hm) {                                                   // uniform: one step per distinct row
+                const int j = __builtin_ctzll(hm);
+                hm &= hm - 1;
+                sg += (uint32_t)__builtin_amdgcn_readlane((int)my, j) < my;
+            }
+            if (head) {
+                int i1, i2, i3;
+                decode_f64(p, my, i1, i2, i3);
+                lds.seg_start[sg] = lt;
+                lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
+            }
+            if (lane == 0) lds.seg_start[nsegs_small] = n;
         } else {
             for (int p0 = w * FB_PIECE; p0 < n; p0 += NWAVE * FB_PIECE) fb_sort_piece(lds, p0, min(FB_PIECE, n - p0));
             __syncthreads();
         }
         for (int i0 = 0; i0 < n; i0 += W) {
             const int nw = min(W, n - i0);
-            // Runs of equal rows inside the window.  Every wave finds them with ballots and writes
-            // the same values (start, digits of the row), so no barrier is needed before it reads them.
-            int nsegs = 0;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const int e = b * WAVE + lane;
-                const bool in = e < nw;
-                const uint32_t r = in ? lds.sr[i0 + e] : 0u;
-                bool head = in;
-                if (in && e > 0) head = r != lds.sr[i0 + e - 1];
-                const uint64_t hm = __ballot(head);
-                if (head) {
-                    const int sg = nsegs + __popcll(hm & lanemask_lt());
-                    int i1, i2, i3;
-                    decode_f64(p, r, i1, i2, i3);
-                    lds.seg_start[sg] = e;
-                    lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
+            int nsegs = nsegs_small;
+            if (n > FB_PIECE) {
+                // Runs of equal rows inside the window.  Every wave finds them with ballots and writes the
+                // same values (start, digits of the row), so no barrier is needed before it reads them.
+                for (int b = 0; b * WAVE < nw; ++b) {
+                    const int e = b * WAVE + lane;
+                    const bool in = e < nw;
+                    const uint32_t r = in ? lds.sr[i0 + e] : 0u;
+                    bool head = in;
+                    if (in && e > 0) head = r != lds.sr[i0 + e - 1];
+                    const uint64_t hm = __ballot(head);
+                    if (head) {
+                        const int sg = nsegs + __popcll(hm & lanemask_lt());
+                        int i1, i2, i3;
+                        decode_f64(p, r, i1, i2, i3);
+                        lds.seg_start[sg] = e;
+                        lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
+                    }
+                    nsegs += __popcll(hm);
                 }
-                nsegs += __popcll(hm);
+                if (lane == 0) lds.seg_start[nsegs] = nw;
             }
-            if (lane == 0) lds.seg_start[nsegs] = nw;
+            TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
             float bm[UB][RQ][V];
             if (ROLE != 1) bm_load(0, nsegs, bm);
+            TT_STAMP(3);
             stage_items(base, i0, nw * NQ, 0, min(SB, nsegs));
             __syncthreads();
+            TT_STAMP(4);
             if (nsegs < nw) {                                              // uniform: some row occurs more than once
                 // sum each run into its first entry, in list order (a run has at most 64 entries)
                 for (int item = t; item < nsegs * N; item += WG) {
@@ -418,12 +487,21 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                     const int e0 = lds.seg_start[sg], e1 = lds.seg_start[sg + 1];
                     if (e1 - e0 > 1) {
                         float sum = stage[e0 * N + j];
-                        for (int e = e0 + 1; e < e1; ++e) sum += stage[e * N + j];
+                        int e = e0 + 1;
+                        for (; e + 8 <= e1; e += 8) {
+                            float x[8];
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) x[q] = stage[(e + q) * N + j];
+#pragma unroll
+                            for (int q = 0; q < 8; ++q) sum += x[q];
+                        }
+                        for (; e < e1; ++e) sum += stage[e * N + j];
                         stage[e0 * N + j] = sum;
                     }
                 }
                 __syncthreads();
             }
+            TT_STAMP(5);
             consume(0, 0, nsegs, bm);
             for (int ub0 = UB; ub0 < nsegs; ub0 += UB) {
                 const int sb0 = (ub0 / SB) * SB;
@@ -436,21 +514,33 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 consume(ub0, sb0, nsegs, bm);
             }
             __syncthreads();                                             // before the LDS lists are reused
+            TT_STAMP(6);
         }
     };
 
     // Scan FB_SCAN positions per round; if a round selects more than FB_CAP entries (an adversarial
     // index stream), redo it in pieces of FB_CAP positions, which always fit.
+    // The caller has already loaded the rows of the first round into rowv.
     int span = FB_SCAN;
     for (int lo = 0; lo < L;) {
         const int hi = min(L, lo + span);
-        const int n = fb_select<C>(lds, p, ROLE, s, indices, slot, lo, hi);
+        if (lo > 0 || span != FB_SCAN) fb_load_rows(indices, slot, lo, hi, rowv);
+        const int n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi);
         if (n > FB_CAP) { span = FB_CAP; continue; }
         if (n) { any = true; process(n, lo); }
         lo = hi;
         if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
     }
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+    auto flush = [&]() __attribute__((always_inline)) {
+        TT_STAMP(7);
+        if (g_tt_prof && threadIdx.x == 0)
+            for (int i = 0; i < 10; ++i) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
+    };
+    if (!any) { flush(); return; }
+#else
     if (!any) return;
+#endif
 
     if (ROLE == 1) {
         if (active) {
@@ -497,6 +587,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             dst[e] += sum;
         }
     }
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+    flush();
+#endif
 }
 
 template <typename C>
@@ -510,12 +603,16 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(TT_BWD_WAVES
 #if defined(TT_PROFILE)
     const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
 #endif
+    // The index loads do not depend on the role: issue them before anything else.
+    uint32_t rowv[FB_ITER];
+    fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
+    __builtin_amdgcn_sched_barrier(0);
     // role and slice of this workgroup, without branches so that all kernel arguments load together
     const int g = blockIdx.x;
     const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
     const int role = ge1 + ge2;
     const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3);
+    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, rowv);
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
         g_tt_prof[blockIdx.x * 16 + 11] = t_begin;

@@ -231,25 +231,42 @@ __global__ __launch_bounds__(WG) void bwd_cache_kernel(int N, int K, int G, cons
 
 // ---- SGD (Section 5) ------------------------------------------------------------------
 // x <- x - lr * g over up to four arrays in one launch (three cores and the cache lines).
+// Work is split in float4 items (arrays are 16-byte aligned); the last count % 4 elements of
+// an array are handled as scalars by the threads that follow the float4 items.
 struct SgdArgs {
     float *x[4];
     float *g[4];
     int64_t count[4];
-    int64_t start[5];     // prefix sums of count
+    int64_t start4[5];    // prefix sums of count / 4
+    int64_t tail[5];      // prefix sums of count % 4
 };
 
 __global__ __launch_bounds__(WG) void sgd_kernel(SgdArgs a, float lr, int zero_grad)
 {
-    const int64_t total = a.start[4];
+    const int64_t total4 = a.start4[4], total = total4 + a.tail[4];
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < total; i += (int64_t)gridDim.x * WG) {
-        int k = 0;
+        if (i < total4) {
+            int k = 0;
 #pragma unroll
-        for (int q = 1; q < 4; ++q) k += (i >= a.start[q]);
-        const int64_t e = i - a.start[k];
-        float *x = a.x[k];
-        float *g = a.g[k];
-        x[e] = fmaf(-lr, g[e], x[e]);
-        if (zero_grad) g[e] = 0.f;
+            for (int q = 1; q < 4; ++q) k += (i >= a.start4[q]);
+            const int64_t e = i - a.start4[k];
+            float4 *x = reinterpret_cast<float4 *>(a.x[k]) + e;
+            float4 *g = reinterpret_cast<float4 *>(a.g[k]) + e;
+            float4 xv = *x;
+            const float4 gv = *g;
+            xv.x = fmaf(-lr, gv.x, xv.x); xv.y = fmaf(-lr, gv.y, xv.y);
+            xv.z = fmaf(-lr, gv.z, xv.z); xv.w = fmaf(-lr, gv.w, xv.w);
+            *x = xv;
+            if (zero_grad) *g = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            const int64_t j = i - total4;
+            int k = 0;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) k += (j >= a.tail[q]);
+            const int64_t e = (a.count[k] & ~(int64_t)3) + (j - a.tail[k]);
+            a.x[k][e] = fmaf(-lr, a.g[k][e], a.x[k][e]);
+            if (zero_grad) a.g[k][e] = 0.f;
+        }
     }
 }
 
