@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 POOL = 16                      # distinct batches cycled through, so caches see a stream
 
+# HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the counter reads for a 256 MiB copy (factors 2.000 and 1.000); the runs and figures
+# are in profiles/hbm_traffic_bench_kaggle_r32.md.  Only valid for the workload they were taken on.
+MEASURED_TRAFFIC = {"kaggle_r32": {"fwd": 9.93e6, "bwd": 16.82e6, "sgd": 7.96e6}}
+
 
 def algorithmic_bytes(t, L, n_bags, touched_floats):
     """Bytes the method must move per launch (no re-reads, no intermediates).
@@ -53,6 +58,9 @@ def main():
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
                          "stream: every kernel is launched from Python")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run ten 256 MiB device-to-device copies (a kernel of known traffic, used to "
+                         "scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus %d is not supported "
@@ -65,6 +73,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "10 copies", "bytes_read_per_copy": src.numel() * 4,
+                          "bytes_written_per_copy": src.numel() * 4}))
+        return
     wl = W.WORKLOADS[args.workload]
     assert len(wl.tables) == 1, "bench.py times single-table workloads"
     t = wl.tables[0]
@@ -143,7 +160,8 @@ def main():
     dominant = max(stage_ms, key=stage_ms.get)
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get(dominant),
                 "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms}}

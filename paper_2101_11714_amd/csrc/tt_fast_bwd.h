@@ -37,9 +37,6 @@ constexpr int FB_SCAN = 2048;               // positions scanned per round
 constexpr int FB_ITER = FB_SCAN / WG;       // positions per lane and round
 constexpr int FB_PIECE = WAVE;              // entries sorted together
 constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
-#ifndef TT_BWD_WAVES
-#define TT_BWD_WAVES 3                      // waves per SIMD the register allocation must allow
-#endif
 
 #if defined(TT_PROFILE)
 __device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], debug builds only
@@ -60,6 +57,8 @@ struct FbCfg {
     static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
     static constexpr int BMR = C::RQ * C::V;                // registers per row for the wave's part of G2[i2]
     static constexpr int UBMAX = 4;
+    // register budget: three workgroups per CU (one wave each per SIMD) for the small slices, fewer for the large
+    static constexpr int WAVES_PER_SIMD = BMR <= 8 ? 3 : (BMR <= 32 ? 2 : 1);
     static constexpr int UB = BMR >= 8 * UBMAX ? 1 : (8 * UBMAX / BMR > UBMAX ? UBMAX : 8 * UBMAX / BMR);   // rows in flight per wave
     static_assert(W <= FB_CAP && (W % FB_PIECE == 0 || W < FB_PIECE), "windows hold whole pieces");
     static_assert(SB % UB == 0, "register batches must not straddle LDS batches");
@@ -213,7 +212,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 {
     using F = FbCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
-    constexpr int W = F::W, NB = F::NB, NQ = N / 4, SB = F::SB, UB = F::UB, SMALL = F::SMALL;
+    constexpr int W = F::W, NQ = N / 4, SB = F::SB, UB = F::UB, SMALL = F::SMALL;
     // float4 of small operands per row: G1 slice (needed by the G2 and G3 owners) and G3 slice (G1, G2 owners)
     constexpr int PA = C::sA / 4, PC = C::sC / 4;
     static_assert((PA & (PA - 1)) == 0 && (PC & (PC - 1)) == 0 && (NQ & (NQ - 1)) == 0, "item counts must be powers of two");
@@ -593,7 +592,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 }
 
 template <typename C>
-__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(TT_BWD_WAVES))) void bwd_fast_kernel(
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WAVES_PER_SIMD))) void bwd_fast_kernel(
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3,
     const int64_t *__restrict__ indices, int L, const int64_t *__restrict__ offsets, int n_bags,
     const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
