@@ -82,9 +82,12 @@ const char *tt_last_error(void);
 /* Smallest table capacity tt_cache_build accepts for K rows (a power of two). */
 int64_t tt_cache_table_capacity(int64_t K);
 
-/* Bytes of device workspace that tt_emb_fwd / tt_emb_bwd need for L positions in
- * n_bags bags (with_cache != 0 if a cache will be passed).  0 on a bad shape. */
-size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int with_cache);
+/* Bytes of device workspace that is always enough for tt_emb_fwd / tt_emb_bwd with L
+ * positions in n_bags bags and a cache of cache_rows rows (0 = no cache).  tt_emb_fwd needs
+ * none.  tt_emb_bwd needs none for a short index stream without a cache; with a cache, or from
+ * 16384 positions on (it then groups the positions with a device sort first), it reports
+ * TT_ERR_WORKSPACE if the workspace is missing or too small.  Returns 0 on a bad shape. */
+size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows);
 
 /* Bytes of device workspace tt_cache_build needs for n_cand candidates. */
 size_t tt_cache_build_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, int64_t K);
@@ -176,9 +179,10 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
                        int64_t *uniq, int32_t *count, int32_t *perm, int64_t *n_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
-/* 1 (default): shapes with a specialised kernel use it.  0: every call takes the
- * shape-generic kernels.  Process-wide; meant for tests.  Returns the old value. */
-int tt_emb_debug_set_fast_path(int enabled);
+/* Kernel selection, process-wide, meant for tests.  1 (default): shapes with a specialised
+ * kernel use it, and the backward groups long index streams first.  0: every call takes the
+ * shape-generic kernels.  2: as 1, but the backward always groups first.  Returns the old value. */
+int tt_emb_debug_set_fast_path(int mode);
 
 #ifdef __cplusplus
 }

@@ -59,7 +59,7 @@ def lib():
         l.tt_cache_table_capacity.argtypes = [C.c_int64]
         for name in ("tt_emb_workspace_bytes", "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes"):
             getattr(l, name).restype = C.c_size_t
-        l.tt_emb_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int]
+        l.tt_emb_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
         l.tt_cache_build_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64]
         l.tt_emb_dedup_workspace_bytes.argtypes = [C.c_int64]
         vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
@@ -132,8 +132,8 @@ class Cache:
         return C.byref(self.c)
 
 
-def workspace_bytes(shape: TTShape, L: int, n_bags: int, with_cache: bool) -> int:
-    return int(lib().tt_emb_workspace_bytes(C.byref(shape), L, n_bags, int(with_cache)))
+def workspace_bytes(shape: TTShape, L: int, n_bags: int, cache_rows: int = 0) -> int:
+    return int(lib().tt_emb_workspace_bytes(C.byref(shape), L, n_bags, int(cache_rows)))
 
 
 def _ws(nbytes: int, device) -> torch.Tensor:
@@ -232,5 +232,6 @@ def tt_emb_debug_dedup(shape: TTShape, indices: torch.Tensor, which: int, slot: 
     return uniq[:nu], count[:nu], perm[:kept]
 
 
-def set_fast_path(enabled: bool) -> bool:
-    return bool(lib().tt_emb_debug_set_fast_path(int(enabled)))
+def set_fast_path(mode: int) -> int:
+    """0: generic kernels, 1: specialised (default), 2: specialised + grouping pre-pass always."""
+    return int(lib().tt_emb_debug_set_fast_path(int(mode)))

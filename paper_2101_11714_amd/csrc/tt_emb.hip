@@ -14,13 +14,15 @@
 #include "tt_generic.h"
 #include "tt_fast.h"
 #include "tt_fast_bwd.h"
+#include "tt_group.h"
 
 using namespace tt;
 
 namespace {
 
 thread_local char g_err[512] = "";
-int g_fast_path = 1;
+int g_fast_path = 1;                       // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
+constexpr int64_t GROUP_MIN_L = 16384;    // from this many positions on the backward groups them first (tt_group.h)
 
 int fail(int code, const char *fmt, ...)
 {
@@ -120,9 +122,12 @@ int allow_lds(K kernel, size_t bytes)
 
 inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-size_t fwd_bwd_ws_bytes(int64_t L, int with_cache)
+// workspace of tt_emb_bwd: slot of every position (with a cache) | grouping pre-pass
+size_t slot_ws_bytes(int64_t L, int with_cache) { return with_cache ? align256((size_t)(L > 0 ? L : 1) * 4) : 0; }
+
+size_t fwd_bwd_ws_bytes(const Params &p, int64_t L, int64_t K)
 {
-    return 256 + (with_cache ? align256((size_t)(L > 0 ? L : 1) * 4) : 0);
+    return 256 + slot_ws_bytes(L, K != 0) + group_ws_layout(nullptr, L, p.m1 + p.m2 + p.m3 + (int)K, p.N).bytes;
 }
 
 }  // namespace
@@ -131,10 +136,10 @@ extern "C" {
 
 const char *tt_last_error(void) { return g_err; }
 
-int tt_emb_debug_set_fast_path(int enabled)
+int tt_emb_debug_set_fast_path(int mode)
 {
     int old = g_fast_path;
-    g_fast_path = enabled ? 1 : 0;
+    g_fast_path = mode < 0 ? 0 : (mode > 2 ? 2 : mode);
     return old;
 }
 
@@ -145,11 +150,13 @@ int64_t tt_cache_table_capacity(int64_t K)
     return cap;
 }
 
-size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int with_cache)
+size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows)
 {
     (void)n_bags;
-    if (check_shape(shape, nullptr) != TT_OK || L < 0) return 0;
-    return fwd_bwd_ws_bytes(L, with_cache);
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
+    if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
+    return fwd_bwd_ws_bytes(p, L, cache_rows);
 }
 
 size_t tt_emb_dedup_workspace_bytes(int64_t L)
@@ -216,8 +223,10 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
     CacheDev cd;
     if ((rc = check_cache(cache, &cd, false))) return rc;
     if (cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
-    const size_t need = fwd_bwd_ws_bytes(L, cd.K != 0);
-    if (cd.K && (!workspace || workspace_bytes < need))
+    const bool fast = g_fast_path && fast_bwd_supported(p);
+    const bool grouped = fast && (g_fast_path == 2 || L >= GROUP_MIN_L);
+    const size_t need = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
+    if ((cd.K || grouped) && (!workspace || workspace_bytes < need))
         return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     if (L == 0) return TT_OK;
     hipStream_t st = (hipStream_t)stream;
@@ -228,28 +237,53 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                             (size_t)(max_slice + p.sA + p.sC + p.n1 * p.cols + p.N) * sizeof(float);
     const int G = WG / p.N > 0 ? WG / p.N : 1;
     const size_t lds_cache = sizeof(SelectLds<GEN_CH>) + (size_t)G * p.N * sizeof(float);
-    const bool fast = g_fast_path && fast_bwd_supported(p);
     if (!fast && (rc = allow_lds(bwd_generic_kernel, lds_core))) return rc;
-    if (cd.K && (rc = allow_lds(bwd_cache_kernel, lds_cache))) return rc;
+    if (cd.K && !grouped && (rc = allow_lds(bwd_cache_kernel, lds_cache))) return rc;
 
+    if (offsets && n_bags > 0 && L % n_bags == 0) {                       // a guess for the bag of a position
+        p.bagP = (uint32_t)(L / n_bags);
+        p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
+    }
     int32_t *slot = nullptr;
     if (cd.K) {
         slot = (int32_t *)workspace;
         hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
-        hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
-                           offsets, (int)n_bags, alpha, grad_output, grad_cache);
     }
-    if (fast) {
-        if (offsets && n_bags > 0 && L % n_bags == 0) {
-            p.bagP = (uint32_t)(L / n_bags);
-            p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
+    if (grouped) {
+        // group the positions by the slices / cache slots they touch, then run the owners on their lists
+        const int nb3 = p.m1 + p.m2 + p.m3, nbins = nb3 + cd.K;
+        GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
+        const int n = 3 * (int)L;
+        if (3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
+        hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, p, indices, (int)L, slot, cd.K, g.sort.k0);
+        hipLaunchKernelGGL(grp_clear_kernel, dim3(cdiv(nbins + 1, WG)), dim3(WG), 0, st, g.off, g.end, nbins, g.crange);
+        int bits = 1;
+        while ((1 << bits) <= nbins) ++bits;
+        uint64_t *ks; uint32_t *vs;
+        hipError_t es = radix_sort(g.sort, n, bits, st, &ks, &vs);
+        if (es != hipSuccess) return hip_fail(es, "grouping sort");
+        hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
+        if (cd.K) {
+            const int tiles = cdiv(L, GT);
+            hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
+                               (int)n_bags, alpha, grad_output, grad_cache, g.part);
+            hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, g.crange, g.part,
+                               grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                 grad_cores[0], grad_cores[1], grad_cores[2], st);
+                 grad_cores[0], grad_cores[1], grad_cores[2], vs, g.off, g.end, st);
     } else {
-        hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
-                           cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
-                           grad_output, grad_cores[0], grad_cores[1], grad_cores[2]);
+        if (cd.K)
+            hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
+                               offsets, (int)n_bags, alpha, grad_output, grad_cache);
+        if (fast) {
+            fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
+                     grad_cores[0], grad_cores[1], grad_cores[2], nullptr, nullptr, nullptr, st);
+        } else {
+            hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
+                               cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
+                               grad_output, grad_cores[0], grad_cores[1], grad_cores[2]);
+        }
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "backward launch");

@@ -70,8 +70,8 @@ struct __align__(16) FbLds {
     float small[FbCfg<C>::SB * FbCfg<C>::SMALL];            // must follow stage[]: both are written through one index
     uint32_t rows[FB_CAP + 16];                             // selected row ids (+ padding read by the sort)
     uint32_t sr[FB_CAP];                                    // sorted by (row, k) inside each piece
-    uint16_t klist[FB_CAP];                                 // positions k - base of the selected entries
-    uint16_t sk[FB_CAP];
+    uint32_t klist[FB_CAP];                                 // positions k of the selected entries
+    uint32_t sk[FB_CAP];
     int seg_start[FbCfg<C>::W + 1];                         // first entry of each run of equal rows
     int seg_i1[FbCfg<C>::W], seg_i2[FbCfg<C>::W], seg_i3[FbCfg<C>::W];   // its digits
     int wcnt[NWAVE];
@@ -161,7 +161,7 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
         for (int it = 0; it < FB_ITER; ++it) {
             if ((masks[it] >> lane) & 1ull) {
                 const int pos = off + __popcll(masks[it] & lt);
-                lds.klist[pos] = (uint16_t)(wlo + it * WAVE + lane - lo);
+                lds.klist[pos] = (uint32_t)(wlo + it * WAVE + lane);
                 lds.rows[pos] = rowv[it];
             }
             off += __popcll(masks[it]);
@@ -208,7 +208,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         const float *__restrict__ alpha, const int32_t *__restrict__ slot,
                                         const float *__restrict__ grad_out, float *__restrict__ dG1,
                                         float *__restrict__ dG2, float *__restrict__ dG3,
-                                        uint32_t (&rowv)[FB_ITER])
+                                        const uint32_t *__restrict__ gvals, const int *__restrict__ goff,
+                                        const int *__restrict__ gend, uint32_t (&rowv)[FB_ITER])
 {
     using F = FbCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
@@ -241,7 +242,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     // ---- staging: gather float4 items from global memory into LDS, two per thread and pass ----
     // Item list of a pass: the window's gradients [0, n_g), then the G1 slices of rows
     // [sb0, sb0 + nb) (unless the G1 owner), then their G3 slices (unless the G3 owner).
-    auto stage_items = [&](int base, int i0, int n_g, int sb0, int nb) __attribute__((always_inline)) {
+    auto stage_items = [&](int i0, int n_g, int sb0, int nb) __attribute__((always_inline)) {
         const int n_a = ROLE != 0 ? nb * PA : 0;
         const int n_c = ROLE != 2 ? nb * PC : 0;
         const int total = n_g + n_a + n_c;
@@ -261,7 +262,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 o1[q] = 0;
                 if (item < n_g) {
                     const int e = item / NQ, f = item % NQ;
-                    const int k = base + (int)lds.sk[i0 + e];
+                    const int k = (int)lds.sk[i0 + e];
                     if (alpha) scale[q] = alpha[k];
                     int row = k;
                     if (offsets) {
@@ -401,8 +402,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
-    // one round: entries lds.klist / lds.rows [0, n), positions relative to `base`
-    auto process = [&](int n, int base) __attribute__((always_inline)) {
+    // one round: entries lds.klist / lds.rows [0, n)
+    auto process = [&](int n) __attribute__((always_inline)) {
         TT_STAMP(1); TT_NOTE(8, n);
         int nsegs_small = 0;
         if (n <= FB_PIECE) {
@@ -476,7 +477,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             float bm[UB][RQ][V];
             if (ROLE != 1) bm_load(0, nsegs, bm);
             TT_STAMP(3);
-            stage_items(base, i0, nw * NQ, 0, min(SB, nsegs));
+            stage_items(i0, nw * NQ, 0, min(SB, nsegs));
             __syncthreads();
             TT_STAMP(4);
             if (nsegs < nw) {                                              // uniform: some row occurs more than once
@@ -507,7 +508,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 if (ROLE != 1) bm_load(ub0, nsegs, bm);
                 if (ub0 == sb0) {                                        // next batch of small operands
                     __syncthreads();
-                    stage_items(base, i0, 0, sb0, min(SB, nsegs - sb0));
+                    stage_items(i0, 0, sb0, min(SB, nsegs - sb0));
                     __syncthreads();
                 }
                 consume(ub0, sb0, nsegs, bm);
@@ -517,18 +518,39 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
-    // Scan FB_SCAN positions per round; if a round selects more than FB_CAP entries (an adversarial
-    // index stream), redo it in pieces of FB_CAP positions, which always fit.
-    // The caller has already loaded the rows of the first round into rowv.
-    int span = FB_SCAN;
-    for (int lo = 0; lo < L;) {
-        const int hi = min(L, lo + span);
-        if (lo > 0 || span != FB_SCAN) fb_load_rows(indices, slot, lo, hi, rowv);
-        const int n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi);
-        if (n > FB_CAP) { span = FB_CAP; continue; }
-        if (n) { any = true; process(n, lo); }
-        lo = hi;
-        if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+    if (gvals) {
+        // The lookups were grouped by a pre-pass (tt_group.h): this slice's list is
+        // gvals[goff[bin] .. gend[bin]), payload = item number * L + k, in the order of k.
+        const int bin = (ROLE == 0 ? 0 : (ROLE == 1 ? p.m1 : p.m1 + p.m2)) + s;
+        const int b0 = goff[bin], b1 = gend[bin];
+        const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
+        for (int lo = b0; lo < b1; lo += FB_CAP) {
+            const int n = min(FB_CAP, b1 - lo);
+            __syncthreads();                                               // the previous round is done with the lists
+            for (int i = t; i < n; i += WG) {
+                const uint32_t k = gvals[lo + i] - sub;
+                lds.klist[i] = k;
+                lds.rows[i] = (uint32_t)indices[k];
+            }
+            if (t < 16) lds.rows[n + t] = FB_NONE;                         // padding read by the sort
+            __syncthreads();
+            any = true;
+            process(n);
+        }
+    } else {
+        // Scan FB_SCAN positions per round; if a round selects more than FB_CAP entries (an adversarial
+        // index stream), redo it in pieces of FB_CAP positions, which always fit.  The caller has
+        // already loaded the rows of the first round into rowv.
+        int span = FB_SCAN;
+        for (int lo = 0; lo < L;) {
+            const int hi = min(L, lo + span);
+            if (lo > 0 || span != FB_SCAN) fb_load_rows(indices, slot, lo, hi, rowv);
+            const int n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi);
+            if (n > FB_CAP) { span = FB_CAP; continue; }
+            if (n) { any = true; process(n); }
+            lo = hi;
+            if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+        }
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
     auto flush = [&]() __attribute__((always_inline)) {
@@ -596,7 +618,8 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3,
     const int64_t *__restrict__ indices, int L, const int64_t *__restrict__ offsets, int n_bags,
     const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
-    float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3)
+    float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
+    const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend)
 {
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
@@ -604,14 +627,14 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 #endif
     // The index loads do not depend on the role: issue them before anything else.
     uint32_t rowv[FB_ITER];
-    fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
+    if (!gvals) fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
     __builtin_amdgcn_sched_barrier(0);
     // role and slice of this workgroup, without branches so that all kernel arguments load together
     const int g = blockIdx.x;
     const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
     const int role = ge1 + ge2;
     const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, rowv);
+    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, rowv);
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
         g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
@@ -623,25 +646,27 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 template <typename C>
 static inline void launch_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
-                              const float *go, float *dG1, float *dG2, float *dG3, hipStream_t st)
+                              const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
+                              const int *goff, const int *gend, hipStream_t st)
 {
     hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(p.m1 + p.m2 + p.m3), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
-                       n_bags, alpha, slot, go, dG1, dG2, dG3);
+                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend);
 }
 
 static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >= 0; }
 
 static inline void fast_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx, int L,
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
-                            float *dG1, float *dG2, float *dG3, hipStream_t st)
+                            float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
+                            const int *gend, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
     default: break;
     }
 }

@@ -1,0 +1,220 @@
+// Grouping pre-pass of the backward pass for long index streams.
+//
+// For a few thousand lookups every slice owner of the backward kernel finds its lookups by
+// scanning the whole index array; that costs nothing next to a kernel launch.  For long
+// streams (multi-hot bags) the scan would dominate, so the lookups are grouped once, with
+// the device radix sort: every position k contributes three items keyed by the slice it
+// touches in core 1, 2 and 3, or, if its row is cached (Section 4.2 of the paper), one item
+// keyed by its cache slot.  After a stable sort by key the items of one key are one
+// contiguous list, in the order of k: exactly the list the owner's own scan would build.
+//
+// Keys: [0, m1) slices of G1, [m1, m1+m2) of G2, [m1+m2, nb3) of G3 (nb3 = m1+m2+m3),
+// [nb3, nb3+K) cache slots, nb3+K = unused item (sorts last).  The payload of an item is
+// r * L + k with r the item's number (0..2), so a list owner recovers k without a division.
+//
+// The gradient of the cached rows is a segmented sum over the sorted cached items: one wave
+// per tile of 64 items adds up the runs of equal slots in order; runs inside a tile are
+// written at once, runs that cross tile borders leave partial sums that the wave owning the
+// run's first tile adds up, tile by tile.  No atomics; the order of summation is fixed.
+#pragma once
+
+#include "tt_common.h"
+#include "tt_sort.h"
+
+namespace tt {
+
+constexpr int GT = 64;                      // sorted items per tile of the cached-row reduction
+
+struct GroupWs {
+    SortWs sort;                            // for 3 L items
+    int *off, *end;                         // [nbins + 1] list bounds per key, in the sorted arrays
+    int *crange;                            // [2] first and one-past-last sorted position of the cached items
+    float *part;                            // [tiles][2][N] partial sums of runs that cross tile borders
+    size_t bytes;
+};
+
+static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
+{
+    GroupWs g;
+    const int64_t n = 3 * (L > 0 ? L : 1);
+    g.sort = sort_ws_layout(ws, n);
+    char *p = (char *)ws;
+    size_t off = g.sort.bytes;
+    auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
+    g.off = (int *)take(((size_t)nbins + 1) * 4);
+    g.end = (int *)take(((size_t)nbins + 1) * 4);
+    g.crange = (int *)take(16);
+    const int64_t tiles = (L + GT - 1) / GT + 1;
+    g.part = (float *)take((size_t)tiles * 2 * N * 4);
+    g.bytes = off + 256;
+    return g;
+}
+
+// items[r * L + k]: key of item r of position k (see the file comment)
+__global__ __launch_bounds__(WG) void grp_keys_kernel(Params p, const int64_t *__restrict__ indices, int L,
+                                                      const int32_t *__restrict__ slot, int K,
+                                                      uint64_t *__restrict__ keys)
+{
+    const int k = blockIdx.x * WG + threadIdx.x;
+    if (k >= L) return;
+    const int nb3 = p.m1 + p.m2 + p.m3;
+    const uint64_t unused = (uint64_t)(nb3 + K);
+    const int sl = slot ? slot[k] : -1;
+    if (sl >= 0) {
+        keys[k] = (uint64_t)(nb3 + sl);
+        keys[(size_t)L + k] = unused;
+        keys[2 * (size_t)L + k] = unused;
+    } else {
+        int i1, i2, i3;
+        decode(p, (uint32_t)indices[k], i1, i2, i3);
+        keys[k] = (uint64_t)i1;
+        keys[(size_t)L + k] = (uint64_t)(p.m1 + i2);
+        keys[2 * (size_t)L + k] = (uint64_t)(p.m1 + p.m2 + i3);
+    }
+}
+
+__global__ __launch_bounds__(WG) void grp_clear_kernel(int *__restrict__ off, int *__restrict__ end, int nbins,
+                                                       int *__restrict__ crange)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i <= nbins) { off[i] = 0; end[i] = 0; }
+    if (i < 2) crange[i] = 0;
+}
+
+// list bounds of every key that occurs, and the range of the cached items
+__global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restrict__ ks, int n, int nb3, int nbins,
+                                                        int *__restrict__ off, int *__restrict__ end,
+                                                        int *__restrict__ crange)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i >= n) return;
+    const int key = (int)ks[i];
+    if (key >= nbins) return;                                    // unused items
+    const int prev = i > 0 ? (int)ks[i - 1] : -1;
+    const int next = i + 1 < n ? (int)ks[i + 1] : nbins;
+    if (prev != key) off[key] = i;
+    if (next != key) end[key] = i + 1;
+    if (key >= nb3) {
+        if (prev < nb3) crange[0] = i;
+        if (next >= nbins) crange[1] = i + 1;
+    }
+}
+
+// bag of position k: fixed bag length if the caller found one, else a search
+__device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restrict__ offsets, int n_bags, int k)
+{
+    if (!offsets) return k;
+    if (p.bagP) {
+        int g = (int)fast_div((uint32_t)k, p.bagP, p.mgP);
+        g = g < n_bags ? g : n_bags - 1;
+        if (offsets[g] <= (int64_t)k && (int64_t)k < offsets[g + 1]) return g;
+    }
+    return bag_of(offsets, n_bags, k);
+}
+
+// One wave per tile of GT sorted cached items.  Lane j owns columns j, j + 64, ... of a row.
+__global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint64_t *__restrict__ ks,
+                                                            const uint32_t *__restrict__ vs,
+                                                            const int *__restrict__ crange,
+                                                            const int64_t *__restrict__ offsets, int n_bags,
+                                                            const float *__restrict__ alpha,
+                                                            const float *__restrict__ grad_out,
+                                                            float *__restrict__ grad_cache, float *__restrict__ part)
+{
+    constexpr int MAXC = 4;                                       // N <= 256 columns
+    const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int cb = crange[0], ce = crange[1];
+    const int i0 = cb + tile * GT;
+    if (i0 >= ce) return;
+    const int i1 = min(ce, i0 + GT);
+    const int key_prev = i0 > cb ? (int)ks[i0 - 1] : -1;
+    const int key_next = i1 < ce ? (int)ks[i1] : -1;
+    float sum[MAXC] = {0.f, 0.f, 0.f, 0.f};
+    int cur = (int)ks[i0];
+    bool first = true;
+    auto flush = [&](int key, bool run_ends_here) {
+        // a run that began in an earlier tile, or continues into the next one, leaves a partial sum
+        const bool from_left = first && key == key_prev;
+        const bool to_right = !run_ends_here;
+        if (from_left || to_right) {
+            float *dst = part + ((size_t)tile * 2 + (from_left ? 0 : 1)) * N;
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c)
+                if (lane + 64 * c < N) dst[lane + 64 * c] = sum[c];
+        } else {
+            float *dst = grad_cache + (size_t)(key - nb3) * N;
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c)
+                if (lane + 64 * c < N) dst[lane + 64 * c] += sum[c];
+        }
+        first = false;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) sum[c] = 0.f;
+    };
+    for (int e0 = i0; e0 < i1; e0 += 8) {
+        int key[8];
+        float w[8];
+        float g[8][MAXC];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int i = min(e0 + q, i1 - 1);
+            key[q] = (int)ks[i];
+            const int k = (int)vs[i];                              // cached items are item 0: payload = k
+            w[q] = alpha ? alpha[k] : 1.f;
+            const int bag = grp_bag(p, offsets, n_bags, k);
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c)
+                g[q][c] = lane + 64 * c < N ? grad_out[(size_t)bag * N + lane + 64 * c] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (e0 + q < i1) {                                     // uniform
+                if (key[q] != cur) { flush(cur, true); cur = key[q]; }
+#pragma unroll
+                for (int c = 0; c < MAXC; ++c) sum[c] = fmaf(w[q], g[q][c], sum[c]);
+            }
+        }
+    }
+    flush(cur, cur != key_next);
+}
+
+// The wave of the tile in which a border-crossing run begins adds up its partial sums.
+__global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint64_t *__restrict__ ks,
+                                                           const int *__restrict__ crange,
+                                                           const float *__restrict__ part,
+                                                           float *__restrict__ grad_cache)
+{
+    constexpr int MAXC = 4;
+    const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int cb = crange[0], ce = crange[1];
+    const int i0 = cb + tile * GT;
+    if (i0 >= ce) return;
+    const int i1 = min(ce, i0 + GT);
+    if (i1 >= ce) return;                                          // nothing to the right
+    const int key = (int)ks[i1 - 1];
+    if ((int)ks[i1] != key) return;                                // the last run ends in this tile
+    const bool single = (int)ks[i0] == key;
+    if (single && i0 > cb && (int)ks[i0 - 1] == key) return;       // a middle tile of the run: not the owner
+    float sum[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) sum[c] = lane + 64 * c < N ? part[((size_t)tile * 2 + 1) * N + lane + 64 * c] : 0.f;
+    for (int u = tile + 1;; ++u) {
+        const int u0 = cb + u * GT;
+        if (u0 >= ce || (int)ks[u0] != key) break;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+            if (lane + 64 * c < N) sum[c] += part[((size_t)u * 2 + 0) * N + lane + 64 * c];
+        const int u1 = min(ce, u0 + GT);
+        if ((int)ks[u1 - 1] != key) break;                         // the run ended inside tile u
+    }
+    float *dst = grad_cache + (size_t)(key - nb3) * N;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+        if (lane + 64 * c < N) dst[lane + 64 * c] += sum[c];
+}
+
+}  // namespace tt

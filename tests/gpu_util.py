@@ -70,11 +70,10 @@ class DeviceTable:
     def bwd(self, cache=None, grad_cores=None, grad_cache=None, use_offsets=True):
         if grad_cores is None:
             grad_cores = [torch.zeros_like(x) for x in self.g]
-        ws = None
-        if cache is not None:
-            if grad_cache is None:
-                grad_cache = torch.zeros_like(cache.rows)
-            ws = torch.empty(B.workspace_bytes(self.shape, self.L, self.n_bags, True), dtype=torch.uint8, device=dev())
+        if cache is not None and grad_cache is None:
+            grad_cache = torch.zeros_like(cache.rows)
+        ws = torch.empty(B.workspace_bytes(self.shape, self.L, self.n_bags, cache.K if cache is not None else 0),
+                         dtype=torch.uint8, device=dev())
         B.tt_emb_bwd(self.shape, self.g, self.idx, self.off if use_offsets else None, self.n_bags, self.go,
                      grad_cores, alpha=self.alpha, cache=cache, grad_cache=grad_cache, workspace=ws)
         torch.cuda.synchronize()

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 SINGLE = ["tiny", "kaggle_r32", "sweep_r8", "sweep_r16", "sweep_r32", "sweep_r64", "terabyte_r64"]
 
 
-@pytest.fixture(params=[True, False], ids=["fast", "generic"])
+@pytest.fixture(params=[1, 0, 2], ids=["fast", "generic", "grouped"])
 def path(request):
     old = B.set_fast_path(request.param)
     yield request.param
