@@ -267,7 +267,7 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
             const int tiles = cdiv(L, GT);
             hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
                                (int)n_bags, alpha, grad_output, grad_cache, g.part);
-            hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, g.crange, g.part,
+            hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, g.crange, g.end, g.part,
                                grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,

@@ -112,7 +112,9 @@ __device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restric
     return bag_of(offsets, n_bags, k);
 }
 
-// One wave per tile of GT sorted cached items.  Lane j owns columns j, j + 64, ... of a row.
+// One wave per tile of GT = 64 sorted cached items.  Lane e first fetches key, position, weight
+// and bag of item e (one round trip for the whole tile); then the rows of the upstream gradient
+// are read 16 items at a time, lane j owning columns j, j + 64, ..., and added run by run.
 __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint64_t *__restrict__ ks,
                                                             const uint32_t *__restrict__ vs,
                                                             const int *__restrict__ crange,
@@ -122,6 +124,7 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
                                                             float *__restrict__ grad_cache, float *__restrict__ part)
 {
     constexpr int MAXC = 4;                                       // N <= 256 columns
+    static_assert(GT == WAVE, "one item per lane");
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
@@ -129,10 +132,18 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
     const int i0 = cb + tile * GT;
     if (i0 >= ce) return;
     const int i1 = min(ce, i0 + GT);
+    const int cnt = i1 - i0;
     const int key_prev = i0 > cb ? (int)ks[i0 - 1] : -1;
     const int key_next = i1 < ce ? (int)ks[i1] : -1;
+    // item of this lane
+    const int ie = min(i0 + lane, i1 - 1);
+    const int my_key = (int)ks[ie];
+    const int my_k = (int)vs[ie];                                 // cached items are item 0: payload = k
+    const float my_w = alpha ? alpha[my_k] : 1.f;
+    const int my_bag = grp_bag(p, offsets, n_bags, my_k);
+
     float sum[MAXC] = {0.f, 0.f, 0.f, 0.f};
-    int cur = (int)ks[i0];
+    int cur = __builtin_amdgcn_readfirstlane(my_key);
     bool first = true;
     auto flush = [&](int key, bool run_ends_here) {
         // a run that began in an earlier tile, or continues into the next one, leaves a partial sum
@@ -153,36 +164,36 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) sum[c] = 0.f;
     };
-    for (int e0 = i0; e0 < i1; e0 += 8) {
-        int key[8];
-        float w[8];
-        float g[8][MAXC];
+    for (int e0 = 0; e0 < cnt; e0 += 16) {
+        float g[16][MAXC];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int i = min(e0 + q, i1 - 1);
-            key[q] = (int)ks[i];
-            const int k = (int)vs[i];                              // cached items are item 0: payload = k
-            w[q] = alpha ? alpha[k] : 1.f;
-            const int bag = grp_bag(p, offsets, n_bags, k);
+        for (int q = 0; q < 16; ++q) {
+            const int e = min(e0 + q, cnt - 1);
+            const int bag = __builtin_amdgcn_readlane(my_bag, e);
 #pragma unroll
             for (int c = 0; c < MAXC; ++c)
                 g[q][c] = lane + 64 * c < N ? grad_out[(size_t)bag * N + lane + 64 * c] : 0.f;
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (e0 + q < i1) {                                     // uniform
-                if (key[q] != cur) { flush(cur, true); cur = key[q]; }
+        for (int q = 0; q < 16; ++q) {
+            const int e = e0 + q;
+            if (e < cnt) {                                         // uniform
+                const int key = __builtin_amdgcn_readlane(my_key, e);
+                const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), e));
+                if (key != cur) { flush(cur, true); cur = key; }
 #pragma unroll
-                for (int c = 0; c < MAXC; ++c) sum[c] = fmaf(w[q], g[q][c], sum[c]);
+                for (int c = 0; c < MAXC; ++c) sum[c] = fmaf(w, g[q][c], sum[c]);
             }
         }
     }
     flush(cur, cur != key_next);
 }
 
-// The wave of the tile in which a border-crossing run begins adds up its partial sums.
+// The wave of the tile in which a border-crossing run begins adds up its partial sums, in
+// tile order.  The run's last item is known from the list bounds, so the loads are independent.
 __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint64_t *__restrict__ ks,
                                                            const int *__restrict__ crange,
+                                                           const int *__restrict__ gend,
                                                            const float *__restrict__ part,
                                                            float *__restrict__ grad_cache)
 {
@@ -199,17 +210,25 @@ __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint6
     if ((int)ks[i1] != key) return;                                // the last run ends in this tile
     const bool single = (int)ks[i0] == key;
     if (single && i0 > cb && (int)ks[i0 - 1] == key) return;       // a middle tile of the run: not the owner
+    const int last_tile = (gend[key] - 1 - cb) / GT;               // tile that holds the run's last item
     float sum[MAXC];
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) sum[c] = lane + 64 * c < N ? part[((size_t)tile * 2 + 1) * N + lane + 64 * c] : 0.f;
-    for (int u = tile + 1;; ++u) {
-        const int u0 = cb + u * GT;
-        if (u0 >= ce || (int)ks[u0] != key) break;
+    for (int u0 = tile + 1; u0 <= last_tile; u0 += 16) {
+        float x[16][MAXC];
 #pragma unroll
-        for (int c = 0; c < MAXC; ++c)
-            if (lane + 64 * c < N) sum[c] += part[((size_t)u * 2 + 0) * N + lane + 64 * c];
-        const int u1 = min(ce, u0 + GT);
-        if ((int)ks[u1 - 1] != key) break;                         // the run ended inside tile u
+        for (int q = 0; q < 16; ++q) {
+            const int u = min(u0 + q, last_tile);
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c)
+                x[q][c] = lane + 64 * c < N ? part[((size_t)u * 2 + 0) * N + lane + 64 * c] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (u0 + q <= last_tile) {
+#pragma unroll
+                for (int c = 0; c < MAXC; ++c) sum[c] += x[q][c];
+            }
     }
     float *dst = grad_cache + (size_t)(key - nb3) * N;
 #pragma unroll

@@ -32,30 +32,64 @@ __global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict_
 }
 
 // In-place exclusive scan of data[0..total); data[total] receives the sum.  One workgroup.
+// A step covers SCAN_SUB sub-blocks of 4096 values; a thread loads one uint4 of each (coalesced,
+// all loads of the step in flight together) and the sub-blocks are scanned one after the other.
+// `data` must be 16-byte aligned; it is padded to a multiple of 4 values (see sort_ws_layout).
+constexpr int SCAN_SUB = 4;
+
 __global__ __launch_bounds__(SCAN_WG) void scan_kernel(uint32_t *__restrict__ data, int total)
 {
     __shared__ uint32_t wsum[SCAN_WG / WAVE];
-    __shared__ uint32_t carry;
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    if (t == 0) carry = 0;
-    __syncthreads();
-    for (int base = 0; base < total; base += SCAN_WG) {
-        int i = base + t;
-        uint32_t v = i < total ? data[i] : 0u;
-        uint32_t inc = v;
+    uint32_t carry = 0;                                            // same value in every thread
+    for (int base = 0; base < total; base += SCAN_SUB * SCAN_WG * 4) {
+        uint4 v[SCAN_SUB];
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint32_t o = __shfl_up(inc, d);
-            if (lane >= d) inc += o;
+        for (int q = 0; q < SCAN_SUB; ++q) {
+            const int i = base + q * SCAN_WG * 4 + t * 4;
+            v[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (i + 3 < total) {
+                v[q] = *reinterpret_cast<const uint4 *>(data + i);
+            } else if (i < total) {
+                v[q].x = data[i];
+                if (i + 1 < total) v[q].y = data[i + 1];
+                if (i + 2 < total) v[q].z = data[i + 2];
+            }
         }
-        if (lane == 63) wsum[w] = inc;
-        __syncthreads();
-        uint32_t pre = carry;
-        for (int j = 0; j < w; ++j) pre += wsum[j];
-        if (i < total) data[i] = pre + inc - v;
-        __syncthreads();
-        if (t == SCAN_WG - 1) carry = pre + inc;
-        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < SCAN_SUB; ++q) {
+            const int i = base + q * SCAN_WG * 4 + t * 4;
+            const uint32_t mine = v[q].x + v[q].y + v[q].z + v[q].w;
+            uint32_t inc = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                uint32_t o = __shfl_up(inc, d);
+                if (lane >= d) inc += o;
+            }
+            __syncthreads();                                       // wsum of the previous sub-block has been read
+            if (lane == 63) wsum[w] = inc;
+            __syncthreads();
+            uint32_t pre = carry, all = 0;
+#pragma unroll
+            for (int j = 0; j < SCAN_WG / WAVE; ++j) {
+                const uint32_t x = wsum[j];
+                if (j < w) pre += x;
+                all += x;
+            }
+            carry += all;
+            uint4 o;
+            o.x = pre + inc - mine;
+            o.y = o.x + v[q].x;
+            o.z = o.y + v[q].y;
+            o.w = o.z + v[q].z;
+            if (i + 3 < total) {
+                *reinterpret_cast<uint4 *>(data + i) = o;
+            } else if (i < total) {
+                data[i] = o.x;
+                if (i + 1 < total) data[i + 1] = o.y;
+                if (i + 2 < total) data[i + 2] = o.z;
+            }
+        }
     }
     if (t == 0) data[total] = carry;
 }
