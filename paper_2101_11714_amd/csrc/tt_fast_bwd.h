@@ -36,6 +36,7 @@ constexpr int FB_CAP = 512;                 // list entries a workgroup handles 
 constexpr int FB_SCAN = 2048;               // positions scanned per round
 constexpr int FB_ITER = FB_SCAN / WG;       // positions per lane and round
 constexpr int FB_PIECE = WAVE;              // entries sorted together
+constexpr int FB_WCAP = FB_CAP / NWAVE;     // entries one wave may select per round
 constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
 
 #if defined(TT_PROFILE)
@@ -49,6 +50,10 @@ __device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], d
 #define TT_NOTE(i, v) do { } while (0)
 #endif
 
+// *dst += x where no other thread touches *dst.  (An add performed by the memory system, without
+// a returned value, was measured and is slower here than load, add, store.)
+__device__ __forceinline__ void add_to(float *dst, float x) { *dst += x; }
+
 template <typename C>
 struct FbCfg {
     static constexpr int W = 4096 / C::N;                   // sorted entries per window
@@ -56,10 +61,12 @@ struct FbCfg {
     static constexpr int SB = 16;                           // distinct rows whose small operands sit in LDS
     static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
     static constexpr int BMR = C::RQ * C::V;                // registers per row for the wave's part of G2[i2]
-    static constexpr int UBMAX = 4;
     // register budget: three workgroups per CU (one wave each per SIMD) for the small slices, fewer for the large
-    static constexpr int WAVES_PER_SIMD = BMR <= 8 ? 3 : (BMR <= 32 ? 2 : 1);
-    static constexpr int UB = BMR >= 8 * UBMAX ? 1 : (8 * UBMAX / BMR > UBMAX ? UBMAX : 8 * UBMAX / BMR);   // rows in flight per wave
+    static constexpr int WAVES_PER_SIMD = (BMR <= 8 || (BMR <= 32 && C::N <= 16)) ? 3 : (BMR <= 32 ? 2 : 1);
+    // rows of G2 in flight per wave: up to 4, within 32 registers (8 rows / 64 registers was measured: slower,
+    // the extra loads and the idle row slots of short lists cost more than the saved round trip)
+    static constexpr int BUDGET = 32;
+    static constexpr int UB = BUDGET / BMR >= 4 ? 4 : (BUDGET / BMR >= 1 ? BUDGET / BMR : 1);
     static_assert(W <= FB_CAP && (W % FB_PIECE == 0 || W < FB_PIECE), "windows hold whole pieces");
     static_assert(SB % UB == 0, "register batches must not straddle LDS batches");
 };
@@ -68,13 +75,13 @@ template <typename C>
 struct __align__(16) FbLds {
     float stage[FbCfg<C>::W * C::N];                        // alpha_k * grad_out[bag(k)] of the window's entries (16 KB)
     float small[FbCfg<C>::SB * FbCfg<C>::SMALL];            // must follow stage[]: both are written through one index
-    uint32_t rows[FB_CAP + 16];                             // selected row ids (+ padding read by the sort)
-    uint32_t sr[FB_CAP];                                    // sorted by (row, k) inside each piece
+    uint32_t rows[FB_CAP];                                  // selected row ids: four sub-lists, see fb_select
     uint32_t klist[FB_CAP];                                 // positions k of the selected entries
-    uint32_t sk[FB_CAP];
-    int seg_start[FbCfg<C>::W + 1];                         // first entry of each run of equal rows
+    int epos[FbCfg<C>::W];                                  // staged position of each entry of the window (runs contiguous)
+    int seg_start[FbCfg<C>::W + 1];                         // staged position of the first entry of each run of equal rows
     int seg_i1[FbCfg<C>::W], seg_i2[FbCfg<C>::W], seg_i3[FbCfg<C>::W];   // its digits
-    int wcnt[NWAVE];
+    int pcnt[NWAVE];                                        // runs per piece of a long window
+    int wcnt[2][NWAVE];
 };
 
 // Row ids of the positions [lo, hi), hi - lo <= FB_SCAN, FB_ITER per lane: wave w covers a
@@ -101,12 +108,19 @@ __device__ __forceinline__ void fb_load_rows(const int64_t *__restrict__ indices
     }
 }
 
-// Stable compaction of the positions in [lo, hi) (rows in rowv, see fb_load_rows) that select
-// slice s of the role's core.  Returns the number of matches; the lists are written only if
-// that number is <= FB_CAP.
+// Stable selection of the positions in [lo, hi) (rows in rowv, see fb_load_rows) that select
+// slice s of the role's core.  Wave w appends its matches, in order, to its own sub-list
+// lds.klist / lds.rows [w * FB_WCAP ...): the list of the workgroup is the concatenation of the
+// four sub-lists (fb_slot), so one barrier is enough.  wc[] receives the sub-list lengths.
+// Returns the number of matches, or FB_CAP + 1 if a sub-list would overflow (nothing usable
+// has been written then).  `round` alternates the counters between calls.
 template <typename C>
 __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
-                                         const uint32_t (&rowv)[FB_ITER], int lo, int hi)
+                                         const uint32_t (&rowv)[FB_ITER], int lo, int hi, int round, int (&wc)[NWAVE]
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+                                         , unsigned long long *ts
+#endif
+                                         )
 {
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int span = ((hi - lo + WG - 1) / WG) * WAVE;      // positions per wave
@@ -146,19 +160,13 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
             cnt += __popcll(masks[it]);
         }
     }
-    if (lane == 0) lds.wcnt[w] = cnt;
-    __syncthreads();
-    int off = 0, total = 0;
-#pragma unroll
-    for (int j = 0; j < NWAVE; ++j) {
-        const int c = lds.wcnt[j];
-        if (j < w) off += c;
-        total += c;
-    }
-    if (total > 0 && total <= FB_CAP) {
+    TT_STAMP(12);
+    if (cnt > 0 && cnt <= FB_WCAP) {                                        // uniform in the wave
         const uint64_t lt = lanemask_lt();
+        int off = w * FB_WCAP;
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
+            if (masks[it] == 0) continue;                                   // uniform: most are empty
             if ((masks[it] >> lane) & 1ull) {
                 const int pos = off + __popcll(masks[it] & lt);
                 lds.klist[pos] = (uint32_t)(wlo + it * WAVE + lane);
@@ -166,38 +174,32 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
             }
             off += __popcll(masks[it]);
         }
-        if (t < 16) lds.rows[total + t] = FB_NONE;          // padding read by the sort
     }
+    int *wcnt = lds.wcnt[round & 1];
+    if (lane == 0) wcnt[w] = cnt;
     __syncthreads();
-    return total;
+    TT_STAMP(13);
+    int total = 0;
+    bool fits = true;
+#pragma unroll
+    for (int j = 0; j < NWAVE; ++j) {
+        wc[j] = wcnt[j];
+        total += wc[j];
+        fits = fits && wc[j] <= FB_WCAP;
+    }
+    return fits ? total : FB_CAP + 1;
 }
 
-// Sort one piece [p0, p0 + cnt), cnt <= 64, of the selected entries by (row, position) into
-// lds.sr / lds.sk at the same positions: lane i ranks entry p0 + i among the piece.  Only the
-// last piece can be shorter than 64; what is read past its end is the FB_NONE padding, which is
-// greater than any row.
-template <typename C>
-__device__ __forceinline__ void fb_sort_piece(FbLds<C> &lds, int p0, int cnt)
+// LDS position of entry e of the workgroup's list, given the sub-list lengths (see fb_select)
+__device__ __forceinline__ int fb_slot(const int (&wc)[NWAVE], int e)
 {
-    const int lane = threadIdx.x & 63;
-    if (lane < cnt) {
-        const uint32_t my = lds.rows[p0 + lane];
-        int lt = 0, eq = 0;
-        for (int j = 0; j < cnt; j += 16) {
-            uint4 r[4];
+    int sl = e, pre = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(&lds.rows[p0 + j + 4 * q]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int jj = j + 4 * q;
-                lt += (r[q].x < my) + (r[q].y < my) + (r[q].z < my) + (r[q].w < my);
-                eq += (r[q].x == my && jj + 0 < lane) + (r[q].y == my && jj + 1 < lane) + (r[q].z == my && jj + 2 < lane) +
-                      (r[q].w == my && jj + 3 < lane);
-            }
-        }
-        lds.sk[p0 + lt + eq] = lds.klist[p0 + lane];
-        lds.sr[p0 + lt + eq] = my;
+    for (int j = 0; j + 1 < NWAVE; ++j) {
+        pre += wc[j];
+        if (e >= pre) sl = e - pre + (j + 1) * FB_WCAP;
     }
+    return sl;
 }
 
 template <typename C>
@@ -235,70 +237,90 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
     bool any = false;
 #if defined(TT_PROFILE) && TT_PROFILE == 2
-    unsigned long long ts[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long ts[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     TT_STAMP(0);
 #endif
 
-    // ---- staging: gather float4 items from global memory into LDS, two per thread and pass ----
-    // Item list of a pass: the window's gradients [0, n_g), then the G1 slices of rows
-    // [sb0, sb0 + nb) (unless the G1 owner), then their G3 slices (unless the G3 owner).
-    auto stage_items = [&](int i0, int n_g, int sb0, int nb) __attribute__((always_inline)) {
+    // ---- staging: gather float4 items from global memory into LDS ----
+    // One item in flight: its value, and for a gradient item what is needed to confirm the bag.
+    struct Item {
+        float4 val;
+        float scale;
+        int dst, chk_k, chk_f;
+        int o0, o1;                                                       // offsets are < 2^31: the low words suffice
+    };
+    // float4 f of alpha_k * grad_out[bag(k)]: the bag is guessed (exact for fixed-length bags) and
+    // its row is loaded while the two offsets that confirm the guess are in flight
+    auto grad_issue = [&](int k, int f, Item &r) __attribute__((always_inline)) {
+        r.scale = alpha ? alpha[k] : 1.f;
+        r.chk_k = -1;
+        r.chk_f = f;
+        r.o0 = 0;
+        r.o1 = 0;
+        int row = k;
+        if (offsets) {
+            int gs = p.bagP ? (int)fast_div((uint32_t)k, p.bagP, p.mgP) : (int)((float)k * ((float)n_bags / (float)L));
+            gs = gs < n_bags ? gs : n_bags - 1;
+            const int *olo = reinterpret_cast<const int *>(offsets);      // little endian: low word first
+            r.o0 = olo[2 * gs];
+            r.o1 = olo[2 * gs + 2];
+            r.chk_k = k;
+            row = gs;
+        }
+        r.val = *reinterpret_cast<const float4 *>(grad_out + (uint32_t)row * (uint32_t)N + 4u * (uint32_t)f);
+    };
+    auto item_finish = [&](const Item &r) __attribute__((always_inline)) {
+        float4 g = r.val;
+        if (r.chk_k >= 0 && !(r.o0 <= r.chk_k && r.chk_k < r.o1)) {       // ragged bags
+            const int bag = bag_of(offsets, n_bags, r.chk_k);
+            g = *reinterpret_cast<const float4 *>(grad_out + (size_t)bag * N + 4 * r.chk_f);
+        }
+        g.x *= r.scale; g.y *= r.scale; g.z *= r.scale; g.w *= r.scale;
+        return g;
+    };
+    // Item list of a pass, up to IPT items per thread, all loads of a pass in flight together: the
+    // gradients of entries [0, n_g / NQ) of the window that starts at list entry i0 (entry e goes
+    // to its staged position lds.epos[e]), then the G1 slices of rows [sb0, sb0 + nb) (unless the
+    // G1 owner), then their G3 slices (unless the G3 owner).
+    constexpr int IPT = N <= 16 ? 4 : 2;
+    auto stage_items = [&](int i0, int n_g, int sb0, int nb, const int (&wc)[NWAVE]) __attribute__((always_inline)) {
         const int n_a = ROLE != 0 ? nb * PA : 0;
         const int n_c = ROLE != 2 ? nb * PC : 0;
         const int total = n_g + n_a + n_c;
-        for (int it0 = 0; it0 < total; it0 += 2 * WG) {                   // uniform
-            float4 val[2];
-            float scale[2];
-            int dst[2], chk_k[2], chk_f[2];
-            int64_t o0[2], o1[2];
+        for (int it0 = 0; it0 < total; it0 += IPT * WG) {                 // uniform
+            Item r[IPT];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < IPT; ++q) {
                 const int item = min(it0 + q * WG + t, total - 1);        // past the end: repeat the last item
-                const float *src;
-                scale[q] = 1.f;
-                chk_k[q] = -1;
-                chk_f[q] = 0;
-                o0[q] = 0;
-                o1[q] = 0;
                 if (item < n_g) {
                     const int e = item / NQ, f = item % NQ;
-                    const int k = (int)lds.sk[i0 + e];
-                    if (alpha) scale[q] = alpha[k];
-                    int row = k;
-                    if (offsets) {
-                        // guess the bag (exact for fixed-length bags); its row is loaded while the two
-                        // offsets that confirm the guess are in flight
-                        int gs = p.bagP ? (int)fast_div((uint32_t)k, p.bagP, p.mgP)
-                                        : (int)((float)k * ((float)n_bags / (float)L));
-                        gs = gs < n_bags ? gs : n_bags - 1;
-                        o0[q] = offsets[gs];
-                        o1[q] = offsets[gs + 1];
-                        chk_k[q] = k;
-                        chk_f[q] = f;
-                        row = gs;
-                    }
-                    src = grad_out + (uint32_t)row * (uint32_t)N + 4u * (uint32_t)f;
-                    dst[q] = 4 * item;                                    // = stage[e * N + 4 f]
-                } else if (item < n_g + n_a) {
-                    const int x = item - n_g, u = x / PA, f = x % PA;
-                    src = G1 + (uint32_t)lds.seg_i1[sb0 + u] * (uint32_t)C::sA + 4u * (uint32_t)f;
-                    dst[q] = W * N + u * SMALL + 4 * f;                   // small[] follows stage[] in LDS
+                    grad_issue((int)lds.klist[fb_slot(wc, i0 + e)], f, r[q]);
+                    r[q].dst = 4 * (NQ * lds.epos[e] + f);                // = stage[position * N + 4 f]
                 } else {
-                    const int x = item - n_g - n_a, u = x / PC, f = x % PC;
-                    src = G3 + (uint32_t)lds.seg_i3[sb0 + u] * (uint32_t)C::sC + 4u * (uint32_t)f;
-                    dst[q] = W * N + u * SMALL + C::sA + 4 * f;
+                    const float *src;
+                    if (item < n_g + n_a) {
+                        const int x = item - n_g, u = x / PA, f = x % PA;
+                        src = G1 + (uint32_t)lds.seg_i1[sb0 + u] * (uint32_t)C::sA + 4u * (uint32_t)f;
+                        r[q].dst = W * N + u * SMALL + 4 * f;             // small[] follows stage[] in LDS
+                    } else {
+                        const int x = item - n_g - n_a, u = x / PC, f = x % PC;
+                        src = G3 + (uint32_t)lds.seg_i3[sb0 + u] * (uint32_t)C::sC + 4u * (uint32_t)f;
+                        r[q].dst = W * N + u * SMALL + C::sA + 4 * f;
+                    }
+                    r[q].scale = 1.f;
+                    r[q].chk_k = -1;
+                    r[q].chk_f = 0;
+                    r[q].o0 = 0;
+                    r[q].o1 = 0;
+                    r[q].val = *reinterpret_cast<const float4 *>(src);
                 }
-                val[q] = *reinterpret_cast<const float4 *>(src);
+                if ((q & 1) && it0 + (q + 1) * WG >= total) break;        // uniform: the pass ends here
             }
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                float4 g = val[q];
-                if (chk_k[q] >= 0 && !(o0[q] <= (int64_t)chk_k[q] && (int64_t)chk_k[q] < o1[q])) {   // ragged bags
-                    const int bag = bag_of(offsets, n_bags, chk_k[q]);
-                    g = *reinterpret_cast<const float4 *>(grad_out + (size_t)bag * N + 4 * chk_f[q]);
-                }
-                g.x *= scale[q]; g.y *= scale[q]; g.z *= scale[q]; g.w *= scale[q];
-                if (it0 + q * WG + t < total) *reinterpret_cast<float4 *>(&stage[dst[q]]) = g;
+            for (int q = 0; q < IPT; ++q) {
+                if (it0 + q * WG >= total) break;                         // uniform
+                const float4 g = item_finish(r[q]);
+                if (it0 + q * WG + t < total) *reinterpret_cast<float4 *>(&stage[r[q].dst]) = g;
             }
         }
     };
@@ -321,155 +343,163 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     // so each row reads exactly one dY.  No branches on the row count: rows past the end repeat
     // the last one with a zero weight, so the LDS reads of the batch can be in flight together.
     auto consume = [&](int ub0, int sb0, int nsegs, const float (&bm)[UB][RQ][V]) __attribute__((always_inline)) {
-        const float *sm[UB];
-        const float *dyp[UB];
-        float keep[UB];
+        constexpr int UH = UB < 4 ? UB : 4;                             // rows whose LDS reads are in flight together
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            const int sg = min(ub0 + u, nsegs - 1);
-            keep[u] = ub0 + u < nsegs ? 1.f : 0.f;
-            sm[u] = lds.small + (sg - sb0) * SMALL;
-            dyp[u] = stage + lds.seg_start[sg] * N + j2 * N3;
-        }
-        if (ROLE == 2) {
-            // T0 partial over this wave's rows a, then dG3 partial
-            float t0[UB][N1][V];
+        for (int h = 0; h < UB; h += UH) {
+            const float *sm[UH];
+            const float *dyp[UH];
+            float keep[UH];
 #pragma unroll
-            for (int u = 0; u < UB; ++u) {
-#pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) t0[u][j1][v] = 0.f;
-#pragma unroll
-                for (int aa = 0; aa < RQ; ++aa)
-#pragma unroll
-                    for (int j1 = 0; j1 < N1; ++j1) {
-                        const float av = sm[u][j1 * R + a0 + aa];
-#pragma unroll
-                        for (int v = 0; v < V; ++v) t0[u][j1][v] = fmaf(av, bm[u][aa][v], t0[u][j1][v]);
-                    }
+            for (int u = 0; u < UH; ++u) {
+                const int sg = min(ub0 + h + u, nsegs - 1);
+                keep[u] = ub0 + h + u < nsegs ? 1.f : 0.f;
+                sm[u] = lds.small + (sg - sb0) * SMALL;
+                dyp[u] = stage + lds.seg_start[sg] * N + j2 * N3;
             }
+            if (ROLE == 2) {
+                // T0 partial over this wave's rows a, then dG3 partial
+                float t0[UH][N1][V];
 #pragma unroll
-            for (int u = 0; u < UB; ++u)
+                for (int u = 0; u < UH; ++u) {
 #pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) {
-                    const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+                    for (int j1 = 0; j1 < N1; ++j1)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        const float tk = t0[u][j1][v] * keep[u];
-                        acc[v * N3 + 0] = fmaf(tk, q.x, acc[v * N3 + 0]);
-                        acc[v * N3 + 1] = fmaf(tk, q.y, acc[v * N3 + 1]);
-                        acc[v * N3 + 2] = fmaf(tk, q.z, acc[v * N3 + 2]);
-                        acc[v * N3 + 3] = fmaf(tk, q.w, acc[v * N3 + 3]);
-                    }
-                }
-        } else {
-            // dT0'[j1][c0+v] = sum_j3 dY[(j1,j2)][j3] C[b0+v][j3]
-            float dt[UB][N1][V];
-#pragma unroll
-            for (int u = 0; u < UB; ++u)
-#pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) {
-                    const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        const float4 cv = *reinterpret_cast<const float4 *>(&sm[u][C::sA + (b0 + v) * N3]);
-                        dt[u][j1][v] = keep[u] * fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
-                    }
-                }
-            if (ROLE == 1) {
-#pragma unroll
-                for (int u = 0; u < UB; ++u)
+                        for (int v = 0; v < V; ++v) t0[u][j1][v] = 0.f;
 #pragma unroll
                     for (int aa = 0; aa < RQ; ++aa)
 #pragma unroll
                         for (int j1 = 0; j1 < N1; ++j1) {
                             const float av = sm[u][j1 * R + a0 + aa];
 #pragma unroll
-                            for (int v = 0; v < V; ++v) acc[aa * V + v] = fmaf(av, dt[u][j1][v], acc[aa * V + v]);
+                            for (int v = 0; v < V; ++v) t0[u][j1][v] = fmaf(av, bm[h + u][aa][v], t0[u][j1][v]);
                         }
+                }
+#pragma unroll
+                for (int u = 0; u < UH; ++u)
+#pragma unroll
+                    for (int j1 = 0; j1 < N1; ++j1) {
+                        const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+#pragma unroll
+                        for (int v = 0; v < V; ++v) {
+                            const float tk = t0[u][j1][v] * keep[u];
+                            acc[v * N3 + 0] = fmaf(tk, q.x, acc[v * N3 + 0]);
+                            acc[v * N3 + 1] = fmaf(tk, q.y, acc[v * N3 + 1]);
+                            acc[v * N3 + 2] = fmaf(tk, q.z, acc[v * N3 + 2]);
+                            acc[v * N3 + 3] = fmaf(tk, q.w, acc[v * N3 + 3]);
+                        }
+                    }
             } else {
+                // dT0'[j1][c0+v] = sum_j3 dY[(j1,j2)][j3] C[b0+v][j3]
+                float dt[UH][N1][V];
 #pragma unroll
-                for (int u = 0; u < UB; ++u)
+                for (int u = 0; u < UH; ++u)
 #pragma unroll
-                    for (int aa = 0; aa < RQ; ++aa)
+                    for (int j1 = 0; j1 < N1; ++j1) {
+                        const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
 #pragma unroll
-                        for (int j1 = 0; j1 < N1; ++j1)
+                        for (int v = 0; v < V; ++v) {
+                            const float4 cv = *reinterpret_cast<const float4 *>(&sm[u][C::sA + (b0 + v) * N3]);
+                            dt[u][j1][v] = keep[u] * fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
+                        }
+                    }
+                if (ROLE == 1) {
 #pragma unroll
-                            for (int v = 0; v < V; ++v)
-                                acc[j1 * RQ + aa] = fmaf(dt[u][j1][v], bm[u][aa][v], acc[j1 * RQ + aa]);
+                    for (int u = 0; u < UH; ++u)
+#pragma unroll
+                        for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                            for (int j1 = 0; j1 < N1; ++j1) {
+                                const float av = sm[u][j1 * R + a0 + aa];
+#pragma unroll
+                                for (int v = 0; v < V; ++v) acc[aa * V + v] = fmaf(av, dt[u][j1][v], acc[aa * V + v]);
+                            }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < UH; ++u)
+#pragma unroll
+                        for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                            for (int j1 = 0; j1 < N1; ++j1)
+#pragma unroll
+                                for (int v = 0; v < V; ++v)
+                                    acc[j1 * RQ + aa] = fmaf(dt[u][j1][v], bm[h + u][aa][v], acc[j1 * RQ + aa]);
+                }
             }
         }
     };
 
-    // one round: entries lds.klist / lds.rows [0, n)
-    auto process = [&](int n) __attribute__((always_inline)) {
-        TT_STAMP(1); TT_NOTE(8, n);
-        int nsegs_small = 0;
-        if (n <= FB_PIECE) {
-            // One piece: every wave sorts it by itself (same result everywhere, no barrier) and finds
-            // the runs in rank space.  An entry is the head of its run iff no equal row precedes it
-            // in the list; its run starts at sorted position lt, and the run's index is the number
-            // of heads with a smaller row.
-            const bool in = lane < n;
-            const uint32_t my = in ? lds.rows[lane] : FB_NONE;
-            int lt = 0, eq = 0;
-            for (int j = 0; j < n; j += 16) {
-                uint4 r[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(&lds.rows[j + 4 * q]);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int jj = j + 4 * q;
-                    lt += (r[q].x < my) + (r[q].y < my) + (r[q].z < my) + (r[q].w < my);
-                    eq += (r[q].x == my && jj + 0 < lane) + (r[q].y == my && jj + 1 < lane) + (r[q].z == my && jj + 2 < lane) +
-                          (r[q].w == my && jj + 3 < lane);
-                }
-            }
-            if (in) lds.sk[lt + eq] = lds.klist[lane];
-            const bool head = in && eq == 0;
-            uint64_t hm = __ballot(head);
-            nsegs_small = __popcll(hm);
-            int sg = 0;
-            while (hm) {                                                   // uniform: one step per distinct row
-                const int j = __builtin_ctzll(hm);
-                hm &= hm - 1;
-                sg += (uint32_t)__builtin_amdgcn_readlane((int)my, j) < my;
-            }
-            if (head) {
-                int i1, i2, i3;
-                decode_f64(p, my, i1, i2, i3);
-                lds.seg_start[sg] = lt;
-                lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
-            }
-            if (lane == 0) lds.seg_start[nsegs_small] = n;
-        } else {
-            for (int p0 = w * FB_PIECE; p0 < n; p0 += NWAVE * FB_PIECE) fb_sort_piece(lds, p0, min(FB_PIECE, n - p0));
-            __syncthreads();
+    // Runs of equal rows among the entries [e0, e0 + len) of the list, len <= 64, lane e holding
+    // entry e0 + e: one ballot per distinct row gives the lanes of its run.  The runs are laid out
+    // one after the other in the order of their first entries, each in list order: mypos is the
+    // lane's position in that layout, mysg the number of the run if the lane is its first entry
+    // (else -1).  Returns the number of runs.
+    auto analyse = [&](const int (&wc)[NWAVE], int e0, int len, int &mysg, int &mypos, int &i1, int &i2, int &i3)
+                       __attribute__((always_inline)) {
+        const uint32_t my = lane < len ? lds.rows[fb_slot(wc, e0 + lane)] : FB_NONE;
+        decode_f64(p, my, i1, i2, i3);
+        uint64_t rem = __ballot(lane < len);
+        int pos = 0, cnt = 0;
+        mysg = -1;
+        mypos = 0;
+        while (rem) {                                                      // uniform: one step per distinct row
+            const int j = __builtin_ctzll(rem);
+            const uint32_t rj = (uint32_t)__builtin_amdgcn_readlane((int)my, j);
+            const uint64_t m = __ballot(my == rj);                         // the run of this row, in list order
+            rem &= ~m;
+            if (my == rj) mypos = pos + __popcll(m & lanemask_lt());
+            if (lane == j) mysg = cnt;
+            pos += __popcll(m);
+            ++cnt;
         }
+        return cnt;
+    };
+
+    // One round: the n selected entries, entry e at fb_slot(wc, e) of lds.klist / lds.rows.
+    auto process = [&](int n, const int (&wc)[NWAVE]) __attribute__((always_inline)) {
+        TT_STAMP(1); TT_NOTE(8, n);
         for (int i0 = 0; i0 < n; i0 += W) {
             const int nw = min(W, n - i0);
-            int nsegs = nsegs_small;
-            if (n > FB_PIECE) {
-                // Runs of equal rows inside the window.  Every wave finds them with ballots and writes the
-                // same values (start, digits of the row), so no barrier is needed before it reads them.
-                for (int b = 0; b * WAVE < nw; ++b) {
-                    const int e = b * WAVE + lane;
-                    const bool in = e < nw;
-                    const uint32_t r = in ? lds.sr[i0 + e] : 0u;
-                    bool head = in;
-                    if (in && e > 0) head = r != lds.sr[i0 + e - 1];
-                    const uint64_t hm = __ballot(head);
-                    if (head) {
-                        const int sg = nsegs + __popcll(hm & lanemask_lt());
-                        int i1, i2, i3;
-                        decode_f64(p, r, i1, i2, i3);
-                        lds.seg_start[sg] = e;
-                        lds.seg_i1[sg] = i1; lds.seg_i2[sg] = i2; lds.seg_i3[sg] = i3;
-                    }
-                    nsegs += __popcll(hm);
+            // A short window's gradients are loaded while it is analysed (one float4 per thread).
+            constexpr bool EARLY = FB_PIECE * NQ <= WG;
+            const bool early_done = EARLY && nw <= FB_PIECE;
+            Item early;
+            if (early_done) {
+                const int e = min(t / NQ, nw - 1), f = t % NQ;
+                grad_issue((int)lds.klist[fb_slot(wc, i0 + e)], f, early);
+            }
+            int nsegs, mysg, mypos, i1, i2, i3;
+            if (W <= FB_PIECE || nw <= FB_PIECE) {
+                // one piece: every wave analyses it by itself (same result everywhere, no barrier)
+                nsegs = analyse(wc, i0, nw, mysg, mypos, i1, i2, i3);
+                TT_STAMP(15);
+                if (lane < nw) lds.epos[lane] = mypos;
+                if (mysg >= 0) {                                           // first entry of its run
+                    lds.seg_start[mysg] = mypos;
+                    lds.seg_i1[mysg] = i1; lds.seg_i2[mysg] = i2; lds.seg_i3[mysg] = i3;
                 }
                 if (lane == 0) lds.seg_start[nsegs] = nw;
+            } else {
+                // several pieces of 64 entries: wave w analyses piece w; equal rows of different pieces
+                // stay separate runs (the gradient is linear in dY)
+                const int len = min(FB_PIECE, nw - w * FB_PIECE);          // <= 0: no piece for this wave
+                const int cnt = analyse(wc, i0 + w * FB_PIECE, len, mysg, mypos, i1, i2, i3);
+                if (lane == 0) lds.pcnt[w] = cnt;
+                __syncthreads();
+                int base = 0;
+                nsegs = 0;
+#pragma unroll
+                for (int j = 0; j < NWAVE; ++j) {
+                    const int c = lds.pcnt[j];
+                    if (j < w) base += c;
+                    nsegs += c;
+                }
+                if (lane < len) lds.epos[w * FB_PIECE + lane] = w * FB_PIECE + mypos;
+                if (mysg >= 0) {
+                    lds.seg_start[base + mysg] = w * FB_PIECE + mypos;
+                    lds.seg_i1[base + mysg] = i1; lds.seg_i2[base + mysg] = i2; lds.seg_i3[base + mysg] = i3;
+                }
+                if (t == 0) lds.seg_start[nsegs] = nw;
+                __syncthreads();
             }
             TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
@@ -477,7 +507,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             float bm[UB][RQ][V];
             if (ROLE != 1) bm_load(0, nsegs, bm);
             TT_STAMP(3);
-            stage_items(i0, nw * NQ, 0, min(SB, nsegs));
+            stage_items(i0, early_done ? 0 : nw * NQ, 0, min(SB, nsegs), wc);
+            if (early_done) {
+                const float4 g = item_finish(early);
+                if (t < nw * NQ) *reinterpret_cast<float4 *>(&stage[4 * (NQ * lds.epos[t / NQ] + t % NQ)]) = g;
+            }
             __syncthreads();
             TT_STAMP(4);
             if (nsegs < nw) {                                              // uniform: some row occurs more than once
@@ -502,14 +536,15 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 __syncthreads();
             }
             TT_STAMP(5);
-            consume(0, 0, nsegs, bm);
-            for (int ub0 = UB; ub0 < nsegs; ub0 += UB) {
+            for (int ub0 = 0; ub0 < nsegs; ub0 += UB) {
                 const int sb0 = (ub0 / SB) * SB;
-                if (ROLE != 1) bm_load(ub0, nsegs, bm);
-                if (ub0 == sb0) {                                        // next batch of small operands
-                    __syncthreads();
-                    stage_items(i0, 0, sb0, min(SB, nsegs - sb0));
-                    __syncthreads();
+                if (ub0 > 0) {
+                    if (ROLE != 1) bm_load(ub0, nsegs, bm);
+                    if (ub0 == sb0) {                                    // next batch of small operands
+                        __syncthreads();
+                        stage_items(i0, 0, sb0, min(SB, nsegs - sb0), wc);
+                        __syncthreads();
+                    }
                 }
                 consume(ub0, sb0, nsegs, bm);
             }
@@ -518,45 +553,49 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
-    if (gvals) {
-        // The lookups were grouped by a pre-pass (tt_group.h): this slice's list is
-        // gvals[goff[bin] .. gend[bin]), payload = item number * L + k, in the order of k.
-        const int bin = (ROLE == 0 ? 0 : (ROLE == 1 ? p.m1 : p.m1 + p.m2)) + s;
-        const int b0 = goff[bin], b1 = gend[bin];
-        const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
-        for (int lo = b0; lo < b1; lo += FB_CAP) {
-            const int n = min(FB_CAP, b1 - lo);
-            __syncthreads();                                               // the previous round is done with the lists
+    // The list of a round comes from the workgroup's own scan of FB_SCAN positions, or, if the
+    // lookups were grouped by a pre-pass (tt_group.h), from this slice's list
+    // gvals[goff[bin] .. gend[bin]) (payload = item number * L + k, in the order of k), FB_CAP entries
+    // at a time.  A scan round that selects too many entries (an adversarial index stream) is redone
+    // in pieces of FB_CAP positions, which always fit.  The caller has already loaded the rows of
+    // the first scan round into rowv.  One loop for both, so that the body exists once.
+    const int bin = (ROLE == 0 ? 0 : (ROLE == 1 ? p.m1 : p.m1 + p.m2)) + s;
+    const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
+    int lo = gvals ? goff[bin] : 0;
+    const int end = gvals ? gend[bin] : L;
+    int span = gvals ? FB_CAP : FB_SCAN, round = 0;
+    while (lo < end) {
+        const int hi = min(end, lo + span);
+        int wc[NWAVE] = {0, 0, 0, 0};
+        int n;
+        if (gvals) {
+            n = hi - lo;
             for (int i = t; i < n; i += WG) {
                 const uint32_t k = gvals[lo + i] - sub;
                 lds.klist[i] = k;
                 lds.rows[i] = (uint32_t)indices[k];
             }
-            if (t < 16) lds.rows[n + t] = FB_NONE;                         // padding read by the sort
             __syncthreads();
-            any = true;
-            process(n);
-        }
-    } else {
-        // Scan FB_SCAN positions per round; if a round selects more than FB_CAP entries (an adversarial
-        // index stream), redo it in pieces of FB_CAP positions, which always fit.  The caller has
-        // already loaded the rows of the first round into rowv.
-        int span = FB_SCAN;
-        for (int lo = 0; lo < L;) {
-            const int hi = min(L, lo + span);
+            wc[0] = n;                                                     // one contiguous list
+        } else {
             if (lo > 0 || span != FB_SCAN) fb_load_rows(indices, slot, lo, hi, rowv);
-            const int n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi);
+#if defined(TT_PROFILE) && TT_PROFILE == 2
+            n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, wc, ts);
+#else
+            n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, wc);
+#endif
             if (n > FB_CAP) { span = FB_CAP; continue; }
-            if (n) { any = true; process(n); }
-            lo = hi;
-            if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
         }
+        if (n) { any = true; process(n, wc); }
+        lo = hi;
+        if (!gvals && span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
     auto flush = [&]() __attribute__((always_inline)) {
         TT_STAMP(7);
         if (g_tt_prof && threadIdx.x == 0)
-            for (int i = 0; i < 10; ++i) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
+            for (int i = 0; i < 16; ++i)
+                if (i < 10 || i > 11) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
     };
     if (!any) { flush(); return; }
 #else
@@ -569,7 +608,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
             for (int aa = 0; aa < RQ; ++aa)
 #pragma unroll
-                for (int v = 0; v < V; ++v) dst[aa * C::COLS + v] += acc[aa * V + v];
+                for (int v = 0; v < V; ++v) add_to(&dst[aa * C::COLS + v], acc[aa * V + v]);
         }
     } else if (ROLE == 0) {
         float red[NACC1];
@@ -583,7 +622,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int i = 0; i < ReduceKeep<NACC1, WAVE>::value; ++i) {
                 const int idx = base + i;                                  // = j1 * RQ + aa
                 const int j1 = idx / RQ, aa = idx % RQ;
-                dst[j1 * R + a0 + aa] += red[i];
+                add_to(&dst[j1 * R + a0 + aa], red[i]);
             }
         }
     } else {
@@ -605,7 +644,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int ww = 0; ww < NWAVE; ++ww)
 #pragma unroll
                 for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
-            dst[e] += sum;
+            add_to(&dst[e], sum);
         }
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
