@@ -62,7 +62,7 @@ struct FbCfg {
     static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
     static constexpr int BMR = C::RQ * C::V;                // registers per row for the wave's part of G2[i2]
     // register budget: three workgroups per CU (one wave each per SIMD) for the small slices, fewer for the large
-    static constexpr int WAVES_PER_SIMD = (BMR <= 8 || (BMR <= 32 && C::N <= 16)) ? 3 : (BMR <= 32 ? 2 : 1);
+    static constexpr int WAVES_PER_SIMD = BMR <= 32 ? 3 : 1;
     // rows of G2 in flight per wave: up to 4, within 32 registers (8 rows / 64 registers was measured: slower,
     // the extra loads and the idle row slots of short lists cost more than the saved round trip)
     static constexpr int BUDGET = 32;
@@ -246,7 +246,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     struct Item {
         float4 val;
         float scale;
-        int dst, chk_k, chk_f;
+        int dst, chk_k;                                                   // dst = 4 (NQ position + f)
         int o0, o1;                                                       // offsets are < 2^31: the low words suffice
     };
     // float4 f of alpha_k * grad_out[bag(k)]: the bag is guessed (exact for fixed-length bags) and
@@ -254,7 +254,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     auto grad_issue = [&](int k, int f, Item &r) __attribute__((always_inline)) {
         r.scale = alpha ? alpha[k] : 1.f;
         r.chk_k = -1;
-        r.chk_f = f;
         r.o0 = 0;
         r.o1 = 0;
         int row = k;
@@ -273,7 +272,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         float4 g = r.val;
         if (r.chk_k >= 0 && !(r.o0 <= r.chk_k && r.chk_k < r.o1)) {       // ragged bags
             const int bag = bag_of(offsets, n_bags, r.chk_k);
-            g = *reinterpret_cast<const float4 *>(grad_out + (size_t)bag * N + 4 * r.chk_f);
+            g = *reinterpret_cast<const float4 *>(grad_out + (size_t)bag * N + 4 * ((r.dst / 4) % NQ));
         }
         g.x *= r.scale; g.y *= r.scale; g.z *= r.scale; g.w *= r.scale;
         return g;
@@ -282,7 +281,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     // gradients of entries [0, n_g / NQ) of the window that starts at list entry i0 (entry e goes
     // to its staged position lds.epos[e]), then the G1 slices of rows [sb0, sb0 + nb) (unless the
     // G1 owner), then their G3 slices (unless the G3 owner).
-    constexpr int IPT = N <= 16 ? 4 : 2;
+    constexpr int IPT = N <= 16 ? 3 : 2;
     auto stage_items = [&](int i0, int n_g, int sb0, int nb, const int (&wc)[NWAVE]) __attribute__((always_inline)) {
         const int n_a = ROLE != 0 ? nb * PA : 0;
         const int n_c = ROLE != 2 ? nb * PC : 0;
@@ -309,12 +308,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                     }
                     r[q].scale = 1.f;
                     r[q].chk_k = -1;
-                    r[q].chk_f = 0;
                     r[q].o0 = 0;
                     r[q].o1 = 0;
                     r[q].val = *reinterpret_cast<const float4 *>(src);
                 }
-                if ((q & 1) && it0 + (q + 1) * WG >= total) break;        // uniform: the pass ends here
+                if (it0 + (q + 1) * WG >= total) break;                   // uniform: the pass ends here
             }
 #pragma unroll
             for (int q = 0; q < IPT; ++q) {
@@ -466,6 +464,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             if (early_done) {
                 const int e = min(t / NQ, nw - 1), f = t % NQ;
                 grad_issue((int)lds.klist[fb_slot(wc, i0 + e)], f, early);
+                early.dst = 4 * f;
             }
             int nsegs, mysg, mypos, i1, i2, i3;
             if (W <= FB_PIECE || nw <= FB_PIECE) {
@@ -504,8 +503,15 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
-            float bm[UB][RQ][V];
-            if (ROLE != 1) bm_load(0, nsegs, bm);
+            // two register buffers for the small slices: the next batch of rows is in flight while one is used
+            constexpr bool DB = false;                                   // measured with two buffers for R <= 32: no gain
+            float bm[UB][RQ][V], bm2[DB ? UB : 1][RQ][V];
+            if (ROLE != 1) {
+                bm_load(0, nsegs, bm);
+                if constexpr (DB) {
+                    if (nsegs > UB) bm_load(UB, nsegs, bm2);
+                }
+            }
             TT_STAMP(3);
             stage_items(i0, early_done ? 0 : nw * NQ, 0, min(SB, nsegs), wc);
             if (early_done) {
@@ -536,10 +542,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 __syncthreads();
             }
             TT_STAMP(5);
-            for (int ub0 = 0; ub0 < nsegs; ub0 += UB) {
+            static_assert(SB % (2 * UB) == 0, "small operands are restaged only in front of the first buffer");
+            for (int ub0 = 0; ub0 < nsegs; ub0 += (DB ? 2 : 1) * UB) {
                 const int sb0 = (ub0 / SB) * SB;
                 if (ub0 > 0) {
-                    if (ROLE != 1) bm_load(ub0, nsegs, bm);
+                    if (!DB && ROLE != 1) bm_load(ub0, nsegs, bm);
                     if (ub0 == sb0) {                                    // next batch of small operands
                         __syncthreads();
                         stage_items(i0, 0, sb0, min(SB, nsegs - sb0), wc);
@@ -547,6 +554,13 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                     }
                 }
                 consume(ub0, sb0, nsegs, bm);
+                if constexpr (DB) {
+                    if (ROLE != 1 && ub0 + 2 * UB < nsegs) bm_load(ub0 + 2 * UB, nsegs, bm);
+                    if (ub0 + UB < nsegs) {
+                        consume(ub0 + UB, sb0, nsegs, bm2);
+                        if (ROLE != 1 && ub0 + 3 * UB < nsegs) bm_load(ub0 + 3 * UB, nsegs, bm2);
+                    }
+                }
             }
             __syncthreads();                                             // before the LDS lists are reused
             TT_STAMP(6);
