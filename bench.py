@@ -4,9 +4,11 @@ A "step" is one pass of the whole path over one batch of synthetic input:
 forward, backward and the SGD update of the cores, at the Kaggle-shaped R = 32
 configuration (10,131,227 rows as 200x220x250, dimension 16 as 2x2x4, 2048 bags
 of one index, Zipf(1.05) indices).  All inputs are resident in HBM before the
-timed region.  Prints ONE JSON line.
+timed region.  By default the backward pass and the SGD update are one call
+(tt_emb_bwd_sgd, two sets of cores used in turn); --step separate times
+tt_emb_bwd + tt_emb_sgd_update instead.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32] [--step fused|separate]
 """
 
 from __future__ import annotations
@@ -38,6 +40,7 @@ def algorithmic_bytes(t, L, n_bags, touched_floats):
     backward: the same reads plus the upstream gradient row, and one write of every
               touched core slice.
     sgd     : read x, read g, write x for every core element.
+    bwd_sgd : the fused call; no gradient buffers exist.
     """
     S = 4 * (t.n[0] * t.r[1] + t.r[1] * t.n[1] * t.r[2] + t.r[2] * t.n[2])
     N = t.dim
@@ -45,7 +48,9 @@ def algorithmic_bytes(t, L, n_bags, touched_floats):
     bwd = L * (S + 8) + n_bags * 4 * N + 4 * touched_floats
     total = sum(t.core_size(k) for k in range(3))
     sgd = 12 * total
-    return {"fwd": fwd, "bwd": bwd, "sgd": sgd}
+    # fused backward + SGD: the backward's reads, plus one read and one write of every core element
+    bwd_sgd = L * (S + 8) + n_bags * 4 * N + 8 * total
+    return {"fwd": fwd, "bwd": bwd, "sgd": sgd, "bwd_sgd": bwd_sgd}
 
 
 def main():
@@ -54,6 +59,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="kaggle_r32")
+    ap.add_argument("--step", choices=["fused", "separate"], default="fused",
+                    help="fused: forward, then backward and SGD in one call; separate: three calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
@@ -98,11 +105,19 @@ def main():
     out = torch.empty((n_bags, t.dim), dtype=torch.float32, device=dev)
     lr = 1e-3 * wl.lr            # small, so that thousands of steps keep the cores finite
 
+    cores2 = [torch.empty_like(c) for c in cores]      # the fused step writes the other set of cores
+    assert POOL % 2 == 0                                # so that every graph replay starts on the same set
+
     def step(i):
         j = i % POOL
-        B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out)
-        B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads)
-        B.tt_emb_sgd_update(shape, cores, grads, lr, zero_grad=True)
+        if args.step == "fused":
+            cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
+            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr)
+        else:
+            B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out)
+            B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads)
+            B.tt_emb_sgd_update(shape, cores, grads, lr, zero_grad=True)
 
     def timed(fn, count):
         """ms per call of fn(i), count calls enqueued back to back between two events on the current stream."""
@@ -144,10 +159,16 @@ def main():
     # per-kernel durations: each stage alone, launched back to back on the same stream
     reps = max(POOL * 16, min(steps, 4096))
     ms_fwd = timed_any(lambda i: B.tt_emb_fwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out), reps)
-    ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
-    for g in grads:
-        g.zero_()
-    ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
+    if args.step == "fused":
+        ms_bs = timed_any(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
+                                                     go[i % POOL], lr), reps)
+        stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
+    else:
+        ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
+        for g in grads:
+            g.zero_()
+        ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
+        stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
 
     # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
     b0 = batches_h[0].indices
@@ -156,7 +177,6 @@ def main():
                + np.unique((b0 // m3) % m2).size * t.r[1] * t.n[1] * t.r[2]
                + np.unique(b0 % m3).size * t.r[2] * t.n[2])
     ab = algorithmic_bytes(t, L, n_bags, touched)
-    stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
     dominant = max(stage_ms, key=stage_ms.get)
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
@@ -191,7 +211,7 @@ def main():
         "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
                                "Zipf(%.2f), fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
                                                             n_bags, L // n_bags, wl.zipf_alpha),
-                   "lookups_per_step": L, "launch": args.launch, "wall_s_timed_region": round(wall, 3)},
+                   "lookups_per_step": L, "launch": args.launch, "step": args.step, "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

@@ -131,6 +131,29 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Backward pass and SGD step in one call (Section 3.1, Eq. 4; Alg. 2; Section 5):
+ * cores_out = cores - lr * (gradient of <output, grad_output> for this batch), and,
+ * with a cache, cache->rows -= lr * (gradient of the cached rows), in place
+ * (Section 4.2).  Same result as tt_emb_bwd into zeroed gradients followed by
+ * tt_emb_sgd_update, without the gradient buffers and the second pass.
+ * cores_out: host array of 3 device pointers shaped like the cores; every element
+ *            is written, also in slices that no position touches.  Must not alias
+ *            cores (other workgroups still read the old slices); a training loop
+ *            swaps the two sets after each step.
+ * workspace: tt_emb_bwd_sgd_workspace_bytes(...) bytes (0 needed without a cache,
+ *            below 16,384 positions, for the shapes with a specialised kernel).
+ * L == 0 copies the cores.
+ */
+int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                   const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                   const float *alpha, const tt_cache_t *cache,
+                   const float *grad_output, float lr,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* Always-sufficient workspace size of tt_emb_bwd_sgd; 0 for an invalid shape. */
+size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows);
+
+/*
  * SGD step (Section 5; cached rows per Section 4.2): x <- x - lr * g for every
  * element of the three cores and, if cache != NULL, of cache->rows with
  * grad_cache.  zero_grad != 0 also clears the gradients afterwards.

@@ -24,7 +24,8 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
-           "tt_emb_fwd", "tt_emb_bwd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
+           "tt_emb_bwd_sgd_workspace_bytes",
+           "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
 
@@ -57,14 +58,17 @@ def lib():
         l.tt_last_error.restype = C.c_char_p
         l.tt_cache_table_capacity.restype = C.c_int64
         l.tt_cache_table_capacity.argtypes = [C.c_int64]
-        for name in ("tt_emb_workspace_bytes", "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes"):
+        for name in ("tt_emb_workspace_bytes", "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
+                     "tt_emb_bwd_sgd_workspace_bytes"):
             getattr(l, name).restype = C.c_size_t
         l.tt_emb_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+        l.tt_emb_bwd_sgd_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
         l.tt_cache_build_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64]
         l.tt_emb_dedup_workspace_bytes.argtypes = [C.c_int64]
         vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
         l.tt_emb_fwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_sgd.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
         l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
         l.tt_cache_lookup.argtypes = [vp, vp, i64, vp, vp]
@@ -136,6 +140,10 @@ def workspace_bytes(shape: TTShape, L: int, n_bags: int, cache_rows: int = 0) ->
     return int(lib().tt_emb_workspace_bytes(C.byref(shape), L, n_bags, int(cache_rows)))
 
 
+def bwd_sgd_workspace_bytes(shape: TTShape, L: int, n_bags: int, cache_rows: int = 0) -> int:
+    return int(lib().tt_emb_bwd_sgd_workspace_bytes(C.byref(shape), L, n_bags, int(cache_rows)))
+
+
 def _ws(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
@@ -178,6 +186,25 @@ def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
     _check(lib().tt_emb_bwd(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
                             _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output), _ptr_array(grad_cores),
                             _ptr(grad_cache), _ptr(workspace), wsb, _stream()))
+
+
+def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],
+                   indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
+                   lr: float, alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None,
+                   workspace: Optional[torch.Tensor] = None) -> None:
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(grad_output, torch.float32)
+    for k in range(3):
+        assert cores_out[k].numel() == cores[k].numel()
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_bwd_sgd(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices), indices.numel(),
+                                _ptr(offsets), n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output),
+                                C.c_float(lr), _ptr(workspace), wsb, _stream()))
 
 
 def tt_emb_sgd_update(shape: TTShape, cores: Sequence[torch.Tensor], grad_cores: Sequence[torch.Tensor], lr: float,

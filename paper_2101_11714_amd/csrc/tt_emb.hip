@@ -205,30 +205,47 @@ int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
     return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
 }
 
-int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
-               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
-               const float *alpha, const tt_cache_t *cache,
-               const float *grad_output,
-               float *const grad_cores[3], float *grad_cache,
-               void *workspace, size_t workspace_bytes, void *stream)
+// Backward pass behind tt_emb_bwd (cores_out == nullptr: gradients are added to grad_cores /
+// grad_cache) and tt_emb_bwd_sgd (cores_out != nullptr: the cores after the SGD step are written
+// to cores_out, the cached rows are updated in place; grad_cores / grad_cache are unused).
+static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
+                      const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                      const float *alpha, const tt_cache_t *cache, const float *grad_output,
+                      float *const grad_cores[3], float *grad_cache, float lr, float *const cores_out[3],
+                      void *workspace, size_t workspace_bytes, void *stream)
 {
+    const bool fused = cores_out != nullptr;
     Params p;
     int rc = check_shape(shape, &p);
     if (rc) return rc;
     if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
     if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
-    if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2])
+    if (fused) {
+        if (!cores_out[0] || !cores_out[1] || !cores_out[2]) return fail(TT_ERR_NULL, "cores_out is NULL");
+        for (int k = 0; k < 3; ++k)
+            if (cores_out[k] == cores[k]) return fail(TT_ERR_BAD_ARG, "cores_out must not alias cores");
+    } else if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2]) {
         return fail(TT_ERR_NULL, "grad_cores is NULL");
+    }
     if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
     CacheDev cd;
-    if ((rc = check_cache(cache, &cd, false))) return rc;
-    if (cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
+    if ((rc = check_cache(cache, &cd, fused))) return rc;
+    if (!fused && cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
     const bool fast = g_fast_path && fast_bwd_supported(p);
     const bool grouped = fast && (g_fast_path == 2 || L >= GROUP_MIN_L);
-    const size_t need = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
-    if ((cd.K || grouped) && (!workspace || workspace_bytes < need))
+    const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
+    const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
+    // the fused step keeps the gradient of the cached rows, and without a specialised kernel the
+    // gradients of the cores, in the workspace
+    const size_t gc_bytes = fused && cd.K ? align256((size_t)cd.K * p.N * 4) : 0;
+    size_t g_bytes[3] = {0, 0, 0};
+    if (fused && !fast)
+        for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
+    const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2];
+    const bool wants_ws = cd.K || grouped || (fused && !fast);
+    if (wants_ws && (!workspace || workspace_bytes < need))
         return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-    if (L == 0) return TT_OK;
+    if (L == 0 && !fused) return TT_OK;
     hipStream_t st = (hipStream_t)stream;
 
     // LDS needs of the generic kernels, checked before anything is enqueued
@@ -240,16 +257,40 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
     if (!fast && (rc = allow_lds(bwd_generic_kernel, lds_core))) return rc;
     if (cd.K && !grouped && (rc = allow_lds(bwd_cache_kernel, lds_cache))) return rc;
 
-    if (offsets && n_bags > 0 && L % n_bags == 0) {                       // a guess for the bag of a position
+    float *gtmp[3] = {nullptr, nullptr, nullptr};
+    if (fused) {
+        char *q = (char *)workspace + need_bwd;
+        if (cd.K) {
+            grad_cache = (float *)q;
+            q += gc_bytes;
+            const int64_t n = (int64_t)cd.K * p.N;
+            hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, grad_cache, n, 0.f);
+        }
+        if (!fast) {
+            for (int k = 0; k < 3; ++k) {
+                gtmp[k] = (float *)q;
+                q += g_bytes[k];
+                hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(core_floats[k], WG) < 1024 ? cdiv(core_floats[k], WG) : 1024),
+                                   dim3(WG), 0, st, gtmp[k], core_floats[k], 0.f);
+            }
+            grad_cores = gtmp;
+        }
+    }
+    float *o1 = fused && fast ? cores_out[0] : nullptr, *o2 = fused && fast ? cores_out[1] : nullptr,
+          *o3 = fused && fast ? cores_out[2] : nullptr;
+    float *d1 = grad_cores ? grad_cores[0] : nullptr, *d2 = grad_cores ? grad_cores[1] : nullptr,
+          *d3 = grad_cores ? grad_cores[2] : nullptr;
+
+    if (offsets && n_bags > 0 && L > 0 && L % n_bags == 0) {              // a guess for the bag of a position
         p.bagP = (uint32_t)(L / n_bags);
         p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
     }
     int32_t *slot = nullptr;
-    if (cd.K) {
+    if (cd.K && L > 0) {
         slot = (int32_t *)workspace;
         hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
     }
-    if (grouped) {
+    if (grouped && L > 0) {
         // group the positions by the slices / cache slots they touch, then run the owners on their lists
         const int nb3 = p.m1 + p.m2 + p.m3, nbins = nb3 + cd.K;
         GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
@@ -271,22 +312,66 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                                grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                 grad_cores[0], grad_cores[1], grad_cores[2], vs, g.off, g.end, st);
+                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, st);
     } else {
-        if (cd.K)
+        if (cd.K && L > 0)
             hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
                                offsets, (int)n_bags, alpha, grad_output, grad_cache);
         if (fast) {
             fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                     grad_cores[0], grad_cores[1], grad_cores[2], nullptr, nullptr, nullptr, st);
-        } else {
+                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, st);
+        } else if (L > 0) {
             hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
                                cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
-                               grad_output, grad_cores[0], grad_cores[1], grad_cores[2]);
+                               grad_output, d1, d2, d3);
+        }
+    }
+    if (fused) {
+        if (!fast)
+            for (int k = 0; k < 3; ++k)
+                hipLaunchKernelGGL(sgd_out_kernel, dim3(cdiv(core_floats[k], WG) < 2048 ? cdiv(core_floats[k], WG) : 2048),
+                                   dim3(WG), 0, st, cores[k], gtmp[k], cores_out[k], core_floats[k], lr);
+        if (cd.K) {
+            const int64_t n = (int64_t)cd.K * p.N;
+            hipLaunchKernelGGL(sgd_out_kernel, dim3(cdiv(n, WG) < 2048 ? cdiv(n, WG) : 2048), dim3(WG), 0, st,
+                               cache->rows, grad_cache, cache->rows, n, lr);
         }
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "backward launch");
+}
+
+int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               const float *grad_output,
+               float *const grad_cores[3], float *grad_cache,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, grad_cores, grad_cache,
+                      0.f, nullptr, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                   const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                   const float *alpha, const tt_cache_t *cache,
+                   const float *grad_output, float lr,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
+    return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
+                      lr, cores_out, workspace, workspace_bytes, stream);
+}
+
+size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows)
+{
+    (void)n_bags;
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
+    if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
+    size_t n = fwd_bwd_ws_bytes(p, L, cache_rows) + align256((size_t)cache_rows * p.N * 4);
+    n += align256((size_t)p.m1 * p.sA * 4) + align256((size_t)p.m2 * p.sB * 4) + align256((size_t)p.m3 * p.sC * 4);
+    return n;
 }
 
 int tt_emb_sgd_update(const tt_shape_t *shape, float *const cores[3], float *const grad_cores[3],

@@ -211,9 +211,14 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         const float *__restrict__ grad_out, float *__restrict__ dG1,
                                         float *__restrict__ dG2, float *__restrict__ dG3,
                                         const uint32_t *__restrict__ gvals, const int *__restrict__ goff,
-                                        const int *__restrict__ gend, uint32_t (&rowv)[FB_ITER])
+                                        const int *__restrict__ gend, float lr, float *__restrict__ o1,
+                                        float *__restrict__ o2, float *__restrict__ o3, uint32_t (&rowv)[FB_ITER])
 {
     using F = FbCfg<C>;
+    // Two ways to finish: add the slice gradient to dG1/dG2/dG3 (o1 == nullptr), or write the
+    // slice after its SGD step, x - lr * gradient, to o1/o2/o3 (every slice is written then, also
+    // one that no lookup touches).
+    const bool fused = o1 != nullptr;
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
     constexpr int W = F::W, NQ = N / 4, SB = F::SB, UB = F::UB, SMALL = F::SMALL;
     // float4 of small operands per row: G1 slice (needed by the G2 and G3 owners) and G3 slice (G1, G2 owners)
@@ -503,15 +508,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
-            // two register buffers for the small slices: the next batch of rows is in flight while one is used
-            constexpr bool DB = false;                                   // measured with two buffers for R <= 32: no gain
-            float bm[UB][RQ][V], bm2[DB ? UB : 1][RQ][V];
-            if (ROLE != 1) {
-                bm_load(0, nsegs, bm);
-                if constexpr (DB) {
-                    if (nsegs > UB) bm_load(UB, nsegs, bm2);
-                }
-            }
+            float bm[UB][RQ][V];
+            if (ROLE != 1) bm_load(0, nsegs, bm);
             TT_STAMP(3);
             stage_items(i0, early_done ? 0 : nw * NQ, 0, min(SB, nsegs), wc);
             if (early_done) {
@@ -542,11 +540,10 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 __syncthreads();
             }
             TT_STAMP(5);
-            static_assert(SB % (2 * UB) == 0, "small operands are restaged only in front of the first buffer");
-            for (int ub0 = 0; ub0 < nsegs; ub0 += (DB ? 2 : 1) * UB) {
+            for (int ub0 = 0; ub0 < nsegs; ub0 += UB) {
                 const int sb0 = (ub0 / SB) * SB;
                 if (ub0 > 0) {
-                    if (!DB && ROLE != 1) bm_load(ub0, nsegs, bm);
+                    if (ROLE != 1) bm_load(ub0, nsegs, bm);
                     if (ub0 == sb0) {                                    // next batch of small operands
                         __syncthreads();
                         stage_items(i0, 0, sb0, min(SB, nsegs - sb0), wc);
@@ -554,13 +551,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                     }
                 }
                 consume(ub0, sb0, nsegs, bm);
-                if constexpr (DB) {
-                    if (ROLE != 1 && ub0 + 2 * UB < nsegs) bm_load(ub0 + 2 * UB, nsegs, bm);
-                    if (ub0 + UB < nsegs) {
-                        consume(ub0 + UB, sb0, nsegs, bm2);
-                        if (ROLE != 1 && ub0 + 3 * UB < nsegs) bm_load(ub0 + 3 * UB, nsegs, bm2);
-                    }
-                }
             }
             __syncthreads();                                             // before the LDS lists are reused
             TT_STAMP(6);
@@ -611,18 +601,22 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int i = 0; i < 16; ++i)
                 if (i < 10 || i > 11) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
     };
-    if (!any) { flush(); return; }
+    if (!any && !fused) { flush(); return; }
 #else
-    if (!any) return;
+    if (!any && !fused) return;
 #endif
 
     if (ROLE == 1) {
         if (active) {
-            float *dst = dG2 + (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
+            const size_t at = (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
 #pragma unroll
             for (int aa = 0; aa < RQ; ++aa)
 #pragma unroll
-                for (int v = 0; v < V; ++v) add_to(&dst[aa * C::COLS + v], acc[aa * V + v]);
+                for (int v = 0; v < V; ++v) {
+                    const size_t i = at + aa * C::COLS + v;
+                    if (fused) o2[i] = fmaf(-lr, acc[aa * V + v], G2[i]);
+                    else add_to(&dG2[i], acc[aa * V + v]);
+                }
         }
     } else if (ROLE == 0) {
         float red[NACC1];
@@ -631,12 +625,13 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         group_reduce<NACC1, WAVE>(red, lane);
         if (lane < ReduceKeep<NACC1, WAVE>::writers) {
             const int base = reduce_base<NACC1, WAVE>(lane);
-            float *dst = dG1 + (size_t)s * C::sA;
 #pragma unroll
             for (int i = 0; i < ReduceKeep<NACC1, WAVE>::value; ++i) {
                 const int idx = base + i;                                  // = j1 * RQ + aa
                 const int j1 = idx / RQ, aa = idx % RQ;
-                add_to(&dst[j1 * R + a0 + aa], red[i]);
+                const size_t at = (size_t)s * C::sA + j1 * R + a0 + aa;
+                if (fused) o1[at] = fmaf(-lr, red[i], G1[at]);
+                else add_to(&dG1[at], red[i]);
             }
         }
     } else {
@@ -650,7 +645,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 for (int j3 = 0; j3 < N3; ++j3) part[(w * C::COLS + c0 + v) * N3 + j3] = acc[v * N3 + j3];
         }
         __syncthreads();
-        float *dst = dG3 + (size_t)s * C::sC;
         for (int e = t; e < C::sC; e += WG) {
             const int b = e / N3, j3 = e - b * N3;
             float sum = 0.f;
@@ -658,7 +652,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int ww = 0; ww < NWAVE; ++ww)
 #pragma unroll
                 for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
-            add_to(&dst[e], sum);
+            const size_t at = (size_t)s * C::sC + e;
+            if (fused) o3[at] = fmaf(-lr, sum, G3[at]);
+            else add_to(&dG3[at], sum);
         }
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
@@ -672,7 +668,8 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     const int64_t *__restrict__ indices, int L, const int64_t *__restrict__ offsets, int n_bags,
     const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
     float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
-    const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend)
+    const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend,
+    float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3)
 {
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
@@ -687,7 +684,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
     const int role = ge1 + ge2;
     const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, rowv);
+    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, rowv);
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
         g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
@@ -700,10 +697,11 @@ template <typename C>
 static inline void launch_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
                               const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
-                              const int *goff, const int *gend, hipStream_t st)
+                              const int *goff, const int *gend, float lr, float *o1, float *o2, float *o3,
+                              hipStream_t st)
 {
     hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(p.m1 + p.m2 + p.m3), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
-                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend);
+                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3);
 }
 
 static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >= 0; }
@@ -711,15 +709,15 @@ static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >
 static inline void fast_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx, int L,
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
                             float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
-                            const int *gend, hipStream_t st)
+                            const int *gend, float lr, float *o1, float *o2, float *o3, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
     default: break;
     }
 }

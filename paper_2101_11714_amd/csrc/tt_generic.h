@@ -270,6 +270,19 @@ __global__ __launch_bounds__(WG) void sgd_kernel(SgdArgs a, float lr, int zero_g
     }
 }
 
+__global__ __launch_bounds__(WG) void fill_f32_kernel(float *__restrict__ p, int64_t n, float v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;
+}
+
+// out = x - lr * g (out may be x itself)
+__global__ __launch_bounds__(WG) void sgd_out_kernel(const float *x, const float *__restrict__ g, float *out, int64_t n,
+                                                     float lr)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG)
+        out[i] = fmaf(-lr, g[i], x[i]);
+}
+
 // ---- cache map --------------------------------------------------------------------------
 
 __global__ __launch_bounds__(WG) void fill_u64_kernel(uint64_t *__restrict__ p, int64_t n, uint64_t v)

@@ -79,6 +79,16 @@ class DeviceTable:
         torch.cuda.synchronize()
         return grad_cores, grad_cache
 
+    def bwd_sgd(self, lr, cache=None, use_offsets=True):
+        """Fused backward + SGD: returns the new cores (the cache lines are updated in place)."""
+        out = [torch.full_like(x, float("nan")) for x in self.g]
+        ws = torch.empty(B.bwd_sgd_workspace_bytes(self.shape, self.L, self.n_bags, cache.K if cache is not None else 0),
+                         dtype=torch.uint8, device=dev())
+        B.tt_emb_bwd_sgd(self.shape, self.g, out, self.idx, self.off if use_offsets else None, self.n_bags, self.go,
+                         lr, alpha=self.alpha, cache=cache, workspace=ws)
+        torch.cuda.synchronize()
+        return out
+
     def build_cache(self, K: int, rows=None, counts=None):
         if rows is None:
             rows, counts = W.warmup_counts(self.wl, self.wl.tables.index(self.t))

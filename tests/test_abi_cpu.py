@@ -57,6 +57,8 @@ def test_bad_shapes_are_rejected(mutate, code):
     assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, one, None, 0, None) == code
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, arr, None, None, 0, None) == code
     assert l.tt_emb_sgd_update(C.byref(s), arr, arr, C.c_float(0.1), None, None, 0, None) == code
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, arr, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == code
+    assert l.tt_emb_bwd_sgd_workspace_bytes(C.byref(s), 1, 1, 0) == 0
     assert l.tt_emb_workspace_bytes(C.byref(s), 1, 1, 0) == 0
     assert len(l.tt_last_error()) > 0
 
@@ -84,6 +86,12 @@ def test_null_and_bad_arguments():
     assert l.tt_emb_fwd(C.byref(s), arr, one, 2, None, 1, None, None, one, None, 0, None) == -3   # no offsets, L != n_bags
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, None, arr, None, None, 0, None) == -1
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, holes, None, None, 0, None) == -1
+    # the fused step: no output cores, output aliasing the input
+    out = (C.c_void_p * 3)(16, 16, 16)
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, None, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -1
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, holes, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -1
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, arr, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -3
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, out, one, 1, None, 1, None, None, None, C.c_float(0.1), None, 0, None) == -1
     # a cache without its gradient buffer, and without workspace
     cache = B.TTCache(4, 16, 8, 8, 8)
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(cache), one, arr, None, None, 0, None) == -1

@@ -210,6 +210,83 @@ def test_other_shapes_take_the_generic_kernels():
         assert_close(dg[k].cpu().numpy(), ref[k], "odd dG%d" % (k + 1))
 
 
+# ------------------------------------------------------------------ fused backward + SGD
+
+@pytest.mark.parametrize("name", SINGLE)
+def test_fused_backward_sgd_matches_oracle(name, path):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl)
+    before = [x.clone() for x in d.g]
+    new = d.bwd_sgd(wl.lr)
+    ref_g, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref_g[k], wl.lr), "%s fused core %d" % (name, k + 1))
+        assert torch.equal(d.g[k], before[k])                      # the input cores are not written
+    # same bits as the two separate calls, and from run to run
+    dg, _ = d.bwd()
+    B.tt_emb_sgd_update(d.shape, d.g, dg, wl.lr)
+    torch.cuda.synchronize()
+    again = DeviceTable(wl).bwd_sgd(wl.lr)
+    for k in range(3):
+        assert torch.equal(new[k], d.g[k])
+        assert torch.equal(new[k], again[k])
+
+
+def test_fused_ragged_weighted_and_empty(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(16)
+    lens = np.array([0, 3, 0, 1, 700, 2, 0, 1500, 1, 0], dtype=np.int64)
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, t.num_rows, int(off[-1]))
+    idx[100:400] = 77
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(idx.size)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    new = d.bwd_sgd(0.05)
+    ref, _ = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], 0.05), "fused ragged core %d" % (k + 1))
+    # no lookups at all: the step copies the cores
+    empty = W.Batch(np.zeros(0, np.int64), np.zeros(4, np.int64), rng.standard_normal((3, t.dim)).astype(np.float32))
+    d0 = DeviceTable(wl, batch=empty)
+    new0 = d0.bwd_sgd(0.05)
+    for k in range(3):
+        assert torch.equal(new0[k], d0.g[k])
+
+
+def test_fused_other_shapes():
+    shape = W.TableShape(2 * 3 * 5 * 7, (6, 5, 7), (3, 2, 5), (1, 4, 7, 1))
+    wl = W.Workload("odd", (shape,), 50, (0, 6), "uniform", 0.0, "normal0.1", 21)
+    d = DeviceTable(wl, with_alpha=True)
+    new = d.bwd_sgd(0.1)
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], 0.1), "fused odd core %d" % (k + 1))
+
+
+@pytest.mark.parametrize("name,table", [("tiny", 0), ("multihot_cache", 0), ("multihot_cache", 6)])
+def test_fused_with_cache(name, table, path):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl, table=table)
+    if name == "tiny":
+        rows, counts = np.unique(d.batch.indices, return_counts=True)
+        rows, counts, K = rows.astype(np.int64), counts.astype(np.int64), 20
+        cache, _, _ = d.build_cache(K, rows, counts)
+    else:
+        K = W.cache_size(wl, table)
+        cache, rows, counts = d.build_cache(K)
+    keys = ora.cache_select(rows, counts, K)
+    crow = (ora.cache_fill(d.oshape, d.cores, keys) * 1.5).astype(np.float32)
+    cache.rows.copy_(torch.from_numpy(crow))
+    new = d.bwd_sgd(wl.lr, cache=cache)
+    rg, rc = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, cache_keys=keys)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], rg[k], wl.lr), "%s fused core %d" % (name, k + 1))
+    assert_close(cache.rows.cpu().numpy()[:K], ora.sgd(crow, rc, wl.lr), "%s fused cache lines" % name)
+
+
 # ------------------------------------------------------------------ cache
 
 def test_cache_on_tiny(path):
