@@ -199,3 +199,35 @@ def dedup(keys) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     kept = C.c_int64(0)
     u = int(_load().ora_dedup(_p(k), C.c_int64(k.size), _p(uniq), _p(count), _p(perm), C.byref(kept)))
     return uniq[:u].copy(), count[:u].copy(), perm[:kept.value].copy()
+
+
+# ---- access-frequency tracking and the semi-dynamic cache (Section 4.2) -------------------
+# Plain Python on purpose: a dictionary row -> number of accesses is the definition of what the
+# open-addressing hash table of the paper holds.
+
+def freq_update(counts: dict, indices) -> dict:
+    """Add the accesses of one index stream to the running counts (in place, also returned)."""
+    for i in _i64(indices).tolist():
+        counts[i] = counts.get(i, 0) + 1
+    return counts
+
+
+def freq_export(counts: dict) -> Tuple[np.ndarray, np.ndarray]:
+    """(rows, counts) of every tracked row, ascending by row."""
+    rows = np.array(sorted(counts), dtype=np.int64)
+    return rows, np.array([counts[int(r)] for r in rows], dtype=np.int64)
+
+
+def cache_refill(shape: Shape, cores, old_keys, old_rows, cand_rows, cand_counts, K: int):
+    """One refill of the semi-dynamic cache: the K most used candidates become the cached set
+    (same order rule as cache_select).  A row that was cached before keeps its line, with the
+    weights it has learned; a row that enters is initialised from the cores; what an evicted
+    line has learned is dropped.  Returns (keys, rows)."""
+    old_keys = _i64(old_keys)
+    old_rows = np.asarray(old_rows, dtype=np.float32).reshape(old_keys.size, shape.dim)
+    where = {int(k): s for s, k in enumerate(old_keys.tolist())}
+    keys = cache_select(cand_rows, cand_counts, K)
+    rows = np.empty((K, shape.dim), dtype=np.float32)
+    for s, k in enumerate(keys.tolist()):
+        rows[s] = old_rows[where[k]] if k in where else row(shape, cores, k)
+    return keys, rows

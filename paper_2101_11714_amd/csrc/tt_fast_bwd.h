@@ -3,16 +3,17 @@
 // One workgroup owns one core slice: workgroups [0, m1) own G1[s], the next m2 own G2[s],
 // the last m3 own G3[s].  The owner
 //   1. scans the index array and keeps, in order, the positions whose digit selects its
-//      slice (ballot compaction, no atomics),
-//   2. sorts that short list by row id in pieces of 64 entries, each piece by one wave with a
-//      rank sort, so that equal rows become adjacent,
-//   3. stages alpha_k * grad_out[bag(k)] of every entry in LDS and sums each run of equal rows
-//      into its first entry: one dY per distinct row (a row that shows up in two pieces is
-//      simply handled twice: the gradient is linear in dY),
+//      slice (ballots; every wave appends to its own sub-list, no atomics),
+//   2. finds the runs of equal rows in pieces of 64 entries, lane e holding entry e, with one
+//      ballot per distinct row, and lays the runs out one after the other (a row that shows up
+//      in two pieces is simply handled twice: the gradient is linear in dY),
+//   3. stages alpha_k * grad_out[bag(k)] of every entry in LDS at its position in that layout
+//      and sums each run into its first entry: one dY per distinct row,
 //   4. stages the small operands of every distinct row (its G1 and/or G3 slice) in LDS, all
 //      loads in flight together, and streams the large one (the G2 slice, for the G1 and G3
 //      owners) through registers several rows at a time,
-//   5. accumulates its slice gradient in registers and adds it to grad_cores once.
+//   5. accumulates its slice gradient in registers and either adds it to grad_cores once or
+//      writes the slice after its SGD step to a second set of cores.
 // All four waves walk over the same rows; wave w owns rows a in [w RQ, (w+1) RQ) of the
 // unfolded G2 slice (R x n2 R), lane l owns columns c0 .. c0+V-1:
 //   G2 owner: dG2[a][c]  += sum_j1 A[j1][a] dT0'[j1][c]              (reads no G2 at all)

@@ -368,3 +368,59 @@ def test_dedup_matches_library_sort():
     assert np.array_equal(perm, kept[np.argsort(keys[kept], kind="stable")])
     e = ora.dedup(np.array([], dtype=np.int64))
     assert e[0].size == 0 and e[1].size == 0 and e[2].size == 0
+
+
+# ---- frequency tracking and refill (Section 4.2) ------------------------------------------
+
+def test_freq_counts_match_library_unique():
+    import collections
+    rng = np.random.default_rng(41)
+    counts = {}
+    streams = [rng.zipf(1.3, 5000) % 977 for _ in range(4)]
+    for s in streams:
+        ora.freq_update(counts, s)
+    rows, cnt = ora.freq_export(counts)
+    u, c = np.unique(np.concatenate(streams), return_counts=True)
+    assert np.array_equal(rows, u) and np.array_equal(cnt, c)
+    brute = collections.Counter(int(x) for s in streams for x in s)
+    assert {int(r): int(k) for r, k in zip(rows, cnt)} == dict(brute)
+
+
+def test_refill_keeps_survivors_and_reinitialises_newcomers():
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    shape = ora.Shape.of(t)
+    cores = W.make_cores(t, wl.init, wl.seed)
+    rng = np.random.default_rng(42)
+    cand = np.arange(40, dtype=np.int64) * 7 % 1000
+    cnt1 = rng.integers(1, 50, cand.size)
+    K = 10
+    # a first fill from nothing is the plain build
+    k1, r1 = ora.cache_refill(shape, cores, np.zeros(0, np.int64), np.zeros((0, t.dim), np.float32), cand, cnt1, K)
+    assert np.array_equal(k1, ora.cache_select(cand, cnt1, K))
+    assert np.array_equal(r1, ora.cache_fill(shape, cores, k1))
+    # the lines learn something; then the popularity shifts
+    learned = (r1 + rng.standard_normal(r1.shape)).astype(np.float32)
+    cnt2 = cnt1.copy()
+    cnt2[rng.permutation(cand.size)[:15]] += 60
+    k2, r2 = ora.cache_refill(shape, cores, k1, learned, cand, cnt2, K)
+    assert np.array_equal(k2, ora.cache_select(cand, cnt2, K))
+    stay = np.intersect1d(k1, k2)
+    assert 0 < stay.size < K                                   # the case has survivors and newcomers
+    for s, k in enumerate(k2):
+        if k in stay:
+            assert np.array_equal(r2[s], learned[list(k1).index(k)])          # learned weights kept, bit for bit
+        else:
+            assert np.array_equal(r2[s], ora.cache_fill(shape, cores, [k])[0])   # from the cores
+    # unchanged popularity: nothing moves
+    k3, r3 = ora.cache_refill(shape, cores, k2, r2, cand, cnt2, K)
+    assert np.array_equal(k3, k2) and np.array_equal(r3, r2)
+    # a row that was evicted and comes back has lost what it learned
+    gone = np.setdiff1d(k1, k2)
+    assert gone.size > 0
+    cnt3 = cnt2.copy()
+    cnt3[np.isin(cand, gone)] += 1000
+    k4, r4 = ora.cache_refill(shape, cores, k2, r2, cand, cnt3, K)
+    for s, k in enumerate(k4):
+        if k in gone:
+            assert np.array_equal(r4[s], ora.cache_fill(shape, cores, [k])[0])
