@@ -75,6 +75,19 @@ typedef struct tt_cache_t {
     uint64_t *table;      /* [capacity] */
 } tt_cache_t;
 
+/* The access-frequency tracker of the semi-dynamic cache (Section 4.2: an open
+ * addressing hash table that tracks how often every row is used).  The struct is
+ * host memory; `table` ([capacity] 64-bit words, private encoding) and `stats`
+ * ([2]: distinct rows tracked, accesses dropped because the table was full) are
+ * device memory that the caller allocates; capacity is a power of two >= 64 and
+ * should be at least twice the number of distinct rows expected.  One row can be
+ * counted up to 2^32 - 1 times between resets. */
+typedef struct tt_freq_t {
+    int64_t capacity;
+    uint64_t *table;      /* [capacity] */
+    int64_t *stats;       /* [2]        */
+} tt_freq_t;
+
 /* Text of the last error on this thread ("" if none).  Host pointer, valid until
  * the next failing call on the same thread. */
 const char *tt_last_error(void);
@@ -175,6 +188,37 @@ int tt_emb_sgd_update(const tt_shape_t *shape, float *const cores[3], float *con
 int tt_cache_build(const tt_shape_t *shape, const float *const cores[3],
                    const int64_t *cand_rows, const int64_t *cand_counts, int64_t n_cand,
                    const tt_cache_t *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One refill of the semi-dynamic cache (Section 4.2: the frequently used rows are
+ * loaded into the cache only every 100s to 1000s of iterations, initialised from
+ * the cores; what an evicted line has learned is discarded).  The K most used
+ * candidates become the cached set, in tt_cache_build's order.  A row that was
+ * cached before keeps its line as it is (with the weights it has learned); a row
+ * that enters is rebuilt from the cores.
+ * cache: a VALID cache (from tt_cache_build or an earlier refill); keys, rows and
+ *        table are replaced.  K and capacity do not change.
+ * Same candidate arrays and workspace rules as tt_cache_build
+ * (tt_cache_refill_workspace_bytes).
+ */
+int tt_cache_refill(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *cand_rows, const int64_t *cand_counts, int64_t n_cand,
+                    const tt_cache_t *cache, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace tt_cache_refill needs. */
+size_t tt_cache_refill_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, int64_t K);
+
+/* Access-frequency tracker (Section 4.2).  tt_freq_reset empties the table;
+ * tt_freq_update counts every entry of indices[0..L) once (integer atomics: the
+ * counts are exact whatever the order); tt_freq_export writes the tracked rows
+ * and their counts, in no particular order, to rows / counts (int64, room for
+ * `capacity` entries) and their number to *n_out (device) - the candidate arrays
+ * of tt_cache_build / tt_cache_refill once the caller has read *n_out.
+ * If the table fills up, further new rows are not tracked and stats[1] counts
+ * the accesses that were dropped. */
+int tt_freq_reset(const tt_freq_t *tracker, void *stream);
+int tt_freq_update(const tt_freq_t *tracker, const int64_t *indices, int64_t L, void *stream);
+int tt_freq_export(const tt_freq_t *tracker, int64_t *rows, int64_t *counts, int64_t *n_out, void *stream);
 
 /* Cache probe (Section 4.2's split into cached and TT indices):
  * slot[k] = slot of indices[k], or -1 if the row is not cached.  slot: int32 [L]. */

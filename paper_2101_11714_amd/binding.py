@@ -24,7 +24,8 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
-           "tt_emb_bwd_sgd_workspace_bytes",
+           "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
+           "tt_freq_reset", "tt_freq_update", "tt_freq_export",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -59,7 +60,7 @@ def lib():
         l.tt_cache_table_capacity.restype = C.c_int64
         l.tt_cache_table_capacity.argtypes = [C.c_int64]
         for name in ("tt_emb_workspace_bytes", "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
-                     "tt_emb_bwd_sgd_workspace_bytes"):
+                     "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes"):
             getattr(l, name).restype = C.c_size_t
         l.tt_emb_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
         l.tt_emb_bwd_sgd_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
@@ -72,6 +73,11 @@ def lib():
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
         l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
         l.tt_cache_lookup.argtypes = [vp, vp, i64, vp, vp]
+        l.tt_cache_refill.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
+        l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
+        l.tt_freq_reset.argtypes = [vp, vp]
+        l.tt_freq_update.argtypes = [vp, vp, i64, vp]
+        l.tt_freq_export.argtypes = [vp, vp, vp, vp, vp]
         l.tt_emb_debug_decode.argtypes = [vp, vp, i64, vp, vp, vp, vp]
         l.tt_emb_debug_dedup.argtypes = [vp, vp, i64, vp, C.c_int, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_debug_set_fast_path.argtypes = [C.c_int]
@@ -225,6 +231,54 @@ def tt_cache_build(shape: TTShape, cores: Sequence[torch.Tensor], cand_rows: tor
     _check(lib().tt_cache_build(C.byref(shape), _ptr_array(cores), _ptr(cand_rows), _ptr(cand_counts), n, cache.ref(),
                                 _ptr(workspace), workspace.numel(), _stream()))
     return cache
+
+
+def tt_cache_refill(shape: TTShape, cores: Sequence[torch.Tensor], cand_rows: torch.Tensor,
+                    cand_counts: torch.Tensor, cache: Cache, workspace: Optional[torch.Tensor] = None) -> Cache:
+    _dev(cand_rows, torch.int64)
+    _dev(cand_counts, torch.int64)
+    n = cand_rows.numel()
+    assert cand_counts.numel() == n
+    if workspace is None:
+        workspace = _ws(lib().tt_cache_refill_workspace_bytes(C.byref(shape), n, cache.K), cand_rows.device)
+    _check(lib().tt_cache_refill(C.byref(shape), _ptr_array(cores), _ptr(cand_rows), _ptr(cand_counts), n, cache.ref(),
+                                 _ptr(workspace), workspace.numel(), _stream()))
+    return cache
+
+
+class TTFreq(C.Structure):
+    _fields_ = [("capacity", C.c_int64), ("table", C.c_void_p), ("stats", C.c_void_p)]
+
+
+class Freq:
+    """Device arrays of an access-frequency tracker and the host struct that points at them."""
+
+    def __init__(self, capacity: int, device):
+        assert capacity >= 64 and capacity & (capacity - 1) == 0
+        self.capacity = capacity
+        self.table = torch.empty(capacity, dtype=torch.int64, device=device)
+        self.stats = torch.zeros(2, dtype=torch.int64, device=device)
+        self._c = TTFreq(capacity, self.table.data_ptr(), self.stats.data_ptr())
+
+    def ref(self):
+        return C.byref(self._c)
+
+
+def tt_freq_reset(freq: Freq) -> None:
+    _check(lib().tt_freq_reset(freq.ref(), _stream()))
+
+
+def tt_freq_update(freq: Freq, indices: torch.Tensor) -> None:
+    _dev(indices, torch.int64)
+    _check(lib().tt_freq_update(freq.ref(), _ptr(indices), indices.numel(), _stream()))
+
+
+def tt_freq_export(freq: Freq, rows: torch.Tensor, counts: torch.Tensor, n_out: torch.Tensor) -> None:
+    _dev(rows, torch.int64)
+    _dev(counts, torch.int64)
+    _dev(n_out, torch.int64)
+    assert rows.numel() >= freq.capacity and counts.numel() >= freq.capacity
+    _check(lib().tt_freq_export(freq.ref(), _ptr(rows), _ptr(counts), _ptr(n_out), _stream()))
 
 
 def tt_cache_lookup(cache: Cache, indices: torch.Tensor, slot: torch.Tensor) -> torch.Tensor:

@@ -15,6 +15,7 @@
 #include "tt_fast.h"
 #include "tt_fast_bwd.h"
 #include "tt_group.h"
+#include "tt_freq.h"
 
 using namespace tt;
 
@@ -462,6 +463,112 @@ int tt_cache_build(const tt_shape_t *shape, const float *const cores[3],
     if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "cache build launch");
     // 4. lines initialised from the cores: one bag per cached row, no cache consulted
     return tt_emb_fwd(shape, cores, out->keys, K, nullptr, K, nullptr, nullptr, out->rows, nullptr, 0, stream);
+}
+
+size_t tt_cache_refill_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, int64_t K)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || n_cand < 0 || K < 0 || K > (1 << 24)) return 0;
+    return sort_ws_layout(nullptr, n_cand > 0 ? n_cand : 1).bytes + align256((size_t)K * 8) +
+           align256((size_t)K * p.N * 4) + 256;
+}
+
+int tt_cache_refill(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *cand_rows, const int64_t *cand_counts, int64_t n_cand,
+                    const tt_cache_t *cache, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (!cache) return fail(TT_ERR_NULL, "cache is NULL");
+    if (n_cand < 0 || n_cand >= (1ll << 31)) return fail(TT_ERR_BAD_ARG, "n_cand out of range");
+    if (cache->K < 0 || cache->K > n_cand) return fail(TT_ERR_BAD_ARG, "K must be in [0, n_cand]");
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, true))) return rc;
+    if (cache->K == 0) return TT_OK;
+    if (!cand_rows || !cand_counts) return fail(TT_ERR_NULL, "candidate arrays are NULL");
+    const size_t need = tt_cache_refill_workspace_bytes(shape, n_cand, cache->K);
+    if (!workspace || workspace_bytes < need)
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const int K = (int)cache->K, n = (int)n_cand;
+    SortWs ws = sort_ws_layout(workspace, n_cand);
+    int64_t *new_keys = (int64_t *)((char *)workspace + ws.bytes);
+    float *new_rows = (float *)((char *)new_keys + align256((size_t)K * 8));
+
+    // 1. the K most used candidates, most used first, ties by row id
+    hipLaunchKernelGGL(cand_keys_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, cand_rows, cand_counts, n, ws.k0);
+    uint64_t *ks; uint32_t *vs;
+    hipError_t e = radix_sort(ws, n, 64, st, &ks, &vs);
+    if (e != hipSuccess) return hip_fail(e, "cache sort");
+    hipLaunchKernelGGL(take_keys_kernel, dim3(cdiv(K, WG)), dim3(WG), 0, st, ks, K, new_keys);
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "cache refill launch");
+    // 2. their lines: a forward pass of one bag per row THROUGH THE OLD CACHE, so a row that stays
+    //    cached keeps its line and a row that enters is rebuilt from the cores
+    rc = tt_emb_fwd(shape, cores, new_keys, K, nullptr, K, nullptr, cache, new_rows, nullptr, 0, stream);
+    if (rc) return rc;
+    // 3. the new set replaces the old one
+    const int64_t nr = (int64_t)K * p.N;
+    hipLaunchKernelGGL(copy_i64_kernel, dim3(cdiv(K, WG)), dim3(WG), 0, st, new_keys, cache->keys, (int64_t)K);
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(cdiv(nr, WG) < 2048 ? cdiv(nr, WG) : 2048), dim3(WG), 0, st, new_rows,
+                       cache->rows, nr);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(cdiv(cache->capacity, WG)), dim3(WG), 0, st, cache->table,
+                       cache->capacity, CACHE_EMPTY);
+    hipLaunchKernelGGL(cache_insert_kernel, dim3(cdiv(K, WG)), dim3(WG), 0, st, cache->keys, K, cache->table,
+                       (uint32_t)(cache->capacity - 1));
+    e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "cache refill launch");
+}
+
+static int check_freq(const tt_freq_t *f, FreqDev *d)
+{
+    if (!f) return fail(TT_ERR_NULL, "tracker is NULL");
+    if (f->capacity < 64 || f->capacity > (1ll << 31) || (f->capacity & (f->capacity - 1)))
+        return fail(TT_ERR_BAD_ARG, "tracker capacity must be a power of two in [64, 2^31]");
+    if (!f->table || !f->stats) return fail(TT_ERR_NULL, "tracker array is NULL");
+    d->table = (unsigned long long *)f->table;
+    d->stats = (unsigned long long *)f->stats;
+    d->mask = (uint32_t)(f->capacity - 1);
+    return TT_OK;
+}
+
+int tt_freq_reset(const tt_freq_t *tracker, void *stream)
+{
+    FreqDev f;
+    int rc = check_freq(tracker, &f);
+    if (rc) return rc;
+    hipLaunchKernelGGL(freq_reset_kernel, dim3(cdiv(tracker->capacity, WG)), dim3(WG), 0, (hipStream_t)stream, f);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "tracker reset launch");
+}
+
+int tt_freq_update(const tt_freq_t *tracker, const int64_t *indices, int64_t L, void *stream)
+{
+    FreqDev f;
+    int rc = check_freq(tracker, &f);
+    if (rc) return rc;
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (L == 0) return TT_OK;
+    if (!indices) return fail(TT_ERR_NULL, "indices is NULL");
+    hipLaunchKernelGGL(freq_update_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, f, indices, (int)L);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "tracker update launch");
+}
+
+int tt_freq_export(const tt_freq_t *tracker, int64_t *rows, int64_t *counts, int64_t *n_out, void *stream)
+{
+    FreqDev f;
+    int rc = check_freq(tracker, &f);
+    if (rc) return rc;
+    if (!rows || !counts || !n_out) return fail(TT_ERR_NULL, "NULL array");
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(freq_zero_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)n_out);
+    hipLaunchKernelGGL(freq_export_kernel, dim3(cdiv(tracker->capacity, WG)), dim3(WG), 0, st, f, rows, counts,
+                       (unsigned long long *)n_out);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "tracker export launch");
 }
 
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,

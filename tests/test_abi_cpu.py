@@ -117,3 +117,24 @@ def test_empty_calls_enqueue_nothing_and_succeed():
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2101_11714_amd", "binding.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")
+
+
+def test_tracker_and_refill_argument_checks():
+    l = B.lib()
+    s = good_shape()
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    one = C.c_void_p(8)
+    good = B.TTFreq(1024, 8, 8)
+    assert l.tt_freq_reset(None, None) == -1
+    assert l.tt_freq_reset(C.byref(B.TTFreq(1000, 8, 8)), None) == -3          # not a power of two
+    assert l.tt_freq_reset(C.byref(B.TTFreq(32, 8, 8)), None) == -3            # too small
+    assert l.tt_freq_reset(C.byref(B.TTFreq(1024, None, 8)), None) == -1
+    assert l.tt_freq_update(C.byref(good), None, 5, None) == -1
+    assert l.tt_freq_update(C.byref(good), one, -1, None) == -3
+    assert l.tt_freq_update(C.byref(good), None, 0, None) == 0
+    assert l.tt_freq_export(C.byref(good), one, one, None, None) == -1
+    cache = B.TTCache(4, 16, 8, 8, 8)
+    assert l.tt_cache_refill(C.byref(s), arr, one, one, 3, C.byref(cache), None, 0, None) == -3     # K > n_cand
+    assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, C.byref(cache), None, 0, None) == -4    # no workspace
+    assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, None, one, 1 << 20, None) == -1
+    assert l.tt_cache_refill_workspace_bytes(C.byref(s), 10, 4) > 0

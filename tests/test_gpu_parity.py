@@ -362,3 +362,105 @@ def test_cache_selection_with_many_ties():
     d = DeviceTable(W.WORKLOADS["kaggle_r32"])
     cache, _, _ = d.build_cache(K, rows, counts)
     assert np.array_equal(cache.keys.cpu().numpy(), ora.cache_select(rows, counts, K))
+
+
+# ------------------------------------------------------------------ frequency tracker and refill
+
+@pytest.mark.parametrize("name", ["kaggle_r32", "multihot_cache"])
+def test_freq_tracker_counts_exactly(name):
+    wl = W.WORKLOADS[name]
+    freq = B.Freq(1 << 19, dev())
+    B.tt_freq_reset(freq)
+    ref = {}
+    for step in range(3):
+        b = W.make_batch(wl, 0, step)
+        B.tt_freq_update(freq, torch.from_numpy(b.indices).to(dev()))
+        ora.freq_update(ref, b.indices)
+    rows = torch.empty(freq.capacity, dtype=torch.int64, device=dev())
+    counts = torch.empty_like(rows)
+    n_out = torch.zeros(1, dtype=torch.int64, device=dev())
+    B.tt_freq_export(freq, rows, counts, n_out)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    r, c = rows[:n].cpu().numpy(), counts[:n].cpu().numpy()
+    order = np.argsort(r)
+    ref_rows, ref_counts = ora.freq_export(ref)
+    assert np.array_equal(r[order], ref_rows) and np.array_equal(c[order], ref_counts)
+    stats = freq.stats.cpu().numpy()
+    assert stats[0] == n and stats[1] == 0
+    # a reset empties it
+    B.tt_freq_reset(freq)
+    B.tt_freq_export(freq, rows, counts, n_out)
+    torch.cuda.synchronize()
+    assert int(n_out.item()) == 0 and int(freq.stats.sum().item()) == 0
+
+
+def test_freq_tracker_full_table_drops_and_says_so():
+    freq = B.Freq(64, dev())
+    B.tt_freq_reset(freq)
+    rng = np.random.default_rng(5)
+    idx = rng.integers(0, 300, 5000).astype(np.int64)
+    B.tt_freq_update(freq, torch.from_numpy(idx).to(dev()))
+    rows = torch.empty(64, dtype=torch.int64, device=dev())
+    counts = torch.empty_like(rows)
+    n_out = torch.zeros(1, dtype=torch.int64, device=dev())
+    B.tt_freq_export(freq, rows, counts, n_out)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    stats = freq.stats.cpu().numpy()
+    assert n == 64 and stats[0] == 64 and stats[1] > 0
+    r, c = rows[:n].cpu().numpy(), counts[:n].cpu().numpy()
+    assert np.unique(r).size == 64
+    true = dict(zip(*np.unique(idx, return_counts=True)))
+    assert all(1 <= c[i] <= true[r[i]] for i in range(n))         # a tracked row never counts too much
+    assert int(c.sum()) + int(stats[1]) == idx.size                # every access is counted or reported dropped
+
+
+@pytest.mark.parametrize("name", ["tiny", "multihot_cache"])
+def test_cache_refill_matches_oracle(name, path):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl)
+    rng = np.random.default_rng(8)
+    if name == "tiny":
+        cand = (np.arange(40, dtype=np.int64) * 7) % 1000
+        cnt1 = rng.integers(1, 50, cand.size).astype(np.int64)
+        cnt2 = cnt1.copy()
+        cnt2[rng.permutation(cand.size)[:15]] += 60
+        K = 10
+    else:
+        # counts of the warm-up stream, then of a later stream tracked on the device
+        cand, cnt1 = W.warmup_counts(wl, 0)
+        K = W.cache_size(wl, 0)
+        freq = B.Freq(1 << 19, dev())
+        B.tt_freq_reset(freq)
+        for step in range(2):
+            B.tt_freq_update(freq, torch.from_numpy(W.make_batch(wl, 0, step).indices).to(dev()))
+        rows = torch.empty(freq.capacity, dtype=torch.int64, device=dev())
+        counts = torch.empty_like(rows)
+        n_out = torch.zeros(1, dtype=torch.int64, device=dev())
+        B.tt_freq_export(freq, rows, counts, n_out)
+        torch.cuda.synchronize()
+        n = int(n_out.item())
+        cand2, cnt2 = rows[:n].cpu().numpy(), counts[:n].cpu().numpy()
+    cache, _, _ = d.build_cache(K, cand, cnt1)
+    k1 = ora.cache_select(cand, cnt1, K)
+    learned = (ora.cache_fill(d.oshape, d.cores, k1) * 1.25 + 0.5).astype(np.float32)
+    cache.rows.copy_(torch.from_numpy(learned))
+    if name == "tiny":
+        cand2 = cand
+    B.tt_cache_refill(d.shape, d.g, torch.from_numpy(cand2).to(dev()), torch.from_numpy(cnt2).to(dev()), cache)
+    torch.cuda.synchronize()
+    k2, r2 = ora.cache_refill(d.oshape, d.cores, k1, learned, cand2, cnt2, K)
+    assert np.array_equal(cache.keys.cpu().numpy(), k2)
+    got = cache.rows.cpu().numpy()[:K]
+    stay = np.isin(k2, k1)
+    assert 0 < stay.sum() < K                                       # survivors and newcomers both occur
+    assert np.array_equal(got[stay], r2[stay])                      # learned lines are kept bit for bit
+    assert_close(got[~stay], r2[~stay], "%s lines of the rows that enter" % name)
+    slot = torch.empty(d.L, dtype=torch.int32, device=dev())
+    B.tt_cache_lookup(cache, d.idx, slot)
+    assert np.array_equal(slot.cpu().numpy(), ora.cache_lookup(d.oshape, k2, d.batch.indices))
+    # the refilled cache serves the forward pass
+    pick, idx, off, _ = sample_bags(d.batch, 64)
+    out = d.fwd(cache=cache)
+    assert_close(out[pick], ora.fwd(d.oshape, d.cores, idx, off, cache_keys=k2, cache_rows=got), "%s forward after refill" % name)
