@@ -552,7 +552,10 @@ int tt_freq_update(const tt_freq_t *tracker, const int64_t *indices, int64_t L, 
     if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
     if (L == 0) return TT_OK;
     if (!indices) return fail(TT_ERR_NULL, "indices is NULL");
-    hipLaunchKernelGGL(freq_update_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, f, indices, (int)L);
+    if (L >= 16384)
+        hipLaunchKernelGGL(freq_update_chunk_kernel, dim3(cdiv(L, FQ_CHUNK)), dim3(WG), 0, (hipStream_t)stream, f, indices, (int)L);
+    else
+        hipLaunchKernelGGL(freq_update_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, f, indices, (int)L);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "tracker update launch");
 }

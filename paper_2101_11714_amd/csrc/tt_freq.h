@@ -56,14 +56,54 @@ __global__ __launch_bounds__(WG) void freq_update_kernel(FreqDev f, const int64_
     const bool in = k < L;
     const uint32_t my = in ? (uint32_t)indices[k] : 0xFFFFFFFFu;
     const int lane = threadIdx.x & 63;
+    // equal rows of the wave are combined without touching memory: the first lane of every
+    // distinct row becomes its leader and learns how many lanes hold it ...
     uint64_t rem = __ballot(in);
+    uint32_t mine = 0;
     while (rem) {                                                  // uniform: one step per distinct row of the wave
         const int j = __builtin_ctzll(rem);
         const uint32_t rj = (uint32_t)__builtin_amdgcn_readlane((int)my, j);
         const uint64_t m = __ballot(my == rj);
         rem &= ~m;
-        if (lane == j) freq_add(f, rj, (uint32_t)__popcll(m));
+        if (lane == j) mine = (uint32_t)__popcll(m);
     }
+    // ... then all leaders update the table at the same time
+    if (mine) freq_add(f, my, mine);
+}
+
+// Long streams: a workgroup first counts its FQ_CHUNK positions in a small table in LDS (LDS
+// atomics; equal rows meet there), then adds every distinct row of the chunk to the device table
+// once.  The hottest row of a Zipf stream then costs one device atomic per chunk, not per wave.
+constexpr int FQ_PER = 4;                       // positions per thread
+constexpr int FQ_CHUNK = FQ_PER * WG;           // positions per workgroup
+constexpr int FQ_T = 2 * FQ_CHUNK;              // LDS table entries (never full)
+
+__global__ __launch_bounds__(WG) void freq_update_chunk_kernel(FreqDev f, const int64_t *__restrict__ indices, int L)
+{
+    __shared__ uint32_t lkey[FQ_T], lcnt[FQ_T];
+    const int t = threadIdx.x;
+    for (int i = t; i < FQ_T; i += WG) { lkey[i] = 0xFFFFFFFFu; lcnt[i] = 0u; }
+    __syncthreads();
+    const int base = blockIdx.x * FQ_CHUNK;
+    uint32_t row[FQ_PER];
+#pragma unroll
+    for (int q = 0; q < FQ_PER; ++q) {
+        const int k = base + q * WG + t;
+        row[q] = k < L ? (uint32_t)indices[k] : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int q = 0; q < FQ_PER; ++q) {
+        if (row[q] == 0xFFFFFFFFu) continue;
+        uint32_t h = cache_hash(row[q], FQ_T - 1);
+        for (;;) {                                                 // ends: at most FQ_CHUNK rows in 2 FQ_CHUNK entries
+            const uint32_t old = atomicCAS(&lkey[h], 0xFFFFFFFFu, row[q]);
+            if (old == 0xFFFFFFFFu || old == row[q]) { atomicAdd(&lcnt[h], 1u); break; }
+            h = (h + 1) & (FQ_T - 1);
+        }
+    }
+    __syncthreads();
+    for (int i = t; i < FQ_T; i += WG)
+        if (lkey[i] != 0xFFFFFFFFu) freq_add(f, lkey[i], lcnt[i]);
 }
 
 // rows / counts of the occupied entries, in no particular order; *n_out = how many
