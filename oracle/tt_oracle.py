@@ -231,3 +231,17 @@ def cache_refill(shape: Shape, cores, old_keys, old_rows, cand_rows, cand_counts
     for s, k in enumerate(keys.tolist()):
         rows[s] = old_rows[where[k]] if k in where else row(shape, cores, k)
     return keys, rows
+
+
+# ---- stored intermediate of the forward pass (Section 4.2, first paragraph) ----------------
+
+def t0(shape: Shape, cores, row_id: int) -> np.ndarray:
+    """The product of the first two core slices of a row, T0 = A . Bm reshaped to (n1 n2) x R2
+    (Section 3.1): the tensor that Alg. 2 recomputes in the backward pass unless the forward
+    pass has kept it.  fp64; row = T0 . C."""
+    i1, i2, _ = (int(x[0]) for x in decode(shape, [row_id]))
+    n1, n2, _ = shape.n
+    _, R1, R2, _ = shape.r
+    A = np.asarray(cores[0], dtype=np.float64).reshape(shape.m[0], n1, R1)[i1]
+    Bm = np.asarray(cores[1], dtype=np.float64).reshape(shape.m[1], R1, n2 * R2)[i2]
+    return (A @ Bm).reshape(n1 * n2, R2)

@@ -424,3 +424,20 @@ def test_refill_keeps_survivors_and_reinitialises_newcomers():
     for s, k in enumerate(k4):
         if k in gone:
             assert np.array_equal(r4[s], ora.cache_fill(shape, cores, [k])[0])
+
+
+def test_stored_intermediate_times_last_core_is_the_row():
+    # unequal factors and ranks, so that a transposed or mis-reshaped T0 fails
+    shape = ora.Shape(3 * 4 * 5, (3, 4, 5), (2, 3, 4), (1, 5, 6, 1))
+    rng = np.random.default_rng(51)
+    cores = [rng.standard_normal((3, 1, 2, 5)).astype(np.float32), rng.standard_normal((4, 5, 3, 6)).astype(np.float32),
+             rng.standard_normal((5, 6, 4, 1)).astype(np.float32)]
+    for r in (0, 17, 59):
+        i1, i2, i3 = (int(x[0]) for x in ora.decode(shape, [r]))
+        T0 = ora.t0(shape, cores, r)
+        assert T0.shape == (6, 6)
+        Cm = cores[2].astype(np.float64).reshape(5, 6, 4)[i3]
+        assert np.allclose((T0 @ Cm).reshape(-1), ora.row(shape, cores, r), rtol=1e-13, atol=1e-13)
+        # element by element from the definition: T0[(j1,j2), b] = sum_a G1[i1][j1][a] G2[i2][a][j2][b]
+        ref = np.einsum("ja,akb->jkb", cores[0].astype(np.float64)[i1, 0], cores[1].astype(np.float64)[i2]).reshape(6, 6)
+        assert np.allclose(T0, ref, rtol=1e-13, atol=1e-13)
