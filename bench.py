@@ -5,10 +5,12 @@ forward, backward and the SGD update of the cores, at the Kaggle-shaped R = 32
 configuration (10,131,227 rows as 200x220x250, dimension 16 as 2x2x4, 2048 bags
 of one index, Zipf(1.05) indices).  All inputs are resident in HBM before the
 timed region.  By default the backward pass and the SGD update are one call
-(tt_emb_bwd_sgd, two sets of cores used in turn); --step separate times
-tt_emb_bwd + tt_emb_sgd_update instead.  Prints ONE JSON line.
+(two sets of cores used in turn) and the forward pass keeps its intermediate T0
+for the backward pass (tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0); --recompute
+uses tt_emb_fwd + tt_emb_bwd_sgd, --step separate times tt_emb_fwd + tt_emb_bwd
++ tt_emb_sgd_update.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32] [--step fused|separate]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32] [--step fused|separate] [--recompute]
 """
 
 from __future__ import annotations
@@ -61,6 +63,10 @@ def main():
     ap.add_argument("--workload", default="kaggle_r32")
     ap.add_argument("--step", choices=["fused", "separate"], default="fused",
                     help="fused: forward, then backward and SGD in one call; separate: three calls")
+    ap.add_argument("--recompute", action="store_true",
+                    help="the backward pass recomputes the forward's intermediate T0 (tt_emb_fwd / tt_emb_bwd_sgd) "
+                         "instead of reading the copy that the forward pass stored "
+                         "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0, the default of the fused step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
@@ -106,14 +112,24 @@ def main():
     lr = 1e-3 * wl.lr            # small, so that thousands of steps keep the cores finite
 
     cores2 = [torch.empty_like(c) for c in cores]      # the fused step writes the other set of cores
+    keep_t0 = args.step == "fused" and not args.recompute
+    # one stored intermediate per batch of the pool (1 MB each at Kaggle R = 32)
+    t0_pool = [torch.empty((L, B.t0_floats(shape)), dtype=torch.float32, device=dev) for _ in range(POOL)] if keep_t0 else None
+
+    def fwd_call(cur, j):
+        if keep_t0:
+            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], n_bags, out, t0_pool[j])
+        else:
+            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out)
+
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
     def step(i):
         j = i % POOL
         if args.step == "fused":
             cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
-            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out)
-            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr)
+            fwd_call(cur, j)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, t0=t0_pool[j] if keep_t0 else None)
         else:
             B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out)
             B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads)
@@ -158,10 +174,11 @@ def main():
 
     # per-kernel durations: each stage alone, launched back to back on the same stream
     reps = max(POOL * 16, min(steps, 4096))
-    ms_fwd = timed_any(lambda i: B.tt_emb_fwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out), reps)
+    ms_fwd = timed_any(lambda i: fwd_call(cores, i % POOL), reps)
     if args.step == "fused":
+        # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
         ms_bs = timed_any(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
-                                                     go[i % POOL], lr), reps)
+                                                     go[i % POOL], lr, t0=t0_pool[i % POOL] if keep_t0 else None), reps)
         stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
     else:
         ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
@@ -177,6 +194,10 @@ def main():
                + np.unique((b0 // m3) % m2).size * t.r[1] * t.n[1] * t.r[2]
                + np.unique(b0 % m3).size * t.r[2] * t.n[2])
     ab = algorithmic_bytes(t, L, n_bags, touched)
+    if keep_t0:                                          # T0 is written once and read once per lookup
+        t0_bytes = L * 4 * B.t0_floats(shape)
+        ab["fwd"] += t0_bytes
+        ab["bwd_sgd"] += t0_bytes
     dominant = max(stage_ms, key=stage_ms.get)
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
@@ -211,7 +232,7 @@ def main():
         "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
                                "Zipf(%.2f), fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
                                                             n_bags, L // n_bags, wl.zipf_alpha),
-                   "lookups_per_step": L, "launch": args.launch, "step": args.step, "wall_s_timed_region": round(wall, 3)},
+                   "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0), "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

@@ -144,6 +144,34 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The stored-intermediate variant (Section 4.2, first paragraph: the recomputation
+ * in Alg. 2 can be eliminated by storing tensors from the forward pass, at the price
+ * of a larger memory footprint).  tt_emb_fwd_keep_t0 is tt_emb_fwd that also writes,
+ * for every position k whose row is not cached, the product of its first two core
+ * slices, t0[k][(j1*n2 + j2)][b] (fp32, n1*n2*r[2] values per position; t0 has room
+ * for L positions; entries of cached positions are not written).  tt_emb_bwd_t0 and
+ * tt_emb_bwd_sgd_t0 are tt_emb_bwd and tt_emb_bwd_sgd given that array for the SAME
+ * indices: the owners of the third core's slices read it instead of recomputing it
+ * (they then read neither G1 nor G2).  Only for the shapes with a specialised kernel
+ * (n = (2,2,4) or (4,4,4), equal ranks 8..64): TT_ERR_UNSUPPORTED otherwise.
+ */
+int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
+                       const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                       const float *alpha, const tt_cache_t *cache,
+                       float *output, float *t0, void *stream);
+int tt_emb_bwd_t0(const tt_shape_t *shape, const float *const cores[3],
+                  const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                  const float *alpha, const tt_cache_t *cache,
+                  const float *grad_output, const float *t0,
+                  float *const grad_cores[3], float *grad_cache,
+                  void *workspace, size_t workspace_bytes, void *stream);
+int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                      const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                      const float *alpha, const tt_cache_t *cache,
+                      const float *grad_output, const float *t0, float lr,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Backward pass and SGD step in one call (Section 3.1, Eq. 4; Alg. 2; Section 5):
  * cores_out = cores - lr * (gradient of <output, grad_output> for this batch), and,
  * with a cache, cache->rows -= lr * (gradient of the cached rows), in place

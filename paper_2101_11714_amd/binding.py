@@ -26,6 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_freq_reset", "tt_freq_update", "tt_freq_export",
+           "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -69,6 +70,9 @@ def lib():
         vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
         l.tt_emb_fwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_fwd_keep_t0.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
+        l.tt_emb_bwd_t0.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_sgd_t0.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_bwd_sgd.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
         l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
@@ -172,11 +176,33 @@ def tt_emb_fwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
     return output
 
 
+def t0_floats(shape: TTShape) -> int:
+    """fp32 values per position of the stored intermediate (n1 n2 r2)."""
+    return shape.n[0] * shape.n[1] * shape.r[2]
+
+
+def tt_emb_fwd_keep_t0(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor,
+                       offsets: Optional[torch.Tensor], n_bags: int, output: torch.Tensor, t0: torch.Tensor,
+                       alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None) -> torch.Tensor:
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(output, torch.float32)
+    _dev(t0, torch.float32)
+    assert t0.numel() >= indices.numel() * t0_floats(shape)
+    _check(lib().tt_emb_fwd_keep_t0(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets),
+                                    n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(t0), _stream()))
+    return output
+
+
 def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor,
                offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
                grad_cores: Sequence[torch.Tensor], alpha: Optional[torch.Tensor] = None,
                cache: Optional[Cache] = None, grad_cache: Optional[torch.Tensor] = None,
-               workspace: Optional[torch.Tensor] = None) -> None:
+               workspace: Optional[torch.Tensor] = None, t0: Optional[torch.Tensor] = None) -> None:
     _dev(indices, torch.int64)
     if offsets is not None:
         _dev(offsets, torch.int64)
@@ -189,6 +215,12 @@ def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
     if grad_cache is not None:
         _dev(grad_cache, torch.float32)
     wsb = workspace.numel() if workspace is not None else 0
+    if t0 is not None:
+        _dev(t0, torch.float32)
+        _check(lib().tt_emb_bwd_t0(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets),
+                                   n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output), _ptr(t0),
+                                   _ptr_array(grad_cores), _ptr(grad_cache), _ptr(workspace), wsb, _stream()))
+        return
     _check(lib().tt_emb_bwd(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
                             _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output), _ptr_array(grad_cores),
                             _ptr(grad_cache), _ptr(workspace), wsb, _stream()))
@@ -197,7 +229,7 @@ def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
 def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],
                    indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
                    lr: float, alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None,
-                   workspace: Optional[torch.Tensor] = None) -> None:
+                   workspace: Optional[torch.Tensor] = None, t0: Optional[torch.Tensor] = None) -> None:
     _dev(indices, torch.int64)
     if offsets is not None:
         _dev(offsets, torch.int64)
@@ -208,6 +240,13 @@ def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Seq
     for k in range(3):
         assert cores_out[k].numel() == cores[k].numel()
     wsb = workspace.numel() if workspace is not None else 0
+    if t0 is not None:
+        _dev(t0, torch.float32)
+        _check(lib().tt_emb_bwd_sgd_t0(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices),
+                                       indices.numel(), _ptr(offsets), n_bags, _ptr(alpha),
+                                       cache.ref() if cache else None, _ptr(grad_output), _ptr(t0), C.c_float(lr),
+                                       _ptr(workspace), wsb, _stream()))
+        return
     _check(lib().tt_emb_bwd_sgd(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices), indices.numel(),
                                 _ptr(offsets), n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output),
                                 C.c_float(lr), _ptr(workspace), wsb, _stream()))

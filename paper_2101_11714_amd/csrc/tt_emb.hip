@@ -173,12 +173,11 @@ size_t tt_cache_build_workspace_bytes(const tt_shape_t *shape, int64_t n_cand, i
     return sort_ws_layout(nullptr, n_cand > 0 ? n_cand : 1).bytes;
 }
 
-int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
-               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
-               const float *alpha, const tt_cache_t *cache,
-               float *output, void *workspace, size_t workspace_bytes, void *stream)
+static int fwd_common(const tt_shape_t *shape, const float *const cores[3],
+                      const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                      const float *alpha, const tt_cache_t *cache, float *output, float *t0_out, bool keep_t0,
+                      void *stream)
 {
-    (void)workspace; (void)workspace_bytes;
     Params p;
     int rc = check_shape(shape, &p);
     if (rc) return rc;
@@ -187,11 +186,16 @@ int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
     if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
     CacheDev cd;
     if ((rc = check_cache(cache, &cd, true))) return rc;
+    if (keep_t0) {
+        if (L > 0 && !t0_out) return fail(TT_ERR_NULL, "t0 is NULL");
+        if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps T0 for this shape");
+    }
     if (n_bags == 0) return TT_OK;
     hipStream_t st = (hipStream_t)stream;
 
-    if (g_fast_path) {
-        int frc = fast_fwd(p, cores[0], cores[1], cores[2], indices, offsets, (int)n_bags, alpha, cd, output, st);
+    if (g_fast_path || keep_t0) {
+        int frc = fast_fwd(p, cores[0], cores[1], cores[2], indices, offsets, (int)n_bags, alpha, cd, output,
+                           keep_t0 ? t0_out : nullptr, st);
         if (frc == 0) {
             hipError_t e = hipGetLastError();
             return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
@@ -206,6 +210,23 @@ int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
     return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
 }
 
+int tt_emb_fwd(const tt_shape_t *shape, const float *const cores[3],
+               const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+               const float *alpha, const tt_cache_t *cache,
+               float *output, void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    return fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, nullptr, false, stream);
+}
+
+int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
+                       const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                       const float *alpha, const tt_cache_t *cache,
+                       float *output, float *t0, void *stream)
+{
+    return fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, t0, true, stream);
+}
+
 // Backward pass behind tt_emb_bwd (cores_out == nullptr: gradients are added to grad_cores /
 // grad_cache) and tt_emb_bwd_sgd (cores_out != nullptr: the cores after the SGD step are written
 // to cores_out, the cached rows are updated in place; grad_cores / grad_cache are unused).
@@ -213,7 +234,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                       const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
                       const float *alpha, const tt_cache_t *cache, const float *grad_output,
                       float *const grad_cores[3], float *grad_cache, float lr, float *const cores_out[3],
-                      void *workspace, size_t workspace_bytes, void *stream)
+                      const float *t0, void *workspace, size_t workspace_bytes, void *stream)
 {
     const bool fused = cores_out != nullptr;
     Params p;
@@ -232,7 +253,8 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     CacheDev cd;
     if ((rc = check_cache(cache, &cd, fused))) return rc;
     if (!fused && cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
-    const bool fast = g_fast_path && fast_bwd_supported(p);
+    if (t0 && !fast_bwd_supported(p)) return fail(TT_ERR_UNSUPPORTED, "no kernel uses a kept T0 for this shape");
+    const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
     const bool grouped = fast && (g_fast_path == 2 || L >= GROUP_MIN_L);
     const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
     const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
@@ -313,14 +335,14 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                                grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, st);
+                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, st);
     } else {
         if (cd.K && L > 0)
             hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
                                offsets, (int)n_bags, alpha, grad_output, grad_cache);
         if (fast) {
             fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, st);
+                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, t0, st);
         } else if (L > 0) {
             hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
                                cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
@@ -350,7 +372,19 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                void *workspace, size_t workspace_bytes, void *stream)
 {
     return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, grad_cores, grad_cache,
-                      0.f, nullptr, workspace, workspace_bytes, stream);
+                      0.f, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_bwd_t0(const tt_shape_t *shape, const float *const cores[3],
+                  const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                  const float *alpha, const tt_cache_t *cache,
+                  const float *grad_output, const float *t0,
+                  float *const grad_cores[3], float *grad_cache,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (L > 0 && !t0) return fail(TT_ERR_NULL, "t0 is NULL");
+    return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, grad_cores, grad_cache,
+                      0.f, nullptr, t0, workspace, workspace_bytes, stream);
 }
 
 int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
@@ -361,7 +395,19 @@ int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *
 {
     if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
     return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
-                      lr, cores_out, workspace, workspace_bytes, stream);
+                      lr, cores_out, nullptr, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                      const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                      const float *alpha, const tt_cache_t *cache,
+                      const float *grad_output, const float *t0, float lr,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
+    if (L > 0 && !t0) return fail(TT_ERR_NULL, "t0 is NULL");
+    return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
+                      lr, cores_out, t0, workspace, workspace_bytes, stream);
 }
 
 size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows)

@@ -43,6 +43,19 @@ __device__ __forceinline__ void load_vec(const float *__restrict__ p, float (&o)
     }
 }
 
+template <int V>
+__device__ __forceinline__ void store_vec(float *__restrict__ p, const float (&o)[V])
+{
+    if constexpr (V == 1) {
+        p[0] = o[0];
+    } else if constexpr (V == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(o[0], o[1]);
+    } else {
+        static_assert(V == 4, "V must be 1, 2 or 4");
+        *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 // Sum NV values per lane over an aligned group of LN lanes.  While more than one value
 // is left, each step halves the values a lane keeps (the lane whose bit D is set keeps
 // the upper half); then plain butterfly adds.  Afterwards a lane holds KEEP =
@@ -104,7 +117,7 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
                                                       const int64_t *__restrict__ indices,
                                                       const int64_t *__restrict__ offsets, int n_bags,
                                                       const float *__restrict__ alpha, CacheDev cache,
-                                                      float *__restrict__ out)
+                                                      float *__restrict__ out, float *__restrict__ t0_out)
 {
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V;
     const int lane = threadIdx.x & 63;
@@ -160,6 +173,11 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
                 for (int v = 0; v < V; ++v) t0[j1][v] = fmaf(av, bv[v], t0[j1][v]);
             }
         }
+        if (t0_out && active) {                             // keep T0[(j1,j2)][b] of this position for the backward pass
+            float *o = t0_out + (size_t)k * (N1 * C::COLS) + c0;
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) store_vec<V>(o + j1 * C::COLS, t0[j1]);
+        }
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const float4 cv = *reinterpret_cast<const float4 *>(Cp + v * N3);
@@ -193,10 +211,10 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
 template <typename C>
 static inline void launch_fwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                               const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd, float *out,
-                              hipStream_t st)
+                              float *t0_out, hipStream_t st)
 {
     hipLaunchKernelGGL(fwd_fast_kernel<C>, dim3((n_bags + NWAVE - 1) / NWAVE), dim3(WG), 0, st, p, G1, G2, G3, idx, off,
-                       n_bags, alpha, cd, out);
+                       n_bags, alpha, cd, out, t0_out);
 }
 
 // id of the specialised configuration for this shape, or -1
@@ -227,15 +245,15 @@ using Cfg444R64 = FastCfg<4, 4, 4, 64, 4>;
 // Returns 0 if a specialised forward kernel was launched, -1 if the shape has none.
 static inline int fast_fwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                            const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd, float *out,
-                           hipStream_t st)
+                           float *t0_out, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_fwd<Cfg224R8>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
-    case 1: launch_fwd<Cfg224R16>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
-    case 2: launch_fwd<Cfg224R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
-    case 3: launch_fwd<Cfg224R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
-    case 4: launch_fwd<Cfg444R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
-    case 5: launch_fwd<Cfg444R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, st); return 0;
+    case 0: launch_fwd<Cfg224R8>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 1: launch_fwd<Cfg224R16>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 2: launch_fwd<Cfg224R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 3: launch_fwd<Cfg224R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 4: launch_fwd<Cfg444R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 5: launch_fwd<Cfg444R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
     default: return -1;
     }
 }

@@ -81,6 +81,7 @@ struct __align__(16) FbLds {
     int epos[FbCfg<C>::W];                                  // staged position of each entry of the window (runs contiguous)
     int seg_start[FbCfg<C>::W + 1];                         // staged position of the first entry of each run of equal rows
     int seg_i1[FbCfg<C>::W], seg_i2[FbCfg<C>::W], seg_i3[FbCfg<C>::W];   // its digits
+    uint32_t seg_k[FbCfg<C>::W];                            // position k of the run's first entry (for the stored T0)
     int pcnt[NWAVE];                                        // runs per piece of a long window
     int wcnt[2][NWAVE];
 };
@@ -213,9 +214,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         float *__restrict__ dG2, float *__restrict__ dG3,
                                         const uint32_t *__restrict__ gvals, const int *__restrict__ goff,
                                         const int *__restrict__ gend, float lr, float *__restrict__ o1,
-                                        float *__restrict__ o2, float *__restrict__ o3, uint32_t (&rowv)[FB_ITER])
+                                        float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
+                                        uint32_t (&rowv)[FB_ITER])
 {
     using F = FbCfg<C>;
+    const bool t0mode = ROLE == 2 && t0 != nullptr;                    // the G3 owner uses the stored T0
     // Two ways to finish: add the slice gradient to dG1/dG2/dG3 (o1 == nullptr), or write the
     // slice after its SGD step, x - lr * gradient, to o1/o2/o3 (every slice is written then, also
     // one that no lookup touches).
@@ -432,14 +435,50 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
+    // G3 owner with the T0 that the forward pass kept (Section 4.2's alternative to recomputing):
+    // dG3[b][j3] += sum_{(j1,j2)} T0[(j1,j2)][b] dY[(j1,j2)][j3] needs no G1 or G2 at all.  Wave w
+    // takes the rows w, w + 4, ...; lane c = (j2, b) reads T0[k][j1][c] of the row's first position k.
+    auto consume_t0 = [&](int nsegs) __attribute__((always_inline)) {
+        constexpr int TB = 4;                                              // rows in flight per wave
+        for (int sg0 = w; sg0 < nsegs; sg0 += NWAVE * TB) {
+            float tv[TB][N1][V];
+            const float *dyp[TB];
+            float keep[TB];
+#pragma unroll
+            for (int q = 0; q < TB; ++q) {
+                const int sg = min(sg0 + q * NWAVE, nsegs - 1);
+                keep[q] = sg0 + q * NWAVE < nsegs ? 1.f : 0.f;
+                const float *src = t0 + (size_t)lds.seg_k[sg] * (N1 * C::COLS) + c0;
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1) load_vec<V>(src + j1 * C::COLS, tv[q][j1]);
+                dyp[q] = stage + lds.seg_start[sg] * N + j2 * N3;
+            }
+#pragma unroll
+            for (int q = 0; q < TB; ++q)
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float4 g = *reinterpret_cast<const float4 *>(dyp[q] + j1 * N2 * N3);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const float tk = tv[q][j1][v] * keep[q];
+                        acc[v * N3 + 0] = fmaf(tk, g.x, acc[v * N3 + 0]);
+                        acc[v * N3 + 1] = fmaf(tk, g.y, acc[v * N3 + 1]);
+                        acc[v * N3 + 2] = fmaf(tk, g.z, acc[v * N3 + 2]);
+                        acc[v * N3 + 3] = fmaf(tk, g.w, acc[v * N3 + 3]);
+                    }
+                }
+        }
+    };
+
     // Runs of equal rows among the entries [e0, e0 + len) of the list, len <= 64, lane e holding
     // entry e0 + e: one ballot per distinct row gives the lanes of its run.  The runs are laid out
     // one after the other in the order of their first entries, each in list order: mypos is the
     // lane's position in that layout, mysg the number of the run if the lane is its first entry
     // (else -1).  Returns the number of runs.
-    auto analyse = [&](const int (&wc)[NWAVE], int e0, int len, int &mysg, int &mypos, int &i1, int &i2, int &i3)
-                       __attribute__((always_inline)) {
+    auto analyse = [&](const int (&wc)[NWAVE], int e0, int len, int &mysg, int &mypos, int &i1, int &i2, int &i3,
+                       uint32_t &myk) __attribute__((always_inline)) {
         const uint32_t my = lane < len ? lds.rows[fb_slot(wc, e0 + lane)] : FB_NONE;
+        myk = (t0mode && lane < len) ? lds.klist[fb_slot(wc, e0 + lane)] : 0u;
         decode_f64(p, my, i1, i2, i3);
         uint64_t rem = __ballot(lane < len);
         int pos = 0, cnt = 0;
@@ -473,21 +512,23 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 early.dst = 4 * f;
             }
             int nsegs, mysg, mypos, i1, i2, i3;
+            uint32_t myk;
             if (W <= FB_PIECE || nw <= FB_PIECE) {
                 // one piece: every wave analyses it by itself (same result everywhere, no barrier)
-                nsegs = analyse(wc, i0, nw, mysg, mypos, i1, i2, i3);
+                nsegs = analyse(wc, i0, nw, mysg, mypos, i1, i2, i3, myk);
                 TT_STAMP(15);
                 if (lane < nw) lds.epos[lane] = mypos;
                 if (mysg >= 0) {                                           // first entry of its run
                     lds.seg_start[mysg] = mypos;
                     lds.seg_i1[mysg] = i1; lds.seg_i2[mysg] = i2; lds.seg_i3[mysg] = i3;
+                    if (t0mode) lds.seg_k[mysg] = myk;
                 }
                 if (lane == 0) lds.seg_start[nsegs] = nw;
             } else {
                 // several pieces of 64 entries: wave w analyses piece w; equal rows of different pieces
                 // stay separate runs (the gradient is linear in dY)
                 const int len = min(FB_PIECE, nw - w * FB_PIECE);          // <= 0: no piece for this wave
-                const int cnt = analyse(wc, i0 + w * FB_PIECE, len, mysg, mypos, i1, i2, i3);
+                const int cnt = analyse(wc, i0 + w * FB_PIECE, len, mysg, mypos, i1, i2, i3, myk);
                 if (lane == 0) lds.pcnt[w] = cnt;
                 __syncthreads();
                 int base = 0;
@@ -502,6 +543,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 if (mysg >= 0) {
                     lds.seg_start[base + mysg] = w * FB_PIECE + mypos;
                     lds.seg_i1[base + mysg] = i1; lds.seg_i2[base + mysg] = i2; lds.seg_i3[base + mysg] = i3;
+                    if (t0mode) lds.seg_k[base + mysg] = myk;
                 }
                 if (t == 0) lds.seg_start[nsegs] = nw;
                 __syncthreads();
@@ -510,9 +552,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
             float bm[UB][RQ][V];
-            if (ROLE != 1) bm_load(0, nsegs, bm);
+            if (ROLE != 1 && !t0mode) bm_load(0, nsegs, bm);
             TT_STAMP(3);
-            stage_items(i0, early_done ? 0 : nw * NQ, 0, min(SB, nsegs), wc);
+            stage_items(i0, early_done ? 0 : nw * NQ, 0, t0mode ? 0 : min(SB, nsegs), wc);
             if (early_done) {
                 const float4 g = item_finish(early);
                 if (t < nw * NQ) *reinterpret_cast<float4 *>(&stage[4 * (NQ * lds.epos[t / NQ] + t % NQ)]) = g;
@@ -541,7 +583,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 __syncthreads();
             }
             TT_STAMP(5);
-            for (int ub0 = 0; ub0 < nsegs; ub0 += UB) {
+            if (t0mode) consume_t0(nsegs);
+            for (int ub0 = 0; ub0 < (t0mode ? 0 : nsegs); ub0 += UB) {
                 const int sb0 = (ub0 / SB) * SB;
                 if (ub0 > 0) {
                     if (ROLE != 1) bm_load(ub0, nsegs, bm);
@@ -670,7 +713,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
     float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
     const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend,
-    float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3)
+    float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0)
 {
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
@@ -685,7 +728,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
     const int role = ge1 + ge2;
     const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, rowv);
+    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv);
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
         g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
@@ -699,10 +742,10 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
                               const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
                               const int *goff, const int *gend, float lr, float *o1, float *o2, float *o3,
-                              hipStream_t st)
+                              const float *t0, hipStream_t st)
 {
     hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(p.m1 + p.m2 + p.m3), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
-                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3);
+                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0);
 }
 
 static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >= 0; }
@@ -710,15 +753,16 @@ static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >
 static inline void fast_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx, int L,
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
                             float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
-                            const int *gend, float lr, float *o1, float *o2, float *o3, hipStream_t st)
+                            const int *gend, float lr, float *o1, float *o2, float *o3, const float *t0,
+                            hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
     default: break;
     }
 }

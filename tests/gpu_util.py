@@ -67,7 +67,14 @@ class DeviceTable:
         torch.cuda.synchronize()
         return out.cpu().numpy()
 
-    def bwd(self, cache=None, grad_cores=None, grad_cache=None, use_offsets=True):
+    def fwd_keep_t0(self, cache=None):
+        out = torch.full((self.n_bags, self.t.dim), float("nan"), dtype=torch.float32, device=dev())
+        t0 = torch.full((self.L, B.t0_floats(self.shape)), float("nan"), dtype=torch.float32, device=dev())
+        B.tt_emb_fwd_keep_t0(self.shape, self.g, self.idx, self.off, self.n_bags, out, t0, alpha=self.alpha, cache=cache)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), t0
+
+    def bwd(self, cache=None, grad_cores=None, grad_cache=None, use_offsets=True, t0=None):
         if grad_cores is None:
             grad_cores = [torch.zeros_like(x) for x in self.g]
         if cache is not None and grad_cache is None:
@@ -75,17 +82,17 @@ class DeviceTable:
         ws = torch.empty(B.workspace_bytes(self.shape, self.L, self.n_bags, cache.K if cache is not None else 0),
                          dtype=torch.uint8, device=dev())
         B.tt_emb_bwd(self.shape, self.g, self.idx, self.off if use_offsets else None, self.n_bags, self.go,
-                     grad_cores, alpha=self.alpha, cache=cache, grad_cache=grad_cache, workspace=ws)
+                     grad_cores, alpha=self.alpha, cache=cache, grad_cache=grad_cache, workspace=ws, t0=t0)
         torch.cuda.synchronize()
         return grad_cores, grad_cache
 
-    def bwd_sgd(self, lr, cache=None, use_offsets=True):
+    def bwd_sgd(self, lr, cache=None, use_offsets=True, t0=None):
         """Fused backward + SGD: returns the new cores (the cache lines are updated in place)."""
         out = [torch.full_like(x, float("nan")) for x in self.g]
         ws = torch.empty(B.bwd_sgd_workspace_bytes(self.shape, self.L, self.n_bags, cache.K if cache is not None else 0),
                          dtype=torch.uint8, device=dev())
         B.tt_emb_bwd_sgd(self.shape, self.g, out, self.idx, self.off if use_offsets else None, self.n_bags, self.go,
-                         lr, alpha=self.alpha, cache=cache, workspace=ws)
+                         lr, alpha=self.alpha, cache=cache, workspace=ws, t0=t0)
         torch.cuda.synchronize()
         return out
 

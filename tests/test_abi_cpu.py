@@ -138,3 +138,19 @@ def test_tracker_and_refill_argument_checks():
     assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, C.byref(cache), None, 0, None) == -4    # no workspace
     assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, None, one, 1 << 20, None) == -1
     assert l.tt_cache_refill_workspace_bytes(C.byref(s), 10, 4) > 0
+
+
+def test_kept_t0_entry_points_check_their_arguments():
+    l = B.lib()
+    s = good_shape()
+    arr = (C.c_void_p * 3)(8, 8, 8)
+    out = (C.c_void_p * 3)(16, 16, 16)
+    one = C.c_void_p(8)
+    f = C.c_float(0.1)
+    assert l.tt_emb_fwd_keep_t0(C.byref(s), arr, one, 1, None, 1, None, None, one, None, None) == -1      # no t0
+    assert l.tt_emb_bwd_t0(C.byref(s), arr, one, 1, None, 1, None, None, one, None, arr, None, None, 0, None) == -1
+    assert l.tt_emb_bwd_sgd_t0(C.byref(s), arr, out, one, 1, None, 1, None, None, one, None, f, None, 0, None) == -1
+    odd = B.make_shape(210, (6, 5, 7), (3, 2, 5), (1, 4, 7, 1))                                          # no specialised kernel
+    assert l.tt_emb_fwd_keep_t0(C.byref(odd), arr, one, 1, None, 1, None, None, one, one, None) == -6
+    assert l.tt_emb_bwd_t0(C.byref(odd), arr, one, 1, None, 1, None, None, one, one, arr, None, None, 0, None) == -6
+    assert l.tt_emb_bwd_sgd_t0(C.byref(odd), arr, out, one, 1, None, 1, None, None, one, one, f, None, 0, None) == -6

@@ -464,3 +464,67 @@ def test_cache_refill_matches_oracle(name, path):
     pick, idx, off, _ = sample_bags(d.batch, 64)
     out = d.fwd(cache=cache)
     assert_close(out[pick], ora.fwd(d.oshape, d.cores, idx, off, cache_keys=k2, cache_rows=got), "%s forward after refill" % name)
+
+
+# ------------------------------------------------------------------ stored intermediate (T0)
+
+@pytest.mark.parametrize("name", SINGLE)
+def test_forward_keeps_t0(name):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl)
+    out, t0 = d.fwd_keep_t0()
+    assert np.array_equal(out, d.fwd())                             # the output is the plain forward's, bit for bit
+    got = t0.cpu().numpy()
+    pick = np.random.default_rng(3).choice(d.L, min(d.L, 48), replace=False)
+    ref = np.stack([ora.t0(d.oshape, d.cores, int(d.batch.indices[k])).reshape(-1) for k in pick])
+    assert_close(got[pick], ref, "%s T0" % name)
+
+
+@pytest.mark.parametrize("name", SINGLE)
+def test_backward_with_kept_t0(name, path):
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl)
+    _, t0 = d.fwd_keep_t0()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output)
+    dg, _ = d.bwd(t0=t0)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "%s dG%d with kept T0" % (name, k + 1))
+    new = d.bwd_sgd(wl.lr, t0=t0)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], wl.lr), "%s fused core %d with kept T0" % (name, k + 1))
+    # only the third core's owners use T0: the other two gradients are the recomputing kernel's, bit for bit
+    # (a kept T0 always takes the specialised kernel, so the comparison needs it on the other side too)
+    if path != 0:
+        plain, _ = d.bwd()
+        assert torch.equal(dg[0], plain[0]) and torch.equal(dg[1], plain[1])
+
+
+def test_kept_t0_ragged_weighted_with_cache(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(17)
+    lens = np.array([0, 3, 0, 1, 700, 2, 0, 1500, 1, 0], dtype=np.int64)
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, t.num_rows, int(off[-1]))
+    idx[100:400] = 77
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(idx.size)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    rows, counts = np.unique(idx, return_counts=True)
+    K = 25
+    cache, _, _ = d.build_cache(K, rows.astype(np.int64), counts.astype(np.int64))
+    keys = ora.cache_select(rows, counts, K)
+    out, t0 = d.fwd_keep_t0(cache=cache)
+    if path != 0:                                                   # keeping T0 always takes the specialised kernel
+        assert np.array_equal(out, d.fwd(cache=cache))
+    assert_close(out, ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha, cache_keys=keys,
+                              cache_rows=cache.rows.cpu().numpy()[:K]), "kept T0 + cache forward")
+    got = t0.cpu().numpy()
+    cached = ora.cache_lookup(d.oshape, keys, idx) >= 0
+    assert np.isnan(got[cached]).all() and not np.isnan(got[~cached]).any()     # cached positions keep no T0
+    dg, dc = d.bwd(cache=cache, t0=t0)
+    rg, rc = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha, cache_keys=keys)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), rg[k], "kept T0 + cache dG%d" % (k + 1))
+    assert_close(dc.cpu().numpy()[:K], rc, "kept T0 + cache dCache")
