@@ -31,7 +31,9 @@ POOL = 16                      # distinct batches cycled through, so caches see 
 # HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the counter reads for a 256 MiB copy (factors 2.000 and 1.000); the runs and figures
 # are in profiles/hbm_traffic_bench_kaggle_r32.md.  Only valid for the workload they were taken on.
-MEASURED_TRAFFIC = {"kaggle_r32": {"fwd": 9.93e6, "bwd_sgd": 15.42e6, "bwd": 16.84e6, "sgd": 7.96e6}}
+MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 10.98e6, "bwd_sgd": 13.12e6},
+                                   "recompute": {"fwd": 9.93e6, "bwd_sgd": 15.42e6},
+                                   "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}}}
 
 
 def algorithmic_bytes(t, L, n_bags, touched_floats):
@@ -202,7 +204,8 @@ def main():
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get(dominant),
+                "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get(
+                    "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
                 "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms}}
