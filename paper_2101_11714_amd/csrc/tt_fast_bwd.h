@@ -245,6 +245,32 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
     bool any = false;
+    // Fused SGD step: every workgroup rewrites its slice, so the old values are loaded now and the
+    // last phase does not wait for them (where that takes few registers).
+    constexpr int KEEP1 = ReduceKeep<NACC1, WAVE>::value;
+    constexpr int PF3 = (C::sC + WG - 1) / WG;
+    constexpr int PFMAX = NACC2 > KEEP1 ? (NACC2 > PF3 ? NACC2 : PF3) : (KEEP1 > PF3 ? KEEP1 : PF3);
+    constexpr bool PREFETCH = PFMAX <= 8;
+    float old[PREFETCH ? PFMAX : 1];
+    if (PREFETCH && fused) {
+        if (ROLE == 1) {
+            const float *src = G2 + (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;    // inactive lanes: c0 = 0, in range
+#pragma unroll
+            for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                for (int v = 0; v < V; ++v) old[aa * V + v] = src[aa * C::COLS + v];
+        } else if (ROLE == 0) {
+            const int base = reduce_base<NACC1, WAVE>(lane < ReduceKeep<NACC1, WAVE>::writers ? lane : 0);
+#pragma unroll
+            for (int i = 0; i < KEEP1; ++i) {
+                const int idx = base + i;
+                old[i] = G1[(size_t)s * C::sA + (idx / RQ) * R + a0 + idx % RQ];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < PF3; ++i) old[i] = G3[(size_t)s * C::sC + min(t + i * WG, C::sC - 1)];
+        }
+    }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
     unsigned long long ts[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     TT_STAMP(0);
@@ -346,6 +372,18 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
+    // ACH consecutive values of a row of A from LDS: four at a time where the wave's part of the row allows it
+    constexpr int ACH = RQ % 4 == 0 ? 4 : RQ;
+    auto load_a = [&](const float *src, float (&ax)[ACH]) __attribute__((always_inline)) {
+        if constexpr (ACH == 4) {
+            const float4 av = *reinterpret_cast<const float4 *>(src);
+            ax[0] = av.x; ax[1] = av.y; ax[2] = av.z; ax[3] = av.w;
+        } else {
+#pragma unroll
+            for (int aa = 0; aa < ACH; ++aa) ax[aa] = src[aa];
+        }
+    };
+
     // Rows [ub0, ub0 + UB) of the window.  Every run has been summed into its first staged entry,
     // so each row reads exactly one dY.  No branches on the row count: rows past the end repeat
     // the last one with a zero weight, so the LDS reads of the batch can be in flight together.
@@ -373,12 +411,16 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                         for (int v = 0; v < V; ++v) t0[u][j1][v] = 0.f;
 #pragma unroll
-                    for (int aa = 0; aa < RQ; ++aa)
+                    for (int j1 = 0; j1 < N1; ++j1)
 #pragma unroll
-                        for (int j1 = 0; j1 < N1; ++j1) {
-                            const float av = sm[u][j1 * R + a0 + aa];
+                        for (int a4 = 0; a4 < RQ; a4 += ACH) {
+                            float ax[ACH];
+                            load_a(&sm[u][j1 * R + a0 + a4], ax);
 #pragma unroll
-                            for (int v = 0; v < V; ++v) t0[u][j1][v] = fmaf(av, bm[h + u][aa][v], t0[u][j1][v]);
+                            for (int q = 0; q < ACH; ++q)
+#pragma unroll
+                                for (int v = 0; v < V; ++v)
+                                    t0[u][j1][v] = fmaf(ax[q], bm[h + u][a4 + q][v], t0[u][j1][v]);
                         }
                 }
 #pragma unroll
@@ -413,12 +455,16 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                     for (int u = 0; u < UH; ++u)
 #pragma unroll
-                        for (int aa = 0; aa < RQ; ++aa)
+                        for (int j1 = 0; j1 < N1; ++j1)
 #pragma unroll
-                            for (int j1 = 0; j1 < N1; ++j1) {
-                                const float av = sm[u][j1 * R + a0 + aa];
+                            for (int a4 = 0; a4 < RQ; a4 += ACH) {
+                                float ax[ACH];
+                                load_a(&sm[u][j1 * R + a0 + a4], ax);
 #pragma unroll
-                                for (int v = 0; v < V; ++v) acc[aa * V + v] = fmaf(av, dt[u][j1][v], acc[aa * V + v]);
+                                for (int q = 0; q < ACH; ++q)
+#pragma unroll
+                                    for (int v = 0; v < V; ++v)
+                                        acc[(a4 + q) * V + v] = fmaf(ax[q], dt[u][j1][v], acc[(a4 + q) * V + v]);
                             }
                 } else {
 #pragma unroll
@@ -658,7 +704,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     const size_t i = at + aa * C::COLS + v;
-                    if (fused) o2[i] = fmaf(-lr, acc[aa * V + v], G2[i]);
+                    if (fused) o2[i] = fmaf(-lr, acc[aa * V + v], PREFETCH ? old[aa * V + v] : G2[i]);
                     else add_to(&dG2[i], acc[aa * V + v]);
                 }
         }
@@ -674,7 +720,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 const int idx = base + i;                                  // = j1 * RQ + aa
                 const int j1 = idx / RQ, aa = idx % RQ;
                 const size_t at = (size_t)s * C::sA + j1 * R + a0 + aa;
-                if (fused) o1[at] = fmaf(-lr, red[i], G1[at]);
+                if (fused) o1[at] = fmaf(-lr, red[i], PREFETCH ? old[i] : G1[at]);
                 else add_to(&dG1[at], red[i]);
             }
         }
@@ -689,16 +735,20 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 for (int j3 = 0; j3 < N3; ++j3) part[(w * C::COLS + c0 + v) * N3 + j3] = acc[v * N3 + j3];
         }
         __syncthreads();
-        for (int e = t; e < C::sC; e += WG) {
-            const int b = e / N3, j3 = e - b * N3;
-            float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < NWAVE; ++ww)
+        for (int i = 0; i < PF3; ++i) {
+            const int e = t + i * WG;
+            if (e < C::sC) {
+                const int b = e / N3, j3 = e - b * N3;
+                float sum = 0.f;
 #pragma unroll
-                for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
-            const size_t at = (size_t)s * C::sC + e;
-            if (fused) o3[at] = fmaf(-lr, sum, G3[at]);
-            else add_to(&dG3[at], sum);
+                for (int ww = 0; ww < NWAVE; ++ww)
+#pragma unroll
+                    for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
+                const size_t at = (size_t)s * C::sC + e;
+                if (fused) o3[at] = fmaf(-lr, sum, PREFETCH ? old[i] : G3[at]);
+                else add_to(&dG3[at], sum);
+            }
         }
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
