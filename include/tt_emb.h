@@ -255,6 +255,23 @@ int tt_cache_lookup(const tt_cache_t *cache, const int64_t *indices, int64_t L,
 
 /* ---- exports used by the parity tests ------------------------------------ */
 
+/*
+ * Uncompressed EmbeddingBag on the same GPU, the comparison of the microbenchmarks
+ * (Sections 6.6-6.7: the TT kernels against an ordinary EmbeddingBag for pooling
+ * factors 1, 10, 100 and for cache hit rates up to 99 %).  Not part of the TT path.
+ * table: fp32 [num_rows][N], N a power of two in [4, 256].
+ * tt_dense_bag_fwd:      output[b] = sum over the bag of alpha[k] * table[indices[k]].
+ * tt_dense_bag_bwd_sgd:  table[indices[k]] -= lr * alpha[k] * grad_output[bag(k)] for
+ *                        every position (sparse SGD with floating-point atomics: the
+ *                        order in which duplicates are applied is not fixed).
+ */
+int tt_dense_bag_fwd(const float *table, int64_t num_rows, int32_t N,
+                     const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                     const float *alpha, float *output, void *stream);
+int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
+                         const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                         const float *alpha, const float *grad_output, float lr, void *stream);
+
 /* Digits of every index (Section 3.1): i1, i2, i3 are int32 [L]. */
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                         int32_t *i1, int32_t *i2, int32_t *i3, void *stream);

@@ -25,7 +25,7 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
-           "tt_freq_reset", "tt_freq_update", "tt_freq_export",
+           "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
            "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
@@ -79,6 +79,8 @@ def lib():
         l.tt_cache_lookup.argtypes = [vp, vp, i64, vp, vp]
         l.tt_cache_refill.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
         l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
+        l.tt_dense_bag_fwd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, vp]
+        l.tt_dense_bag_bwd_sgd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp]
         l.tt_freq_reset.argtypes = [vp, vp]
         l.tt_freq_update.argtypes = [vp, vp, i64, vp]
         l.tt_freq_export.argtypes = [vp, vp, vp, vp, vp]
@@ -355,3 +357,22 @@ def tt_emb_debug_dedup(shape: TTShape, indices: torch.Tensor, which: int, slot: 
 def set_fast_path(mode: int) -> int:
     """0: generic kernels, 1: specialised (default), 2: specialised + grouping pre-pass always."""
     return int(lib().tt_emb_debug_set_fast_path(int(mode)))
+
+
+def tt_dense_bag_fwd(table: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,
+                     output: torch.Tensor, alpha: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(table, torch.float32)
+    _dev(indices, torch.int64)
+    _dev(output, torch.float32)
+    _check(lib().tt_dense_bag_fwd(_ptr(table), table.shape[0], table.shape[1], _ptr(indices), indices.numel(),
+                                  _ptr(offsets), n_bags, _ptr(alpha), _ptr(output), _stream()))
+    return output
+
+
+def tt_dense_bag_bwd_sgd(table: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,
+                         grad_output: torch.Tensor, lr: float, alpha: Optional[torch.Tensor] = None) -> None:
+    _dev(table, torch.float32)
+    _dev(indices, torch.int64)
+    _dev(grad_output, torch.float32)
+    _check(lib().tt_dense_bag_bwd_sgd(_ptr(table), table.shape[0], table.shape[1], _ptr(indices), indices.numel(),
+                                      _ptr(offsets), n_bags, _ptr(alpha), _ptr(grad_output), C.c_float(lr), _stream()))

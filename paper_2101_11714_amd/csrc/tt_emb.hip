@@ -16,6 +16,7 @@
 #include "tt_fast_bwd.h"
 #include "tt_group.h"
 #include "tt_freq.h"
+#include "tt_dense.h"
 
 using namespace tt;
 
@@ -618,6 +619,44 @@ int tt_freq_export(const tt_freq_t *tracker, int64_t *rows, int64_t *counts, int
                        (unsigned long long *)n_out);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "tracker export launch");
+}
+
+static int check_dense(const float *table, int64_t num_rows, int32_t N, const int64_t *indices, int64_t L,
+                       const int64_t *offsets, int64_t n_bags)
+{
+    if (num_rows <= 0 || N <= 0 || N % 4 || N > 256 || (N & (N - 1))) return fail(TT_ERR_BAD_ARG, "N must be a power of two in [4, 256]");
+    int rc = check_lookup_args(indices, L, n_bags, offsets);
+    if (rc) return rc;
+    if (!table) return fail(TT_ERR_NULL, "table is NULL");
+    return TT_OK;
+}
+
+int tt_dense_bag_fwd(const float *table, int64_t num_rows, int32_t N,
+                     const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                     const float *alpha, float *output, void *stream)
+{
+    int rc = check_dense(table, num_rows, N, indices, L, offsets, n_bags);
+    if (rc) return rc;
+    if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
+    if (n_bags == 0) return TT_OK;
+    hipLaunchKernelGGL(dense_fwd_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, table, (int)N,
+                       indices, offsets, (int)n_bags, alpha, output);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "dense forward launch");
+}
+
+int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
+                         const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                         const float *alpha, const float *grad_output, float lr, void *stream)
+{
+    int rc = check_dense(table, num_rows, N, indices, L, offsets, n_bags);
+    if (rc) return rc;
+    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (n_bags == 0 || L == 0) return TT_OK;
+    hipLaunchKernelGGL(dense_bwd_sgd_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, table, (int)N,
+                       indices, offsets, (int)n_bags, alpha, grad_output, lr);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "dense backward launch");
 }
 
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,

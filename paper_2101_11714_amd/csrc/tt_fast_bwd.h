@@ -63,7 +63,7 @@ struct FbCfg {
     static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
     static constexpr int BMR = C::RQ * C::V;                // registers per row for the wave's part of G2[i2]
     // register budget: three workgroups per CU (one wave each per SIMD) for the small slices, fewer for the large
-    static constexpr int WAVES_PER_SIMD = BMR <= 32 ? 3 : 1;
+    static constexpr int WAVES_PER_SIMD = BMR <= 32 ? 3 : 2;
     // rows of G2 in flight per wave: up to 4, within 32 registers (8 rows / 64 registers was measured: slower,
     // the extra loads and the idle row slots of short lists cost more than the saved round trip)
     static constexpr int BUDGET = 32;
@@ -112,13 +112,15 @@ __device__ __forceinline__ void fb_load_rows(const int64_t *__restrict__ indices
 
 // Stable selection of the positions in [lo, hi) (rows in rowv, see fb_load_rows) that select
 // slice s of the role's core.  Wave w appends its matches, in order, to its own sub-list
-// lds.klist / lds.rows [w * FB_WCAP ...): the list of the workgroup is the concatenation of the
-// four sub-lists (fb_slot), so one barrier is enough.  wc[] receives the sub-list lengths.
-// Returns the number of matches, or FB_CAP + 1 if a sub-list would overflow (nothing usable
-// has been written then).  `round` alternates the counters between calls.
+// lds.klist / lds.rows [w * FB_WCAP ...), which already holds fill[w] entries of earlier rounds:
+// the list of the workgroup is the concatenation of the four sub-lists (fb_slot), so one barrier
+// is enough.  wc[] receives the number of matches of every wave in this round.  If one of the
+// sub-lists would overflow, the entries written are to be ignored (they lie behind fill[]).
+// `round` alternates the counters between calls.
 template <typename C>
 __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
-                                         const uint32_t (&rowv)[FB_ITER], int lo, int hi, int round, int (&wc)[NWAVE]
+                                         const uint32_t (&rowv)[FB_ITER], int lo, int hi, int round,
+                                         const int (&fill)[NWAVE], int (&wc)[NWAVE]
 #if defined(TT_PROFILE) && TT_PROFILE == 2
                                          , unsigned long long *ts
 #endif
@@ -163,9 +165,12 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
         }
     }
     TT_STAMP(12);
-    if (cnt > 0 && cnt <= FB_WCAP) {                                        // uniform in the wave
+    int myfill = 0;
+#pragma unroll
+    for (int j = 0; j < NWAVE; ++j) myfill = j == w ? fill[j] : myfill;
+    if (cnt > 0 && myfill + cnt <= FB_WCAP) {                               // uniform in the wave
         const uint64_t lt = lanemask_lt();
-        int off = w * FB_WCAP;
+        int off = w * FB_WCAP + myfill;
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
             if (masks[it] == 0) continue;                                   // uniform: most are empty
@@ -182,14 +187,12 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
     __syncthreads();
     TT_STAMP(13);
     int total = 0;
-    bool fits = true;
 #pragma unroll
     for (int j = 0; j < NWAVE; ++j) {
         wc[j] = wcnt[j];
         total += wc[j];
-        fits = fits && wc[j] <= FB_WCAP;
     }
-    return fits ? total : FB_CAP + 1;
+    return total;
 }
 
 // LDS position of entry e of the workgroup's list, given the sub-list lengths (see fb_select)
@@ -647,42 +650,67 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
-    // The list of a round comes from the workgroup's own scan of FB_SCAN positions, or, if the
-    // lookups were grouped by a pre-pass (tt_group.h), from this slice's list
+    // The list comes from the workgroup's own scan of the index array, FB_SCAN positions per round,
+    // or, if the lookups were grouped by a pre-pass (tt_group.h), from this slice's list
     // gvals[goff[bin] .. gend[bin]) (payload = item number * L + k, in the order of k), FB_CAP entries
-    // at a time.  A scan round that selects too many entries (an adversarial index stream) is redone
-    // in pieces of FB_CAP positions, which always fit.  The caller has already loaded the rows of
-    // the first scan round into rowv.  One loop for both, so that the body exists once.
+    // at a time.  A scan keeps appending the matches of its rounds to the list and processes it
+    // when the next round no longer fits (and once at the end): the cost of a list is paid per
+    // list, not per round.  A round that alone selects too many entries (an adversarial index
+    // stream) is redone in pieces of FB_CAP positions, which always fit.  The caller has already
+    // loaded the rows of the first scan round into rowv.  One loop for both sources, so that the
+    // body exists once.
     const int bin = (ROLE == 0 ? 0 : (ROLE == 1 ? p.m1 : p.m1 + p.m2)) + s;
     const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
     int lo = gvals ? goff[bin] : 0;
     const int end = gvals ? gend[bin] : L;
     int span = gvals ? FB_CAP : FB_SCAN, round = 0;
+    int fill[NWAVE] = {0, 0, 0, 0};                                    // entries of the sub-lists (scan only)
     while (lo < end) {
         const int hi = min(end, lo + span);
-        int wc[NWAVE] = {0, 0, 0, 0};
-        int n;
+        int pw[NWAVE] = {0, 0, 0, 0}, pn = 0;                              // the list to process in this turn, if any
         if (gvals) {
-            n = hi - lo;
-            for (int i = t; i < n; i += WG) {
+            pn = hi - lo;
+            for (int i = t; i < pn; i += WG) {
                 const uint32_t k = gvals[lo + i] - sub;
                 lds.klist[i] = k;
                 lds.rows[i] = (uint32_t)indices[k];
             }
             __syncthreads();
-            wc[0] = n;                                                     // one contiguous list
+            pw[0] = pn;                                                    // one contiguous list
+            lo = hi;
         } else {
-            if (lo > 0 || span != FB_SCAN) fb_load_rows(indices, slot, lo, hi, rowv);
+            if (lo > 0 || span != FB_SCAN || round > 0) fb_load_rows(indices, slot, lo, hi, rowv);
+            int wc[NWAVE];
 #if defined(TT_PROFILE) && TT_PROFILE == 2
-            n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, wc, ts);
+            fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, fill, wc, ts);
 #else
-            n = fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, wc);
+            fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, fill, wc);
 #endif
-            if (n > FB_CAP) { span = FB_CAP; continue; }
+            bool too_big = false, over = false;
+#pragma unroll
+            for (int j = 0; j < NWAVE; ++j) {
+                too_big = too_big || wc[j] > FB_WCAP;
+                over = over || fill[j] + wc[j] > FB_WCAP;
+            }
+            if (too_big) {
+                span = FB_CAP;                                             // redo the round in pieces
+            } else {
+                if (!over) {                                               // the round's matches join the list
+#pragma unroll
+                    for (int j = 0; j < NWAVE; ++j) fill[j] += wc[j];
+                    lo = hi;
+                    if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+                }
+                if (over || lo >= end) {                                   // process what has been collected
+#pragma unroll                                                             // (after "over" the round is redone)
+                    for (int j = 0; j < NWAVE; ++j) { pw[j] = fill[j]; pn += fill[j]; fill[j] = 0; }
+                }
+            }
         }
-        if (n) { any = true; process(n, wc); }
-        lo = hi;
-        if (!gvals && span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+        if (pn > 0) {
+            any = true;
+            process(pn, pw);
+        }
     }
 #if defined(TT_PROFILE) && TT_PROFILE == 2
     auto flush = [&]() __attribute__((always_inline)) {

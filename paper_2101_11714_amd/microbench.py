@@ -1,0 +1,133 @@
+"""Microbenchmarks of the TT-EmbeddingBag kernels against an uncompressed EmbeddingBag on the
+same GPU (the studies of Sections 6.6 and 6.7 of the paper, on synthetic inputs):
+
+  pooling : pooling factor P in {1, 10, 100} x TT rank, Kaggle-shaped table (10,131,227 rows,
+            dimension 16), 2048 samples per step, Zipf(1.05) indices, no cache;
+  hitrate : cache hit rate 0 .. 99 %, a 10 M-row table of dimension 64 at rank 32 with a cache
+            of 0.01 % of its rows, 2048 samples per step, P in {10, 100}.
+
+A step is forward + backward + SGD.  TT: tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0; dense:
+tt_dense_bag_fwd + tt_dense_bag_bwd_sgd.  Every step sequence is captured in a HIP graph, so
+the figures are GPU times.  Prints a markdown table.
+
+    python -m paper_2101_11714_amd.microbench [pooling] [hitrate]
+"""
+
+from __future__ import annotations
+
+import dataclasses
+import sys
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+N_BAGS = 2048
+STEPS = 8            # steps per captured graph (distinct batches)
+
+
+def _graph_us(fn) -> float:
+    """GPU microseconds per call of fn(j), j = 0..STEPS-1, replayed from a HIP graph."""
+    for j in range(STEPS):
+        fn(j)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for j in range(STEPS):
+            fn(j)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * STEPS)
+
+
+class _Table:
+    def __init__(self, shape: W.TableShape, init: str, seed: int, dev):
+        self.shape, self.dev = shape, dev
+        self.c = B.shape_of(shape)
+        self.cores = [torch.from_numpy(x).to(dev) for x in W.make_cores(shape, init, seed)]
+        self.cores2 = [torch.empty_like(x) for x in self.cores]
+        self.dense = torch.empty((shape.num_rows, shape.dim), dtype=torch.float32, device=dev).normal_(0, 0.01)
+
+    def time(self, batches, cache=None, lr=1e-6):
+        dev, n_bags = self.dev, batches[0].offsets.size - 1
+        idx = [torch.from_numpy(b.indices).to(dev) for b in batches]
+        off = [torch.from_numpy(b.offsets).to(dev) for b in batches]
+        go = [torch.from_numpy(b.grad_output).to(dev) for b in batches]
+        L = idx[0].numel()
+        out = torch.empty((n_bags, self.shape.dim), dtype=torch.float32, device=dev)
+        t0 = [torch.empty((L, B.t0_floats(self.c)), dtype=torch.float32, device=dev) for _ in batches]
+        ws = torch.empty(B.bwd_sgd_workspace_bytes(self.c, L, n_bags, cache.K if cache else 0), dtype=torch.uint8, device=dev)
+
+        def tt_step(j):
+            cur, nxt = (self.cores, self.cores2) if j % 2 == 0 else (self.cores2, self.cores)
+            B.tt_emb_fwd_keep_t0(self.c, cur, idx[j], off[j], n_bags, out, t0[j], cache=cache)
+            B.tt_emb_bwd_sgd(self.c, cur, nxt, idx[j], off[j], n_bags, go[j], lr, cache=cache, workspace=ws, t0=t0[j])
+
+        def dense_step(j):
+            B.tt_dense_bag_fwd(self.dense, idx[j], off[j], n_bags, out)
+            B.tt_dense_bag_bwd_sgd(self.dense, idx[j], off[j], n_bags, go[j], lr)
+
+        return _graph_us(tt_step), _graph_us(dense_step)
+
+
+def pooling(dev):
+    print("## Pooling factor x TT rank (Kaggle-shaped table, %d samples per step, no cache)\n" % N_BAGS)
+    print("| P | lookups/step | R | TT step us | dense step us | TT / dense | TT us per sample | TT M lookups/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for R in (8, 16, 32, 64):
+        base = W.WORKLOADS["sweep_r%d" % R]
+        tab = _Table(base.tables[0], base.init, base.seed, dev)
+        for P in (1, 10, 100):
+            wl = dataclasses.replace(base, n_bags=N_BAGS, bag_len=(P, P))
+            batches = [W.make_batch(wl, 0, j) for j in range(STEPS)]
+            tt, dn = tab.time(batches)
+            L = N_BAGS * P
+            print("| %d | %d | %d | %.1f | %.1f | %.1f | %.4f | %.1f |" % (P, L, R, tt, dn, tt / dn, tt / N_BAGS, L / tt), flush=True)
+        del tab
+        torch.cuda.empty_cache()
+
+
+def hitrate(dev):
+    wl = W.WORKLOADS["multihot_cache"]
+    shape = wl.tables[0]
+    K = W.cache_size(wl, 0)
+    print("\n## Cache hit rate (table of %d rows, dimension %d, R = %d, cache of %d rows, %d samples per step)\n"
+          % (shape.num_rows, shape.dim, shape.r[1], K, N_BAGS))
+    print("| P | hit rate | TT+cache step us | dense step us | TT / dense | TT M lookups/s |")
+    print("|---|---|---|---|---|---|")
+    tab = _Table(shape, wl.init, wl.seed, dev)
+    rng = np.random.default_rng(77)
+    cached = np.sort(rng.choice(shape.num_rows, K, replace=False)).astype(np.int64)
+    cache = B.Cache(K, shape.dim, dev)
+    B.tt_cache_build(tab.c, tab.cores, torch.from_numpy(cached).to(dev),
+                     torch.ones(K, dtype=torch.int64, device=dev), cache)
+    for P in (10, 100):
+        for h in (0.0, 0.5, 0.75, 0.9, 0.95, 0.99):
+            batches = [W.make_hit_rate_batch(shape, cached, N_BAGS, P, h, 100 + j) for j in range(STEPS)]
+            tt, dn = tab.time(batches, cache=cache)
+            L = N_BAGS * P
+            print("| %d | %.0f %% | %.1f | %.1f | %.1f | %.1f |" % (P, 100 * h, tt, dn, tt / dn, L / tt), flush=True)
+
+
+def main():
+    assert torch.cuda.is_available(), "the microbenchmarks need a GPU"
+    dev = torch.device("cuda:0")
+    which = sys.argv[1:] or ["pooling", "hitrate"]
+    print("# TT-EmbeddingBag against an uncompressed EmbeddingBag on one MI355X (forward + backward + SGD per step)\n")
+    if "pooling" in which:
+        pooling(dev)
+    if "hitrate" in which:
+        hitrate(dev)
+
+
+if __name__ == "__main__":
+    main()

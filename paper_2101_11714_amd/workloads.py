@@ -221,3 +221,24 @@ def warmup_counts(wl: Workload, table: int = 0) -> Tuple[np.ndarray, np.ndarray]
 
 def cache_size(wl: Workload, table: int = 0) -> int:
     return int(math.ceil(wl.cache_fraction * wl.tables[table].num_rows)) if wl.cache_fraction else 0
+
+
+def make_hit_rate_batch(shape: TableShape, cached_rows: np.ndarray, n_bags: int, bag_len: int, hit_rate: float,
+                        seed: int) -> Batch:
+    """A batch whose share of cached positions is controlled (the synthetic samples of the paper's
+    hit-rate study, Section 6.7): every position is, with probability hit_rate, a row drawn uniformly
+    from cached_rows, else a row drawn uniformly from the rest of the table."""
+    rng = np.random.default_rng([seed, 700, n_bags, bag_len, int(round(hit_rate * 10000))])
+    L = n_bags * bag_len
+    cached_rows = np.asarray(cached_rows, dtype=np.int64)
+    idx = rng.integers(0, shape.num_rows, L, dtype=np.int64)
+    is_cached = np.isin(idx, cached_rows)
+    while is_cached.any():                                   # a miss must really miss
+        idx[is_cached] = rng.integers(0, shape.num_rows, int(is_cached.sum()), dtype=np.int64)
+        is_cached = np.isin(idx, cached_rows)
+    hit = rng.random(L) < hit_rate
+    if cached_rows.size:
+        idx[hit] = cached_rows[rng.integers(0, cached_rows.size, int(hit.sum()))]
+    offsets = np.arange(n_bags + 1, dtype=np.int64) * bag_len
+    grad = rng.standard_normal((n_bags, shape.dim)).astype(np.float32)
+    return Batch(idx, offsets, grad, None)

@@ -528,3 +528,36 @@ def test_kept_t0_ragged_weighted_with_cache(path):
     for k in range(3):
         assert_close(dg[k].cpu().numpy(), rg[k], "kept T0 + cache dG%d" % (k + 1))
     assert_close(dc.cpu().numpy()[:K], rc, "kept T0 + cache dCache")
+
+
+# ------------------------------------------------------------------ the uncompressed comparison kernels
+
+@pytest.mark.parametrize("N,lens", [(16, (1, 1)), (16, (0, 7)), (64, (0, 30)), (256, (1, 3))])
+def test_dense_embedding_bag_matches_its_definition(N, lens):
+    rng = np.random.default_rng(61)
+    rows, n_bags = 5000, 300
+    table = rng.standard_normal((rows, N)).astype(np.float32)
+    bl = rng.integers(lens[0], lens[1] + 1, n_bags)
+    off = np.zeros(n_bags + 1, dtype=np.int64)
+    np.cumsum(bl, out=off[1:])
+    L = int(off[-1])
+    idx = rng.integers(0, rows, L).astype(np.int64)
+    idx[: L // 3] = 17                                             # a hot row
+    alpha = (0.5 + rng.random(L)).astype(np.float32)
+    go = rng.standard_normal((n_bags, N)).astype(np.float32)
+    bag = np.repeat(np.arange(n_bags), bl)
+    ref_out = np.zeros((n_bags, N))
+    np.add.at(ref_out, bag, alpha[:, None].astype(np.float64) * table[idx])
+    d = dev()
+    tb = torch.from_numpy(table).to(d)
+    out = torch.full((n_bags, N), float("nan"), dtype=torch.float32, device=d)
+    B.tt_dense_bag_fwd(tb, torch.from_numpy(idx).to(d), torch.from_numpy(off).to(d), n_bags, out, alpha=torch.from_numpy(alpha).to(d))
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), ref_out, "dense forward")
+    lr = 0.05
+    ref_tab = table.astype(np.float64)
+    np.add.at(ref_tab, idx, -lr * alpha[:, None].astype(np.float64) * go[bag])
+    B.tt_dense_bag_bwd_sgd(tb, torch.from_numpy(idx).to(d), torch.from_numpy(off).to(d), n_bags, torch.from_numpy(go).to(d), lr,
+                           alpha=torch.from_numpy(alpha).to(d))
+    torch.cuda.synchronize()
+    assert_close(tb.cpu().numpy(), ref_tab, "dense sparse SGD")
