@@ -98,7 +98,7 @@ int64_t tt_cache_table_capacity(int64_t K);
 /* Bytes of device workspace that is always enough for tt_emb_fwd / tt_emb_bwd with L
  * positions in n_bags bags and a cache of cache_rows rows (0 = no cache).  tt_emb_fwd needs
  * none.  tt_emb_bwd needs none for a short index stream without a cache; with a cache, or from
- * 16384 positions on (it then groups the positions with a device sort first), it reports
+ * 32768 positions on (16384 with a cache; it then groups the positions with a device sort first), it reports
  * TT_ERR_WORKSPACE if the workspace is missing or too small.  Returns 0 on a bad shape. */
 size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows);
 
@@ -182,7 +182,7 @@ int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], floa
  *            cores (other workgroups still read the old slices); a training loop
  *            swaps the two sets after each step.
  * workspace: tt_emb_bwd_sgd_workspace_bytes(...) bytes (0 needed without a cache,
- *            below 16,384 positions, for the shapes with a specialised kernel).
+ *            below 32,768 positions, for the shapes with a specialised kernel).
  * L == 0 copies the cores.
  */
 int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],

@@ -24,7 +24,9 @@ namespace {
 
 thread_local char g_err[512] = "";
 int g_fast_path = 1;                       // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
-constexpr int64_t GROUP_MIN_L = 16384;    // from this many positions on the backward groups them first (tt_group.h)
+// from this many positions on the backward groups them first (tt_group.h)
+constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
+constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
 
 int fail(int code, const char *fmt, ...)
 {
@@ -256,7 +258,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if (!fused && cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
     if (t0 && !fast_bwd_supported(p)) return fail(TT_ERR_UNSUPPORTED, "no kernel uses a kept T0 for this shape");
     const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
-    const bool grouped = fast && (g_fast_path == 2 || L >= GROUP_MIN_L);
+    const bool grouped = fast && (g_fast_path == 2 || L >= (cd.K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
     const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
     const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
     // the fused step keeps the gradient of the cached rows, and without a specialised kernel the
