@@ -6,7 +6,7 @@
 // the device radix sort: every position k contributes three items keyed by the slice it
 // touches in core 1, 2 and 3, or, if its row is cached (Section 4.2 of the paper), one item
 // keyed by its cache slot.  After a stable sort by key the items of one key are one
-// contiguous list, in the order of k: exactly the list the owner's own scan would build.
+// contiguous list, in the order of k: the list a scan of the positions in order would build.
 //
 // Keys: [0, m1) slices of G1, [m1, m1+m2) of G2, [m1+m2, nb3) of G3 (nb3 = m1+m2+m3),
 // [nb3, nb3+K) cache slots, nb3+K = unused item (sorts last).  The payload of an item is
