@@ -245,3 +245,18 @@ def t0(shape: Shape, cores, row_id: int) -> np.ndarray:
     A = np.asarray(cores[0], dtype=np.float64).reshape(shape.m[0], n1, R1)[i1]
     Bm = np.asarray(cores[1], dtype=np.float64).reshape(shape.m[1], R1, n2 * R2)[i2]
     return (A @ Bm).reshape(n1 * n2, R2)
+
+
+# ---- mean pooling (Section 4.1: a bag is pooled by summation or by averaging) --------------
+
+def mean_weights(offsets, alpha=None) -> np.ndarray:
+    """Per-position weights that turn the weighted sum of Eq. 5 into the bag average:
+    w[k] = alpha[k] / (number of positions of the bag of k)."""
+    offsets = _i64(offsets)
+    L = int(offsets[-1])
+    w = np.ones(L, dtype=np.float64) if alpha is None else np.asarray(alpha, dtype=np.float64).copy()
+    for b in range(offsets.size - 1):
+        lo, hi = int(offsets[b]), int(offsets[b + 1])
+        if hi > lo:
+            w[lo:hi] /= float(hi - lo)
+    return w.astype(np.float32)

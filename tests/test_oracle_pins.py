@@ -441,3 +441,27 @@ def test_stored_intermediate_times_last_core_is_the_row():
         # element by element from the definition: T0[(j1,j2), b] = sum_a G1[i1][j1][a] G2[i2][a][j2][b]
         ref = np.einsum("ja,akb->jkb", cores[0].astype(np.float64)[i1, 0], cores[1].astype(np.float64)[i2]).reshape(6, 6)
         assert np.allclose(T0, ref, rtol=1e-13, atol=1e-13)
+
+
+def test_mean_pooling_matches_library_mean_mode():
+    wl, shape, cores, batch = tiny()
+    w = torch.from_numpy(dense_table(shape, cores))
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(batch.indices), w,
+                                            torch.from_numpy(batch.offsets[:-1]), mode="mean")
+    mw = ora.mean_weights(batch.offsets)
+    lens = np.diff(batch.offsets)
+    assert np.allclose(np.add.reduceat(mw.astype(np.float64), batch.offsets[:-1][lens > 0]), 1.0, atol=1e-6)
+    out = ora.fwd(shape, cores, batch.indices, batch.offsets, alpha=mw)
+    np.testing.assert_allclose(out, ref.numpy(), rtol=1e-6, atol=1e-8)   # the weights are rounded to fp32
+    # gradients of the mean through library autograd
+    ct = [torch.tensor(np.asarray(c, dtype=np.float64), requires_grad=True) for c in cores]
+    o = torch.nn.functional.embedding_bag(torch.from_numpy(batch.indices), dense_table_torch(ct),
+                                          torch.from_numpy(batch.offsets[:-1]), mode="mean")
+    (o * torch.from_numpy(batch.grad_output.astype(np.float64))).sum().backward()
+    g, _ = ora.bwd(shape, cores, batch.indices, batch.offsets, batch.grad_output, alpha=mw)
+    for k in range(3):
+        np.testing.assert_allclose(g[k], ct[k].grad.numpy(), rtol=1e-5, atol=1e-8)
+    # with per-position weights on top, and an empty bag
+    off = np.array([0, 3, 3, 4], dtype=np.int64)
+    al = np.array([2.0, 4.0, 6.0, 8.0], dtype=np.float32)
+    assert np.allclose(ora.mean_weights(off, al), [2 / 3, 4 / 3, 2.0, 8.0])
