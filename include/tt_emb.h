@@ -144,6 +144,15 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Mean pooling (Section 4.1: the rows of a bag are pooled by summation or by
+ * averaging).  weights[k] = alpha[k] / (number of positions of the bag of k), alpha
+ * == NULL meaning 1: passed as `alpha` to the forward and backward entry points they
+ * give the bag average and its gradients.  offsets as above (n_bags + 1 entries,
+ * offsets[n_bags] = L); weights: fp32 [L]; an empty bag has no positions to weigh.
+ */
+int tt_emb_mean_weights(const int64_t *offsets, int64_t n_bags, int64_t L, const float *alpha, float *weights, void *stream);
+
+/*
  * The stored-intermediate variant (Section 4.2, first paragraph: the recomputation
  * in Alg. 2 can be eliminated by storing tensors from the forward pass, at the price
  * of a larger memory footprint).  tt_emb_fwd_keep_t0 is tt_emb_fwd that also writes,

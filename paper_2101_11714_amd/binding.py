@@ -25,7 +25,7 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
-           "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
+           "tt_emb_mean_weights", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
            "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
@@ -81,6 +81,7 @@ def lib():
         l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
         l.tt_dense_bag_fwd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, vp]
         l.tt_dense_bag_bwd_sgd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp]
+        l.tt_emb_mean_weights.argtypes = [vp, i64, i64, vp, vp, vp]
         l.tt_freq_reset.argtypes = [vp, vp]
         l.tt_freq_update.argtypes = [vp, vp, i64, vp]
         l.tt_freq_export.argtypes = [vp, vp, vp, vp, vp]
@@ -376,3 +377,14 @@ def tt_dense_bag_bwd_sgd(table: torch.Tensor, indices: torch.Tensor, offsets: Op
     _dev(grad_output, torch.float32)
     _check(lib().tt_dense_bag_bwd_sgd(_ptr(table), table.shape[0], table.shape[1], _ptr(indices), indices.numel(),
                                       _ptr(offsets), n_bags, _ptr(alpha), _ptr(grad_output), C.c_float(lr), _stream()))
+
+
+def tt_emb_mean_weights(offsets: torch.Tensor, n_bags: int, L: int, weights: torch.Tensor,
+                        alpha: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(offsets, torch.int64)
+    _dev(weights, torch.float32)
+    assert offsets.numel() == n_bags + 1 and weights.numel() >= L
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _check(lib().tt_emb_mean_weights(_ptr(offsets), n_bags, L, _ptr(alpha), _ptr(weights), _stream()))
+    return weights

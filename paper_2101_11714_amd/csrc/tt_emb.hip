@@ -661,6 +661,18 @@ int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
     return e == hipSuccess ? TT_OK : hip_fail(e, "dense backward launch");
 }
 
+int tt_emb_mean_weights(const int64_t *offsets, int64_t n_bags, int64_t L, const float *alpha, float *weights, void *stream)
+{
+    if (n_bags < 0 || L < 0) return fail(TT_ERR_BAD_ARG, "negative count");
+    if (n_bags >= (1ll << 31) || L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "count >= 2^31");
+    if (L == 0 || n_bags == 0) return TT_OK;
+    if (!offsets || !weights) return fail(TT_ERR_NULL, "NULL array");
+    hipLaunchKernelGGL(mean_weights_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, offsets,
+                       (int)n_bags, alpha, weights);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "mean weights launch");
+}
+
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                         int32_t *i1, int32_t *i2, int32_t *i3, void *stream)
 {

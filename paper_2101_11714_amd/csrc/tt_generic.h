@@ -283,6 +283,19 @@ __global__ __launch_bounds__(WG) void sgd_out_kernel(const float *x, const float
         out[i] = fmaf(-lr, g[i], x[i]);
 }
 
+// w[k] = alpha[k] / (length of the bag of k): the weights that turn sum pooling into mean pooling.
+// One wave per bag.
+__global__ __launch_bounds__(WG) void mean_weights_kernel(const int64_t *__restrict__ offsets, int n_bags,
+                                                          const float *__restrict__ alpha, float *__restrict__ w)
+{
+    const int lane = threadIdx.x & 63;
+    const int bag = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    if (bag >= n_bags) return;
+    const int64_t k0 = offsets[bag], k1 = offsets[bag + 1];
+    const float len = (float)(k1 - k0);
+    for (int64_t k = k0 + lane; k < k1; k += WAVE) w[k] = (alpha ? alpha[k] : 1.f) / len;
+}
+
 // ---- cache map --------------------------------------------------------------------------
 
 __global__ __launch_bounds__(WG) void fill_u64_kernel(uint64_t *__restrict__ p, int64_t n, uint64_t v)

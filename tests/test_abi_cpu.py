@@ -154,3 +154,12 @@ def test_kept_t0_entry_points_check_their_arguments():
     assert l.tt_emb_fwd_keep_t0(C.byref(odd), arr, one, 1, None, 1, None, None, one, one, None) == -6
     assert l.tt_emb_bwd_t0(C.byref(odd), arr, one, 1, None, 1, None, None, one, one, arr, None, None, 0, None) == -6
     assert l.tt_emb_bwd_sgd_t0(C.byref(odd), arr, out, one, 1, None, 1, None, None, one, one, f, None, 0, None) == -6
+
+
+def test_mean_weights_argument_checks():
+    l = B.lib()
+    one = C.c_void_p(8)
+    assert l.tt_emb_mean_weights(one, -1, 4, None, one, None) == -3
+    assert l.tt_emb_mean_weights(None, 2, 4, None, one, None) == -1
+    assert l.tt_emb_mean_weights(one, 2, 4, None, None, None) == -1
+    assert l.tt_emb_mean_weights(None, 0, 0, None, None, None) == 0

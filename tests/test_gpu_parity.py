@@ -561,3 +561,30 @@ def test_dense_embedding_bag_matches_its_definition(N, lens):
                            alpha=torch.from_numpy(alpha).to(d))
     torch.cuda.synchronize()
     assert_close(tb.cpu().numpy(), ref_tab, "dense sparse SGD")
+
+
+# ------------------------------------------------------------------ mean pooling
+
+def test_mean_pooling_weights_and_passes(path):
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(71)
+    lens = np.array([0, 3, 0, 1, 130, 2, 0, 65, 1, 0], dtype=np.int64)
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, t.num_rows, int(off[-1]))
+    alpha = (0.5 + rng.random(idx.size)).astype(np.float32)
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32), None)
+    d = DeviceTable(wl, batch=batch)
+    for al in (None, alpha):
+        w = torch.full((d.L,), float("nan"), dtype=torch.float32, device=dev())
+        B.tt_emb_mean_weights(d.off, d.n_bags, d.L, w, alpha=None if al is None else torch.from_numpy(al).to(dev()))
+        torch.cuda.synchronize()
+        ref_w = ora.mean_weights(off, al)
+        np.testing.assert_allclose(w.cpu().numpy(), ref_w, rtol=2e-7)      # one division, one rounding
+        d.alpha = w
+        assert_close(d.fwd(), ora.fwd(d.oshape, d.cores, idx, off, alpha=ref_w), "mean forward")
+        dg, _ = d.bwd()
+        rg, _ = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=ref_w)
+        for k in range(3):
+            assert_close(dg[k].cpu().numpy(), rg[k], "mean dG%d" % (k + 1))
