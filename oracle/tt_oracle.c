@@ -25,6 +25,7 @@
  * not here, and are "parity unpinned" harness conventions.
  */
 
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -330,4 +331,58 @@ int64_t ora_dedup(const int64_t *keys, int64_t L, int64_t *uniq, int32_t *count,
     *n_kept = n;
     free(kp);
     return u;
+}
+
+
+/* ---- sampled Gaussian initialisation (Section 3.2, Alg. 3) ----------------
+ * Every entry of every core is drawn from N(0,1) and redrawn while it lies
+ * within two standard deviations of zero (the text wants fewer values close to
+ * zero, so the test is on |x|; the listing prints it without the absolute
+ * value); then the cores are scaled so that an entry of the reconstructed table
+ * has variance 1/(3 num_rows), the N(0, 1/3n) target of Section 3.2: an entry is
+ * a sum of R1 R2 products of three core entries of second moment v each, hence
+ * scale = (1 / (3 num_rows R1 R2 v^3))^(1/6) with v = E[z^2 | |z| > 2].
+ *
+ * The random numbers come from a counter-based generator, so that any other
+ * implementation can draw the same ones: for core c, element e, attempt t,
+ *   h  = mix(mix(seed + GOLD (c + 1)) ^ e),  a = mix(h + T_MUL t),  b = mix(a ^ B_XOR),
+ *   u1 = ((a >> 11) + 0.5) 2^-53,  u2 = (b >> 11) 2^-53,
+ *   z  = sqrt(-2 ln u1) cos(2 pi u2)            (Box-Muller, in fp64),
+ * mix being the finaliser of SplitMix64. */
+static uint64_t ora_mix64(uint64_t x)
+{
+    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27; x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+double ora_sampled_gaussian_draw(uint64_t seed, int core, uint64_t element, int *attempts)
+{
+    const uint64_t h = ora_mix64(ora_mix64(seed + 0x9E3779B97F4A7C15ull * (uint64_t)(core + 1)) ^ element);
+    for (int t = 0;; ++t) {
+        const uint64_t a = ora_mix64(h + 0xD1342543DE82EF95ull * (uint64_t)t);
+        const uint64_t b = ora_mix64(a ^ 0xA0761D6478BD642Full);
+        const double u1 = ((double)(a >> 11) + 0.5) * (1.0 / 9007199254740992.0);
+        const double u2 = (double)(b >> 11) * (1.0 / 9007199254740992.0);
+        const double z = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+        if (fabs(z) > 2.0) {
+            if (attempts) *attempts = t + 1;
+            return z;
+        }
+    }
+}
+
+double ora_sampled_gaussian_scale(int64_t num_rows, int R1, int R2)
+{
+    const double phi2 = exp(-2.0) / sqrt(6.283185307179586476925286766559);     /* density of N(0,1) at 2 */
+    const double tail = 0.5 * erfc(2.0 / sqrt(2.0));                            /* P(z > 2) */
+    const double v = 1.0 + 2.0 * phi2 / tail;                                   /* E[z^2 | |z| > 2] */
+    return pow(1.0 / (3.0 * (double)num_rows * (double)R1 * (double)R2 * v * v * v), 1.0 / 6.0);
+}
+
+void ora_init_sampled_gaussian(uint64_t seed, int core, int64_t count, double scale, float *out)
+{
+    for (int64_t e = 0; e < count; ++e)
+        out[e] = (float)(ora_sampled_gaussian_draw(seed, core, (uint64_t)e, 0) * scale);
 }

@@ -24,7 +24,7 @@ def build(force: bool = False) -> str:
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC])
+                               "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -260,3 +260,31 @@ def mean_weights(offsets, alpha=None) -> np.ndarray:
         if hi > lo:
             w[lo:hi] /= float(hi - lo)
     return w.astype(np.float32)
+
+
+# ---- sampled Gaussian initialisation (Section 3.2, Alg. 3) ---------------------------------
+
+def sampled_gaussian_scale(shape: Shape) -> float:
+    l = _load()
+    l.ora_sampled_gaussian_scale.restype = C.c_double
+    return float(l.ora_sampled_gaussian_scale(C.c_int64(shape.num_rows), C.c_int(shape.r[1]), C.c_int(shape.r[2])))
+
+
+def sampled_gaussian_draw(seed: int, core: int, element: int) -> Tuple[float, int]:
+    """One accepted N(0,1) draw with |z| > 2 and the number of attempts it took."""
+    l = _load()
+    l.ora_sampled_gaussian_draw.restype = C.c_double
+    att = C.c_int(0)
+    z = l.ora_sampled_gaussian_draw(C.c_uint64(seed), C.c_int(core), C.c_uint64(element), C.byref(att))
+    return float(z), int(att.value)
+
+
+def init_sampled_gaussian(shape: Shape, seed: int) -> List[np.ndarray]:
+    """The three cores after Alg. 3 (flat fp32 arrays in storage order)."""
+    scale = sampled_gaussian_scale(shape)
+    cores = []
+    for k in range(3):
+        out = np.empty(shape.core_size(k), dtype=np.float32)
+        _load().ora_init_sampled_gaussian(C.c_uint64(seed), C.c_int(k), C.c_int64(out.size), C.c_double(scale), _p(out))
+        cores.append(out)
+    return cores

@@ -465,3 +465,39 @@ def test_mean_pooling_matches_library_mean_mode():
     off = np.array([0, 3, 3, 4], dtype=np.int64)
     al = np.array([2.0, 4.0, 6.0, 8.0], dtype=np.float32)
     assert np.allclose(ora.mean_weights(off, al), [2 / 3, 4 / 3, 2.0, 8.0])
+
+
+# ---- sampled Gaussian initialisation (Section 3.2, Alg. 3) ---------------------------------
+
+def test_sampled_gaussian_draws_are_the_tail_of_a_standard_normal():
+    import math
+    n = 20000
+    z, att = zip(*(ora.sampled_gaussian_draw(2024, 1, e) for e in range(n)))
+    z, att = np.array(z), np.array(att)
+    assert np.all(np.abs(z) > 2.0)                                  # nothing within two sigma of zero
+    p_tail = math.erfc(2.0 / math.sqrt(2.0))                        # P(|z| > 2) = 0.0455
+    assert abs(att.mean() - 1.0 / p_tail) < 0.05 / p_tail           # geometric number of attempts: the draws are N(0,1)
+    assert abs((z > 0).mean() - 0.5) < 0.015                        # symmetric
+    v = 1.0 + 2.0 * math.exp(-2.0) / math.sqrt(2.0 * math.pi) / (0.5 * p_tail)
+    assert abs((z * z).mean() - v) < 0.03 * v                       # E[z^2 | |z| > 2] = 5.75 (closed form)
+    # tail shape: P(|z| > 2.5 | |z| > 2) from the normal distribution
+    assert abs((np.abs(z) > 2.5).mean() - math.erfc(2.5 / math.sqrt(2.0)) / p_tail) < 0.015
+    # different cores, elements and seeds give different streams; the same arguments the same value
+    assert ora.sampled_gaussian_draw(2024, 1, 5) == ora.sampled_gaussian_draw(2024, 1, 5)
+    assert len({ora.sampled_gaussian_draw(s, c, e)[0] for s in (1, 2) for c in (0, 1, 2) for e in (0, 1)}) == 12
+
+
+def test_sampled_gaussian_cores_give_the_target_variance():
+    # Section 3.2: the product of the cores should approximate N(0, 1/(3 n)), n = number of rows
+    shape = ora.Shape(20 * 20 * 25, (20, 20, 25), (2, 2, 4), (1, 8, 8, 1))
+    cores = ora.init_sampled_gaussian(shape, 7)
+    scale = ora.sampled_gaussian_scale(shape)
+    assert np.all(np.abs(cores[1]) > 2.0 * scale * (1 - 1e-6))
+    g = [c.reshape(shape.m[k], shape.r[k], shape.n[k], shape.r[k + 1]).astype(np.float64) for k, c in enumerate(cores)]
+    rng = np.random.default_rng(3)
+    rows = rng.integers(0, shape.num_rows, 4000)
+    i1, i2, i3 = rows // 500, (rows // 25) % 20, rows % 25
+    w = np.einsum("kja,kaxb,kby->kjxy", g[0][i1, 0], g[1][i2], g[2][i3, :, :, 0]).reshape(rows.size, -1)
+    target = 1.0 / (3.0 * shape.num_rows)
+    assert abs(w.var() / target - 1.0) < 0.1
+    assert abs(w.mean()) < 0.05 * np.sqrt(target)
