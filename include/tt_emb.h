@@ -144,6 +144,17 @@ int tt_emb_bwd(const tt_shape_t *shape, const float *const cores[3],
                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Sampled Gaussian initialisation of the cores (Section 3.2, Alg. 3): every entry is
+ * drawn from N(0,1), redrawn while it lies within two standard deviations of zero,
+ * and scaled by (1 / (3 num_rows r1 r2 v^3))^(1/6), v = E[z^2 | |z| > 2] = 5.75, so
+ * that an entry of the reconstructed table has variance 1 / (3 num_rows).  The draws
+ * come from a counter-based generator keyed by (seed, core, element, attempt) and are
+ * therefore the same on every run and launch shape (its definition is in the
+ * library's tt_init.h).  cores: host array of 3 device pointers, overwritten.
+ */
+int tt_init_sampled_gaussian(const tt_shape_t *shape, float *const cores[3], uint64_t seed, void *stream);
+
+/*
  * Mean pooling (Section 4.1: the rows of a bag are pooled by summation or by
  * averaging).  weights[k] = alpha[k] / (number of positions of the bag of k), alpha
  * == NULL meaning 1: passed as `alpha` to the forward and backward entry points they

@@ -25,7 +25,7 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
-           "tt_emb_mean_weights", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
+           "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
            "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
@@ -81,6 +81,7 @@ def lib():
         l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
         l.tt_dense_bag_fwd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, vp]
         l.tt_dense_bag_bwd_sgd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp]
+        l.tt_init_sampled_gaussian.argtypes = [vp, vp, C.c_uint64, vp]
         l.tt_emb_mean_weights.argtypes = [vp, i64, i64, vp, vp, vp]
         l.tt_freq_reset.argtypes = [vp, vp]
         l.tt_freq_update.argtypes = [vp, vp, i64, vp]
@@ -388,3 +389,7 @@ def tt_emb_mean_weights(offsets: torch.Tensor, n_bags: int, L: int, weights: tor
         _dev(alpha, torch.float32)
     _check(lib().tt_emb_mean_weights(_ptr(offsets), n_bags, L, _ptr(alpha), _ptr(weights), _stream()))
     return weights
+
+
+def tt_init_sampled_gaussian(shape: TTShape, cores: Sequence[torch.Tensor], seed: int) -> None:
+    _check(lib().tt_init_sampled_gaussian(C.byref(shape), _ptr_array(cores), C.c_uint64(seed), _stream()))

@@ -17,6 +17,7 @@
 #include "tt_group.h"
 #include "tt_freq.h"
 #include "tt_dense.h"
+#include "tt_init.h"
 
 using namespace tt;
 
@@ -671,6 +672,23 @@ int tt_emb_mean_weights(const int64_t *offsets, int64_t n_bags, int64_t L, const
                        (int)n_bags, alpha, weights);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "mean weights launch");
+}
+
+int tt_init_sampled_gaussian(const tt_shape_t *shape, float *const cores[3], uint64_t seed, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    const double scale = sampled_gaussian_scale(shape->num_rows, p.R1, p.R2);
+    const int64_t count[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
+    for (int k = 0; k < 3; ++k) {
+        const int grid = cdiv(count[k], WG) < 4096 ? cdiv(count[k], WG) : 4096;
+        hipLaunchKernelGGL(init_sampled_gaussian_kernel, dim3(grid), dim3(WG), 0, (hipStream_t)stream, cores[k], count[k], k,
+                           seed, scale);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "initialisation launch");
 }
 
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,

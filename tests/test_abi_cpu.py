@@ -163,3 +163,12 @@ def test_mean_weights_argument_checks():
     assert l.tt_emb_mean_weights(None, 2, 4, None, one, None) == -1
     assert l.tt_emb_mean_weights(one, 2, 4, None, None, None) == -1
     assert l.tt_emb_mean_weights(None, 0, 0, None, None, None) == 0
+
+
+def test_init_argument_checks():
+    l = B.lib()
+    s = good_shape()
+    holes = (C.c_void_p * 3)(8, None, 8)
+    assert l.tt_init_sampled_gaussian(None, holes, 1, None) == -1
+    assert l.tt_init_sampled_gaussian(C.byref(s), None, 1, None) == -1
+    assert l.tt_init_sampled_gaussian(C.byref(s), holes, 1, None) == -1

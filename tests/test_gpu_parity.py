@@ -588,3 +588,29 @@ def test_mean_pooling_weights_and_passes(path):
         rg, _ = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=ref_w)
         for k in range(3):
             assert_close(dg[k].cpu().numpy(), rg[k], "mean dG%d" % (k + 1))
+
+
+# ------------------------------------------------------------------ sampled Gaussian initialisation
+
+@pytest.mark.parametrize("name", ["tiny", "kaggle_r32"])
+def test_sampled_gaussian_init_matches_oracle(name):
+    t = W.WORKLOADS[name].tables[0]
+    shape, oshape = B.shape_of(t), ora.Shape.of(t)
+    cores = [torch.full((oshape.core_size(k),), float("nan"), dtype=torch.float32, device=dev()) for k in range(3)]
+    B.tt_init_sampled_gaussian(shape, cores, 12345)
+    torch.cuda.synchronize()
+    ref = ora.init_sampled_gaussian(oshape, 12345)
+    scale = ora.sampled_gaussian_scale(oshape)
+    for k in range(3):
+        got = cores[k].cpu().numpy()
+        # same draws (the generator is integer work), the transform within a few fp64 roundings: at most the
+        # last bit of the fp32 result may differ
+        np.testing.assert_allclose(got, ref[k], rtol=2e-7, atol=0)
+        assert np.all(np.abs(got) > 2.0 * scale * (1 - 1e-6))
+    again = [torch.empty_like(c) for c in cores]
+    B.tt_init_sampled_gaussian(shape, again, 12345)
+    other = [torch.empty_like(c) for c in cores]
+    B.tt_init_sampled_gaussian(shape, other, 12346)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, c) for a, c in zip(again, cores))
+    assert not torch.equal(other[1], cores[1])
