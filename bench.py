@@ -36,7 +36,19 @@ MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 10.98e6, "bwd_sgd": 13.12e
                                    "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}}}
 
 
-def algorithmic_bytes(t, L, n_bags, touched_floats):
+FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published
+
+
+def algorithmic_flops(t, L_tt, keep_t0):
+    """fp32 flops of the method for L_tt uncached lookups: F1 = 2 n1 R n2 R for T0, F2 = 2 n1 n2 R n3 for the row;
+    the backward is 3 F1 + 2 F2 with recomputation (Alg. 2), 2 F1 + 2 F2 when T0 is kept."""
+    F1 = 2 * t.n[0] * t.r[1] * t.n[1] * t.r[2]
+    F2 = 2 * t.n[0] * t.n[1] * t.r[2] * t.n[2]
+    bwd = (2 if keep_t0 else 3) * F1 + 2 * F2
+    return {"fwd": L_tt * (F1 + F2), "bwd": L_tt * bwd, "bwd_sgd": L_tt * bwd, "sgd": 2 * sum(t.core_size(k) for k in range(3))}
+
+
+def algorithmic_bytes(t, L, n_bags, touched_floats, n_cached=0):
     """Bytes the method must move per launch (no re-reads, no intermediates).
 
     forward : every lookup reads its three slices (S bytes) and its index, every bag
@@ -48,12 +60,14 @@ def algorithmic_bytes(t, L, n_bags, touched_floats):
     """
     S = 4 * (t.n[0] * t.r[1] + t.r[1] * t.n[1] * t.r[2] + t.r[2] * t.n[2])
     N = t.dim
-    fwd = L * (S + 8) + n_bags * 4 * N
-    bwd = L * (S + 8) + n_bags * 4 * N + 4 * touched_floats
+    # a cached position reads (forward) or updates (backward) its cache line instead of three slices
+    reads = (L - n_cached) * (S + 8) + n_cached * (4 * N + 8)
+    fwd = reads + n_bags * 4 * N
+    bwd = reads + n_bags * 4 * N + 4 * touched_floats
     total = sum(t.core_size(k) for k in range(3))
     sgd = 12 * total
     # fused backward + SGD: the backward's reads, plus one read and one write of every core element
-    bwd_sgd = L * (S + 8) + n_bags * 4 * N + 8 * total
+    bwd_sgd = reads + n_bags * 4 * N + 8 * total
     return {"fwd": fwd, "bwd": bwd, "sgd": sgd, "bwd_sgd": bwd_sgd}
 
 
@@ -63,6 +77,9 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="kaggle_r32")
+    ap.add_argument("--table", type=int, default=0, help="which table of a multi-table workload")
+    ap.add_argument("--weights", choices=["none", "alpha", "mean"], default="none",
+                    help="alpha: per-position weights (Eq. 5); mean: average pooling (tt_emb_mean_weights)")
     ap.add_argument("--step", choices=["fused", "separate"], default="fused",
                     help="fused: forward, then backward and SGD in one call; separate: three calls")
     ap.add_argument("--recompute", action="store_true",
@@ -98,31 +115,48 @@ def main():
                           "bytes_written_per_copy": src.numel() * 4}))
         return
     wl = W.WORKLOADS[args.workload]
-    assert len(wl.tables) == 1, "bench.py times single-table workloads"
-    t = wl.tables[0]
+    tab = args.table
+    t = wl.tables[tab]
     shape = B.shape_of(t)
-    cores_h = W.make_cores(t, wl.init, wl.seed)
+    cores_h = W.make_cores(t, wl.init, wl.seed, tab)
     cores = [torch.from_numpy(c).to(dev) for c in cores_h]
     grads = [torch.zeros_like(c) for c in cores]
-    batches_h = [W.make_batch(wl, 0, step) for step in range(POOL)]
+    batches_h = [W.make_batch(wl, tab, step, with_alpha=args.weights == "alpha") for step in range(POOL)]
     idx = [torch.from_numpy(b.indices).to(dev) for b in batches_h]
     off = [torch.from_numpy(b.offsets).to(dev) for b in batches_h]
     go = [torch.from_numpy(b.grad_output).to(dev) for b in batches_h]
     n_bags = wl.n_bags
-    L = int(batches_h[0].indices.size)
+    Ls = [int(b.indices.size) for b in batches_h]       # bags of random length: the batches differ a little
+    L = int(round(sum(Ls) / POOL))
     out = torch.empty((n_bags, t.dim), dtype=torch.float32, device=dev)
     lr = 1e-3 * wl.lr            # small, so that thousands of steps keep the cores finite
+    # per-position weights: none, the batch's alpha, or the weights of mean pooling
+    alpha = [None] * POOL
+    if args.weights == "alpha":
+        alpha = [torch.from_numpy(b.alpha).to(dev) for b in batches_h]
+    elif args.weights == "mean":
+        alpha = [B.tt_emb_mean_weights(off[j], n_bags, Ls[j], torch.empty(Ls[j], dtype=torch.float32, device=dev)) for j in range(POOL)]
+    # the cache of the workloads that have one, filled from the counts of the warm-up stream
+    K = W.cache_size(wl, tab)
+    cache, grad_cache, keys_h = None, None, None
+    if K:
+        rows_h, counts_h = W.warmup_counts(wl, tab)
+        cache = B.Cache(K, t.dim, dev)
+        B.tt_cache_build(shape, cores, torch.from_numpy(rows_h).to(dev), torch.from_numpy(counts_h).to(dev), cache)
+        grad_cache = torch.zeros_like(cache.rows)
+        keys_h = cache.keys.cpu().numpy()
+    ws = torch.empty(max(B.bwd_sgd_workspace_bytes(shape, max(Ls), n_bags, K), 256), dtype=torch.uint8, device=dev)
 
     cores2 = [torch.empty_like(c) for c in cores]      # the fused step writes the other set of cores
     keep_t0 = args.step == "fused" and not args.recompute
     # one stored intermediate per batch of the pool (1 MB each at Kaggle R = 32)
-    t0_pool = [torch.empty((L, B.t0_floats(shape)), dtype=torch.float32, device=dev) for _ in range(POOL)] if keep_t0 else None
+    t0_pool = [torch.empty((max(Ls[j], 1), B.t0_floats(shape)), dtype=torch.float32, device=dev) for j in range(POOL)] if keep_t0 else None
 
     def fwd_call(cur, j):
         if keep_t0:
-            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], n_bags, out, t0_pool[j])
+            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], n_bags, out, t0_pool[j], alpha=alpha[j], cache=cache)
         else:
-            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out)
+            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
 
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
@@ -131,11 +165,13 @@ def main():
         if args.step == "fused":
             cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
             fwd_call(cur, j)
-            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, t0=t0_pool[j] if keep_t0 else None)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
+                             workspace=ws, t0=t0_pool[j] if keep_t0 else None)
         else:
-            B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out)
-            B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads)
-            B.tt_emb_sgd_update(shape, cores, grads, lr, zero_grad=True)
+            B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
+            B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads, alpha=alpha[j], cache=cache,
+                         grad_cache=grad_cache, workspace=ws)
+            B.tt_emb_sgd_update(shape, cores, grads, lr, cache=cache, grad_cache=grad_cache, zero_grad=True)
 
     def timed(fn, count):
         """ms per call of fn(i), count calls enqueued back to back between two events on the current stream."""
@@ -180,13 +216,16 @@ def main():
     if args.step == "fused":
         # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
         ms_bs = timed_any(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
-                                                     go[i % POOL], lr, t0=t0_pool[i % POOL] if keep_t0 else None), reps)
+                                                     go[i % POOL], lr, alpha=alpha[i % POOL], cache=cache, workspace=ws,
+                                                     t0=t0_pool[i % POOL] if keep_t0 else None), reps)
         stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
     else:
-        ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads), reps)
+        ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads,
+                                                  alpha=alpha[i % POOL], cache=cache, grad_cache=grad_cache, workspace=ws), reps)
         for g in grads:
             g.zero_()
-        ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, zero_grad=True), reps)
+        ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, cache=cache, grad_cache=grad_cache,
+                                                         zero_grad=True), reps)
         stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
 
     # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
@@ -195,9 +234,11 @@ def main():
     touched = (np.unique(b0 // (m2 * m3)).size * t.n[0] * t.r[1]
                + np.unique((b0 // m3) % m2).size * t.r[1] * t.n[1] * t.r[2]
                + np.unique(b0 % m3).size * t.r[2] * t.n[2])
-    ab = algorithmic_bytes(t, L, n_bags, touched)
+    n_cached = int(np.isin(b0, keys_h).sum()) if keys_h is not None else 0
+    ab = algorithmic_bytes(t, Ls[0], n_bags, touched, n_cached)
+    af = algorithmic_flops(t, Ls[0] - n_cached, keep_t0)
     if keep_t0:                                          # T0 is written once and read once per lookup
-        t0_bytes = L * 4 * B.t0_floats(shape)
+        t0_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape)
         ab["fwd"] += t0_bytes
         ab["bwd_sgd"] += t0_bytes
     dominant = max(stage_ms, key=stage_ms.get)
@@ -208,7 +249,10 @@ def main():
                     "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
                 "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
-                "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms}}
+                "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms},
+                "fp32_tflops": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12, 3),
+                "fp32_frac": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 5),
+                "cache_hit_rate": round(n_cached / Ls[0], 4) if keys_h is not None else None}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -216,12 +260,16 @@ def main():
         oshape = ora.Shape.of(t)
         budget, done, spent = 10.0, 0, 0.0
         oc = [c.copy() for c in cores_h]
-        while done < 3 or (spent < budget and done < POOL):
+        crow = ora.cache_fill(oshape, oc, keys_h) if keys_h is not None else None
+        al_h = [None if a is None else a.cpu().numpy() for a in alpha]
+        while done < 1 or (spent < budget and done < POOL):
             b = batches_h[done % POOL]
             s0 = time.perf_counter()
-            ora.fwd(oshape, oc, b.indices, b.offsets)
-            dg, _ = ora.bwd(oshape, oc, b.indices, b.offsets, b.grad_output)
+            ora.fwd(oshape, oc, b.indices, b.offsets, alpha=al_h[done % POOL], cache_keys=keys_h, cache_rows=crow)
+            dg, dc = ora.bwd(oshape, oc, b.indices, b.offsets, b.grad_output, alpha=al_h[done % POOL], cache_keys=keys_h)
             oc = [ora.sgd(oc[k], dg[k].astype(np.float32), lr) for k in range(3)]
+            if crow is not None:
+                crow = ora.sgd(crow, dc.astype(np.float32), lr)
             spent += time.perf_counter() - s0
             done += 1
         cpu = {"value": round(done * L / spent, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
@@ -233,8 +281,11 @@ def main():
         "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
-                               "Zipf(%.2f), fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
-                                                            n_bags, L // n_bags, wl.zipf_alpha),
+                               "Zipf(%.2f)%s%s, fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
+                                                                n_bags, L // max(n_bags, 1), wl.zipf_alpha,
+                                                                ", cache of %d rows" % K if K else "",
+                                                                ", weights: %s" % args.weights if args.weights != "none" else ""),
+                   "table": tab,
                    "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0), "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
