@@ -288,3 +288,68 @@ def init_sampled_gaussian(shape: Shape, seed: int) -> List[np.ndarray]:
         _load().ora_init_sampled_gaussian(C.c_uint64(seed), C.c_int(k), C.c_int64(out.size), C.c_double(scale), _p(out))
         cores.append(out)
     return cores
+
+
+# ---- general number of cores (Section 4.1: "can be generalized to any arbitrary TT dimension") --
+# Plain numpy, fp64.  A shape is (num_rows, m[d], n[d], r[d+1]) with r[0] = r[d] = 1; core k is
+# stored [m_k][r_k][n_k][r_{k+1}] like the three-core case.
+
+def _digits_d(m, i: int):
+    out = []
+    for mk in reversed(m):
+        out.append(i % mk)
+        i //= mk
+    return out[::-1]
+
+
+def _slices_d(m, n, r, cores, i: int):
+    d = len(m)
+    dig = _digits_d(m, i)
+    return [np.asarray(cores[k], dtype=np.float64).reshape(m[k], r[k], n[k], r[k + 1])[dig[k]] for k in range(d)]
+
+
+def row_d(m, n, r, cores, i: int) -> np.ndarray:
+    """Row i of the table: the chain of Eq. 3 over d cores, partial products reshaped row-major."""
+    sl = _slices_d(m, n, r, cores, i)
+    p = sl[0].reshape(n[0], r[1])                                  # (n1) x R1
+    for k in range(1, len(m)):
+        p = (p @ sl[k].reshape(r[k], n[k] * r[k + 1])).reshape(-1, r[k + 1])
+    return p.reshape(-1)
+
+
+def fwd_d(m, n, r, cores, indices, offsets, alpha=None) -> np.ndarray:
+    idx, off = _i64(indices), _i64(offsets)
+    N = int(np.prod(n))
+    out = np.zeros((off.size - 1, N))
+    for b in range(off.size - 1):
+        for k in range(int(off[b]), int(off[b + 1])):
+            out[b] += (1.0 if alpha is None else float(alpha[k])) * row_d(m, n, r, cores, int(idx[k]))
+    return out.astype(np.float32)
+
+
+def bwd_d(m, n, r, cores, indices, offsets, grad_output, alpha=None) -> List[np.ndarray]:
+    """Gradients of <output, grad_output> with respect to every core (Eq. 4 for any d): for the slice
+    of core k used by a lookup, dG_k[a][j_k][b] = sum over the other column digits of
+    left[j_<k][a] * dY[j_<k, j_k, j_>k] * right[b][j_>k], left / right being the products of the
+    slices before / after core k."""
+    d = len(m)
+    idx, off = _i64(indices), _i64(offsets)
+    go = np.asarray(grad_output, dtype=np.float64)
+    grads = [np.zeros((m[k], r[k], n[k], r[k + 1])) for k in range(d)]
+    for b in range(off.size - 1):
+        for pos in range(int(off[b]), int(off[b + 1])):
+            i = int(idx[pos])
+            dig = _digits_d(m, i)
+            sl = _slices_d(m, n, r, cores, i)
+            dY = (1.0 if alpha is None else float(alpha[pos])) * go[b]
+            for k in range(d):
+                left = np.ones((1, 1))                              # (prod n_<k) x r_k
+                for q in range(k):
+                    left = (left @ sl[q].reshape(r[q], n[q] * r[q + 1])).reshape(-1, r[q + 1])
+                right = np.ones((1, 1))                             # r_{k+1} x (prod n_>k)
+                for q in range(d - 1, k, -1):
+                    right = (sl[q].reshape(r[q] * n[q], r[q + 1]) @ right).reshape(r[q], -1)
+                nl, nr = left.shape[0], right.shape[1]
+                dy3 = dY.reshape(nl, n[k], nr)
+                grads[k][dig[k]] += np.einsum("la,ljr,br->ajb", left, dy3, right)
+    return [g.astype(np.float32) for g in grads]

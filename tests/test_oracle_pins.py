@@ -501,3 +501,72 @@ def test_sampled_gaussian_cores_give_the_target_variance():
     target = 1.0 / (3.0 * shape.num_rows)
     assert abs(w.var() / target - 1.0) < 0.1
     assert abs(w.mean()) < 0.05 * np.sqrt(target)
+
+
+# ---- general number of cores ----------------------------------------------------------------
+
+def _random_shape_d(d, rng):
+    m = [int(x) for x in rng.integers(2, 5, d)]
+    n = [int(x) for x in rng.integers(1, 4, d)]
+    r = [1] + [int(x) for x in rng.integers(2, 5, d - 1)] + [1]
+    cores = [rng.standard_normal((m[k], r[k], n[k], r[k + 1])).astype(np.float32) for k in range(d)]
+    return m, n, r, cores
+
+
+def _dense_d(m, n, r, cores):
+    """The whole table from Eq. 2, one einsum over all cores (independent of row_d)."""
+    d = len(m)
+    g = [c.astype(np.float64) for c in cores]                       # written out per d to keep it readable
+    if d == 2:
+        w = np.einsum("pxiy,qyjz->pqij", g[0], g[1])
+    elif d == 3:
+        w = np.einsum("pxiy,qyjz,rzkw->pqrijk", g[0], g[1], g[2])
+    else:
+        w = np.einsum("pxiy,qyjz,rzkw,swlv->pqrsijkl", g[0], g[1], g[2], g[3])
+    return w.reshape(int(np.prod(m)), int(np.prod(n)))
+
+
+@pytest.mark.parametrize("d", [2, 3, 4])
+def test_general_d_rows_and_gradients(d):
+    rng = np.random.default_rng(80 + d)
+    m, n, r, cores = _random_shape_d(d, rng)
+    rows, N = int(np.prod(m)), int(np.prod(n))
+    w = _dense_d(m, n, r, cores)
+    for i in (0, rows // 2, rows - 1):
+        np.testing.assert_allclose(ora.row_d(m, n, r, cores, i), w[i], rtol=1e-12, atol=1e-12)
+    lens = np.array([2, 0, 3, 1])
+    off = np.zeros(5, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, rows, int(off[-1]))
+    idx[1] = idx[0]                                                 # a repeated row
+    alpha = (0.5 + rng.random(idx.size)).astype(np.float32)
+    go = rng.standard_normal((4, N)).astype(np.float32)
+    wt = torch.from_numpy(w)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(idx), wt, torch.from_numpy(off[:-1]), mode="sum",
+                                            per_sample_weights=torch.from_numpy(alpha.astype(np.float64)))
+    np.testing.assert_allclose(ora.fwd_d(m, n, r, cores, idx, off, alpha), ref.numpy(), rtol=1e-6, atol=1e-7)
+    # gradients through library autograd on the dense reconstruction
+    ct = [torch.tensor(c.astype(np.float64), requires_grad=True) for c in cores]
+    if d == 2:
+        wd = torch.einsum("pxiy,qyjz->pqij", ct[0], ct[1])
+    elif d == 3:
+        wd = torch.einsum("pxiy,qyjz,rzkw->pqrijk", ct[0], ct[1], ct[2])
+    else:
+        wd = torch.einsum("pxiy,qyjz,rzkw,swlv->pqrsijkl", ct[0], ct[1], ct[2], ct[3])
+    o = torch.nn.functional.embedding_bag(torch.from_numpy(idx), wd.reshape(rows, N), torch.from_numpy(off[:-1]), mode="sum",
+                                          per_sample_weights=torch.from_numpy(alpha.astype(np.float64)))
+    (o * torch.from_numpy(go.astype(np.float64))).sum().backward()
+    g = ora.bwd_d(m, n, r, cores, idx, off, go, alpha)
+    for k in range(d):
+        np.testing.assert_allclose(g[k], ct[k].grad.numpy(), rtol=1e-5, atol=1e-6)
+
+
+def test_general_d_with_three_cores_is_the_three_core_oracle():
+    wl, shape, cores, batch = tiny()
+    m, n, r = list(shape.m), list(shape.n), list(shape.r)
+    np.testing.assert_allclose(ora.fwd_d(m, n, r, cores, batch.indices, batch.offsets),
+                               ora.fwd(shape, cores, batch.indices, batch.offsets), rtol=1e-6, atol=1e-8)
+    g3, _ = ora.bwd(shape, cores, batch.indices, batch.offsets, batch.grad_output)
+    gd = ora.bwd_d(m, n, r, cores, batch.indices, batch.offsets, batch.grad_output)
+    for k in range(3):
+        np.testing.assert_allclose(gd[k].reshape(-1), np.asarray(g3[k]).reshape(-1), rtol=1e-5, atol=1e-7)
