@@ -88,6 +88,18 @@ typedef struct tt_freq_t {
     int64_t *stats;       /* [2]        */
 } tt_freq_t;
 
+/* Shape of a table with any number of cores d in {2, 3, 4} (Section 4.1: the
+ * algorithms are given for three cores and generalise to any TT dimension).  Host
+ * memory.  Core k is fp32 [m[k]][r[k]][n[k]][r[k+1]], r[0] = r[d] = 1; the row digits
+ * are mixed radix with digit 0 most significant.  Entries past d are ignored. */
+typedef struct tt_shape_d_t {
+    int32_t d;
+    int64_t num_rows;
+    int32_t m[4];
+    int32_t n[4];
+    int32_t r[5];
+} tt_shape_d_t;
+
 /* Text of the last error on this thread ("" if none).  Host pointer, valid until
  * the next failing call on the same thread. */
 const char *tt_last_error(void);
@@ -274,6 +286,24 @@ int tt_cache_lookup(const tt_cache_t *cache, const int64_t *indices, int64_t L,
                     int32_t *slot, void *stream);
 
 /* ---- exports used by the parity tests ------------------------------------ */
+
+/*
+ * Forward, backward and SGD step for d = 2, 3 or 4 cores (Section 4.1; Eq. 3-6 with the
+ * chain of products extended or shortened).  Same conventions as tt_emb_fwd / tt_emb_bwd /
+ * tt_emb_sgd_update (CSR bags, optional alpha, "+=" into grad_cores, deterministic),
+ * without a cache and without a workspace.  cores / grad_cores: host arrays whose first d
+ * entries are device pointers.  Plain kernels, meant for shapes off the tuned three-core
+ * path: N, every core slice and every intermediate product of the chain must not exceed
+ * 4096 values (TT_ERR_UNSUPPORTED otherwise).
+ */
+int tt_embd_fwd(const tt_shape_d_t *shape, const float *const cores[4],
+                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                const float *alpha, float *output, void *stream);
+int tt_embd_bwd(const tt_shape_d_t *shape, const float *const cores[4],
+                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                const float *alpha, const float *grad_output, float *const grad_cores[4], void *stream);
+int tt_embd_sgd_update(const tt_shape_d_t *shape, float *const cores[4], float *const grad_cores[4], float lr,
+                       int zero_grad, void *stream);
 
 /*
  * Uncompressed EmbeddingBag on the same GPU, the comparison of the microbenchmarks

@@ -25,7 +25,7 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
-           "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
+           "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
            "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
@@ -81,6 +81,9 @@ def lib():
         l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
         l.tt_dense_bag_fwd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, vp]
         l.tt_dense_bag_bwd_sgd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp]
+        l.tt_embd_fwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp]
+        l.tt_embd_bwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp]
+        l.tt_embd_sgd_update.argtypes = [vp, vp, vp, f32, C.c_int, vp]
         l.tt_init_sampled_gaussian.argtypes = [vp, vp, C.c_uint64, vp]
         l.tt_emb_mean_weights.argtypes = [vp, i64, i64, vp, vp, vp]
         l.tt_freq_reset.argtypes = [vp, vp]
@@ -393,3 +396,50 @@ def tt_emb_mean_weights(offsets: torch.Tensor, n_bags: int, L: int, weights: tor
 
 def tt_init_sampled_gaussian(shape: TTShape, cores: Sequence[torch.Tensor], seed: int) -> None:
     _check(lib().tt_init_sampled_gaussian(C.byref(shape), _ptr_array(cores), C.c_uint64(seed), _stream()))
+
+
+class TTShapeD(C.Structure):
+    _fields_ = [("d", C.c_int32), ("num_rows", C.c_int64), ("m", C.c_int32 * 4), ("n", C.c_int32 * 4), ("r", C.c_int32 * 5)]
+
+
+def make_shape_d(num_rows: int, m: Sequence[int], n: Sequence[int], r: Sequence[int]) -> TTShapeD:
+    d = len(m)
+    assert len(n) == d and len(r) == d + 1
+    s = TTShapeD()
+    s.d, s.num_rows = d, num_rows
+    for k in range(d):
+        s.m[k], s.n[k] = m[k], n[k]
+    for k in range(d + 1):
+        s.r[k] = r[k]
+    return s
+
+
+def _ptr_array_d(ts: Sequence[torch.Tensor]):
+    arr = (C.c_void_p * 4)()
+    for k, t in enumerate(ts):
+        arr[k] = _dev(t, torch.float32).data_ptr()
+    return arr
+
+
+def tt_embd_fwd(shape: TTShapeD, cores: Sequence[torch.Tensor], indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                n_bags: int, output: torch.Tensor, alpha: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indices, torch.int64)
+    _dev(output, torch.float32)
+    _check(lib().tt_embd_fwd(C.byref(shape), _ptr_array_d(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                             _ptr(alpha), _ptr(output), _stream()))
+    return output
+
+
+def tt_embd_bwd(shape: TTShapeD, cores: Sequence[torch.Tensor], indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                n_bags: int, grad_output: torch.Tensor, grad_cores: Sequence[torch.Tensor],
+                alpha: Optional[torch.Tensor] = None) -> None:
+    _dev(indices, torch.int64)
+    _dev(grad_output, torch.float32)
+    _check(lib().tt_embd_bwd(C.byref(shape), _ptr_array_d(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                             _ptr(alpha), _ptr(grad_output), _ptr_array_d(grad_cores), _stream()))
+
+
+def tt_embd_sgd_update(shape: TTShapeD, cores: Sequence[torch.Tensor], grad_cores: Sequence[torch.Tensor], lr: float,
+                       zero_grad: bool = False) -> None:
+    _check(lib().tt_embd_sgd_update(C.byref(shape), _ptr_array_d(cores), _ptr_array_d(grad_cores), C.c_float(lr),
+                                    int(zero_grad), _stream()))

@@ -18,6 +18,7 @@
 #include "tt_freq.h"
 #include "tt_dense.h"
 #include "tt_init.h"
+#include "tt_anyd.h"
 
 using namespace tt;
 
@@ -689,6 +690,105 @@ int tt_init_sampled_gaussian(const tt_shape_t *shape, float *const cores[3], uin
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "initialisation launch");
+}
+
+static int check_shape_d(const tt_shape_d_t *sh, ShapeD *out)
+{
+    if (!sh) return fail(TT_ERR_NULL, "shape is NULL");
+    if (sh->d < 2 || sh->d > DMAX) return fail(TT_ERR_BAD_SHAPE, "d must be 2, 3 or 4");
+    if (sh->r[0] != 1 || sh->r[sh->d] != 1) return fail(TT_ERR_BAD_SHAPE, "boundary ranks must be 1");
+    ShapeD s;
+    memset(&s, 0, sizeof(s));
+    s.d = sh->d;
+    int64_t rows = 1, N = 1;
+    for (int k = 0; k < sh->d; ++k) {
+        if (sh->m[k] <= 0 || sh->n[k] <= 0 || sh->r[k] <= 0 || sh->r[k + 1] <= 0)
+            return fail(TT_ERR_BAD_SHAPE, "factors and ranks must be positive");
+        s.m[k] = sh->m[k]; s.n[k] = sh->n[k]; s.r[k] = sh->r[k];
+        rows *= sh->m[k];
+        N *= sh->n[k];
+        if (rows >= (1ll << 31) || N > DBUF) return fail(TT_ERR_UNSUPPORTED, "table too large for the general-d kernels");
+        const int64_t slice = (int64_t)sh->r[k] * sh->n[k] * sh->r[k + 1];
+        if (slice > DBUF) return fail(TT_ERR_UNSUPPORTED, "a core slice exceeds %d values", DBUF);
+        s.slice[k] = (int)slice;
+    }
+    s.r[sh->d] = 1;
+    s.N = (int)N;
+    if (sh->num_rows <= 0 || sh->num_rows > rows) return fail(TT_ERR_BAD_SHAPE, "num_rows must be in [1, prod(m)]");
+    // every intermediate of the chain has to fit one LDS buffer
+    int64_t nl = 1;
+    for (int k = 0; k < sh->d; ++k) {
+        int64_t nr = 1;
+        for (int q = k + 1; q < sh->d; ++q) nr *= sh->n[q];
+        const int64_t left = nl * sh->r[k], right = (int64_t)sh->r[k + 1] * nr, tt = (int64_t)sh->r[k] * sh->n[k] * nr;
+        nl *= sh->n[k];
+        const int64_t part = nl * sh->r[k + 1];
+        if (left > DBUF || right > DBUF || tt > DBUF || part > DBUF)
+            return fail(TT_ERR_UNSUPPORTED, "an intermediate product exceeds %d values", DBUF);
+    }
+    if (out) *out = s;
+    return TT_OK;
+}
+
+int tt_embd_fwd(const tt_shape_d_t *shape, const float *const cores[4],
+                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                const float *alpha, float *output, void *stream)
+{
+    ShapeD s;
+    int rc = check_shape_d(shape, &s);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if (!cores) return fail(TT_ERR_NULL, "cores is NULL");
+    for (int k = 0; k < s.d; ++k)
+        if (!cores[k]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
+    if (n_bags == 0) return TT_OK;
+    const int grid = (int)(n_bags < 16384 ? n_bags : 16384);
+    hipLaunchKernelGGL(fwd_anyd_kernel, dim3(grid), dim3(WG), 0, (hipStream_t)stream, s, cores[0], cores[1],
+                       s.d > 2 ? cores[2] : nullptr, s.d > 3 ? cores[3] : nullptr, indices, offsets, (int)n_bags, alpha, output);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
+}
+
+int tt_embd_bwd(const tt_shape_d_t *shape, const float *const cores[4],
+                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                const float *alpha, const float *grad_output, float *const grad_cores[4], void *stream)
+{
+    ShapeD s;
+    int rc = check_shape_d(shape, &s);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if (!cores || !grad_cores) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
+    for (int k = 0; k < s.d; ++k)
+        if (!cores[k] || !grad_cores[k]) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
+    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (L == 0) return TT_OK;
+    int grid = 0;
+    for (int k = 0; k < s.d; ++k) grid += s.m[k];
+    hipLaunchKernelGGL(bwd_anyd_kernel, dim3(grid), dim3(WG), 0, (hipStream_t)stream, s, cores[0], cores[1],
+                       s.d > 2 ? cores[2] : nullptr, s.d > 3 ? cores[3] : nullptr, indices, (int)L, offsets, (int)n_bags,
+                       alpha, grad_output, grad_cores[0], grad_cores[1], s.d > 2 ? grad_cores[2] : nullptr,
+                       s.d > 3 ? grad_cores[3] : nullptr);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "backward launch");
+}
+
+int tt_embd_sgd_update(const tt_shape_d_t *shape, float *const cores[4], float *const grad_cores[4], float lr,
+                       int zero_grad, void *stream)
+{
+    ShapeD s;
+    int rc = check_shape_d(shape, &s);
+    if (rc) return rc;
+    if (!cores || !grad_cores) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
+    for (int k = 0; k < s.d; ++k)
+        if (!cores[k] || !grad_cores[k]) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
+    for (int k = 0; k < s.d; ++k) {
+        const int64_t n = (int64_t)s.m[k] * s.slice[k];
+        hipLaunchKernelGGL(sgd_plain_kernel, dim3(cdiv(n, WG) < 2048 ? cdiv(n, WG) : 2048), dim3(WG), 0, (hipStream_t)stream,
+                           cores[k], grad_cores[k], n, lr, zero_grad);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "sgd launch");
 }
 
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,

@@ -172,3 +172,24 @@ def test_init_argument_checks():
     assert l.tt_init_sampled_gaussian(None, holes, 1, None) == -1
     assert l.tt_init_sampled_gaussian(C.byref(s), None, 1, None) == -1
     assert l.tt_init_sampled_gaussian(C.byref(s), holes, 1, None) == -1
+
+
+def test_general_d_shape_and_argument_checks():
+    l = B.lib()
+    arr = (C.c_void_p * 4)(8, 8, 8, 8)
+    one = C.c_void_p(8)
+    good = B.make_shape_d(1000, (10, 10, 10), (2, 2, 4), (1, 8, 8, 1))
+    assert C.sizeof(B.TTShapeD) == 72 and B.TTShapeD.num_rows.offset == 8 and B.TTShapeD.m.offset == 16
+    assert l.tt_embd_fwd(C.byref(good), arr, one, 1, None, 1, None, None, None) == -1          # no output
+    assert l.tt_embd_fwd(C.byref(good), arr, None, 0, None, 0, None, None, None) == 0
+    for bad, code in [(B.make_shape_d(10, (10,), (4,), (1, 1)), -2),                                # d = 1
+                      (B.make_shape_d(100, (10, 10), (4, 4), (2, 8, 1)), -2),                        # r[0] != 1
+                      (B.make_shape_d(101, (10, 10), (4, 4), (1, 8, 1)), -2),                        # more rows than prod(m)
+                      (B.make_shape_d(100, (10, 10), (4, 4), (1, 0, 1)), -2),
+                      (B.make_shape_d(100, (10, 10), (64, 128), (1, 8, 1)), -6),                     # N > 4096
+                      (B.make_shape_d(1000, (10, 10, 10), (4, 4, 4), (1, 64, 64, 1)), -6)]:          # slice > 4096
+        assert l.tt_embd_fwd(C.byref(bad), arr, one, 1, None, 1, None, one, None) == code
+        assert l.tt_embd_bwd(C.byref(bad), arr, one, 1, None, 1, None, one, arr, None) == code
+        assert l.tt_embd_sgd_update(C.byref(bad), arr, arr, C.c_float(0.1), 0, None) == code
+    holes = (C.c_void_p * 4)(8, None, 8, 8)
+    assert l.tt_embd_bwd(C.byref(good), arr, one, 1, None, 1, None, one, holes, None) == -1

@@ -614,3 +614,63 @@ def test_sampled_gaussian_init_matches_oracle(name):
     torch.cuda.synchronize()
     assert all(torch.equal(a, c) for a, c in zip(again, cores))
     assert not torch.equal(other[1], cores[1])
+
+
+# ------------------------------------------------------------------ any number of cores
+
+@pytest.mark.parametrize("d,m,n,r", [
+    (2, (40, 25), (4, 4), (1, 16, 1)),
+    (3, (10, 10, 10), (2, 2, 4), (1, 8, 8, 1)),
+    (4, (6, 5, 7, 4), (2, 3, 2, 2), (1, 4, 7, 5, 1)),
+    (4, (8, 8, 8, 8), (2, 2, 2, 2), (1, 16, 16, 16, 1)),
+])
+def test_general_d_matches_oracle(d, m, n, r):
+    rng = np.random.default_rng(90 + d + m[0])
+    rows, N = int(np.prod(m)), int(np.prod(n))
+    cores = [(0.3 * rng.standard_normal((m[k], r[k], n[k], r[k + 1]))).astype(np.float32) for k in range(d)]
+    n_bags = 40
+    lens = rng.integers(0, 9, n_bags)
+    lens[3] = 300                                                  # more than one scan chunk
+    off = np.zeros(n_bags + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    L = int(off[-1])
+    idx = rng.integers(0, rows, L).astype(np.int64)
+    idx[10:60] = idx[9]                                            # a hot row
+    alpha = (0.5 + rng.random(L)).astype(np.float32)
+    go = rng.standard_normal((n_bags, N)).astype(np.float32)
+    dv = dev()
+    shape = B.make_shape_d(rows, m, n, r)
+    g = [torch.from_numpy(c).to(dv) for c in cores]
+    ti, to, ta, tg = (torch.from_numpy(x).to(dv) for x in (idx, off, alpha, go))
+    out = torch.full((n_bags, N), float("nan"), dtype=torch.float32, device=dv)
+    B.tt_embd_fwd(shape, g, ti, to, n_bags, out, alpha=ta)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), ora.fwd_d(m, n, r, cores, idx, off, alpha), "d=%d forward" % d)
+    marker = 3.5
+    grads = [torch.full_like(x, marker) for x in g]
+    B.tt_embd_bwd(shape, g, ti, to, n_bags, tg, grads, alpha=ta)
+    torch.cuda.synchronize()
+    ref = ora.bwd_d(m, n, r, cores, idx, off, go, alpha)
+    for k in range(d):
+        assert_close(grads[k].cpu().numpy() - marker, ref[k], "d=%d dG%d" % (d, k + 1))      # "+=" on top of the marker
+    again = [torch.full_like(x, marker) for x in g]
+    B.tt_embd_bwd(shape, g, ti, to, n_bags, tg, again, alpha=ta)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(again, grads))    # deterministic
+    only = [(x - marker) for x in grads]
+    B.tt_embd_sgd_update(shape, g, only, 0.1, zero_grad=True)
+    torch.cuda.synchronize()
+    for k in range(d):
+        assert_close(g[k].cpu().numpy(), ora.sgd(cores[k], ref[k], 0.1), "d=%d sgd core %d" % (d, k + 1))
+        assert float(only[k].abs().max()) == 0.0
+
+
+def test_general_d_three_cores_agree_with_the_tuned_path():
+    wl = W.WORKLOADS["tiny"]
+    d = DeviceTable(wl)
+    t = wl.tables[0]
+    shape = B.make_shape_d(t.num_rows, t.m, t.n, t.r)
+    out = torch.empty((d.n_bags, t.dim), dtype=torch.float32, device=dev())
+    B.tt_embd_fwd(shape, d.g, d.idx, d.off, d.n_bags, out)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), d.fwd(), "general-d against tuned forward")
