@@ -387,6 +387,41 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
+    // dT0'[j1][c] = sum_j3 dY[(j1,j2)][j3] C[b][j3] is the same in all four waves: where it is exactly as large
+    // as the G3 slice it is made from (n1 n2 R = R n3), wave w computes it once for the rows w, w + 4, ... of
+    // the batch of small operands and puts it in the place of that slice, which nobody needs afterwards.
+    constexpr bool DTPRE = N1 * C::COLS == C::sC;
+    auto load_lds_vec = [&](const float *src, float (&x)[V]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = src[v];
+    };
+    auto dt_prepare = [&](int sb0, int nb) __attribute__((always_inline)) {
+        if (!DTPRE || ROLE == 2) return;
+        for (int u = w; u < nb; u += NWAVE) {                              // uniform per wave
+            float *smu = lds.small + u * SMALL;
+            const float *dy = stage + lds.seg_start[sb0 + u] * N + j2 * N3;
+            float d[N1][V];
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) {
+                const float4 q = *reinterpret_cast<const float4 *>(dy + j1 * N2 * N3);
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const float4 cv = *reinterpret_cast<const float4 *>(&smu[C::sA + (b0 + v) * N3]);
+                    d[j1][v] = fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
+                }
+            }
+            // all lanes of the wave have read the slice before any of them overwrites it
+            __builtin_amdgcn_wave_barrier();
+            if (active) {
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) smu[C::sA + j1 * C::COLS + c0 + v] = d[j1][v];
+            }
+        }
+        __syncthreads();
+    };
+
     // Rows [ub0, ub0 + UB) of the window.  Every run has been summed into its first staged entry,
     // so each row reads exactly one dY.  No branches on the row count: rows past the end repeat
     // the last one with a zero weight, so the LDS reads of the batch can be in flight together.
@@ -447,11 +482,18 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 for (int u = 0; u < UH; ++u)
 #pragma unroll
                     for (int j1 = 0; j1 < N1; ++j1) {
-                        const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+                        if constexpr (DTPRE) {                     // computed once per row by dt_prepare
+                            float x[V];
+                            load_lds_vec(&sm[u][C::sA + j1 * C::COLS + c0], x);
 #pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            const float4 cv = *reinterpret_cast<const float4 *>(&sm[u][C::sA + (b0 + v) * N3]);
-                            dt[u][j1][v] = keep[u] * fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
+                            for (int v = 0; v < V; ++v) dt[u][j1][v] = keep[u] * x[v];
+                        } else {
+                            const float4 q = *reinterpret_cast<const float4 *>(dyp[u] + j1 * N2 * N3);
+#pragma unroll
+                            for (int v = 0; v < V; ++v) {
+                                const float4 cv = *reinterpret_cast<const float4 *>(&sm[u][C::sA + (b0 + v) * N3]);
+                                dt[u][j1][v] = keep[u] * fmaf(q.x, cv.x, fmaf(q.y, cv.y, fmaf(q.z, cv.z, q.w * cv.w)));
+                            }
                         }
                     }
                 if (ROLE == 1) {
@@ -631,6 +673,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 }
                 __syncthreads();
             }
+            dt_prepare(0, min(SB, nsegs));
             TT_STAMP(5);
             if (t0mode) consume_t0(nsegs);
             for (int ub0 = 0; ub0 < (t0mode ? 0 : nsegs); ub0 += UB) {
@@ -641,6 +684,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                         __syncthreads();
                         stage_items(i0, 0, sb0, min(SB, nsegs - sb0), wc);
                         __syncthreads();
+                        dt_prepare(sb0, min(SB, nsegs - sb0));
                     }
                 }
                 consume(ub0, sb0, nsegs, bm);
