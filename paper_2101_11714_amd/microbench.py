@@ -6,11 +6,14 @@ same GPU (the studies of Sections 6.6 and 6.7 of the paper, on synthetic inputs)
   hitrate : cache hit rate 0 .. 99 %, a 10 M-row table of dimension 64 at rank 32 with a cache
             of 0.01 % of its rows, 2048 samples per step, P in {10, 100}.
 
+  tables  : the seven independent tables of the multi-hot workload (8192 samples x 20 indices each,
+            caches of 0.01 %), one after the other on one stream against one stream per table.
+
 A step is forward + backward + SGD.  TT: tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0; dense:
 tt_dense_bag_fwd + tt_dense_bag_bwd_sgd.  Every step sequence is captured in a HIP graph, so
 the figures are GPU times.  Prints a markdown table.
 
-    python -m paper_2101_11714_amd.microbench [pooling] [hitrate]
+    python -m paper_2101_11714_amd.microbench [pooling] [hitrate] [tables]
 """
 
 from __future__ import annotations
@@ -118,15 +121,90 @@ def hitrate(dev):
             print("| %d | %.0f %% | %.1f | %.1f | %.1f | %.1f |" % (P, 100 * h, tt, dn, tt / dn, L / tt), flush=True)
 
 
+def tables(dev):
+    """All tables of the multi-hot workload in one step: their kernels are independent, so a stream per
+    table lets the GPU overlap one table's latency-bound kernels with another's."""
+    wl = W.WORKLOADS["multihot_cache"]
+    nt, nb = len(wl.tables), 2                                      # two distinct batches per table
+    print("\n## The %d tables of the multi-hot workload in one step (%d samples x %d indices per table, caches of 0.01 %%)\n"
+          % (nt, wl.n_bags, wl.bag_len[0]))
+    state = []
+    for tb in range(nt):
+        shape = wl.tables[tb]
+        c = B.shape_of(shape)
+        cores = [torch.from_numpy(x).to(dev) for x in W.make_cores(shape, wl.init, wl.seed, tb)]
+        cores2 = [torch.empty_like(x) for x in cores]
+        K = W.cache_size(wl, tb)
+        rows, counts = W.warmup_counts(wl, tb)
+        cache = B.Cache(K, shape.dim, dev)
+        B.tt_cache_build(c, cores, torch.from_numpy(rows).to(dev), torch.from_numpy(counts).to(dev), cache)
+        bs = [W.make_batch(wl, tb, j) for j in range(nb)]
+        L = bs[0].indices.size
+        state.append(dict(
+            c=c, cores=cores, cores2=cores2, cache=cache, L=L,
+            idx=[torch.from_numpy(b.indices).to(dev) for b in bs], off=[torch.from_numpy(b.offsets).to(dev) for b in bs],
+            go=[torch.from_numpy(b.grad_output).to(dev) for b in bs],
+            out=torch.empty((wl.n_bags, shape.dim), dtype=torch.float32, device=dev),
+            t0=[torch.empty((L, B.t0_floats(c)), dtype=torch.float32, device=dev) for _ in bs],
+            ws=torch.empty(B.bwd_sgd_workspace_bytes(c, L, wl.n_bags, K), dtype=torch.uint8, device=dev)))
+    total = sum(s["L"] for s in state)
+
+    def step(s, j):
+        cur, nxt = (s["cores"], s["cores2"]) if j % 2 == 0 else (s["cores2"], s["cores"])
+        B.tt_emb_fwd_keep_t0(s["c"], cur, s["idx"][j], s["off"][j], wl.n_bags, s["out"], s["t0"][j], cache=s["cache"])
+        B.tt_emb_bwd_sgd(s["c"], cur, nxt, s["idx"][j], s["off"][j], wl.n_bags, s["go"][j], 1e-6, cache=s["cache"],
+                         workspace=s["ws"], t0=s["t0"][j])
+
+    def run(streams):
+        main_stream = torch.cuda.current_stream()
+        for j in range(nb):
+            for tb, s in enumerate(state):
+                if streams is None:
+                    step(s, j)
+                else:
+                    streams[tb].wait_stream(main_stream)
+                    with torch.cuda.stream(streams[tb]):
+                        step(s, j)
+            if streams is not None:
+                for st in streams:
+                    main_stream.wait_stream(st)
+
+    def graph_us(streams):
+        run(streams)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run(streams)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * nb)
+
+    seq = graph_us(None)
+    par = graph_us([torch.cuda.Stream() for _ in range(nt)])
+    print("| launch | step us (all %d tables) | M lookups/s |" % nt)
+    print("|---|---|---|")
+    print("| one stream, table after table | %.1f | %.1f |" % (seq, total / seq))
+    print("| one stream per table | %.1f | %.1f |" % (par, total / par), flush=True)
+
+
 def main():
     assert torch.cuda.is_available(), "the microbenchmarks need a GPU"
     dev = torch.device("cuda:0")
-    which = sys.argv[1:] or ["pooling", "hitrate"]
+    which = sys.argv[1:] or ["pooling", "hitrate", "tables"]
     print("# TT-EmbeddingBag against an uncompressed EmbeddingBag on one MI355X (forward + backward + SGD per step)\n")
     if "pooling" in which:
         pooling(dev)
     if "hitrate" in which:
         hitrate(dev)
+    if "tables" in which:
+        tables(dev)
 
 
 if __name__ == "__main__":
