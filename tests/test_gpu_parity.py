@@ -674,3 +674,69 @@ def test_general_d_three_cores_agree_with_the_tuned_path():
     B.tt_embd_fwd(shape, d.g, d.idx, d.off, d.n_bags, out)
     torch.cuda.synchronize()
     assert_close(out.cpu().numpy(), d.fwd(), "general-d against tuned forward")
+
+
+# ------------------------------------------------------------------ the benchmark's launch configuration
+
+def test_graph_replays_of_the_benchmark_step_match_eager_calls():
+    """bench.py replays a HIP graph of steps (forward keeping T0, then backward + SGD into the other
+    set of cores).  Every replay must leave the same cores as the same steps launched one by one,
+    and those match the oracle."""
+    wl = W.WORKLOADS["kaggle_r32"]
+    t = wl.tables[0]
+    shape, oshape = B.shape_of(t), ora.Shape.of(t)
+    cores_h = W.make_cores(t, wl.init, wl.seed)
+    batches = [W.make_batch(wl, 0, j) for j in range(2)]
+    d = dev()
+    idx = [torch.from_numpy(b.indices).to(d) for b in batches]
+    off = [torch.from_numpy(b.offsets).to(d) for b in batches]
+    go = [torch.from_numpy(b.grad_output).to(d) for b in batches]
+    lr = 0.01
+
+    def fresh():
+        a = [torch.from_numpy(c).to(d) for c in cores_h]
+        return a, [torch.empty_like(x) for x in a]
+
+    def two_steps(a, b, out, t0):
+        for j in range(2):
+            cur, nxt = (a, b) if j == 0 else (b, a)
+            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], wl.n_bags, out, t0[j])
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], lr, t0=t0[j])
+
+    def buffers():
+        return (torch.empty((wl.n_bags, t.dim), dtype=torch.float32, device=d),
+                [torch.empty((wl.n_bags, B.t0_floats(shape)), dtype=torch.float32, device=d) for _ in range(2)])
+
+    # eager: three times two steps, keeping the cores after every pair
+    a, b = fresh()
+    out, t0 = buffers()
+    eager = []
+    for _ in range(3):
+        two_steps(a, b, out, t0)
+        torch.cuda.synchronize()
+        eager.append([x.clone() for x in a])
+    # graph: capture the pair once, replay it three times with other work in between
+    ga, gb = fresh()
+    gout, gt0 = buffers()
+    two_steps(ga, gb, gout, gt0)                                   # warm-up outside the capture
+    for k in range(3):
+        ga[k].copy_(torch.from_numpy(cores_h[k]))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        two_steps(ga, gb, gout, gt0)
+    for k in range(3):
+        ga[k].copy_(torch.from_numpy(cores_h[k]))                  # the capture does not run anything
+    for rep in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        for k in range(3):
+            assert torch.equal(ga[k], eager[rep][k]), (rep, k)
+        _ = (gout * 2).sum().item()                                # unrelated eager work between replays
+    # and the first pair against the oracle
+    oc = [c.copy() for c in cores_h]
+    for j in range(2):
+        dg, _ = ora.bwd(oshape, oc, batches[j].indices, batches[j].offsets, batches[j].grad_output)
+        oc = [ora.sgd(oc[k], dg[k], lr) for k in range(3)]
+    for k in range(3):
+        assert_close(eager[0][k].cpu().numpy(), oc[k], "two benchmark steps, core %d" % (k + 1))
