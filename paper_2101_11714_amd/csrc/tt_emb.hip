@@ -314,7 +314,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
     }
     int32_t *slot = nullptr;
-    if (cd.K && L > 0) {
+    if (cd.K && L > 0 && !grouped) {                                      // the grouping pre-pass probes the cache itself
         slot = (int32_t *)workspace;
         hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
     }
@@ -324,8 +324,9 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
         const int n = 3 * (int)L;
         if (3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
-        hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, p, indices, (int)L, slot, cd.K, g.sort.k0);
-        hipLaunchKernelGGL(grp_clear_kernel, dim3(cdiv(nbins + 1, WG)), dim3(WG), 0, st, g.off, g.end, nbins, g.crange);
+        const int64_t kthreads = L > nbins + 1 ? L : nbins + 1;
+        hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(kthreads, WG)), dim3(WG), 0, st, p, indices, (int)L, cd, g.sort.k0, g.off,
+                           g.end, nbins, g.crange);
         int bits = 1;
         while ((1 << bits) <= nbins) ++bits;
         uint64_t *ks; uint32_t *vs;

@@ -50,35 +50,32 @@ static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
     return g;
 }
 
-// items[r * L + k]: key of item r of position k (see the file comment)
+// items[r * L + k]: key of item r of position k (see the file comment); the cache is probed here.
+// The first threads also clear the list bounds that grp_bounds_kernel fills after the sort.
 __global__ __launch_bounds__(WG) void grp_keys_kernel(Params p, const int64_t *__restrict__ indices, int L,
-                                                      const int32_t *__restrict__ slot, int K,
-                                                      uint64_t *__restrict__ keys)
+                                                      CacheDev cache, uint64_t *__restrict__ keys,
+                                                      int *__restrict__ off, int *__restrict__ end, int nbins,
+                                                      int *__restrict__ crange)
 {
     const int k = blockIdx.x * WG + threadIdx.x;
+    if (k <= nbins) { off[k] = 0; end[k] = 0; }
+    if (k < 2) crange[k] = 0;
     if (k >= L) return;
     const int nb3 = p.m1 + p.m2 + p.m3;
-    const uint64_t unused = (uint64_t)(nb3 + K);
-    const int sl = slot ? slot[k] : -1;
+    const uint64_t unused = (uint64_t)(nb3 + cache.K);
+    const uint32_t row = (uint32_t)indices[k];
+    const int sl = cache.K ? cache_probe(cache, row) : -1;
     if (sl >= 0) {
         keys[k] = (uint64_t)(nb3 + sl);
         keys[(size_t)L + k] = unused;
         keys[2 * (size_t)L + k] = unused;
     } else {
         int i1, i2, i3;
-        decode(p, (uint32_t)indices[k], i1, i2, i3);
+        decode(p, row, i1, i2, i3);
         keys[k] = (uint64_t)i1;
         keys[(size_t)L + k] = (uint64_t)(p.m1 + i2);
         keys[2 * (size_t)L + k] = (uint64_t)(p.m1 + p.m2 + i3);
     }
-}
-
-__global__ __launch_bounds__(WG) void grp_clear_kernel(int *__restrict__ off, int *__restrict__ end, int nbins,
-                                                       int *__restrict__ crange)
-{
-    const int i = blockIdx.x * WG + threadIdx.x;
-    if (i <= nbins) { off[i] = 0; end[i] = 0; }
-    if (i < 2) crange[i] = 0;
 }
 
 // list bounds of every key that occurs, and the range of the cached items
