@@ -186,8 +186,11 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
     flush(cur, cur != key_next);
 }
 
-// The wave of the tile in which a border-crossing run begins adds up its partial sums, in
-// tile order.  The run's last item is known from the list bounds, so the loads are independent.
+// A run that crosses tile borders is finished by the workgroup in whose tiles it begins: its four
+// waves add up the partial sums of the run's later tiles, wave w taking every fourth tile, and
+// the four results are added in wave order.  The run's last item is known from the list bounds,
+// so all loads are independent.  A workgroup looks at its NWAVE tiles one after the other (most
+// hold no such run).
 __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint64_t *__restrict__ ks,
                                                            const int *__restrict__ crange,
                                                            const int *__restrict__ gend,
@@ -195,42 +198,57 @@ __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint6
                                                            float *__restrict__ grad_cache)
 {
     constexpr int MAXC = 4;
+    __shared__ float red[NWAVE][MAXC * WAVE];
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
-    const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int cb = crange[0], ce = crange[1];
-    const int i0 = cb + tile * GT;
-    if (i0 >= ce) return;
-    const int i1 = min(ce, i0 + GT);
-    if (i1 >= ce) return;                                          // nothing to the right
-    const int key = (int)ks[i1 - 1];
-    if ((int)ks[i1] != key) return;                                // the last run ends in this tile
-    const bool single = (int)ks[i0] == key;
-    if (single && i0 > cb && (int)ks[i0 - 1] == key) return;       // a middle tile of the run: not the owner
-    const int last_tile = (gend[key] - 1 - cb) / GT;               // tile that holds the run's last item
-    float sum[MAXC];
+    for (int q = 0; q < NWAVE; ++q) {                              // every test below is uniform in the workgroup
+        const int tile = blockIdx.x * NWAVE + q;
+        const int i0 = cb + tile * GT;
+        if (i0 >= ce) break;
+        const int i1 = min(ce, i0 + GT);
+        if (i1 >= ce) break;                                       // nothing to the right
+        const int key = (int)ks[i1 - 1];
+        if ((int)ks[i1] != key) continue;                          // the last run ends in this tile
+        const bool single = (int)ks[i0] == key;
+        if (single && i0 > cb && (int)ks[i0 - 1] == key) continue; // a middle tile of the run: it begins elsewhere
+        const int last_tile = (gend[key] - 1 - cb) / GT;           // tile that holds the run's last item
+        float sum[MAXC];
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) sum[c] = lane + 64 * c < N ? part[((size_t)tile * 2 + 1) * N + lane + 64 * c] : 0.f;
-    for (int u0 = tile + 1; u0 <= last_tile; u0 += 16) {
-        float x[16][MAXC];
+        for (int c = 0; c < MAXC; ++c)
+            sum[c] = (w == 0 && lane + 64 * c < N) ? part[((size_t)tile * 2 + 1) * N + lane + 64 * c] : 0.f;
+        for (int u0 = tile + 1 + w; u0 <= last_tile; u0 += 16 * NWAVE) {
+            float x[16][MAXC];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int u = min(u0 + q, last_tile);
+            for (int j = 0; j < 16; ++j) {
+                const int u = min(u0 + j * NWAVE, last_tile);
 #pragma unroll
-            for (int c = 0; c < MAXC; ++c)
-                x[q][c] = lane + 64 * c < N ? part[((size_t)u * 2 + 0) * N + lane + 64 * c] : 0.f;
+                for (int c = 0; c < MAXC; ++c)
+                    x[j][c] = lane + 64 * c < N ? part[((size_t)u * 2 + 0) * N + lane + 64 * c] : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (u0 + j * NWAVE <= last_tile) {
+#pragma unroll
+                    for (int c = 0; c < MAXC; ++c) sum[c] += x[j][c];
+                }
         }
 #pragma unroll
-        for (int q = 0; q < 16; ++q)
-            if (u0 + q <= last_tile) {
+        for (int c = 0; c < MAXC; ++c) red[w][lane + 64 * c] = sum[c];
+        __syncthreads();
+        if (w == 0) {
+            float *dst = grad_cache + (size_t)(key - nb3) * N;
 #pragma unroll
-                for (int c = 0; c < MAXC; ++c) sum[c] += x[q][c];
-            }
+            for (int c = 0; c < MAXC; ++c)
+                if (lane + 64 * c < N) {
+                    float tot = red[0][lane + 64 * c];
+#pragma unroll
+                    for (int j = 1; j < NWAVE; ++j) tot += red[j][lane + 64 * c];
+                    dst[lane + 64 * c] += tot;
+                }
+        }
+        __syncthreads();
     }
-    float *dst = grad_cache + (size_t)(key - nb3) * N;
-#pragma unroll
-    for (int c = 0; c < MAXC; ++c)
-        if (lane + 64 * c < N) dst[lane + 64 * c] += sum[c];
 }
 
 }  // namespace tt
