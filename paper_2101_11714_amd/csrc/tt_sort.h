@@ -14,21 +14,23 @@ constexpr int SCAN_WG = 1024;
 static inline int rs_blocks(int64_t n) { return (int)((n + RS_TILE - 1) / RS_TILE); }
 
 // hist[bin * nblk + blk] = number of keys of tile blk whose digit is bin.
-__global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict__ keys, int n, int shift,
+// A pass sorts by `db` <= 8 bits of the key, taken at `shift` (1 << db bins).
+__global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict__ keys, int n, int shift, int db,
                                                      uint32_t *__restrict__ hist, int nblk)
 {
     __shared__ uint32_t h[256];
     const int t = threadIdx.x;
+    const uint32_t mask = (1u << db) - 1u;
     h[t] = 0;
     __syncthreads();
     const int base = blockIdx.x * RS_TILE;
 #pragma unroll
     for (int s = 0; s < RS_SUB; ++s) {
         int i = base + s * WG + t;
-        if (i < n) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+        if (i < n) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & mask], 1u);
     }
     __syncthreads();
-    hist[t * nblk + blockIdx.x] = h[t];
+    if (t <= (int)mask) hist[t * nblk + blockIdx.x] = h[t];
 }
 
 // In-place exclusive scan of data[0..total); data[total] receives the sum.  One workgroup.
@@ -97,25 +99,25 @@ __global__ __launch_bounds__(SCAN_WG) void scan_kernel(uint32_t *__restrict__ da
 // Stable scatter of one pass.  vin == nullptr means payload = position.
 __global__ __launch_bounds__(WG) void rs_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
                                                         uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
-                                                        int n, int shift, const uint32_t *__restrict__ hist, int nblk)
+                                                        int n, int shift, int db, const uint32_t *__restrict__ hist, int nblk)
 {
     __shared__ uint32_t base[256];
     __shared__ uint32_t cnt[NWAVE][256];
     const int t = threadIdx.x, w = t >> 6;
-    base[t] = hist[t * nblk + blockIdx.x];
+    const uint32_t mask = (1u << db) - 1u;
+    base[t] = t <= (int)mask ? hist[t * nblk + blockIdx.x] : 0u;
     const int tile = blockIdx.x * RS_TILE;
     for (int s = 0; s < RS_SUB; ++s) {
         const int i = tile + s * WG + t;
         const bool valid = i < n;
         const uint64_t key = valid ? kin[i] : 0ull;
-        const uint32_t dg = (uint32_t)(key >> shift) & 255u;
+        const uint32_t dg = (uint32_t)(key >> shift) & mask;
 #pragma unroll
         for (int j = 0; j < NWAVE; ++j) cnt[j][t] = 0;
         __syncthreads();
         // lanes of this wave that hold the same digit
         uint64_t same = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
+        for (int b = 0; b < db; ++b) {                              // uniform
             const bool bit = (dg >> b) & 1u;
             const uint64_t bal = __ballot(bit);
             same &= bit ? bal : ~bal;
@@ -254,10 +256,13 @@ static inline hipError_t radix_sort(const SortWs &s, int n, int bits, hipStream_
     uint32_t *vin = nullptr, *vout = s.v0;
     const int nblk = rs_blocks(n);
     bool first = true;
-    for (int shift = 0; shift < bits; shift += 8) {
-        hipLaunchKernelGGL(rs_hist_kernel, dim3(nblk), dim3(WG), 0, st, kin, n, shift, s.hist, nblk);
-        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, s.hist, 256 * nblk);
-        hipLaunchKernelGGL(rs_scatter_kernel, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift,
+    // as few passes as 8-bit digits allow, the bits spread evenly over them (a narrow digit means a short scan)
+    const int npass = (bits + 7) / 8;
+    const int db = (bits + npass - 1) / npass;
+    for (int shift = 0; shift < bits; shift += db) {
+        hipLaunchKernelGGL(rs_hist_kernel, dim3(nblk), dim3(WG), 0, st, kin, n, shift, db, s.hist, nblk);
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, s.hist, (1 << db) * nblk);
+        hipLaunchKernelGGL(rs_scatter_kernel, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift, db,
                            s.hist, nblk);
         uint64_t *tk = kin; kin = kout; kout = tk;
         if (first) { vin = s.v0; vout = s.v1; first = false; }
