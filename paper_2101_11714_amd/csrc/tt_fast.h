@@ -108,9 +108,11 @@ struct ReduceKeep {
 };
 
 // ---- forward ---------------------------------------------------------------------
-// One wave per bag.  The partial products of stage 1 are accumulated over the bag's
-// lookups (and cached rows are added on the lane with b0 = 0) before one shuffle
-// reduction per bag.
+// One wave per bag.  The wave reads the bag's positions 64 at a time and probes the cache
+// for all of them at once; cached rows are summed 64 / (N/4) at a time as float4 pieces,
+// the other positions go through the cores one after the other.  The partial products of
+// stage 1 are accumulated over the bag's lookups before one shuffle reduction per bag,
+// and the sum of the cached rows is added to the result at the end.
 template <typename C>
 __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__restrict__ G1,
                                                       const float *__restrict__ G2, const float *__restrict__ G3,
@@ -132,70 +134,105 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
 
     const int k0 = offsets ? (int)offsets[bag] : bag;
     const int k1 = offsets ? (int)offsets[bag + 1] : bag + 1;
-    for (int k = k0; k < k1; ++k) {
-        const uint32_t row = (uint32_t)__builtin_amdgcn_readfirstlane((int)indices[k]);
-        const float w = alpha ? alpha[k] : 1.f;
+    // cached rows: NG = 64 / NQ of them per step, lane (g, f) adds float4 f of the g-th one
+    constexpr int NQ = C::N / 4, NG = WAVE / NQ;
+    const int cg = lane / NQ, cf = lane % NQ;
+    float4 cacc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int kb = k0; kb < k1; kb += WAVE) {
+        // The wave reads up to 64 positions of the bag at once and probes the cache for all of them, so the
+        // chain index -> probe -> row data is walked once per 64 positions, not once per position.
+        int pk = kb + lane;
+        const bool valid = pk < k1;
+        uint32_t prow = valid ? (uint32_t)indices[pk] : 0u;
+        float pw = valid && alpha ? alpha[pk] : 1.f;
+        int nb = k1 - kb < WAVE ? k1 - kb : WAVE, first = 0;       // positions first .. nb-1 go through the cores
         if (cache.K) {
-            const int slot = __builtin_amdgcn_readfirstlane(cache_probe(cache, row));
-            if (slot >= 0) {
-                if (active && b0 == 0) {
-                    const float *cr = cache.rows + (size_t)slot * C::N + j2 * N3;
-#pragma unroll
-                    for (int j1 = 0; j1 < N1; ++j1) {
-                        const float4 t = *reinterpret_cast<const float4 *>(cr + j1 * N2 * N3);
-                        acc[j1 * N3 + 0] = fmaf(w, t.x, acc[j1 * N3 + 0]);
-                        acc[j1 * N3 + 1] = fmaf(w, t.y, acc[j1 * N3 + 1]);
-                        acc[j1 * N3 + 2] = fmaf(w, t.z, acc[j1 * N3 + 2]);
-                        acc[j1 * N3 + 3] = fmaf(w, t.w, acc[j1 * N3 + 3]);
+            int pslot = valid ? cache_probe(cache, prow) : -1;
+            const uint64_t hits = __ballot(pslot >= 0), lt = lanemask_lt();
+            const int nhit = __popcll(hits);
+            if (nhit) {
+                // hits to lanes 0 .. nhit-1, the rest behind them, both in their old order
+                const int dst = 4 * (pslot >= 0 ? __popcll(hits & lt) : nhit + __popcll(~hits & lt));
+                pslot = __builtin_amdgcn_ds_permute(dst, pslot);
+                pk = __builtin_amdgcn_ds_permute(dst, pk);
+                prow = (uint32_t)__builtin_amdgcn_ds_permute(dst, (int)prow);
+                pw = __int_as_float(__builtin_amdgcn_ds_permute(dst, __float_as_int(pw)));
+                for (int h0 = 0; h0 < nhit; h0 += NG) {
+                    const int h = h0 + cg;
+                    const int sl = __shfl(pslot, h & 63);
+                    const float w = __shfl(pw, h & 63);
+                    if (h < nhit) {
+                        const float4 t = *reinterpret_cast<const float4 *>(cache.rows + (size_t)sl * C::N + 4 * cf);
+                        cacc.x = fmaf(w, t.x, cacc.x); cacc.y = fmaf(w, t.y, cacc.y);
+                        cacc.z = fmaf(w, t.z, cacc.z); cacc.w = fmaf(w, t.w, cacc.w);
                     }
                 }
-                continue;
+                first = nhit;
             }
         }
-        int i1, i2, i3;
-        decode(p, row, i1, i2, i3);
-        const float *A = G1 + (size_t)i1 * C::sA;
-        const float *B = G2 + (size_t)i2 * C::sB + c0;
-        const float *Cp = G3 + (size_t)i3 * C::sC + b0 * N3;
-        float t0[N1][V];
+        for (int j = first; j < nb; ++j) {
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)prow, j);
+            const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pw), j));
+            const int k = __builtin_amdgcn_readlane(pk, j);
+            int i1, i2, i3;
+            decode(p, row, i1, i2, i3);
+            const float *A = G1 + (size_t)i1 * C::sA;
+            const float *B = G2 + (size_t)i2 * C::sB + c0;
+            const float *Cp = G3 + (size_t)i3 * C::sC + b0 * N3;
+            float t0[N1][V];
 #pragma unroll
-        for (int j1 = 0; j1 < N1; ++j1)
+            for (int j1 = 0; j1 < N1; ++j1)
 #pragma unroll
-            for (int v = 0; v < V; ++v) t0[j1][v] = 0.f;
+                for (int v = 0; v < V; ++v) t0[j1][v] = 0.f;
 #pragma unroll
-        for (int a = 0; a < R; ++a) {
-            float bv[V];
-            load_vec<V>(B + a * C::COLS, bv);
+            for (int a = 0; a < R; ++a) {
+                float bv[V];
+                load_vec<V>(B + a * C::COLS, bv);
 #pragma unroll
-            for (int j1 = 0; j1 < N1; ++j1) {
-                const float av = A[j1 * R + a];
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float av = A[j1 * R + a];
 #pragma unroll
-                for (int v = 0; v < V; ++v) t0[j1][v] = fmaf(av, bv[v], t0[j1][v]);
+                    for (int v = 0; v < V; ++v) t0[j1][v] = fmaf(av, bv[v], t0[j1][v]);
+                }
             }
-        }
-        if (t0_out && active) {                             // keep T0[(j1,j2)][b] of this position for the backward pass
-            float *o = t0_out + (size_t)k * (N1 * C::COLS) + c0;
+            if (t0_out && active) {                             // keep T0[(j1,j2)][b] of this position for the backward pass
+                float *o = t0_out + (size_t)k * (N1 * C::COLS) + c0;
 #pragma unroll
-            for (int j1 = 0; j1 < N1; ++j1) store_vec<V>(o + j1 * C::COLS, t0[j1]);
-        }
+                for (int j1 = 0; j1 < N1; ++j1) store_vec<V>(o + j1 * C::COLS, t0[j1]);
+            }
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const float4 cv = *reinterpret_cast<const float4 *>(Cp + v * N3);
+            for (int v = 0; v < V; ++v) {
+                const float4 cv = *reinterpret_cast<const float4 *>(Cp + v * N3);
 #pragma unroll
-            for (int j1 = 0; j1 < N1; ++j1) {
-                const float tw = w * t0[j1][v];
-                acc[j1 * N3 + 0] = fmaf(tw, cv.x, acc[j1 * N3 + 0]);
-                acc[j1 * N3 + 1] = fmaf(tw, cv.y, acc[j1 * N3 + 1]);
-                acc[j1 * N3 + 2] = fmaf(tw, cv.z, acc[j1 * N3 + 2]);
-                acc[j1 * N3 + 3] = fmaf(tw, cv.w, acc[j1 * N3 + 3]);
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float tw = w * t0[j1][v];
+                    acc[j1 * N3 + 0] = fmaf(tw, cv.x, acc[j1 * N3 + 0]);
+                    acc[j1 * N3 + 1] = fmaf(tw, cv.y, acc[j1 * N3 + 1]);
+                    acc[j1 * N3 + 2] = fmaf(tw, cv.z, acc[j1 * N3 + 2]);
+                    acc[j1 * N3 + 3] = fmaf(tw, cv.w, acc[j1 * N3 + 3]);
+                }
             }
         }
     }
     group_reduce<C::NV, C::LN>(acc, lane);
     constexpr int KEEP = ReduceKeep<C::NV, C::LN>::value;
     const int lg = lane % C::LN;
+    const int base = reduce_base<C::NV, C::LN>(lane);
+    if (cache.K) {
+        // every lane gets the sum of float4 f over the groups, then the writers fetch their elements
+#pragma unroll
+        for (int d = NQ; d < WAVE; d <<= 1) {
+            cacc.x += __shfl_xor(cacc.x, d); cacc.y += __shfl_xor(cacc.y, d);
+            cacc.z += __shfl_xor(cacc.z, d); cacc.w += __shfl_xor(cacc.w, d);
+        }
+#pragma unroll
+        for (int i = 0; i < KEEP; ++i) {
+            const int idx = base + i, j1 = idx / N3, j3 = idx % N3, q = j1 * N2 + j2;
+            const float x = __shfl(cacc.x, q), y = __shfl(cacc.y, q), z = __shfl(cacc.z, q), u = __shfl(cacc.w, q);
+            acc[i] += j3 == 0 ? x : (j3 == 1 ? y : (j3 == 2 ? z : u));
+        }
+    }
     if (active && lg < ReduceKeep<C::NV, C::LN>::writers) {
-        const int base = reduce_base<C::NV, C::LN>(lane);
         float *o = out + (size_t)bag * C::N;
 #pragma unroll
         for (int i = 0; i < KEEP; ++i) {
