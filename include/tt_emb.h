@@ -31,7 +31,10 @@
  *  - Return value: TT_OK or a negative TT_ERR_* code; tt_last_error() gives a
  *    text for the last failure on the calling thread.  No C++ exception crosses
  *    the boundary.  On error nothing has been enqueued.
- *  - Limits: d = 3, num_rows < 2^31, L < 2^31, fp32 data.
+ *  - Every fp32 array (cores, outputs, gradients, cache rows, kept T0) and every
+ *    workspace must start on a 16-byte boundary; TT_ERR_BAD_ARG otherwise.
+ *  - Limits: d = 3, num_rows < 2^31, L < 2^31 (3 L < 2^31 in the backward pass of
+ *    the shapes with a specialised kernel), fp32 data.
  */
 #ifndef TT_EMB_H
 #define TT_EMB_H

@@ -5,6 +5,7 @@
 #include "../../include/tt_emb.h"
 
 #include <stdarg.h>
+#include <initializer_list>
 #include <stdio.h>
 #include <string.h>
 
@@ -95,6 +96,14 @@ int check_cache(const tt_cache_t *c, CacheDev *dev, bool need_rows)
     return TT_OK;
 }
 
+// The kernels move fp32 data in 16-byte pieces: true if any of the given arrays does not start on one.
+bool misaligned(std::initializer_list<const void *> ptrs)
+{
+    uintptr_t bits = 0;
+    for (const void *q : ptrs) bits |= (uintptr_t)q;
+    return (bits & 15) != 0;
+}
+
 int hip_fail(hipError_t e, const char *what)
 {
     return fail(TT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -136,6 +145,13 @@ size_t fwd_bwd_ws_bytes(const Params &p, int64_t L, int64_t K)
     return 256 + slot_ws_bytes(L, K != 0) + group_ws_layout(nullptr, L, p.m1 + p.m2 + p.m3 + (int)K, p.N).bytes;
 }
 
+// partial slice gradients of the roles that the specialised backward kernel splits over several workgroups
+size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
+{
+    const size_t n = fast_bwd_supported(p) ? fast_bwd_split_floats(p, (int)L, grouped) : 0;
+    return n ? align256(n * sizeof(float)) : 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -162,7 +178,7 @@ size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags
     Params p;
     if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
     if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
-    return fwd_bwd_ws_bytes(p, L, cache_rows);
+    return fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes(p, L, false);
 }
 
 size_t tt_emb_dedup_workspace_bytes(int64_t L)
@@ -195,6 +211,8 @@ static int fwd_common(const tt_shape_t *shape, const float *const cores[3],
         if (L > 0 && !t0_out) return fail(TT_ERR_NULL, "t0 is NULL");
         if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps T0 for this shape");
     }
+    if (misaligned({cores[0], cores[1], cores[2], output, t0_out, cd.rows}))
+        return fail(TT_ERR_BAD_ARG, "cores, output, t0 and cache rows must be 16-byte aligned");
     if (n_bags == 0) return TT_OK;
     hipStream_t st = (hipStream_t)stream;
 
@@ -259,8 +277,13 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if ((rc = check_cache(cache, &cd, fused))) return rc;
     if (!fused && cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
     if (t0 && !fast_bwd_supported(p)) return fail(TT_ERR_UNSUPPORTED, "no kernel uses a kept T0 for this shape");
+    if (misaligned({cores[0], cores[1], cores[2], grad_output, t0, cd.rows, workspace}) ||
+        (fused ? misaligned({cores_out[0], cores_out[1], cores_out[2]})
+               : misaligned({grad_cores[0], grad_cores[1], grad_cores[2], grad_cache})))
+        return fail(TT_ERR_BAD_ARG, "cores, gradients, t0, cache rows and workspace must be 16-byte aligned");
     const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
     const bool grouped = fast && (g_fast_path == 2 || L >= (cd.K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+    if (grouped && 3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
     const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
     const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
     // the fused step keeps the gradient of the cached rows, and without a specialised kernel the
@@ -269,8 +292,9 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     size_t g_bytes[3] = {0, 0, 0};
     if (fused && !fast)
         for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
-    const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2];
-    const bool wants_ws = cd.K || grouped || (fused && !fast);
+    const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped) : 0;
+    const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
+    const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
     if (wants_ws && (!workspace || workspace_bytes < need))
         return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     if (L == 0 && !fused) return TT_OK;
@@ -285,6 +309,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if (!fast && (rc = allow_lds(bwd_generic_kernel, lds_core))) return rc;
     if (cd.K && !grouped && (rc = allow_lds(bwd_cache_kernel, lds_cache))) return rc;
 
+    float *split_ws = sp_bytes ? (float *)((char *)workspace + need - sp_bytes) : nullptr;
     float *gtmp[3] = {nullptr, nullptr, nullptr};
     if (fused) {
         char *q = (char *)workspace + need_bwd;
@@ -323,7 +348,6 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         const int nb3 = p.m1 + p.m2 + p.m3, nbins = nb3 + cd.K;
         GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
         const int n = 3 * (int)L;
-        if (3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
         const int64_t kthreads = L > nbins + 1 ? L : nbins + 1;
         hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(kthreads, WG)), dim3(WG), 0, st, p, indices, (int)L, cd, g.sort.k0, g.off,
                            g.end, nbins, g.crange);
@@ -341,14 +365,14 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                                grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, st);
+                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, split_ws, st);
     } else {
         if (cd.K && L > 0)
             hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
                                offsets, (int)n_bags, alpha, grad_output, grad_cache);
         if (fast) {
             fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, t0, st);
+                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, t0, split_ws, st);
         } else if (L > 0) {
             hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
                                cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
@@ -422,7 +446,7 @@ size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_
     Params p;
     if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
     if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
-    size_t n = fwd_bwd_ws_bytes(p, L, cache_rows) + align256((size_t)cache_rows * p.N * 4);
+    size_t n = fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes(p, L, false) + align256((size_t)cache_rows * p.N * 4);
     n += align256((size_t)p.m1 * p.sA * 4) + align256((size_t)p.m2 * p.sB * 4) + align256((size_t)p.m3 * p.sC * 4);
     return n;
 }
@@ -643,6 +667,7 @@ int tt_dense_bag_fwd(const float *table, int64_t num_rows, int32_t N,
     int rc = check_dense(table, num_rows, N, indices, L, offsets, n_bags);
     if (rc) return rc;
     if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
+    if (misaligned({table, output})) return fail(TT_ERR_BAD_ARG, "table and output must be 16-byte aligned");
     if (n_bags == 0) return TT_OK;
     hipLaunchKernelGGL(dense_fwd_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, table, (int)N,
                        indices, offsets, (int)n_bags, alpha, output);
@@ -657,6 +682,7 @@ int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
     int rc = check_dense(table, num_rows, N, indices, L, offsets, n_bags);
     if (rc) return rc;
     if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (misaligned({table, grad_output})) return fail(TT_ERR_BAD_ARG, "table and grad_output must be 16-byte aligned");
     if (n_bags == 0 || L == 0) return TT_OK;
     hipLaunchKernelGGL(dense_bwd_sgd_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, table, (int)N,
                        indices, offsets, (int)n_bags, alpha, grad_output, lr);
@@ -820,15 +846,17 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
     if (which < 0 || which > 3) return fail(TT_ERR_BAD_ARG, "which must be 0..3");
     if (!n_out) return fail(TT_ERR_NULL, "n_out is NULL");
     hipStream_t st = (hipStream_t)stream;
+    if (L > 0) {
+        if (!indices || !uniq || !count || !perm) return fail(TT_ERR_NULL, "NULL array");
+        const size_t need = sort_ws_layout(nullptr, L).bytes;
+        if (!workspace || workspace_bytes < need)
+            return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    }
     hipLaunchKernelGGL(uq_init_kernel, dim3(1), dim3(64), 0, st, n_out, L);
     if (L == 0) {
         hipError_t e0 = hipGetLastError();
         return e0 == hipSuccess ? TT_OK : hip_fail(e0, "dedup launch");
     }
-    if (!indices || !uniq || !count || !perm) return fail(TT_ERR_NULL, "NULL array");
-    const size_t need = sort_ws_layout(nullptr, L).bytes;
-    if (!workspace || workspace_bytes < need)
-        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     SortWs ws = sort_ws_layout(workspace, L);
     const int n = (int)L;
     // number of key bits: the sentinel (all ones) must exceed every real key

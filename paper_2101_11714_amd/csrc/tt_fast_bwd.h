@@ -43,7 +43,16 @@ constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
 #if defined(TT_PROFILE)
 __device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], debug builds only
 #endif
-#if defined(TT_PROFILE) && TT_PROFILE == 2
+#if defined(TT_PROFILE) && TT_PROFILE == 2 && defined(TT_PROFILE_SUM)
+// stamps 1..6 sum the cycles since the previous stamp over all windows of a workgroup (ts[14] = previous stamp)
+#define TT_STAMP(i)                                                                     \
+    do {                                                                                \
+        const unsigned long long now_ = __builtin_readcyclecounter();                   \
+        if ((i) >= 1 && (i) <= 6) ts[(i)] += now_ - ts[14]; else ts[(i)] = now_;         \
+        if ((i) != 15) ts[14] = now_;                                                   \
+    } while (0)
+#define TT_NOTE(i, v) ts[(i)] += (unsigned long long)(v)
+#elif defined(TT_PROFILE) && TT_PROFILE == 2
 #define TT_STAMP(i) ts[(i)] = __builtin_readcyclecounter()
 #define TT_NOTE(i, v) ts[(i)] = (unsigned long long)(v)
 #else
@@ -51,9 +60,32 @@ __device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], d
 #define TT_NOTE(i, v) do { } while (0)
 #endif
 
+typedef float mfma16_t __attribute__((ext_vector_type(16)));
+typedef float mfma4_t __attribute__((ext_vector_type(4)));
+
 // *dst += x where no other thread touches *dst.  (An add performed by the memory system, without
 // a returned value, was measured and is slower here than load, add, store.)
 __device__ __forceinline__ void add_to(float *dst, float x) { *dst += x; }
+
+// Several workgroups may share one slice (only used for the (4,4,4) shapes, whose lists get long and
+// whose rows are expensive): ns[r] workgroups per slice of core r, each takes one part of the
+// positions and, where ns[r] > 1, stores its partial slice gradient at part[r] + (slice ns[r] +
+// part) * slice size instead of finishing the slice; bwd_split_finish_kernel adds the parts up.
+struct FbSplit {
+    int ns[3];
+    float *part[3];
+};
+
+// Part `part` of `nparts` of the positions (scan, gran = FB_CAP) or list entries (grouped, gran = one window of
+// 64) [lo, end), in whole pieces of `gran`.
+__device__ __forceinline__ void fb_part_range(int part, int nparts, int gran, int &lo, int &end)
+{
+    if (nparts > 1) {
+        const int per = (((end - lo + nparts - 1) / nparts + gran - 1) / gran) * gran;
+        lo = min(end, lo + part * per);
+        end = min(end, lo + per);
+    }
+}
 
 template <typename C>
 struct FbCfg {
@@ -68,6 +100,8 @@ struct FbCfg {
     // the extra loads and the idle row slots of short lists cost more than the saved round trip)
     static constexpr int BUDGET = 32;
     static constexpr int UB = BUDGET / BMR >= 4 ? 4 : (BUDGET / BMR >= 1 ? BUDGET / BMR : 1);
+    // (4,4,4) shapes: the G2 owner multiplies on the matrix cores, wave w owning the columns with j2 = w
+    static constexpr bool MFMA = C::N1 == 4 && C::N2 == NWAVE && C::R % 32 == 0;
     static_assert(W <= FB_CAP && (W % FB_PIECE == 0 || W < FB_PIECE), "windows hold whole pieces");
     static_assert(SB % UB == 0, "register batches must not straddle LDS batches");
 };
@@ -218,7 +252,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         const uint32_t *__restrict__ gvals, const int *__restrict__ goff,
                                         const int *__restrict__ gend, float lr, float *__restrict__ o1,
                                         float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
-                                        uint32_t (&rowv)[FB_ITER])
+                                        uint32_t (&rowv)[FB_ITER], int part, int nparts, float *__restrict__ pout)
 {
     using F = FbCfg<C>;
     const bool t0mode = ROLE == 2 && t0 != nullptr;                    // the G3 owner uses the stored T0
@@ -227,6 +261,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     // one that no lookup touches).
     const bool fused = o1 != nullptr;
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V, N = C::N, RQ = C::RQ;
+    constexpr bool MFMA = F::MFMA;
     constexpr int W = F::W, NQ = N / 4, SB = F::SB, UB = F::UB, SMALL = F::SMALL;
     // float4 of small operands per row: G1 slice (needed by the G2 and G3 owners) and G3 slice (G1, G2 owners)
     constexpr int PA = C::sA / 4, PC = C::sC / 4;
@@ -243,10 +278,17 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 
     // accumulators: G1 owner N1*RQ lane partials, G2 owner RQ*V elements, G3 owner V*N3 partials
     constexpr int NACC1 = N1 * RQ, NACC2 = RQ * V, NACC3 = V * N3;
-    constexpr int NACC = NACC1 > NACC2 ? (NACC1 > NACC3 ? NACC1 : NACC3) : (NACC2 > NACC3 ? NACC2 : NACC3);
+    // (on the matrix cores the G2 owner keeps its 32 x 32 result tiles in accm instead)
+    constexpr int NACC = MFMA ? (NACC1 > NACC3 ? NACC1 : NACC3) : (NACC1 > NACC2 ? (NACC1 > NACC3 ? NACC1 : NACC3) : (NACC2 > NACC3 ? NACC2 : NACC3));
     float acc[NACC];
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
+    constexpr int NTILE = MFMA ? (R / 32) * (R / 32) : 1;
+    mfma16_t accm[NTILE];
+#pragma unroll
+    for (int i = 0; i < NTILE; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accm[i][r] = 0.f;
     bool any = false;
     // Fused SGD step: every workgroup rewrites its slice, so the old values are loaded now and the
     // last phase does not wait for them (where that takes few registers).
@@ -496,7 +538,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                             }
                         }
                     }
-                if (ROLE == 1) {
+                if (!MFMA && ROLE == 1) {
 #pragma unroll
                     for (int u = 0; u < UH; ++u)
 #pragma unroll
@@ -511,7 +553,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                     for (int v = 0; v < V; ++v)
                                         acc[(a4 + q) * V + v] = fmaf(ax[q], dt[u][j1][v], acc[(a4 + q) * V + v]);
                             }
-                } else {
+                } else if (ROLE == 0) {
 #pragma unroll
                     for (int u = 0; u < UH; ++u)
 #pragma unroll
@@ -558,6 +600,92 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                         acc[v * N3 + 3] = fmaf(tk, g.w, acc[v * N3 + 3]);
                     }
                 }
+        }
+    };
+
+    // ---- (4,4,4) shapes: the contraction of the G2 owner runs on the matrix cores ----
+    // There wave w owns the R columns c = (j2 = w, b) of the unfolded G2 slice, the operands come
+    // from global memory (L2) straight in the layout the instruction wants, the loads of the next
+    // rows are in flight while the current ones are multiplied, and nothing but dY goes through
+    // LDS.  accm holds the result tiles between windows.  (The G1 owner stays on the vector ALUs:
+    // it streams a whole G2 slice per row and is bound by that traffic, not by its arithmetic; a
+    // version on the matrix cores was measured and was no faster.)
+    constexpr int RT = R / 32;                                            // 32 x 32 tiles per side of a wave's R x R block
+    const int ln = lane & 31, kh = lane >> 5;
+
+    // G2 owner: dG2[a][c] += sum_j1 A[j1][a] dT0'[j1][c] as D(32x32) += A(32x2) B(2x32), two steps
+    // per row (j1 = 2h + k): lane (k = kh, i or j = ln) supplies A[j1][32 ta + ln] and
+    // dT0'[j1][c = w R + 32 tc + ln] = dY[(j1,w)] . C[32 tc + ln], computed by the lane itself.
+    auto consume_g2_mfma = [&](int nsegs) __attribute__((always_inline)) {
+        if constexpr (MFMA) {
+            // ring of PD rows: a slot is refilled with the row PD further on as soon as it has been used
+            constexpr int PD = RT == 1 ? 8 : 4;
+            struct Ops { float a[RT][2]; float4 c[RT]; };
+            auto issue = [&](int i1, int i3, Ops &o) __attribute__((always_inline)) {
+                const float *A = G1 + (size_t)i1 * C::sA + kh * R + ln;
+                const float *Cs = G3 + (size_t)i3 * C::sC + ln * N3;
+#pragma unroll
+                for (int ta = 0; ta < RT; ++ta) {
+                    o.a[ta][0] = A[32 * ta];
+                    o.a[ta][1] = A[2 * R + 32 * ta];
+                    o.c[ta] = *reinterpret_cast<const float4 *>(Cs + 32 * ta * N3);
+                }
+            };
+            Ops ring[PD];
+            {
+                int i1v[PD], i3v[PD];
+#pragma unroll
+                for (int u = 0; u < PD; ++u) {
+                    i1v[u] = lds.seg_i1[min(u, nsegs - 1)];
+                    i3v[u] = lds.seg_i3[min(u, nsegs - 1)];
+                }
+#pragma unroll
+                for (int u = 0; u < PD; ++u)
+                    issue(__builtin_amdgcn_readfirstlane(i1v[u]), __builtin_amdgcn_readfirstlane(i3v[u]), ring[u]);
+            }
+            // No branches inside a turn of the ring: rows past the end repeat the last one with a zero
+            // weight.  Four rows at a time: all their LDS reads (where dY starts, dY itself, the digits
+            // of the rows that take over the ring slots) are in flight together.
+            for (int g0 = 0; g0 < nsegs; g0 += PD) {                      // uniform
+#pragma unroll
+                for (int u0 = 0; u0 < PD; u0 += 4) {
+                    int st[4], i1v[4], i3v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        st[u] = lds.seg_start[min(g0 + u0 + u, nsegs - 1)];
+                        i1v[u] = lds.seg_i1[min(g0 + u0 + u + PD, nsegs - 1)];
+                        i3v[u] = lds.seg_i3[min(g0 + u0 + u + PD, nsegs - 1)];
+                    }
+                    float4 q[4][2];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float *dy = stage + st[u] * N + (kh * N2 + w) * N3;
+                        q[u][0] = *reinterpret_cast<const float4 *>(dy);
+                        q[u][1] = *reinterpret_cast<const float4 *>(dy + 2 * N2 * N3);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float keep = g0 + u0 + u < nsegs ? 1.f : 0.f;
+                        Ops &o = ring[u0 + u];
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            float b[RT];
+#pragma unroll
+                            for (int tc = 0; tc < RT; ++tc) {
+                                const float4 cv = o.c[tc];
+                                b[tc] = keep * fmaf(q[u][h].x, cv.x, fmaf(q[u][h].y, cv.y, fmaf(q[u][h].z, cv.z, q[u][h].w * cv.w)));
+                            }
+#pragma unroll
+                            for (int ta = 0; ta < RT; ++ta)
+#pragma unroll
+                                for (int tc = 0; tc < RT; ++tc)
+                                    accm[ta * RT + tc] =
+                                        __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[ta][h], b[tc], accm[ta * RT + tc], 0, 0, 0);
+                        }
+                        issue(__builtin_amdgcn_readfirstlane(i1v[u]), __builtin_amdgcn_readfirstlane(i3v[u]), o);
+                    }
+                }
+            }
         }
     };
 
@@ -642,10 +770,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
+            const bool mm = MFMA && ROLE == 1;                            // this owner multiplies on the matrix cores
             float bm[UB][RQ][V];
-            if (ROLE != 1 && !t0mode) bm_load(0, nsegs, bm);
+            if (ROLE != 1 && !t0mode && !mm) bm_load(0, nsegs, bm);
             TT_STAMP(3);
-            stage_items(i0, early_done ? 0 : nw * NQ, 0, t0mode ? 0 : min(SB, nsegs), wc);
+            stage_items(i0, early_done ? 0 : nw * NQ, 0, t0mode || mm ? 0 : min(SB, nsegs), wc);
             if (early_done) {
                 const float4 g = item_finish(early);
                 if (t < nw * NQ) *reinterpret_cast<float4 *>(&stage[4 * (NQ * lds.epos[t / NQ] + t % NQ)]) = g;
@@ -673,10 +802,11 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 }
                 __syncthreads();
             }
-            dt_prepare(0, min(SB, nsegs));
+            if (!mm) dt_prepare(0, min(SB, nsegs));
             TT_STAMP(5);
             if (t0mode) consume_t0(nsegs);
-            for (int ub0 = 0; ub0 < (t0mode ? 0 : nsegs); ub0 += UB) {
+            if (mm) consume_g2_mfma(nsegs);
+            for (int ub0 = 0; ub0 < (t0mode || mm ? 0 : nsegs); ub0 += UB) {
                 const int sb0 = (ub0 / SB) * SB;
                 if (ub0 > 0) {
                     if (ROLE != 1) bm_load(ub0, nsegs, bm);
@@ -706,7 +836,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     const int bin = (ROLE == 0 ? 0 : (ROLE == 1 ? p.m1 : p.m1 + p.m2)) + s;
     const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
     int lo = gvals ? goff[bin] : 0;
-    const int end = gvals ? gend[bin] : L;
+    int end = gvals ? gend[bin] : L;
+    fb_part_range(part, nparts, gvals ? FB_PIECE : FB_CAP, lo, end);
+    const int lo0 = lo;
     int span = gvals ? FB_CAP : FB_SCAN, round = 0;
     int fill[NWAVE] = {0, 0, 0, 0};                                    // entries of the sub-lists (scan only)
     while (lo < end) {
@@ -723,7 +855,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             pw[0] = pn;                                                    // one contiguous list
             lo = hi;
         } else {
-            if (lo > 0 || span != FB_SCAN || round > 0) fb_load_rows(indices, slot, lo, hi, rowv);
+            if (lo > lo0 || span != FB_SCAN || round > 0) fb_load_rows(indices, slot, lo, hi, rowv);
             int wc[NWAVE];
 #if defined(TT_PROFILE) && TT_PROFILE == 2
             fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, fill, wc, ts);
@@ -743,7 +875,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                     for (int j = 0; j < NWAVE; ++j) fill[j] += wc[j];
                     lo = hi;
-                    if (span == FB_CAP && (lo % FB_SCAN) == 0) span = FB_SCAN;
+                    if (span == FB_CAP && ((lo - lo0) % FB_SCAN) == 0) span = FB_SCAN;
                 }
                 if (over || lo >= end) {                                   // process what has been collected
 #pragma unroll                                                             // (after "over" the round is redone)
@@ -763,12 +895,27 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int i = 0; i < 16; ++i)
                 if (i < 10 || i > 11) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
     };
-    if (!any && !fused) { flush(); return; }
+    if (!any && !fused && !pout) { flush(); return; }
 #else
-    if (!any && !fused) return;
+    if (!any && !fused && !pout) return;
 #endif
 
-    if (ROLE == 1) {
+    if (MFMA && ROLE == 1) {
+        // result registers of the 32 x 32 tiles: register r of lane (kh, ln) is row 8 (r / 4) + 4 kh + r % 4, column ln
+#pragma unroll
+        for (int ta = 0; ta < (MFMA ? RT : 0); ++ta)
+#pragma unroll
+            for (int tc = 0; tc < RT; ++tc)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int a = 32 * ta + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
+                    const size_t i = (size_t)s * C::sB + (size_t)a * C::COLS + c;
+                    const float g = accm[MFMA ? ta * RT + tc : 0][r];
+                    if (pout) pout[a * C::COLS + c] = g;
+                    else if (fused) o2[i] = fmaf(-lr, g, G2[i]);
+                    else add_to(&dG2[i], g);
+                }
+    } else if (!MFMA && ROLE == 1) {
         if (active) {
             const size_t at = (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
 #pragma unroll
@@ -792,7 +939,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 const int idx = base + i;                                  // = j1 * RQ + aa
                 const int j1 = idx / RQ, aa = idx % RQ;
                 const size_t at = (size_t)s * C::sA + j1 * R + a0 + aa;
-                if (fused) o1[at] = fmaf(-lr, red[i], PREFETCH ? old[i] : G1[at]);
+                if (MFMA && pout) pout[j1 * R + a0 + aa] = red[i];
+                else if (fused) o1[at] = fmaf(-lr, red[i], PREFETCH ? old[i] : G1[at]);
                 else add_to(&dG1[at], red[i]);
             }
         }
@@ -818,7 +966,8 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                     for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
                 const size_t at = (size_t)s * C::sC + e;
-                if (fused) o3[at] = fmaf(-lr, sum, PREFETCH ? old[i] : G3[at]);
+                if (MFMA && pout) pout[e] = sum;
+                else if (fused) o3[at] = fmaf(-lr, sum, PREFETCH ? old[i] : G3[at]);
                 else add_to(&dG3[at], sum);
             }
         }
@@ -835,22 +984,42 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     const float *__restrict__ alpha, const int32_t *__restrict__ slot, const float *__restrict__ grad_out,
     float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
     const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend,
-    float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0)
+    float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
+    FbSplit sp)
 {
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
     const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
 #endif
-    // The index loads do not depend on the role: issue them before anything else.
     uint32_t rowv[FB_ITER];
-    if (!gvals) fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
-    __builtin_amdgcn_sched_barrier(0);
-    // role and slice of this workgroup, without branches so that all kernel arguments load together
-    const int g = blockIdx.x;
-    const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
-    const int role = ge1 + ge2;
-    const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-    fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv);
+    if constexpr (FbCfg<C>::MFMA) {
+        // role, slice and part of this workgroup (see FbSplit); the role is a constant in each copy of the
+        // body here: the three owners differ too much to share registers
+        const int g = blockIdx.x, n0 = p.m1 * sp.ns[0], n1 = p.m2 * sp.ns[1];
+        const int role = (g >= n0) + (g >= n0 + n1);
+        const int q = g - (role == 0 ? 0 : (role == 1 ? n0 : n0 + n1));
+        const int S = sp.ns[role], sl = q / S, part = q - sl * S;
+        float *pout = nullptr;
+        if (S > 1) pout = sp.part[role] + (size_t)q * (role == 0 ? C::sA : (role == 1 ? C::sB : C::sC));
+        if (!gvals) {
+            int lo = 0, end = L;
+            fb_part_range(part, S, FB_CAP, lo, end);
+            fb_load_rows(indices, slot, lo, min(end, lo + FB_SCAN), rowv);
+        }
+        if (role == 0) fb_body<C>(lds, p, 0, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
+        else if (role == 1) fb_body<C>(lds, p, 1, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
+        else fb_body<C>(lds, p, 2, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
+    } else {
+        // The index loads do not depend on the role: issue them before anything else.
+        if (!gvals) fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
+        __builtin_amdgcn_sched_barrier(0);
+        // role and slice of this workgroup, without branches so that all kernel arguments load together
+        const int g = blockIdx.x;
+        const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
+        const int role = ge1 + ge2;
+        const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
+        fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, 0, 1, nullptr);
+    }
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
         g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
@@ -859,15 +1028,89 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 #endif
 }
 
+// Sums the partial slice gradients of a split role (FbSplit) and finishes the slices: adds the sum to dG
+// (out == nullptr) or writes x - lr * sum to out.  One thread per element of the core.
+__global__ __launch_bounds__(WG) void bwd_split_finish_kernel(const float *__restrict__ part, int ns, int slice, int64_t n,
+                                                              const float *__restrict__ x, float *__restrict__ dG,
+                                                              float *__restrict__ out, float lr)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) {
+        const int64_t sl = i / slice, e = i - sl * slice;
+        const float *src = part + sl * ns * slice + e;
+        float sum = 0.f;
+        for (int h = 0; h < ns; ++h) sum += src[(int64_t)h * slice];
+        if (out) out[i] = fmaf(-lr, sum, x[i]);
+        else dG[i] += sum;
+    }
+}
+
+// Split factors for a call: only the (4,4,4) shapes, only where the lists are long enough to pay for the
+// extra pass.  The G1 owners, which stream a G2 slice per row, are split four ways.  Without the grouping
+// pre-pass (medium batches) the longest lists decide the kernel time (one hot row can fill a list), so the
+// other owners are split as well; with it the chip is full anyway and more workgroups only add overhead.
+template <typename C>
+static inline void fb_choose_split(int L, bool grouped, int (&ns)[3])
+{
+    ns[0] = ns[1] = ns[2] = 1;
+    if (FbCfg<C>::MFMA && L >= 4096) {
+        ns[0] = 4;
+        if (!grouped) ns[1] = ns[2] = 2;
+    }
+}
+
+static inline void fast_bwd_split(const Params &p, int L, bool grouped, int (&ns)[3])
+{
+    ns[0] = ns[1] = ns[2] = 1;
+    switch (fast_config(p)) {
+    case 4: fb_choose_split<Cfg444R32>(L, grouped, ns); break;
+    case 5: fb_choose_split<Cfg444R64>(L, grouped, ns); break;
+    default: break;
+    }
+}
+
+// floats of workspace the split needs (0 if nothing is split)
+static inline size_t fast_bwd_split_floats(const Params &p, int L, bool grouped)
+{
+    int ns[3];
+    fast_bwd_split(p, L, grouped, ns);
+    size_t n = 0;
+    if (ns[0] > 1) n += (size_t)ns[0] * p.m1 * p.sA;
+    if (ns[1] > 1) n += (size_t)ns[1] * p.m2 * p.sB;
+    if (ns[2] > 1) n += (size_t)ns[2] * p.m3 * p.sC;
+    return n;
+}
+
 template <typename C>
 static inline void launch_bwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
                               const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
                               const int *goff, const int *gend, float lr, float *o1, float *o2, float *o3,
-                              const float *t0, hipStream_t st)
+                              const float *t0, float *split_ws, hipStream_t st)
 {
-    hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(p.m1 + p.m2 + p.m3), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
-                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0);
+    FbSplit sp;
+    fb_choose_split<C>(L, gvals != nullptr, sp.ns);
+    const int m[3] = {p.m1, p.m2, p.m3}, slice[3] = {p.sA, p.sB, p.sC};
+    float *q = split_ws;
+    int grid = 0;
+    for (int r = 0; r < 3; ++r) {
+        sp.part[r] = nullptr;
+        if (sp.ns[r] > 1) {
+            sp.part[r] = q;
+            q += (size_t)sp.ns[r] * m[r] * slice[r];
+        }
+        grid += sp.ns[r] * m[r];
+    }
+    hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
+    const float *x[3] = {G1, G2, G3};
+    float *dG[3] = {dG1, dG2, dG3}, *out[3] = {o1, o2, o3};
+    for (int r = 0; r < 3; ++r) {
+        if (sp.ns[r] <= 1) continue;
+        const int64_t n = (int64_t)m[r] * slice[r];
+        const int blocks = (int)((n + WG - 1) / WG < 2048 ? (n + WG - 1) / WG : 2048);
+        hipLaunchKernelGGL(bwd_split_finish_kernel, dim3(blocks), dim3(WG), 0, st, sp.part[r], sp.ns[r], slice[r], n, x[r],
+                           dG[r], out[r], lr);
+    }
 }
 
 static inline bool fast_bwd_supported(const Params &p) { return fast_config(p) >= 0; }
@@ -876,15 +1119,15 @@ static inline void fast_bwd(const Params &p, const float *G1, const float *G2, c
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
                             float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
                             const int *gend, float lr, float *o1, float *o2, float *o3, const float *t0,
-                            hipStream_t st)
+                            float *split_ws, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
     default: break;
     }
 }

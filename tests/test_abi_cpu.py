@@ -52,8 +52,8 @@ def test_bad_shapes_are_rejected(mutate, code):
     l = B.lib()
     s = good_shape()
     mutate(s)
-    one = C.c_void_p(8)   # never dereferenced: the shape check comes first
-    arr = (C.c_void_p * 3)(8, 8, 8)
+    one = C.c_void_p(16)   # never dereferenced: the shape check comes first
+    arr = (C.c_void_p * 3)(16, 16, 16)
     assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, one, None, 0, None) == code
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, arr, None, None, 0, None) == code
     assert l.tt_emb_sgd_update(C.byref(s), arr, arr, C.c_float(0.1), None, None, 0, None) == code
@@ -66,17 +66,17 @@ def test_bad_shapes_are_rejected(mutate, code):
 def test_too_many_rows_is_unsupported():
     l = B.lib()
     s = B.make_shape(2 ** 31, (2048, 1024, 1024), (2, 2, 4), (1, 8, 8, 1))
-    arr = (C.c_void_p * 3)(8, 8, 8)
-    one = C.c_void_p(8)
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    one = C.c_void_p(16)
     assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, one, None, 0, None) == -6
 
 
 def test_null_and_bad_arguments():
     l = B.lib()
     s = good_shape()
-    arr = (C.c_void_p * 3)(8, 8, 8)
-    holes = (C.c_void_p * 3)(8, None, 8)
-    one = C.c_void_p(8)
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    holes = (C.c_void_p * 3)(16, None, 16)
+    one = C.c_void_p(16)
     assert l.tt_emb_fwd(None, arr, one, 1, None, 1, None, None, one, None, 0, None) == -1
     assert l.tt_emb_fwd(C.byref(s), None, one, 1, None, 1, None, None, one, None, 0, None) == -1
     assert l.tt_emb_fwd(C.byref(s), holes, one, 1, None, 1, None, None, one, None, 0, None) == -1
@@ -87,16 +87,24 @@ def test_null_and_bad_arguments():
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, None, arr, None, None, 0, None) == -1
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, holes, None, None, 0, None) == -1
     # the fused step: no output cores, output aliasing the input
-    out = (C.c_void_p * 3)(16, 16, 16)
+    out = (C.c_void_p * 3)(32, 32, 32)
     assert l.tt_emb_bwd_sgd(C.byref(s), arr, None, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -1
     assert l.tt_emb_bwd_sgd(C.byref(s), arr, holes, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -1
     assert l.tt_emb_bwd_sgd(C.byref(s), arr, arr, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -3
     assert l.tt_emb_bwd_sgd(C.byref(s), arr, out, one, 1, None, 1, None, None, None, C.c_float(0.1), None, 0, None) == -1
     # a cache without its gradient buffer, and without workspace
-    cache = B.TTCache(4, 16, 8, 8, 8)
+    cache = B.TTCache(4, 16, 16, 16, 16)
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(cache), one, arr, None, None, 0, None) == -1
     assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(cache), one, arr, one, None, 0, None) == -4
-    bad_cap = B.TTCache(100, 100, 8, 8, 8)
+    # fp32 arrays that do not start on a 16-byte boundary
+    odd = C.c_void_p(24)
+    skew = (C.c_void_p * 3)(16, 20, 16)
+    assert l.tt_emb_fwd(C.byref(s), skew, one, 1, None, 1, None, None, one, None, 0, None) == -3
+    assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, None, odd, None, 0, None) == -3
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, odd, arr, None, None, 0, None) == -3
+    assert l.tt_emb_bwd(C.byref(s), arr, one, 1, None, 1, None, None, one, skew, None, None, 0, None) == -3
+    assert l.tt_emb_bwd_sgd(C.byref(s), arr, skew, one, 1, None, 1, None, None, one, C.c_float(0.1), None, 0, None) == -3
+    bad_cap = B.TTCache(100, 100, 16, 16, 16)
     assert l.tt_emb_fwd(C.byref(s), arr, one, 1, None, 1, None, C.byref(bad_cap), one, None, 0, None) == -3
     assert l.tt_cache_lookup(None, one, 1, one, None) == -1
     assert l.tt_cache_build(C.byref(s), arr, one, one, 3, C.byref(cache), None, 0, None) == -3      # K > n_cand
@@ -108,7 +116,7 @@ def test_null_and_bad_arguments():
 def test_empty_calls_enqueue_nothing_and_succeed():
     l = B.lib()
     s = good_shape()
-    arr = (C.c_void_p * 3)(8, 8, 8)
+    arr = (C.c_void_p * 3)(16, 16, 16)
     assert l.tt_emb_fwd(C.byref(s), arr, None, 0, None, 0, None, None, None, None, 0, None) == 0
     assert l.tt_emb_bwd(C.byref(s), arr, None, 0, None, 0, None, None, None, arr, None, None, 0, None) == 0
     assert l.tt_emb_debug_decode(C.byref(s), None, 0, None, None, None, None) == 0
@@ -122,8 +130,8 @@ def test_binding_has_no_cpu_fallback():
 def test_tracker_and_refill_argument_checks():
     l = B.lib()
     s = good_shape()
-    arr = (C.c_void_p * 3)(8, 8, 8)
-    one = C.c_void_p(8)
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    one = C.c_void_p(16)
     good = B.TTFreq(1024, 8, 8)
     assert l.tt_freq_reset(None, None) == -1
     assert l.tt_freq_reset(C.byref(B.TTFreq(1000, 8, 8)), None) == -3          # not a power of two
@@ -133,7 +141,7 @@ def test_tracker_and_refill_argument_checks():
     assert l.tt_freq_update(C.byref(good), one, -1, None) == -3
     assert l.tt_freq_update(C.byref(good), None, 0, None) == 0
     assert l.tt_freq_export(C.byref(good), one, one, None, None) == -1
-    cache = B.TTCache(4, 16, 8, 8, 8)
+    cache = B.TTCache(4, 16, 16, 16, 16)
     assert l.tt_cache_refill(C.byref(s), arr, one, one, 3, C.byref(cache), None, 0, None) == -3     # K > n_cand
     assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, C.byref(cache), None, 0, None) == -4    # no workspace
     assert l.tt_cache_refill(C.byref(s), arr, one, one, 10, None, one, 1 << 20, None) == -1
@@ -143,9 +151,9 @@ def test_tracker_and_refill_argument_checks():
 def test_kept_t0_entry_points_check_their_arguments():
     l = B.lib()
     s = good_shape()
-    arr = (C.c_void_p * 3)(8, 8, 8)
-    out = (C.c_void_p * 3)(16, 16, 16)
-    one = C.c_void_p(8)
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    out = (C.c_void_p * 3)(32, 32, 32)
+    one = C.c_void_p(16)
     f = C.c_float(0.1)
     assert l.tt_emb_fwd_keep_t0(C.byref(s), arr, one, 1, None, 1, None, None, one, None, None) == -1      # no t0
     assert l.tt_emb_bwd_t0(C.byref(s), arr, one, 1, None, 1, None, None, one, None, arr, None, None, 0, None) == -1
@@ -158,7 +166,7 @@ def test_kept_t0_entry_points_check_their_arguments():
 
 def test_mean_weights_argument_checks():
     l = B.lib()
-    one = C.c_void_p(8)
+    one = C.c_void_p(16)
     assert l.tt_emb_mean_weights(one, -1, 4, None, one, None) == -3
     assert l.tt_emb_mean_weights(None, 2, 4, None, one, None) == -1
     assert l.tt_emb_mean_weights(one, 2, 4, None, None, None) == -1
@@ -168,7 +176,7 @@ def test_mean_weights_argument_checks():
 def test_init_argument_checks():
     l = B.lib()
     s = good_shape()
-    holes = (C.c_void_p * 3)(8, None, 8)
+    holes = (C.c_void_p * 3)(16, None, 16)
     assert l.tt_init_sampled_gaussian(None, holes, 1, None) == -1
     assert l.tt_init_sampled_gaussian(C.byref(s), None, 1, None) == -1
     assert l.tt_init_sampled_gaussian(C.byref(s), holes, 1, None) == -1
@@ -176,8 +184,8 @@ def test_init_argument_checks():
 
 def test_general_d_shape_and_argument_checks():
     l = B.lib()
-    arr = (C.c_void_p * 4)(8, 8, 8, 8)
-    one = C.c_void_p(8)
+    arr = (C.c_void_p * 4)(16, 16, 16, 16)
+    one = C.c_void_p(16)
     good = B.make_shape_d(1000, (10, 10, 10), (2, 2, 4), (1, 8, 8, 1))
     assert C.sizeof(B.TTShapeD) == 72 and B.TTShapeD.num_rows.offset == 8 and B.TTShapeD.m.offset == 16
     assert l.tt_embd_fwd(C.byref(good), arr, one, 1, None, 1, None, None, None) == -1          # no output
@@ -191,5 +199,5 @@ def test_general_d_shape_and_argument_checks():
         assert l.tt_embd_fwd(C.byref(bad), arr, one, 1, None, 1, None, one, None) == code
         assert l.tt_embd_bwd(C.byref(bad), arr, one, 1, None, 1, None, one, arr, None) == code
         assert l.tt_embd_sgd_update(C.byref(bad), arr, arr, C.c_float(0.1), 0, None) == code
-    holes = (C.c_void_p * 4)(8, None, 8, 8)
+    holes = (C.c_void_p * 4)(16, None, 16, 16)
     assert l.tt_embd_bwd(C.byref(good), arr, one, 1, None, 1, None, one, holes, None) == -1
