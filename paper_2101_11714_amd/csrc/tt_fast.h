@@ -132,13 +132,61 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
 #pragma unroll
     for (int i = 0; i < C::NV; ++i) acc[i] = 0.f;
 
+    // one position through the cores: T0 = A Bm (kept for the backward pass if asked for), then acc += w T0 C
+    auto through_cores = [&](uint32_t row, float w, int k) __attribute__((always_inline)) {
+        int i1, i2, i3;
+        decode(p, row, i1, i2, i3);
+        const float *A = G1 + (size_t)i1 * C::sA;
+        const float *B = G2 + (size_t)i2 * C::sB + c0;
+        const float *Cp = G3 + (size_t)i3 * C::sC + b0 * N3;
+        float t0[N1][V];
+#pragma unroll
+        for (int j1 = 0; j1 < N1; ++j1)
+#pragma unroll
+            for (int v = 0; v < V; ++v) t0[j1][v] = 0.f;
+#pragma unroll
+        for (int a = 0; a < R; ++a) {
+            float bv[V];
+            load_vec<V>(B + a * C::COLS, bv);
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) {
+                const float av = A[j1 * R + a];
+#pragma unroll
+                for (int v = 0; v < V; ++v) t0[j1][v] = fmaf(av, bv[v], t0[j1][v]);
+            }
+        }
+        if (t0_out && active) {                             // keep T0[(j1,j2)][b] of this position for the backward pass
+            float *o = t0_out + (size_t)k * (N1 * C::COLS) + c0;
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) store_vec<V>(o + j1 * C::COLS, t0[j1]);
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float4 cv = *reinterpret_cast<const float4 *>(Cp + v * N3);
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) {
+                const float tw = w * t0[j1][v];
+                acc[j1 * N3 + 0] = fmaf(tw, cv.x, acc[j1 * N3 + 0]);
+                acc[j1 * N3 + 1] = fmaf(tw, cv.y, acc[j1 * N3 + 1]);
+                acc[j1 * N3 + 2] = fmaf(tw, cv.z, acc[j1 * N3 + 2]);
+                acc[j1 * N3 + 3] = fmaf(tw, cv.w, acc[j1 * N3 + 3]);
+            }
+        }
+    };
+
     const int k0 = offsets ? (int)offsets[bag] : bag;
     const int k1 = offsets ? (int)offsets[bag + 1] : bag + 1;
+    int kb = k0;
+    if (k1 - k0 == 1 && !cache.K) {
+        // one index per bag and no cache (the Criteo-shaped workloads): the shortest chain from index to slices
+        through_cores((uint32_t)__builtin_amdgcn_readfirstlane((int)indices[k0]), alpha ? alpha[k0] : 1.f, k0);
+        kb = k1;
+    }
     // cached rows: NG = 64 / NQ of them per step, lane (g, f) adds float4 f of the g-th one
     constexpr int NQ = C::N / 4, NG = WAVE / NQ;
     const int cg = lane / NQ, cf = lane % NQ;
     float4 cacc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int kb = k0; kb < k1; kb += WAVE) {
+    for (; kb < k1; kb += WAVE) {
         // The wave reads up to 64 positions of the bag at once and probes the cache for all of them, so the
         // chain index -> probe -> row data is walked once per 64 positions, not once per position.
         int pk = kb + lane;
@@ -170,49 +218,9 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
                 first = nhit;
             }
         }
-        for (int j = first; j < nb; ++j) {
-            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)prow, j);
-            const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pw), j));
-            const int k = __builtin_amdgcn_readlane(pk, j);
-            int i1, i2, i3;
-            decode(p, row, i1, i2, i3);
-            const float *A = G1 + (size_t)i1 * C::sA;
-            const float *B = G2 + (size_t)i2 * C::sB + c0;
-            const float *Cp = G3 + (size_t)i3 * C::sC + b0 * N3;
-            float t0[N1][V];
-#pragma unroll
-            for (int j1 = 0; j1 < N1; ++j1)
-#pragma unroll
-                for (int v = 0; v < V; ++v) t0[j1][v] = 0.f;
-#pragma unroll
-            for (int a = 0; a < R; ++a) {
-                float bv[V];
-                load_vec<V>(B + a * C::COLS, bv);
-#pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) {
-                    const float av = A[j1 * R + a];
-#pragma unroll
-                    for (int v = 0; v < V; ++v) t0[j1][v] = fmaf(av, bv[v], t0[j1][v]);
-                }
-            }
-            if (t0_out && active) {                             // keep T0[(j1,j2)][b] of this position for the backward pass
-                float *o = t0_out + (size_t)k * (N1 * C::COLS) + c0;
-#pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) store_vec<V>(o + j1 * C::COLS, t0[j1]);
-            }
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const float4 cv = *reinterpret_cast<const float4 *>(Cp + v * N3);
-#pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) {
-                    const float tw = w * t0[j1][v];
-                    acc[j1 * N3 + 0] = fmaf(tw, cv.x, acc[j1 * N3 + 0]);
-                    acc[j1 * N3 + 1] = fmaf(tw, cv.y, acc[j1 * N3 + 1]);
-                    acc[j1 * N3 + 2] = fmaf(tw, cv.z, acc[j1 * N3 + 2]);
-                    acc[j1 * N3 + 3] = fmaf(tw, cv.w, acc[j1 * N3 + 3]);
-                }
-            }
-        }
+        for (int j = first; j < nb; ++j)
+            through_cores((uint32_t)__builtin_amdgcn_readlane((int)prow, j),
+                          __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pw), j)), __builtin_amdgcn_readlane(pk, j));
     }
     group_reduce<C::NV, C::LN>(acc, lane);
     constexpr int KEEP = ReduceKeep<C::NV, C::LN>::value;
