@@ -317,7 +317,8 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             grad_cache = (float *)q;
             q += gc_bytes;
             const int64_t n = (int64_t)cd.K * p.N;
-            hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, grad_cache, n, 0.f);
+            if (!(grouped && L > 0))                                      // the grouping pre-pass clears it itself
+                hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, grad_cache, n, 0.f);
         }
         if (!fast) {
             for (int k = 0; k < 3; ++k) {
@@ -349,8 +350,10 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
         const int n = 3 * (int)L;
         const int64_t kthreads = L > nbins + 1 ? L : nbins + 1;
+        const bool clear_gc = fused && cd.K;                                // N is a multiple of 4 for these shapes
         hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(kthreads, WG)), dim3(WG), 0, st, p, indices, (int)L, cd, g.sort.k0, g.off,
-                           g.end, nbins, g.crange);
+                           g.end, nbins, g.crange, clear_gc ? (float4 *)grad_cache : nullptr,
+                           clear_gc ? (int64_t)cd.K * p.N / 4 : (int64_t)0);
         int bits = 1;
         while ((1 << bits) <= nbins) ++bits;
         uint64_t *ks; uint32_t *vs;

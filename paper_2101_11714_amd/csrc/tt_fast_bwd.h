@@ -1028,19 +1028,37 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 #endif
 }
 
-// Sums the partial slice gradients of a split role (FbSplit) and finishes the slices: adds the sum to dG
-// (out == nullptr) or writes x - lr * sum to out.  One thread per element of the core.
-__global__ __launch_bounds__(WG) void bwd_split_finish_kernel(const float *__restrict__ part, int ns, int slice, int64_t n,
-                                                              const float *__restrict__ x, float *__restrict__ dG,
-                                                              float *__restrict__ out, float lr)
+// Sums the partial slice gradients of the split roles (FbSplit) and finishes their slices: adds the sum to dG
+// (out == nullptr) or writes x - lr * sum to out.  One thread per float4 of the split cores, all of them in one launch.
+struct FbFinish {
+    const float *part[3], *x[3];
+    float *dG[3], *out[3];
+    int ns[3], slice4[3];                                   // parts per slice, float4 per slice
+    int64_t end4[3];                                        // running total of float4 over the (up to three) cores
+    int n;
+};
+
+__global__ __launch_bounds__(WG) void bwd_split_finish_kernel(FbFinish a, float lr)
 {
-    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) {
-        const int64_t sl = i / slice, e = i - sl * slice;
-        const float *src = part + sl * ns * slice + e;
-        float sum = 0.f;
-        for (int h = 0; h < ns; ++h) sum += src[(int64_t)h * slice];
-        if (out) out[i] = fmaf(-lr, sum, x[i]);
-        else dG[i] += sum;
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < a.end4[a.n - 1]; i += (int64_t)gridDim.x * WG) {
+        const int r = (i >= a.end4[0]) + (a.n > 2 && i >= a.end4[1]);
+        const int64_t j = i - (r ? a.end4[r - 1] : 0);
+        const int64_t sl = j / a.slice4[r], e = j - sl * a.slice4[r];
+        const float4 *src = reinterpret_cast<const float4 *>(a.part[r]) + sl * a.ns[r] * a.slice4[r] + e;
+        float4 sum = src[0];
+        for (int h = 1; h < a.ns[r]; ++h) {
+            const float4 v = src[(int64_t)h * a.slice4[r]];
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        if (a.out[r]) {
+            const float4 x = reinterpret_cast<const float4 *>(a.x[r])[j];
+            reinterpret_cast<float4 *>(a.out[r])[j] =
+                make_float4(fmaf(-lr, sum.x, x.x), fmaf(-lr, sum.y, x.y), fmaf(-lr, sum.z, x.z), fmaf(-lr, sum.w, x.w));
+        } else {
+            float4 *d = reinterpret_cast<float4 *>(a.dG[r]) + j;
+            const float4 g = *d;
+            *d = make_float4(g.x + sum.x, g.y + sum.y, g.z + sum.z, g.w + sum.w);
+        }
     }
 }
 
@@ -1104,12 +1122,24 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
                        n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
     const float *x[3] = {G1, G2, G3};
     float *dG[3] = {dG1, dG2, dG3}, *out[3] = {o1, o2, o3};
+    FbFinish f;
+    f.n = 0;
+    int64_t total4 = 0;
     for (int r = 0; r < 3; ++r) {
         if (sp.ns[r] <= 1) continue;
-        const int64_t n = (int64_t)m[r] * slice[r];
-        const int blocks = (int)((n + WG - 1) / WG < 2048 ? (n + WG - 1) / WG : 2048);
-        hipLaunchKernelGGL(bwd_split_finish_kernel, dim3(blocks), dim3(WG), 0, st, sp.part[r], sp.ns[r], slice[r], n, x[r],
-                           dG[r], out[r], lr);
+        const int i = f.n++;
+        f.part[i] = sp.part[r]; f.x[i] = x[r]; f.dG[i] = dG[r]; f.out[i] = out[r];
+        f.ns[i] = sp.ns[r]; f.slice4[i] = slice[r] / 4;
+        total4 += (int64_t)m[r] * (slice[r] / 4);
+        f.end4[i] = total4;
+    }
+    if (f.n) {
+        for (int i = f.n; i < 3; ++i) {                                    // unused entries: harmless values
+            f.part[i] = f.part[0]; f.x[i] = f.x[0]; f.dG[i] = f.dG[0]; f.out[i] = f.out[0];
+            f.ns[i] = 1; f.slice4[i] = 1; f.end4[i] = total4;
+        }
+        const int64_t blocks = (total4 + WG - 1) / WG;
+        hipLaunchKernelGGL(bwd_split_finish_kernel, dim3((int)(blocks < 4096 ? blocks : 4096)), dim3(WG), 0, st, f, lr);
     }
 }
 

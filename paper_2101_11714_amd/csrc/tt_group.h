@@ -51,15 +51,17 @@ static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
 }
 
 // items[r * L + k]: key of item r of position k (see the file comment); the cache is probed here.
-// The first threads also clear the list bounds that grp_bounds_kernel fills after the sort.
+// The first threads also clear the list bounds that grp_bounds_kernel fills after the sort, and the kernel
+// zeroes nzero4 float4 at `zero` (the gradient of the cached rows in the fused step; may be none).
 __global__ __launch_bounds__(WG) void grp_keys_kernel(Params p, const int64_t *__restrict__ indices, int L,
                                                       CacheDev cache, uint64_t *__restrict__ keys,
                                                       int *__restrict__ off, int *__restrict__ end, int nbins,
-                                                      int *__restrict__ crange)
+                                                      int *__restrict__ crange, float4 *__restrict__ zero, int64_t nzero4)
 {
     const int k = blockIdx.x * WG + threadIdx.x;
     if (k <= nbins) { off[k] = 0; end[k] = 0; }
     if (k < 2) crange[k] = 0;
+    for (int64_t i = k; i < nzero4; i += (int64_t)gridDim.x * WG) zero[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (k >= L) return;
     const int nb3 = p.m1 + p.m2 + p.m3;
     const uint64_t unused = (uint64_t)(nb3 + cache.K);
