@@ -145,10 +145,20 @@ size_t fwd_bwd_ws_bytes(const Params &p, int64_t L, int64_t K)
     return 256 + slot_ws_bytes(L, K != 0) + group_ws_layout(nullptr, L, p.m1 + p.m2 + p.m3 + (int)K, p.N).bytes;
 }
 
-// partial slice gradients of the roles that the specialised backward kernel splits over several workgroups
+// what the specialised backward kernel needs beyond the lists: partial slice gradients of the roles it splits over
+// several workgroups and, for the (4,4,4) shapes, the per-row G1 gradients
+size_t split_ws_bytes(const Params &p, int64_t L, bool grouped);
+
+// enough for either way of running the backward
+size_t split_ws_bytes_max(const Params &p, int64_t L)
+{
+    const size_t a = split_ws_bytes(p, L, false), b = split_ws_bytes(p, L, true);
+    return a > b ? a : b;
+}
+
 size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
 {
-    const size_t n = fast_bwd_supported(p) ? fast_bwd_split_floats(p, (int)L, grouped) : 0;
+    const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
     return n ? align256(n * sizeof(float)) : 0;
 }
 
@@ -178,7 +188,7 @@ size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags
     Params p;
     if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
     if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
-    return fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes(p, L, false);
+    return fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes_max(p, L);
 }
 
 size_t tt_emb_dedup_workspace_bytes(int64_t L)
@@ -449,7 +459,7 @@ size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_
     Params p;
     if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
     if (cache_rows < 0 || cache_rows > (1 << 24)) return 0;
-    size_t n = fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes(p, L, false) + align256((size_t)cache_rows * p.N * 4);
+    size_t n = fwd_bwd_ws_bytes(p, L, cache_rows) + split_ws_bytes_max(p, L) + align256((size_t)cache_rows * p.N * 4);
     n += align256((size_t)p.m1 * p.sA * 4) + align256((size_t)p.m2 * p.sB * 4) + align256((size_t)p.m3 * p.sC * 4);
     return n;
 }

@@ -74,10 +74,16 @@ __device__ __forceinline__ void add_to(float *dst, float x) { *dst += x; }
 struct FbSplit {
     int ns[3];
     float *part[3];
+    float *pbuf;        // (4,4,4) shapes: G1 gradient of every row, [L][n1 R], written by the G2 owners
+    int *pflag;         // [L]: is this position the first of its row's run in its G2 owner's list
 };
 
-// Part `part` of `nparts` of the positions (scan, gran = FB_CAP) or list entries (grouped, gran = one window of
-// 64) [lo, end), in whole pieces of `gran`.
+struct FbNoSplit {};                                        // kernel argument of the shapes that never split
+template <bool SPLITS> struct FbSplitArg { typedef FbSplit type; };
+template <> struct FbSplitArg<false> { typedef FbNoSplit type; };
+
+// Part `part` of `nparts` of the positions (scan, gran = FB_CAP) or list entries (grouped, gran = 16)
+// [lo, end), in whole pieces of `gran`.
 __device__ __forceinline__ void fb_part_range(int part, int nparts, int gran, int &lo, int &end)
 {
     if (nparts > 1) {
@@ -102,6 +108,11 @@ struct FbCfg {
     static constexpr int UB = BUDGET / BMR >= 4 ? 4 : (BUDGET / BMR >= 1 ? BUDGET / BMR : 1);
     // (4,4,4) shapes: the G2 owner multiplies on the matrix cores, wave w owning the columns with j2 = w
     static constexpr bool MFMA = C::N1 == 4 && C::N2 == NWAVE && C::R % 32 == 0;
+    // there the G2 owner works on batches of GB rows: dT0' of the batch as a 4 GB x n2 R matrix (odd row
+    // stride: its columns are read as well as its rows)
+    static constexpr int GB = 8;
+    static constexpr int DTS = C::COLS + 1;
+    static constexpr int SMALL_FLOATS = MFMA ? (4 * GB * DTS + 3) / 4 * 4 : 0;
     static_assert(W <= FB_CAP && (W % FB_PIECE == 0 || W < FB_PIECE), "windows hold whole pieces");
     static_assert(SB % UB == 0, "register batches must not straddle LDS batches");
 };
@@ -109,7 +120,8 @@ struct FbCfg {
 template <typename C>
 struct __align__(16) FbLds {
     float stage[FbCfg<C>::W * C::N];                        // alpha_k * grad_out[bag(k)] of the window's entries (16 KB)
-    float small[FbCfg<C>::SB * FbCfg<C>::SMALL];            // must follow stage[]: both are written through one index
+    float small[FbCfg<C>::SMALL_FLOATS > FbCfg<C>::SB * FbCfg<C>::SMALL ? FbCfg<C>::SMALL_FLOATS
+                                                                       : FbCfg<C>::SB * FbCfg<C>::SMALL];   // must follow stage[]: both are written through one index
     uint32_t rows[FB_CAP];                                  // selected row ids: four sub-lists, see fb_select
     uint32_t klist[FB_CAP];                                 // positions k of the selected entries
     int epos[FbCfg<C>::W];                                  // staged position of each entry of the window (runs contiguous)
@@ -252,10 +264,12 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                                         const uint32_t *__restrict__ gvals, const int *__restrict__ goff,
                                         const int *__restrict__ gend, float lr, float *__restrict__ o1,
                                         float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
-                                        uint32_t (&rowv)[FB_ITER], int part, int nparts, float *__restrict__ pout)
+                                        uint32_t (&rowv)[FB_ITER], int part, int nparts, float *__restrict__ pout,
+                                        float *__restrict__ pbuf, int *__restrict__ pflag, int rh)
 {
     using F = FbCfg<C>;
     const bool t0mode = ROLE == 2 && t0 != nullptr;                    // the G3 owner uses the stored T0
+    const bool needk = t0mode || (F::MFMA && ROLE == 1);               // the positions of the list entries are needed
     // Two ways to finish: add the slice gradient to dG1/dG2/dG3 (o1 == nullptr), or write the
     // slice after its SGD step, x - lr * gradient, to o1/o2/o3 (every slice is written then, also
     // one that no lookup touches).
@@ -283,7 +297,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     float acc[NACC];
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
-    constexpr int NTILE = MFMA ? (R / 32) * (R / 32) : 1;
+    constexpr int NTILE = MFMA ? R / 32 : 1;                              // a G2 owner there has one row tile of 32 rows (rh)
     mfma16_t accm[NTILE];
 #pragma unroll
     for (int i = 0; i < NTILE; ++i)
@@ -603,88 +617,137 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         }
     };
 
-    // ---- (4,4,4) shapes: the contraction of the G2 owner runs on the matrix cores ----
-    // There wave w owns the R columns c = (j2 = w, b) of the unfolded G2 slice, the operands come
-    // from global memory (L2) straight in the layout the instruction wants, the loads of the next
-    // rows are in flight while the current ones are multiplied, and nothing but dY goes through
-    // LDS.  accm holds the result tiles between windows.  (The G1 owner stays on the vector ALUs:
-    // it streams a whole G2 slice per row and is bound by that traffic, not by its arithmetic; a
-    // version on the matrix cores was measured and was no faster.)
-    constexpr int RT = R / 32;                                            // 32 x 32 tiles per side of a wave's R x R block
+    // ---- (4,4,4) shapes: the G2 owner works on the matrix cores and also serves the G1 owner ----
+    // All rows of a G2 owner's list share Bm = G2[s].  The owner therefore computes, besides its own
+    //   dG2[a][c] += sum_j1 A[j1][a] dT0'[j1][c]             D(32x32) += A(32x2) B(2x32), two steps per row,
+    // the G1 gradient of every row of its list,
+    //   P[(row,j1)][a] = sum_c dT0'[(row,j1)][c] Bm[a][c]     D(16x16) += A(16x4) B(4x16) over GB = 8 rows at a
+    //                                                          time (32 lines (row,j1) of dT0' = two tiles of 16),
+    // with Bm held in registers as the B operand, and writes P to pbuf[k] (k = first position of the
+    // row's run; pflag[k'] says for every position whether it is such a first one).  A small kernel
+    // (g1_from_p_kernel) then sums P over the list of every G1 slice: no workgroup streams a G2 slice
+    // per row any more.  dT0' itself is a product of the same kind,
+    //   dT0'[(j1,j2)][b] = sum_j3 dY[(j1,j2)][j3] C[b][j3]    D(16x16) += A(16x4) B(4x16), R / 16 per row,
+    // whose result goes to lds.small as the 4 GB x n2 R matrix (line (row,j1), column c = (j2,b)) that
+    // the other two products read their operands from.  A workgroup owns 32 rows a of the slice (rh);
+    // wave w takes the columns with j2 = w in dG2, rows 2w, 2w+1 of the batch in dT0', and tile
+    // (w / 2, w % 2) of P.  The G1 / G3 slices come from global memory (L2) straight in the operand
+    // layout, one batch ahead.  Two barriers per batch.
+    constexpr int RT = R / 32;                                            // 32-column tiles of a wave's R columns
+    constexpr int GB = F::GB, DTS = F::DTS;
+    constexpr int NKP = MFMA ? C::COLS / 4 : 1;                           // steps of P (four columns each)
     const int ln = lane & 31, kh = lane >> 5;
-
-    // G2 owner: dG2[a][c] += sum_j1 A[j1][a] dT0'[j1][c] as D(32x32) += A(32x2) B(2x32), two steps
-    // per row (j1 = 2h + k): lane (k = kh, i or j = ln) supplies A[j1][32 ta + ln] and
-    // dT0'[j1][c = w R + 32 tc + ln] = dY[(j1,w)] . C[32 tc + ln], computed by the lane itself.
+    const int l16 = lane & 15, q16 = lane >> 4;
+    // Bm^T as B operand of P: step i multiplies columns c = 4 i + q16 with rows a = 32 rh + 16 (w % 2) + l16
+    const bool with_p = pbuf != nullptr;                                  // else the G1 owners do their own work (see launch_bwd)
+    float bmt[NKP];
+    if (MFMA && ROLE == 1 && with_p) {
+#pragma unroll
+        for (int i = 0; i < NKP; ++i)
+            bmt[i] = G2[(size_t)s * C::sB + (size_t)(32 * rh + 16 * (w % 2) + l16) * C::COLS + 4 * i + q16];
+    }
+    constexpr int NCB = R / 16;                                           // 16-wide pieces of b
+    constexpr int SPW = GB / NWAVE;                                       // rows per wave in the dT0' product
+    struct G2Ops {
+        float a[MFMA ? GB : 1][2];                                        // A[2 h + kh][32 rh + ln] of every row of the batch
+        float c[MFMA ? SPW : 1][MFMA ? NCB : 1];                          // C[16 x + l16][q16] of this wave's rows
+    };
+    // operands of the batch of rows that starts at row sb0 of the window (rows past the end repeat the last one)
+    auto g2_fetch = [&](int sb0, int nsegs, G2Ops &o) __attribute__((always_inline)) {
+        if constexpr (MFMA) {
+            int i1v[GB], i3v[SPW];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) i1v[u] = lds.seg_i1[min(sb0 + u, nsegs - 1)];
+#pragma unroll
+            for (int u = 0; u < SPW; ++u) i3v[u] = lds.seg_i3[min(sb0 + SPW * w + u, nsegs - 1)];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const float *A = G1 + (size_t)__builtin_amdgcn_readfirstlane(i1v[u]) * C::sA + kh * R + 32 * rh + ln;
+                o.a[u][0] = A[0];
+                o.a[u][1] = A[2 * R];
+            }
+#pragma unroll
+            for (int u = 0; u < SPW; ++u) {
+                const float *Cs = G3 + (size_t)__builtin_amdgcn_readfirstlane(i3v[u]) * C::sC + l16 * N3 + q16;
+#pragma unroll
+                for (int x = 0; x < NCB; ++x) o.c[u][x] = Cs[16 * x * N3];
+            }
+        }
+    };
+    G2Ops g2cur;                                                          // first batch of a window: fetched before the staging
     auto consume_g2_mfma = [&](int nsegs) __attribute__((always_inline)) {
         if constexpr (MFMA) {
-            // ring of PD rows: a slot is refilled with the row PD further on as soon as it has been used
-            constexpr int PD = RT == 1 ? 8 : 4;
-            struct Ops { float a[RT][2]; float4 c[RT]; };
-            auto issue = [&](int i1, int i3, Ops &o) __attribute__((always_inline)) {
-                const float *A = G1 + (size_t)i1 * C::sA + kh * R + ln;
-                const float *Cs = G3 + (size_t)i3 * C::sC + ln * N3;
+            float *dt = lds.small;                                        // [4 GB][DTS]
+            G2Ops cur = g2cur, nxt;
+            for (int sb0 = 0; sb0 < nsegs; sb0 += GB) {                   // uniform
+                const int nb = min(GB, nsegs - sb0);
+                // 1. dT0' of this wave's rows -> LDS (rows past the end: zeros).  Lane (l16, q16) supplies
+                //    dY[(j1,j2) = l16][j3 = q16] and C[b = 16 x + l16][j3 = q16]; register r of the result is
+                //    (j1 = q16, j2 = r), column b = 16 x + l16.
 #pragma unroll
-                for (int ta = 0; ta < RT; ++ta) {
-                    o.a[ta][0] = A[32 * ta];
-                    o.a[ta][1] = A[2 * R + 32 * ta];
-                    o.c[ta] = *reinterpret_cast<const float4 *>(Cs + 32 * ta * N3);
-                }
-            };
-            Ops ring[PD];
-            {
-                int i1v[PD], i3v[PD];
+                for (int u = 0; u < SPW; ++u) {
+                    const int ub = SPW * w + u;
+                    const float keep = ub < nb ? 1.f : 0.f;
+                    const float dy = keep * stage[lds.seg_start[min(sb0 + ub, nsegs - 1)] * N + l16 * N3 + q16];
 #pragma unroll
-                for (int u = 0; u < PD; ++u) {
-                    i1v[u] = lds.seg_i1[min(u, nsegs - 1)];
-                    i3v[u] = lds.seg_i3[min(u, nsegs - 1)];
-                }
+                    for (int x = 0; x < NCB; ++x) {
+                        mfma4_t d = {0.f, 0.f, 0.f, 0.f};
+                        d = __builtin_amdgcn_mfma_f32_16x16x4f32(dy, cur.c[u][x], d, 0, 0, 0);
 #pragma unroll
-                for (int u = 0; u < PD; ++u)
-                    issue(__builtin_amdgcn_readfirstlane(i1v[u]), __builtin_amdgcn_readfirstlane(i3v[u]), ring[u]);
-            }
-            // No branches inside a turn of the ring: rows past the end repeat the last one with a zero
-            // weight.  Four rows at a time: all their LDS reads (where dY starts, dY itself, the digits
-            // of the rows that take over the ring slots) are in flight together.
-            for (int g0 = 0; g0 < nsegs; g0 += PD) {                      // uniform
-#pragma unroll
-                for (int u0 = 0; u0 < PD; u0 += 4) {
-                    int st[4], i1v[4], i3v[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        st[u] = lds.seg_start[min(g0 + u0 + u, nsegs - 1)];
-                        i1v[u] = lds.seg_i1[min(g0 + u0 + u + PD, nsegs - 1)];
-                        i3v[u] = lds.seg_i3[min(g0 + u0 + u + PD, nsegs - 1)];
-                    }
-                    float4 q[4][2];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float *dy = stage + st[u] * N + (kh * N2 + w) * N3;
-                        q[u][0] = *reinterpret_cast<const float4 *>(dy);
-                        q[u][1] = *reinterpret_cast<const float4 *>(dy + 2 * N2 * N3);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float keep = g0 + u0 + u < nsegs ? 1.f : 0.f;
-                        Ops &o = ring[u0 + u];
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            float b[RT];
-#pragma unroll
-                            for (int tc = 0; tc < RT; ++tc) {
-                                const float4 cv = o.c[tc];
-                                b[tc] = keep * fmaf(q[u][h].x, cv.x, fmaf(q[u][h].y, cv.y, fmaf(q[u][h].z, cv.z, q[u][h].w * cv.w)));
-                            }
-#pragma unroll
-                            for (int ta = 0; ta < RT; ++ta)
-#pragma unroll
-                                for (int tc = 0; tc < RT; ++tc)
-                                    accm[ta * RT + tc] =
-                                        __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[ta][h], b[tc], accm[ta * RT + tc], 0, 0, 0);
-                        }
-                        issue(__builtin_amdgcn_readfirstlane(i1v[u]), __builtin_amdgcn_readfirstlane(i3v[u]), o);
+                        for (int r = 0; r < 4; ++r) dt[(ub * N1 + q16) * DTS + r * R + 16 * x + l16] = d[r];
                     }
                 }
+                __syncthreads();
+                g2_fetch(sb0 + GB, nsegs, nxt);
+                // 2. dG2: per row two steps, j1 = 2 h + kh.  The operands of HB rows are read from LDS first, then
+                //    multiplied, so that the reads are in flight together (the sched_barriers keep that order).
+                constexpr int HB = RT == 1 ? GB : GB / 2;
+#pragma unroll
+                for (int u0 = 0; u0 < GB; u0 += HB) {
+                    float bv[HB][2][RT];
+#pragma unroll
+                    for (int u = 0; u < HB; ++u)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int x = 0; x < RT; ++x) bv[u][h][x] = dt[((u0 + u) * N1 + 2 * h + kh) * DTS + w * R + 32 * x + ln];
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < HB; ++u) {
+                        if (u0 + u >= nb) break;                          // uniform: the rest of the batch is empty
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int tc = 0; tc < RT; ++tc)
+                                accm[tc] = __builtin_amdgcn_mfma_f32_32x32x2f32(cur.a[u0 + u][h], bv[u][h][tc], accm[tc], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // 3. tile (tm, tn) = (w / 2, w % 2) of P: lines 16 tm + l16 of dT0' against Bm^T, four columns per step;
+                //    register r of the result is row u = 4 tm + q16 of the batch, j1 = r, a = 32 rh + 16 tn + l16
+                mfma4_t pa = {0.f, 0.f, 0.f, 0.f};
+                constexpr int IB = 16;                                    // steps whose operands are read together
+                const float *dline = dt + (16 * (w / 2) + l16) * DTS + q16;
+#pragma unroll
+                for (int i0 = 0; i0 < (with_p ? NKP : 0); i0 += IB) {
+                    float dv[IB];
+#pragma unroll
+                    for (int i = 0; i < IB; ++i) dv[i] = dline[4 * (i0 + i)];
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < IB; ++i) pa = __builtin_amdgcn_mfma_f32_16x16x4f32(dv[i], bmt[i0 + i], pa, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                {
+                    const int u = 4 * (w / 2) + q16;
+                    if (with_p && u < nb) {
+                        float *dst = pbuf + (size_t)lds.seg_k[sb0 + u] * C::sA + 32 * rh + 16 * (w % 2) + l16;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) dst[r * R] = pa[r];
+                    }
+                }
+                cur = nxt;
+                __syncthreads();                                          // dT0' has been read by everyone
             }
         }
     };
@@ -697,7 +760,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     auto analyse = [&](const int (&wc)[NWAVE], int e0, int len, int &mysg, int &mypos, int &i1, int &i2, int &i3,
                        uint32_t &myk) __attribute__((always_inline)) {
         const uint32_t my = lane < len ? lds.rows[fb_slot(wc, e0 + lane)] : FB_NONE;
-        myk = (t0mode && lane < len) ? lds.klist[fb_slot(wc, e0 + lane)] : 0u;
+        myk = (needk && lane < len) ? lds.klist[fb_slot(wc, e0 + lane)] : 0u;
         decode_f64(p, my, i1, i2, i3);
         uint64_t rem = __ballot(lane < len);
         int pos = 0, cnt = 0;
@@ -736,11 +799,12 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 // one piece: every wave analyses it by itself (same result everywhere, no barrier)
                 nsegs = analyse(wc, i0, nw, mysg, mypos, i1, i2, i3, myk);
                 TT_STAMP(15);
+                if (MFMA && ROLE == 1 && with_p && w == 0 && lane < nw) pflag[myk] = mysg >= 0;
                 if (lane < nw) lds.epos[lane] = mypos;
                 if (mysg >= 0) {                                           // first entry of its run
                     lds.seg_start[mysg] = mypos;
                     lds.seg_i1[mysg] = i1; lds.seg_i2[mysg] = i2; lds.seg_i3[mysg] = i3;
-                    if (t0mode) lds.seg_k[mysg] = myk;
+                    if (needk) lds.seg_k[mysg] = myk;
                 }
                 if (lane == 0) lds.seg_start[nsegs] = nw;
             } else {
@@ -748,6 +812,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 // stay separate runs (the gradient is linear in dY)
                 const int len = min(FB_PIECE, nw - w * FB_PIECE);          // <= 0: no piece for this wave
                 const int cnt = analyse(wc, i0 + w * FB_PIECE, len, mysg, mypos, i1, i2, i3, myk);
+                if (MFMA && ROLE == 1 && with_p && lane < len) pflag[myk] = mysg >= 0;
                 if (lane == 0) lds.pcnt[w] = cnt;
                 __syncthreads();
                 int base = 0;
@@ -762,7 +827,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 if (mysg >= 0) {
                     lds.seg_start[base + mysg] = w * FB_PIECE + mypos;
                     lds.seg_i1[base + mysg] = i1; lds.seg_i2[base + mysg] = i2; lds.seg_i3[base + mysg] = i3;
-                    if (t0mode) lds.seg_k[base + mysg] = myk;
+                    if (needk) lds.seg_k[base + mysg] = myk;
                 }
                 if (t == 0) lds.seg_start[nsegs] = nw;
                 __syncthreads();
@@ -771,6 +836,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
             const bool mm = MFMA && ROLE == 1;                            // this owner multiplies on the matrix cores
+            if (mm) g2_fetch(0, nsegs, g2cur);
             float bm[UB][RQ][V];
             if (ROLE != 1 && !t0mode && !mm) bm_load(0, nsegs, bm);
             TT_STAMP(3);
@@ -837,7 +903,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     const uint32_t sub = (uint32_t)ROLE * (uint32_t)L;
     int lo = gvals ? goff[bin] : 0;
     int end = gvals ? gend[bin] : L;
-    fb_part_range(part, nparts, gvals ? FB_PIECE : FB_CAP, lo, end);
+    fb_part_range(part, nparts, gvals ? 16 : FB_CAP, lo, end);
     const int lo0 = lo;
     int span = gvals ? FB_CAP : FB_SCAN, round = 0;
     int fill[NWAVE] = {0, 0, 0, 0};                                    // entries of the sub-lists (scan only)
@@ -901,20 +967,18 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #endif
 
     if (MFMA && ROLE == 1) {
-        // result registers of the 32 x 32 tiles: register r of lane (kh, ln) is row 8 (r / 4) + 4 kh + r % 4, column ln
+        // result registers of the 32 x 32 tiles: register r of lane (kh, ln) is row 32 rh + 8 (r / 4) + 4 kh + r % 4, column ln
 #pragma unroll
-        for (int ta = 0; ta < (MFMA ? RT : 0); ++ta)
+        for (int tc = 0; tc < (MFMA ? RT : 0); ++tc)
 #pragma unroll
-            for (int tc = 0; tc < RT; ++tc)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int a = 32 * ta + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
-                    const size_t i = (size_t)s * C::sB + (size_t)a * C::COLS + c;
-                    const float g = accm[MFMA ? ta * RT + tc : 0][r];
-                    if (pout) pout[a * C::COLS + c] = g;
-                    else if (fused) o2[i] = fmaf(-lr, g, G2[i]);
-                    else add_to(&dG2[i], g);
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int a = 32 * rh + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
+                const size_t i = (size_t)s * C::sB + (size_t)a * C::COLS + c;
+                const float g = accm[MFMA ? tc : 0][r];
+                if (pout) pout[a * C::COLS + c] = g;
+                else if (fused) o2[i] = fmaf(-lr, g, G2[i]);
+                else add_to(&dG2[i], g);
+            }
     } else if (!MFMA && ROLE == 1) {
         if (active) {
             const size_t at = (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
@@ -985,7 +1049,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
     const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend,
     float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
-    FbSplit sp)
+    typename FbSplitArg<FbCfg<C>::MFMA>::type sp)
 {
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
@@ -993,11 +1057,15 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 #endif
     uint32_t rowv[FB_ITER];
     if constexpr (FbCfg<C>::MFMA) {
-        // role, slice and part of this workgroup (see FbSplit); the role is a constant in each copy of the
-        // body here: the three owners differ too much to share registers
-        const int g = blockIdx.x, n0 = p.m1 * sp.ns[0], n1 = p.m2 * sp.ns[1];
+        // Role, slice and part of this workgroup (see FbSplit); with sp.pbuf there are no G1 owners here (the G2
+        // owners compute the G1 gradient of every row and g1_from_p_kernel finishes the G1 slices).  The role is
+        // a constant in each copy of the body: the owners differ too much to share registers.  A G2 slice has
+        // R / 32 owners of 32 rows each (they go through the same list).
+        constexpr int RTW = C::R / 32;
+        const int g = blockIdx.x, n0 = sp.pbuf ? 0 : p.m1 * sp.ns[0], n1 = p.m2 * sp.ns[1] * RTW;
         const int role = (g >= n0) + (g >= n0 + n1);
-        const int q = g - (role == 0 ? 0 : (role == 1 ? n0 : n0 + n1));
+        int q = g - (role == 0 ? 0 : (role == 1 ? n0 : n0 + n1)), rh = 0;
+        if (role == 1) { rh = q % RTW; q /= RTW; }
         const int S = sp.ns[role], sl = q / S, part = q - sl * S;
         float *pout = nullptr;
         if (S > 1) pout = sp.part[role] + (size_t)q * (role == 0 ? C::sA : (role == 1 ? C::sB : C::sC));
@@ -1006,9 +1074,10 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
             fb_part_range(part, S, FB_CAP, lo, end);
             fb_load_rows(indices, slot, lo, min(end, lo + FB_SCAN), rowv);
         }
-        if (role == 0) fb_body<C>(lds, p, 0, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
-        else if (role == 1) fb_body<C>(lds, p, 1, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
-        else fb_body<C>(lds, p, 2, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout);
+        if (role == 0) fb_body<C>(lds, p, 0, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, sp.pbuf, sp.pflag, rh);
+        else
+        if (role == 1) fb_body<C>(lds, p, 1, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, sp.pbuf, sp.pflag, rh);
+        else fb_body<C>(lds, p, 2, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, sp.pbuf, sp.pflag, rh);
     } else {
         // The index loads do not depend on the role: issue them before anything else.
         if (!gvals) fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
@@ -1018,7 +1087,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
         const int ge1 = g >= p.m1, ge2 = g >= p.m1 + p.m2;
         const int role = ge1 + ge2;
         const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
-        fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, 0, 1, nullptr);
+        fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, 0, 1, nullptr, nullptr, nullptr, 0);
     }
 #if defined(TT_PROFILE)
     if (g_tt_prof && threadIdx.x == 0) {
@@ -1062,39 +1131,147 @@ __global__ __launch_bounds__(WG) void bwd_split_finish_kernel(FbFinish a, float 
     }
 }
 
-// Split factors for a call: only the (4,4,4) shapes, only where the lists are long enough to pay for the
-// extra pass.  The G1 owners, which stream a G2 slice per row, are split four ways.  Without the grouping
-// pre-pass (medium batches) the longest lists decide the kernel time (one hot row can fill a list), so the
-// other owners are split as well; with it the chip is full anyway and more workgroups only add overhead.
+// (4,4,4) shapes: finishes the G1 slices from the per-row gradients P that the G2 owners wrote (see fb_body).
+// Workgroup s collects the flagged positions whose first digit is s, 8192 candidates per round (all positions,
+// or the slice's list from the grouping pre-pass), every wave appending to its own list, and adds their rows
+// of P: a row is n1 R floats, PA threads read it as float4, WG / PA rows side by side, UN in flight each.
+// Fixed order, no atomics.  out == nullptr: dG1 += sum; else out = G1 - lr * sum.
 template <typename C>
-static inline void fb_choose_split(int L, bool grouped, int (&ns)[3])
+__global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *__restrict__ indices, int L,
+                                                       const int32_t *__restrict__ slot, const uint32_t *__restrict__ gvals,
+                                                       const int *__restrict__ goff, const int *__restrict__ gend,
+                                                       const float *__restrict__ pbuf, const int *__restrict__ pflag,
+                                                       const float *__restrict__ G1, float *__restrict__ dG1,
+                                                       float *__restrict__ out, float lr)
+{
+    constexpr int PA = C::sA / 4, NG = WG / PA, UN = 4;
+    constexpr int ITER = 32, PER = ITER * WAVE;                           // candidates per lane / per wave and round
+    __shared__ uint32_t list[NWAVE][PER];
+    __shared__ int wcnt[NWAVE];
+    __shared__ float4 part[NG][PA];
+    const int s = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int f = t % PA, g = t / PA;
+    const float4 *p4 = reinterpret_cast<const float4 *>(pbuf);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int lo = gvals ? goff[s] : 0, end = gvals ? gend[s] : L;
+    for (int base = lo; base < end; base += NWAVE * PER) {               // uniform
+        // candidates base + w PER + it 64 + lane, ITER per lane, all loads of a round together
+        int n = 0;
+#pragma unroll
+        for (int i0 = 0; i0 < ITER; i0 += 8) {
+            if (base + w * PER + i0 * WAVE >= end) break;                 // uniform per wave
+            uint32_t kk[8];
+            bool take[8];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int c = base + w * PER + (i0 + it) * WAVE + lane;
+                const bool ok = c < end;
+                if (gvals) {
+                    kk[it] = ok ? gvals[c] : 0u;                          // the G1 items carry the position itself
+                    take[it] = ok;
+                } else {
+                    kk[it] = (uint32_t)c;
+                    int i1 = -1, i2, i3;
+                    if (ok) decode(p, (uint32_t)indices[c], i1, i2, i3);
+                    take[it] = ok && i1 == s && !(slot && slot[c] >= 0);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 8; ++it) take[it] = take[it] && pflag[kk[it]] != 0;
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const uint64_t m = __ballot(take[it]);
+                if (take[it]) list[w][n + __popcll(m & lanemask_lt())] = kk[it];
+                n += __popcll(m);
+            }
+        }
+        if (lane == 0) wcnt[w] = n;
+        __syncthreads();
+        int wc[NWAVE], total = 0;
+#pragma unroll
+        for (int j = 0; j < NWAVE; ++j) { wc[j] = wcnt[j]; total += wc[j]; }
+        for (int j0 = g; j0 < total; j0 += NG * UN) {
+            float4 v[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int j = j0 + u * NG;
+                int e = j, ww = 0;
+#pragma unroll
+                for (int x = 0; x + 1 < NWAVE; ++x)
+                    if (e >= wc[x] && ww == x) { e -= wc[x]; ww = x + 1; }
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j < total) v[u] = p4[(size_t)list[ww][e] * PA + f];
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+        }
+        __syncthreads();                                                  // before the lists are reused
+    }
+    part[g][f] = acc;
+    __syncthreads();
+    if (t < PA) {
+        float4 sum = part[0][t];
+#pragma unroll
+        for (int x = 1; x < NG; ++x) {
+            const float4 v = part[x][t];
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        const size_t at = (size_t)s * PA + t;
+        if (out) {
+            const float4 x = reinterpret_cast<const float4 *>(G1)[at];
+            reinterpret_cast<float4 *>(out)[at] =
+                make_float4(fmaf(-lr, sum.x, x.x), fmaf(-lr, sum.y, x.y), fmaf(-lr, sum.z, x.z), fmaf(-lr, sum.w, x.w));
+        } else {
+            float4 *d = reinterpret_cast<float4 *>(dG1) + at;
+            const float4 o = *d;
+            *d = make_float4(o.x + sum.x, o.y + sum.y, o.z + sum.z, o.w + sum.w);
+        }
+    }
+}
+
+// Split factors for a call: only the (4,4,4) shapes, from 4096 positions on (below that the extra pass does not
+// pay).  Two workgroups share a G2 or G3 slice: the longest lists decide the kernel time (without a cache one hot
+// row can fill a list).  With the grouping pre-pass the G2 owners also compute the G1 gradients (fb_with_p), so
+// there are no G1 owners; without it they exist and four of them share a slice (each streams a G2 slice per row).
+template <typename C>
+static inline void fb_choose_split(int L, int (&ns)[3])
 {
     ns[0] = ns[1] = ns[2] = 1;
     if (FbCfg<C>::MFMA && L >= 4096) {
         ns[0] = 4;
-        if (!grouped) ns[1] = ns[2] = 2;
+        ns[1] = ns[2] = 2;
     }
 }
 
-static inline void fast_bwd_split(const Params &p, int L, bool grouped, int (&ns)[3])
+// Do the G2 owners compute the G1 gradients of their rows (and g1_from_p_kernel finish the G1 slices)?  With the
+// grouping pre-pass: the lists are long and full batches of rows amortise the extra product; for the shorter
+// lists of a scan the G1 owners' own pass was measured to be faster.
+template <typename C>
+static inline bool fb_with_p(bool grouped) { return FbCfg<C>::MFMA && grouped; }
+
+static inline void fast_bwd_split(const Params &p, int L, int (&ns)[3])
 {
     ns[0] = ns[1] = ns[2] = 1;
     switch (fast_config(p)) {
-    case 4: fb_choose_split<Cfg444R32>(L, grouped, ns); break;
-    case 5: fb_choose_split<Cfg444R64>(L, grouped, ns); break;
+    case 4: fb_choose_split<Cfg444R32>(L, ns); break;
+    case 5: fb_choose_split<Cfg444R64>(L, ns); break;
     default: break;
     }
 }
 
-// floats of workspace the split needs (0 if nothing is split)
-static inline size_t fast_bwd_split_floats(const Params &p, int L, bool grouped)
+// floats of workspace the specialised kernel may need beyond the lists: partial slices of the split roles, and for
+// the (4,4,4) shapes with the grouping pre-pass the per-row G1 gradients (L n1 R floats) and the flags (L ints)
+static inline size_t fast_bwd_extra_floats(const Params &p, int L, bool grouped)
 {
     int ns[3];
-    fast_bwd_split(p, L, grouped, ns);
+    fast_bwd_split(p, L, ns);
+    const int cfg = fast_config(p);
+    const bool with_p = (cfg == 4 || cfg == 5) && grouped;
     size_t n = 0;
-    if (ns[0] > 1) n += (size_t)ns[0] * p.m1 * p.sA;
+    if (ns[0] > 1 && !with_p) n += (size_t)ns[0] * p.m1 * p.sA;
     if (ns[1] > 1) n += (size_t)ns[1] * p.m2 * p.sB;
     if (ns[2] > 1) n += (size_t)ns[2] * p.m3 * p.sC;
+    if (with_p) n += (size_t)(L > 0 ? L : 1) * p.sA + (size_t)((L > 0 ? L : 1) + 3) / 4 * 4;
     return n;
 }
 
@@ -1103,30 +1280,47 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
                               const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
                               const int *goff, const int *gend, float lr, float *o1, float *o2, float *o3,
-                              const float *t0, float *split_ws, hipStream_t st)
+                              const float *t0, float *extra_ws, hipStream_t st)
 {
+    constexpr bool MFMA = FbCfg<C>::MFMA;
+    const bool with_p = fb_with_p<C>(gvals != nullptr);
     FbSplit sp;
-    fb_choose_split<C>(L, gvals != nullptr, sp.ns);
+    fb_choose_split<C>(L, sp.ns);
     const int m[3] = {p.m1, p.m2, p.m3}, slice[3] = {p.sA, p.sB, p.sC};
-    float *q = split_ws;
+    float *q = extra_ws;
     int grid = 0;
     for (int r = 0; r < 3; ++r) {
         sp.part[r] = nullptr;
+        if (with_p && r == 0) continue;                                    // no G1 owners in the main kernel
         if (sp.ns[r] > 1) {
             sp.part[r] = q;
             q += (size_t)sp.ns[r] * m[r] * slice[r];
         }
-        grid += sp.ns[r] * m[r];
+        grid += sp.ns[r] * m[r] * (MFMA && r == 1 ? C::R / 32 : 1);
     }
-    hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
-                       n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
+    sp.pbuf = nullptr;
+    sp.pflag = nullptr;
+    if (with_p) {
+        sp.pbuf = q;
+        q += (size_t)(L > 0 ? L : 1) * p.sA;
+        sp.pflag = reinterpret_cast<int *>(q);
+    }
+    if constexpr (MFMA)
+        hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+                           n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
+    else
+        hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+                           n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, FbNoSplit());
+    if (with_p)
+        hipLaunchKernelGGL(g1_from_p_kernel<C>, dim3(p.m1), dim3(WG), 0, st, p, idx, L, slot, gvals, goff, gend, sp.pbuf,
+                           sp.pflag, G1, dG1, o1, lr);
     const float *x[3] = {G1, G2, G3};
     float *dG[3] = {dG1, dG2, dG3}, *out[3] = {o1, o2, o3};
     FbFinish f;
     f.n = 0;
     int64_t total4 = 0;
     for (int r = 0; r < 3; ++r) {
-        if (sp.ns[r] <= 1) continue;
+        if (sp.part[r] == nullptr) continue;
         const int i = f.n++;
         f.part[i] = sp.part[r]; f.x[i] = x[r]; f.dG[i] = dG[r]; f.out[i] = out[r];
         f.ns[i] = sp.ns[r]; f.slice4[i] = slice[r] / 4;
@@ -1149,15 +1343,15 @@ static inline void fast_bwd(const Params &p, const float *G1, const float *G2, c
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
                             float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
                             const int *gend, float lr, float *o1, float *o2, float *o3, const float *t0,
-                            float *split_ws, hipStream_t st)
+                            float *extra_ws, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, split_ws, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
     default: break;
     }
 }
