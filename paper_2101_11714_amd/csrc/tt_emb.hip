@@ -349,6 +349,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         p.bagP = (uint32_t)(L / n_bags);
         p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
     }
+    bool cache_merged = false;
     int32_t *slot = nullptr;
     if (cd.K && L > 0 && !grouped) {                                      // the grouping pre-pass probes the cache itself
         slot = (int32_t *)workspace;
@@ -370,22 +371,24 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         hipError_t es = radix_sort(g.sort, n, bits, st, &ks, &vs);
         if (es != hipSuccess) return hip_fail(es, "grouping sort");
         hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
-        if (cd.K) {
-            const int tiles = cdiv(L, GT);
-            hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
+        GrpCacheWork cw{ks, vs, g.crange, g.end, g.part, grad_cache, cd.K ? cdiv(cdiv(L, GT), NWAVE) : 0};
+        cache_merged = cd.K && fast_bwd_takes_cache_work(p, (int)L);     // the owner kernels do the cached rows as well
+        if (cd.K && !cache_merged) {
+            hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
                                (int)n_bags, alpha, grad_output, grad_cache, g.part);
-            hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, p, ks, g.crange, g.end, g.part,
+            hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, g.crange, g.end, g.part,
                                grad_cache);
         }
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, split_ws, st);
+                 d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, split_ws, cache_merged ? &cw : nullptr,
+                 fused && cache_merged ? cache->rows : nullptr, (int64_t)cd.K * p.N, st);
     } else {
         if (cd.K && L > 0)
             hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
                                offsets, (int)n_bags, alpha, grad_output, grad_cache);
         if (fast) {
             fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
-                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, t0, split_ws, st);
+                     d1, d2, d3, nullptr, nullptr, nullptr, lr, o1, o2, o3, t0, split_ws, nullptr, nullptr, 0, st);
         } else if (L > 0) {
             hipLaunchKernelGGL(bwd_generic_kernel, dim3(p.m1 + p.m2 + p.m3), dim3(WG), lds_core, st, p,
                                cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot,
@@ -397,7 +400,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             for (int k = 0; k < 3; ++k)
                 hipLaunchKernelGGL(sgd_out_kernel, dim3(cdiv(core_floats[k], WG) < 2048 ? cdiv(core_floats[k], WG) : 2048),
                                    dim3(WG), 0, st, cores[k], gtmp[k], cores_out[k], core_floats[k], lr);
-        if (cd.K) {
+        if (cd.K && !cache_merged) {
             const int64_t n = (int64_t)cd.K * p.N;
             hipLaunchKernelGGL(sgd_out_kernel, dim3(cdiv(n, WG) < 2048 ? cdiv(n, WG) : 2048), dim3(WG), 0, st,
                                cache->rows, grad_cache, cache->rows, n, lr);

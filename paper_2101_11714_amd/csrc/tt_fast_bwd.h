@@ -30,6 +30,7 @@
 #include <stddef.h>
 
 #include "tt_fast.h"
+#include "tt_group.h"
 
 namespace tt {
 
@@ -76,6 +77,8 @@ struct FbSplit {
     float *part[3];
     float *pbuf;        // (4,4,4) shapes: G1 gradient of every row, [L][n1 R], written by the G2 owners
     int *pflag;         // [L]: is this position the first of its row's run in its G2 owner's list
+    GrpCacheWork cw;    // cached-row tiles that run as extra workgroups behind the n_owner slice owners
+    int n_owner;
 };
 
 struct FbNoSplit {};                                        // kernel argument of the shapes that never split
@@ -1057,6 +1060,11 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 #endif
     uint32_t rowv[FB_ITER];
     if constexpr (FbCfg<C>::MFMA) {
+        if (sp.cw.blocks && (int)blockIdx.x >= sp.n_owner) {             // uniform: this workgroup sums cached-row gradients
+            grp_cache_tile_body(p, (int)blockIdx.x - sp.n_owner, sp.cw.ks, sp.cw.vs, sp.cw.crange, offsets, n_bags, alpha,
+                                grad_out, sp.cw.grad_cache, sp.cw.part);
+            return;
+        }
         // Role, slice and part of this workgroup (see FbSplit); with sp.pbuf there are no G1 owners here (the G2
         // owners compute the G1 gradient of every row and g1_from_p_kernel finishes the G1 slices).  The role is
         // a constant in each copy of the body: the owners differ too much to share registers.  A G2 slice has
@@ -1100,17 +1108,17 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 // Sums the partial slice gradients of the split roles (FbSplit) and finishes their slices: adds the sum to dG
 // (out == nullptr) or writes x - lr * sum to out.  One thread per float4 of the split cores, all of them in one launch.
 struct FbFinish {
-    const float *part[3], *x[3];
-    float *dG[3], *out[3];
-    int ns[3], slice4[3];                                   // parts per slice, float4 per slice
-    int64_t end4[3];                                        // running total of float4 over the (up to three) cores
-    int n;
+    const float *part[4], *x[4];
+    float *dG[4], *out[4];
+    int ns[4], slice4[4];                                   // parts per slice, float4 per slice
+    int64_t end4[4];                                        // running total of float4 over the (up to four) arrays:
+    int n;                                                  // split cores, and the cache lines (one "part": their gradient)
 };
 
 __global__ __launch_bounds__(WG) void bwd_split_finish_kernel(FbFinish a, float lr)
 {
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < a.end4[a.n - 1]; i += (int64_t)gridDim.x * WG) {
-        const int r = (i >= a.end4[0]) + (a.n > 2 && i >= a.end4[1]);
+        const int r = (i >= a.end4[0]) + (i >= a.end4[1]) + (i >= a.end4[2]);
         const int64_t j = i - (r ? a.end4[r - 1] : 0);
         const int64_t sl = j / a.slice4[r], e = j - sl * a.slice4[r];
         const float4 *src = reinterpret_cast<const float4 *>(a.part[r]) + sl * a.ns[r] * a.slice4[r] + e;
@@ -1142,8 +1150,12 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
                                                        const int *__restrict__ goff, const int *__restrict__ gend,
                                                        const float *__restrict__ pbuf, const int *__restrict__ pflag,
                                                        const float *__restrict__ G1, float *__restrict__ dG1,
-                                                       float *__restrict__ out, float lr)
+                                                       float *__restrict__ out, float lr, GrpCacheWork cw)
 {
+    if ((int)blockIdx.x >= p.m1) {                                        // extra workgroups: runs of cached rows that cross tiles
+        grp_cache_fix_body(p, (int)blockIdx.x - p.m1, cw.ks, cw.crange, cw.gend, cw.part, cw.grad_cache);
+        return;
+    }
     constexpr int PA = C::sA / 4, NG = WG / PA, UN = 4;
     constexpr int ITER = 32, PER = ITER * WAVE;                           // candidates per lane / per wave and round
     __shared__ uint32_t list[NWAVE][PER];
@@ -1249,6 +1261,14 @@ static inline void fb_choose_split(int L, int (&ns)[3])
 template <typename C>
 static inline bool fb_with_p(bool grouped) { return FbCfg<C>::MFMA && grouped; }
 
+// With the grouping pre-pass, the backward of the (4,4,4) shapes runs the cached-row reduction as extra workgroups of
+// its own launches (and the SGD step of the cache lines in its finishing kernel) instead of three launches of their own.
+static inline bool fast_bwd_takes_cache_work(const Params &p, int L)
+{
+    const int cfg = fast_config(p);
+    return (cfg == 4 || cfg == 5) && L >= 4096;
+}
+
 static inline void fast_bwd_split(const Params &p, int L, int (&ns)[3])
 {
     ns[0] = ns[1] = ns[2] = 1;
@@ -1280,7 +1300,8 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
                               int L, const int64_t *off, int n_bags, const float *alpha, const int32_t *slot,
                               const float *go, float *dG1, float *dG2, float *dG3, const uint32_t *gvals,
                               const int *goff, const int *gend, float lr, float *o1, float *o2, float *o3,
-                              const float *t0, float *extra_ws, hipStream_t st)
+                              const float *t0, float *extra_ws, const GrpCacheWork *cw, float *cache_rows,
+                              int64_t cache_floats, hipStream_t st)
 {
     constexpr bool MFMA = FbCfg<C>::MFMA;
     const bool with_p = fb_with_p<C>(gvals != nullptr);
@@ -1305,6 +1326,15 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
         q += (size_t)(L > 0 ? L : 1) * p.sA;
         sp.pflag = reinterpret_cast<int *>(q);
     }
+    // the caller's cached-row work rides along (fast_bwd_takes_cache_work): tiles behind the owners, the runs that cross
+    // tiles behind g1_from_p_kernel's workgroups, the SGD step of the cache lines in the finishing kernel
+    const bool with_cw = cw != nullptr && cw->blocks > 0;
+    sp.cw = GrpCacheWork{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    sp.n_owner = grid;
+    if (with_cw) {
+        sp.cw = *cw;
+        grid += cw->blocks;
+    }
     if constexpr (MFMA)
         hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
                            n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
@@ -1312,8 +1342,8 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
         hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
                            n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, FbNoSplit());
     if (with_p)
-        hipLaunchKernelGGL(g1_from_p_kernel<C>, dim3(p.m1), dim3(WG), 0, st, p, idx, L, slot, gvals, goff, gend, sp.pbuf,
-                           sp.pflag, G1, dG1, o1, lr);
+        hipLaunchKernelGGL(g1_from_p_kernel<C>, dim3(p.m1 + sp.cw.blocks), dim3(WG), 0, st, p, idx, L, slot, gvals, goff, gend,
+                           sp.pbuf, sp.pflag, G1, dG1, o1, lr, sp.cw);
     const float *x[3] = {G1, G2, G3};
     float *dG[3] = {dG1, dG2, dG3}, *out[3] = {o1, o2, o3};
     FbFinish f;
@@ -1327,8 +1357,15 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
         total4 += (int64_t)m[r] * (slice[r] / 4);
         f.end4[i] = total4;
     }
+    if (with_cw && cache_rows) {                                           // fused step: lines <- lines - lr * gradient
+        const int i = f.n++;
+        f.part[i] = sp.cw.grad_cache; f.x[i] = cache_rows; f.dG[i] = nullptr; f.out[i] = cache_rows;
+        f.ns[i] = 1; f.slice4[i] = 1;
+        total4 += cache_floats / 4;
+        f.end4[i] = total4;
+    }
     if (f.n) {
-        for (int i = f.n; i < 3; ++i) {                                    // unused entries: harmless values
+        for (int i = f.n; i < 4; ++i) {                                    // unused entries: harmless values
             f.part[i] = f.part[0]; f.x[i] = f.x[0]; f.dG[i] = f.dG[0]; f.out[i] = f.out[0];
             f.ns[i] = 1; f.slice4[i] = 1; f.end4[i] = total4;
         }
@@ -1343,15 +1380,16 @@ static inline void fast_bwd(const Params &p, const float *G1, const float *G2, c
                             const int64_t *off, int n_bags, const float *alpha, const int32_t *slot, const float *go,
                             float *dG1, float *dG2, float *dG3, const uint32_t *gvals, const int *goff,
                             const int *gend, float lr, float *o1, float *o2, float *o3, const float *t0,
-                            float *extra_ws, hipStream_t st)
+                            float *extra_ws, const GrpCacheWork *cw, float *cache_rows, int64_t cache_floats,
+                            hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
-    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
-    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
-    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
-    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
-    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, st); break;
+    case 0: launch_bwd<Cfg224R8>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
+    case 1: launch_bwd<Cfg224R16>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
+    case 2: launch_bwd<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
+    case 3: launch_bwd<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
+    case 4: launch_bwd<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
+    case 5: launch_bwd<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, extra_ws, cw, cache_rows, cache_floats, st); break;
     default: break;
     }
 }

@@ -114,19 +114,19 @@ __device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restric
 // One wave per tile of GT = 64 sorted cached items.  Lane e first fetches key, position, weight
 // and bag of item e (one round trip for the whole tile); then the rows of the upstream gradient
 // are read 16 items at a time, lane j owning columns j, j + 64, ..., and added run by run.
-__global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint64_t *__restrict__ ks,
-                                                            const uint32_t *__restrict__ vs,
-                                                            const int *__restrict__ crange,
-                                                            const int64_t *__restrict__ offsets, int n_bags,
-                                                            const float *__restrict__ alpha,
-                                                            const float *__restrict__ grad_out,
-                                                            float *__restrict__ grad_cache, float *__restrict__ part)
+// (`block` is the workgroup's number among those that do this work: the body also runs as extra workgroups
+// of the backward kernel of the (4,4,4) shapes, next to the slice owners.)
+__device__ __forceinline__ void grp_cache_tile_body(const Params &p, int block, const uint64_t *__restrict__ ks,
+                                                    const uint32_t *__restrict__ vs, const int *__restrict__ crange,
+                                                    const int64_t *__restrict__ offsets, int n_bags,
+                                                    const float *__restrict__ alpha, const float *__restrict__ grad_out,
+                                                    float *__restrict__ grad_cache, float *__restrict__ part)
 {
     constexpr int MAXC = 4;                                       // N <= 256 columns
     static_assert(GT == WAVE, "one item per lane");
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
     const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int tile = block * NWAVE + (threadIdx.x >> 6);
     const int cb = crange[0], ce = crange[1];
     const int i0 = cb + tile * GT;
     if (i0 >= ce) return;
@@ -188,16 +188,25 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
     flush(cur, cur != key_next);
 }
 
+__global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint64_t *__restrict__ ks,
+                                                            const uint32_t *__restrict__ vs,
+                                                            const int *__restrict__ crange,
+                                                            const int64_t *__restrict__ offsets, int n_bags,
+                                                            const float *__restrict__ alpha,
+                                                            const float *__restrict__ grad_out,
+                                                            float *__restrict__ grad_cache, float *__restrict__ part)
+{
+    grp_cache_tile_body(p, blockIdx.x, ks, vs, crange, offsets, n_bags, alpha, grad_out, grad_cache, part);
+}
+
 // A run that crosses tile borders is finished by the workgroup in whose tiles it begins: its four
 // waves add up the partial sums of the run's later tiles, wave w taking every fourth tile, and
 // the four results are added in wave order.  The run's last item is known from the list bounds,
 // so all loads are independent.  A workgroup looks at its NWAVE tiles one after the other (most
 // hold no such run).
-__global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint64_t *__restrict__ ks,
-                                                           const int *__restrict__ crange,
-                                                           const int *__restrict__ gend,
-                                                           const float *__restrict__ part,
-                                                           float *__restrict__ grad_cache)
+__device__ __forceinline__ void grp_cache_fix_body(const Params &p, int block, const uint64_t *__restrict__ ks,
+                                                   const int *__restrict__ crange, const int *__restrict__ gend,
+                                                   const float *__restrict__ part, float *__restrict__ grad_cache)
 {
     constexpr int MAXC = 4;
     __shared__ float red[NWAVE][MAXC * WAVE];
@@ -205,7 +214,7 @@ __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint6
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int cb = crange[0], ce = crange[1];
     for (int q = 0; q < NWAVE; ++q) {                              // every test below is uniform in the workgroup
-        const int tile = blockIdx.x * NWAVE + q;
+        const int tile = block * NWAVE + q;
         const int i0 = cb + tile * GT;
         if (i0 >= ce) break;
         const int i1 = min(ce, i0 + GT);
@@ -252,5 +261,24 @@ __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint6
         __syncthreads();
     }
 }
+
+__global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint64_t *__restrict__ ks,
+                                                           const int *__restrict__ crange,
+                                                           const int *__restrict__ gend,
+                                                           const float *__restrict__ part,
+                                                           float *__restrict__ grad_cache)
+{
+    grp_cache_fix_body(p, blockIdx.x, ks, crange, gend, part, grad_cache);
+}
+
+// The cached-row work of one backward call, for a kernel that runs it as extra workgroups: `blocks`
+// workgroups of grp_cache_tile_body, then (in a later launch) as many of grp_cache_fix_body.
+struct GrpCacheWork {
+    const uint64_t *ks;
+    const uint32_t *vs;
+    const int *crange, *gend;
+    float *part, *grad_cache;
+    int blocks;                                  // 0: nothing to do
+};
 
 }  // namespace tt
