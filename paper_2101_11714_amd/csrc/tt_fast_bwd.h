@@ -1061,7 +1061,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     uint32_t rowv[FB_ITER];
     if constexpr (FbCfg<C>::MFMA) {
         if (sp.cw.blocks && (int)blockIdx.x >= sp.n_owner) {             // uniform: this workgroup sums cached-row gradients
-            grp_cache_tile_body(p, (int)blockIdx.x - sp.n_owner, sp.cw.ks, sp.cw.vs, sp.cw.crange, offsets, n_bags, alpha,
+            grp_cache_tile_body<(C::N + 63) / 64>(p, (int)blockIdx.x - sp.n_owner, sp.cw.ks, sp.cw.vs, sp.cw.crange, offsets, n_bags, alpha,
                                 grad_out, sp.cw.grad_cache, sp.cw.part);
             return;
         }
@@ -1153,7 +1153,7 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
                                                        float *__restrict__ out, float lr, GrpCacheWork cw)
 {
     if ((int)blockIdx.x >= p.m1) {                                        // extra workgroups: runs of cached rows that cross tiles
-        grp_cache_fix_body(p, (int)blockIdx.x - p.m1, cw.ks, cw.crange, cw.gend, cw.part, cw.grad_cache);
+        grp_cache_fix_body<(C::N + 63) / 64>(p, (int)blockIdx.x - p.m1, cw.ks, cw.crange, cw.gend, cw.part, cw.grad_cache);
         return;
     }
     constexpr int PA = C::sA / 4, NG = WG / PA, UN = 4;

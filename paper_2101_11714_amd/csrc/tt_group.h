@@ -116,13 +116,13 @@ __device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restric
 // are read 16 items at a time, lane j owning columns j, j + 64, ..., and added run by run.
 // (`block` is the workgroup's number among those that do this work: the body also runs as extra workgroups
 // of the backward kernel of the (4,4,4) shapes, next to the slice owners.)
+template <int MAXC>                                               // columns per lane: N <= 64 MAXC
 __device__ __forceinline__ void grp_cache_tile_body(const Params &p, int block, const uint64_t *__restrict__ ks,
                                                     const uint32_t *__restrict__ vs, const int *__restrict__ crange,
                                                     const int64_t *__restrict__ offsets, int n_bags,
                                                     const float *__restrict__ alpha, const float *__restrict__ grad_out,
                                                     float *__restrict__ grad_cache, float *__restrict__ part)
 {
-    constexpr int MAXC = 4;                                       // N <= 256 columns
     static_assert(GT == WAVE, "one item per lane");
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
     const int lane = threadIdx.x & 63;
@@ -141,7 +141,9 @@ __device__ __forceinline__ void grp_cache_tile_body(const Params &p, int block, 
     const float my_w = alpha ? alpha[my_k] : 1.f;
     const int my_bag = grp_bag(p, offsets, n_bags, my_k);
 
-    float sum[MAXC] = {0.f, 0.f, 0.f, 0.f};
+    float sum[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) sum[c] = 0.f;
     int cur = __builtin_amdgcn_readfirstlane(my_key);
     bool first = true;
     auto flush = [&](int key, bool run_ends_here) {
@@ -196,49 +198,80 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
                                                             const float *__restrict__ grad_out,
                                                             float *__restrict__ grad_cache, float *__restrict__ part)
 {
-    grp_cache_tile_body(p, blockIdx.x, ks, vs, crange, offsets, n_bags, alpha, grad_out, grad_cache, part);
+    grp_cache_tile_body<4>(p, blockIdx.x, ks, vs, crange, offsets, n_bags, alpha, grad_out, grad_cache, part);   // N <= 256
 }
 
-// A run that crosses tile borders is finished by the workgroup in whose tiles it begins: its four
-// waves add up the partial sums of the run's later tiles, wave w taking every fourth tile, and
-// the four results are added in wave order.  The run's last item is known from the list bounds,
-// so all loads are independent.  A workgroup looks at its NWAVE tiles one after the other (most
-// hold no such run).
+// A run that crosses tile borders is finished where it begins.  Wave w of a workgroup looks at tile
+// 4 block + w; if a run begins there and goes on, its last item is known from the list bounds, so the
+// partial sums of its later tiles can be loaded independently.  A run over a few tiles (nearly all of them)
+// is finished by the wave alone, the four waves working side by side; a long one (the hottest slots) by the
+// whole workgroup: wave w adds every fourth partial sum, NB in flight, and the four results are added in
+// wave order.
+template <int MAXC>
 __device__ __forceinline__ void grp_cache_fix_body(const Params &p, int block, const uint64_t *__restrict__ ks,
                                                    const int *__restrict__ crange, const int *__restrict__ gend,
                                                    const float *__restrict__ part, float *__restrict__ grad_cache)
 {
-    constexpr int MAXC = 4;
+    constexpr int NB = 64 / MAXC;                                  // partial sums in flight per wave (long runs)
+    constexpr int SHORT = 16;                                      // later tiles a wave handles alone
     __shared__ float red[NWAVE][MAXC * WAVE];
+    __shared__ int info[NWAVE][2];                                 // long run that begins in the wave's tile: key, last tile
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int cb = crange[0], ce = crange[1];
-    for (int q = 0; q < NWAVE; ++q) {                              // every test below is uniform in the workgroup
-        const int tile = block * NWAVE + q;
-        const int i0 = cb + tile * GT;
-        if (i0 >= ce) break;
-        const int i1 = min(ce, i0 + GT);
-        if (i1 >= ce) break;                                       // nothing to the right
-        const int key = (int)ks[i1 - 1];
-        if ((int)ks[i1] != key) continue;                          // the last run ends in this tile
-        const bool single = (int)ks[i0] == key;
-        if (single && i0 > cb && (int)ks[i0 - 1] == key) continue; // a middle tile of the run: it begins elsewhere
-        const int last_tile = (gend[key] - 1 - cb) / GT;           // tile that holds the run's last item
+    {
+        const int tile = block * NWAVE + w;
+        const int i0 = cb + tile * GT, i1 = min(ce, i0 + GT);
+        int key = -1, last_tile = 0;
+        bool own = false;
+        if (i0 < ce && i1 < ce) {                                  // else no tile here, or nothing to its right
+            key = (int)ks[i1 - 1];
+            own = (int)ks[i1] == key;                              // the last run goes on in the next tile
+            if (own && (int)ks[i0] == key && i0 > cb && (int)ks[i0 - 1] == key) own = false;   // it begins elsewhere
+            if (own) last_tile = (gend[key] - 1 - cb) / GT;        // tile that holds the run's last item
+        }
+        const bool is_long = own && last_tile - tile > SHORT;
+        if (lane == 0) { info[w][0] = is_long ? key : -1; info[w][1] = last_tile; }
+        if (own && !is_long) {                                     // uniform in the wave
+            float x[SHORT + 1][MAXC];
+#pragma unroll
+            for (int j = 0; j <= SHORT; ++j) {
+                const int u = min(tile + j, last_tile);
+#pragma unroll
+                for (int c = 0; c < MAXC; ++c)
+                    x[j][c] = lane + 64 * c < N ? part[((size_t)u * 2 + (j == 0 ? 1 : 0)) * N + lane + 64 * c] : 0.f;
+            }
+            float *dst = grad_cache + (size_t)(key - nb3) * N;
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c) {
+                float sum = x[0][c];
+#pragma unroll
+                for (int j = 1; j <= SHORT; ++j)
+                    if (tile + j <= last_tile) sum += x[j][c];
+                if (lane + 64 * c < N) dst[lane + 64 * c] += sum;
+            }
+        }
+    }
+    __syncthreads();
+    for (int q = 0; q < NWAVE; ++q) {                              // long runs: uniform in the workgroup
+        const int key = info[q][0];
+        if (key < 0) continue;
+        const int tile = block * NWAVE + q, last_tile = info[q][1];
         float sum[MAXC];
 #pragma unroll
         for (int c = 0; c < MAXC; ++c)
             sum[c] = (w == 0 && lane + 64 * c < N) ? part[((size_t)tile * 2 + 1) * N + lane + 64 * c] : 0.f;
-        for (int u0 = tile + 1 + w; u0 <= last_tile; u0 += 16 * NWAVE) {
-            float x[16][MAXC];
+        for (int u0 = tile + 1 + w; u0 <= last_tile; u0 += NB * NWAVE) {
+            float x[NB][MAXC];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
+            for (int j = 0; j < NB; ++j) {
                 const int u = min(u0 + j * NWAVE, last_tile);
 #pragma unroll
                 for (int c = 0; c < MAXC; ++c)
                     x[j][c] = lane + 64 * c < N ? part[((size_t)u * 2 + 0) * N + lane + 64 * c] : 0.f;
             }
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
+            for (int j = 0; j < NB; ++j)
                 if (u0 + j * NWAVE <= last_tile) {
 #pragma unroll
                     for (int c = 0; c < MAXC; ++c) sum[c] += x[j][c];
@@ -268,7 +301,7 @@ __global__ __launch_bounds__(WG) void grp_cache_fix_kernel(Params p, const uint6
                                                            const float *__restrict__ part,
                                                            float *__restrict__ grad_cache)
 {
-    grp_cache_fix_body(p, blockIdx.x, ks, crange, gend, part, grad_cache);
+    grp_cache_fix_body<4>(p, blockIdx.x, ks, crange, gend, part, grad_cache);                                     // N <= 256
 }
 
 // The cached-row work of one backward call, for a kernel that runs it as extra workgroups: `blocks`
