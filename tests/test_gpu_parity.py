@@ -530,6 +530,57 @@ def test_kept_t0_ragged_weighted_with_cache(path):
     assert_close(dc.cpu().numpy()[:K], rc, "kept T0 + cache dCache")
 
 
+@pytest.mark.parametrize("R", [32, 64])
+@pytest.mark.parametrize("with_cache", [False, True])
+def test_444_shapes_shared_slices_and_matrix_cores(R, with_cache, path):
+    """The (4,4,4) shapes from 4096 positions on: several workgroups share a slice (partial sums in the
+    workspace), the G2 owners work on the matrix cores and, with the grouping pre-pass, also produce the G1
+    gradients; with a cache its reduction rides along.  Ragged weighted bags, a hot row, a list length that
+    is no multiple of anything; gradients are added to non-zero buffers."""
+    import dataclasses
+    t = W.TableShape(12 * 11 * 13, (12, 11, 13), (4, 4, 4), (1, R, R, 1))
+    wl = dataclasses.replace(W.WORKLOADS["tiny"], tables=(t,), name="small444")
+    rng = np.random.default_rng(40 + R)
+    lens = rng.integers(0, 9, 1500).astype(np.int64)
+    lens[7] = 431                                                   # one long bag
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    L = int(off[-1])
+    assert L >= 4096 + 17
+    idx = rng.integers(0, t.num_rows, L)
+    idx[rng.random(L) < 0.1] = 1234                                 # a hot row all over the stream
+    idx[2000:2300] = 99                                             # and a run of equal rows
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(L)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    cache, keys, K = None, None, 0
+    if with_cache:
+        rows, counts = np.unique(idx, return_counts=True)
+        K = 40
+        cache, _, _ = d.build_cache(K, rows.astype(np.int64), counts.astype(np.int64))
+        keys = ora.cache_select(rows, counts, K)
+    crows = cache.rows.cpu().numpy()[:K].copy() if with_cache else None
+    out, t0 = d.fwd_keep_t0(cache=cache)
+    assert_close(out, ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha, cache_keys=keys, cache_rows=crows), "forward")
+    rg, rc = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha, cache_keys=keys)
+    # separate backward, added to what the buffers hold
+    for use_t0 in (False, True):
+        start = [torch.full_like(x, 0.25) for x in d.g]
+        gc0 = torch.full_like(cache.rows, -0.5) if with_cache else None
+        dg, dc = d.bwd(cache=cache, grad_cores=start, grad_cache=gc0, t0=t0 if use_t0 else None)
+        for k in range(3):
+            assert_close(dg[k].cpu().numpy() - 0.25, rg[k], "dG%d (t0 %s)" % (k + 1, use_t0))
+        if with_cache:
+            assert_close(dc.cpu().numpy()[:K] + 0.5, rc, "dCache (t0 %s)" % use_t0)
+    # fused step
+    lr = 0.05
+    new = d.bwd_sgd(lr, cache=cache, t0=t0)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), d.cores[k].astype(np.float64) - lr * rg[k], "fused core %d" % (k + 1))
+    if with_cache:
+        assert_close(cache.rows.cpu().numpy()[:K], crows.astype(np.float64) - lr * rc, "fused cache lines")
+
+
 # ------------------------------------------------------------------ the uncompressed comparison kernels
 
 @pytest.mark.parametrize("N,lens", [(16, (1, 1)), (16, (0, 7)), (64, (0, 30)), (256, (1, 3))])
