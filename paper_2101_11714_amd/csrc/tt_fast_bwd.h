@@ -25,6 +25,14 @@
 // dependent chain short (kernel arguments -> indices -> operands -> result), issues the loads
 // of a phase together, avoids integer multiplies, and keeps the role a run-time value so that
 // the three owners share one copy of the code in the instruction cache.
+//
+// The (4,4,4) shapes (lists of hundreds of entries, rows that cost 16-64 KB of G2 each) differ:
+// the owners are separate copies of the body, the G2 owner works on the matrix cores in batches
+// of rows and, after the grouping pre-pass, also produces the G1 gradient of every row
+// (g1_from_p_kernel then finishes the G1 slices), long lists are shared by several workgroups
+// whose partial slice gradients bwd_split_finish_kernel adds up, and the cached-row reduction
+// of tt_group.h runs as extra workgroups of these launches.  See FbSplit and the comment above
+// consume_g2_mfma.
 #pragma once
 
 #include <stddef.h>
@@ -98,7 +106,9 @@ __device__ __forceinline__ void fb_part_range(int part, int nparts, int gran, in
 
 template <typename C>
 struct FbCfg {
-    static constexpr int W = 4096 / C::N;                   // sorted entries per window
+    // sorted entries per window: 16 KB of upstream gradients; 32 KB for (4,4,4) at R = 64, whose kernel time is the
+    // time of the longest lists and whose other LDS needs leave the room
+    static constexpr int W = (C::N1 == 4 && C::R == 64 ? 8192 : 4096) / C::N;
     static constexpr int NB = (W + WAVE - 1) / WAVE;        // ballots that cover a window
     static constexpr int SB = 16;                           // distinct rows whose small operands sit in LDS
     static constexpr int SMALL = C::sA + C::sC;             // floats per row: G1 slice | G3 slice
