@@ -113,6 +113,36 @@ def test_null_and_bad_arguments():
     assert l.tt_emb_debug_dedup(C.byref(s), one, 5, None, 7, one, one, one, one, one, 1 << 20, None) == -3
 
 
+def test_workspace_rules_of_the_backward():
+    """Which calls need a workspace, and that a missing or short one is refused before anything is enqueued."""
+    l = B.lib()
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    out = (C.c_void_p * 3)(32, 32, 32)
+    one = C.c_void_p(16)
+    small = B.make_shape(10_131_227, (200, 220, 250), (2, 2, 4), (1, 32, 32, 1))
+    big = B.make_shape(10_000_000, (200, 200, 250), (4, 4, 4), (1, 32, 32, 1))
+    # (2,2,4): no workspace below 32768 positions without a cache, one from there on
+    L = 40000
+    need = l.tt_emb_workspace_bytes(C.byref(small), L, L, 0)
+    assert need > 80 * L
+    assert l.tt_emb_bwd(C.byref(small), arr, one, L, None, L, None, None, one, arr, None, None, 0, None) == -4
+    assert l.tt_emb_bwd(C.byref(small), arr, one, L, None, L, None, None, one, arr, None, one, 1024, None) == -4
+    # (4,4,4): the slices are shared from 4096 positions on, which needs room for the partial sums
+    for n in (5000, 40000):
+        need = l.tt_emb_bwd_sgd_workspace_bytes(C.byref(big), n, n, 0)
+        assert need >= 2 * 200 * 32 * 4 * 32 * 4                    # two partial copies of the second core at least
+        assert l.tt_emb_bwd(C.byref(big), arr, one, n, None, n, None, None, one, arr, None, None, 0, None) == -4
+        assert l.tt_emb_bwd_sgd(C.byref(big), arr, out, one, n, None, n, None, None, one, C.c_float(0.1), one, 4096, None) == -4
+    # the query grows with the number of positions and with the cache
+    a = l.tt_emb_workspace_bytes(C.byref(big), 40000, 2000, 0)
+    b = l.tt_emb_workspace_bytes(C.byref(big), 80000, 2000, 0)
+    c = l.tt_emb_workspace_bytes(C.byref(big), 80000, 2000, 1000)
+    assert a < b < c
+    # a workspace that does not start on a 16-byte boundary
+    odd = C.c_void_p(24)
+    assert l.tt_emb_bwd(C.byref(big), arr, one, 5000, None, 5000, None, None, one, arr, None, odd, 1 << 30, None) == -3
+
+
 def test_empty_calls_enqueue_nothing_and_succeed():
     l = B.lib()
     s = good_shape()
