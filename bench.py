@@ -31,7 +31,7 @@ POOL = 16                      # distinct batches cycled through, so caches see 
 # HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the counter reads for a 256 MiB copy (factors 2.000 and 1.000); the runs and figures
 # are in profiles/hbm_traffic_bench_kaggle_r32.md.  Only valid for the workload they were taken on.
-MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 10.98e6, "bwd_sgd": 13.12e6},
+MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 11.00e6, "bwd_sgd": 13.08e6},
                                    "recompute": {"fwd": 9.93e6, "bwd_sgd": 15.42e6},
                                    "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}}}
 
