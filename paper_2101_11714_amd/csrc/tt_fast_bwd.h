@@ -711,20 +711,24 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                     }
                 }
                 __syncthreads();
-                g2_fetch(sb0 + GB, nsegs, nxt);
-                // 2. dG2: per row two steps, j1 = 2 h + kh.  The operands of HB rows are read from LDS first, then
-                //    multiplied, so that the reads are in flight together (the sched_barriers keep that order).
-                constexpr int HB = RT == 1 ? GB : GB / 2;
-#pragma unroll
-                for (int u0 = 0; u0 < GB; u0 += HB) {
-                    float bv[HB][2][RT];
+                if (sb0 + GB < nsegs) g2_fetch(sb0 + GB, nsegs, nxt);     // uniform
+                // 2. dG2: per row two steps, j1 = 2 h + kh;  3. tile (tm, tn) = (w / 2, w % 2) of P: lines 16 tm + l16 of
+                //    dT0' against Bm^T, four columns per step (register r of the result is row u = 4 tm + q16 of the
+                //    batch, j1 = r, a = 32 rh + 16 tn + l16).  Both as groups of 16 multiplications whose operands are
+                //    read from LDS while the group before is multiplied (the sched_barriers keep that order).
+                constexpr int HB = GB / RT;                               // rows per group of dG2
+                constexpr int NGP = NKP / 16;                             // groups of P
+                const float *dline = dt + (16 * (w / 2) + l16) * DTS + q16;
+                auto read_bv = [&](int u0, float (&r)[16]) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < HB; ++u)
 #pragma unroll
                         for (int h = 0; h < 2; ++h)
 #pragma unroll
-                            for (int x = 0; x < RT; ++x) bv[u][h][x] = dt[((u0 + u) * N1 + 2 * h + kh) * DTS + w * R + 32 * x + ln];
-                    __builtin_amdgcn_sched_barrier(0);
+                            for (int x = 0; x < RT; ++x)
+                                r[(u * 2 + h) * RT + x] = dt[((u0 + u) * N1 + 2 * h + kh) * DTS + w * R + 32 * x + ln];
+                };
+                auto mul_bv = [&](int u0, const float (&r)[16]) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < HB; ++u) {
                         if (u0 + u >= nb) break;                          // uniform: the rest of the batch is empty
@@ -732,24 +736,46 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                         for (int h = 0; h < 2; ++h)
 #pragma unroll
                             for (int tc = 0; tc < RT; ++tc)
-                                accm[tc] = __builtin_amdgcn_mfma_f32_32x32x2f32(cur.a[u0 + u][h], bv[u][h][tc], accm[tc], 0, 0, 0);
+                                accm[tc] = __builtin_amdgcn_mfma_f32_32x32x2f32(cur.a[u0 + u][h], r[(u * 2 + h) * RT + tc], accm[tc], 0, 0, 0);
                     }
+                };
+                auto read_dv = [&](int g, float (&r)[16]) __attribute__((always_inline)) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = dline[4 * (16 * g + i)];
+                };
+                mfma4_t pa = {0.f, 0.f, 0.f, 0.f};
+                float ra[16], rb[16];
+                static_assert(HB * 2 * RT == 16 && (RT == 1 || RT == 2) && NGP % 2 == 0, "groups of 16");
+                read_bv(0, ra);
+                if (RT == 2) read_bv(HB, rb);
+                else if (with_p) read_dv(0, rb);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_bv(0, ra);
+                if (RT == 2) {
+                    if (with_p) read_dv(0, ra);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mul_bv(HB, rb);
+                    if (with_p) read_dv(1, rb);
+                    __builtin_amdgcn_sched_barrier(0);
+                } else {
+                    if (with_p) read_dv(1, ra);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // 3. tile (tm, tn) = (w / 2, w % 2) of P: lines 16 tm + l16 of dT0' against Bm^T, four columns per step;
-                //    register r of the result is row u = 4 tm + q16 of the batch, j1 = r, a = 32 rh + 16 tn + l16
-                mfma4_t pa = {0.f, 0.f, 0.f, 0.f};
-                constexpr int IB = 16;                                    // steps whose operands are read together
-                const float *dline = dt + (16 * (w / 2) + l16) * DTS + q16;
+                // now the first two groups of P are in flight: group 0 in ra (rb if RT == 1), group 1 in the other
+                if (with_p) {
 #pragma unroll
-                for (int i0 = 0; i0 < (with_p ? NKP : 0); i0 += IB) {
-                    float dv[IB];
+                    for (int g = 0; g < NGP; g += 2) {
+                        float (&r0)[16] = RT == 2 ? ra : rb;
+                        float (&r1)[16] = RT == 2 ? rb : ra;
 #pragma unroll
-                    for (int i = 0; i < IB; ++i) dv[i] = dline[4 * (i0 + i)];
-                    __builtin_amdgcn_sched_barrier(0);
+                        for (int i = 0; i < 16; ++i) pa = __builtin_amdgcn_mfma_f32_16x16x4f32(r0[i], bmt[16 * g + i], pa, 0, 0, 0);
+                        if (g + 2 < NGP) read_dv(g + 2, r0);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int i = 0; i < IB; ++i) pa = __builtin_amdgcn_mfma_f32_16x16x4f32(dv[i], bmt[i0 + i], pa, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
+                        for (int i = 0; i < 16; ++i) pa = __builtin_amdgcn_mfma_f32_16x16x4f32(r1[i], bmt[16 * (g + 1) + i], pa, 0, 0, 0);
+                        if (g + 3 < NGP) read_dv(g + 3, r1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
                 {
                     const int u = 4 * (w / 2) + q16;
