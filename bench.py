@@ -86,6 +86,9 @@ def main():
                     help="the backward pass recomputes the forward's intermediate T0 (tt_emb_fwd / tt_emb_bwd_sgd) "
                          "instead of reading the copy that the forward pass stored "
                          "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0, the default of the fused step)")
+    ap.add_argument("--offsets", choices=["csr", "none"], default="csr",
+                    help="csr: bags given by an offsets array; none: the boundary's form for one index per bag "
+                         "(offsets == NULL), for the workloads whose bags all hold one index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
@@ -124,6 +127,9 @@ def main():
     batches_h = [W.make_batch(wl, tab, step, with_alpha=args.weights == "alpha") for step in range(POOL)]
     idx = [torch.from_numpy(b.indices).to(dev) for b in batches_h]
     off = [torch.from_numpy(b.offsets).to(dev) for b in batches_h]
+    if args.offsets == "none":                          # the boundary's form for "one index per bag": no offsets array
+        assert wl.bag_len == (1, 1), "--offsets none needs a workload with one index per bag"
+        off = [None] * POOL
     go = [torch.from_numpy(b.grad_output).to(dev) for b in batches_h]
     n_bags = wl.n_bags
     Ls = [int(b.indices.size) for b in batches_h]       # bags of random length: the batches differ a little
