@@ -530,9 +530,9 @@ def test_kept_t0_ragged_weighted_with_cache(path):
     assert_close(dc.cpu().numpy()[:K], rc, "kept T0 + cache dCache")
 
 
-@pytest.mark.parametrize("R", [32, 64])
+@pytest.mark.parametrize("R,n_bags", [(32, 1500), (64, 1500), (32, 6000)])
 @pytest.mark.parametrize("with_cache", [False, True])
-def test_444_shapes_shared_slices_and_matrix_cores(R, with_cache, path):
+def test_444_shapes_shared_slices_and_matrix_cores(R, n_bags, with_cache, path):
     """The (4,4,4) shapes from 4096 positions on: several workgroups share a slice (partial sums in the
     workspace), the G2 owners work on the matrix cores and, with the grouping pre-pass, also produce the G1
     gradients; with a cache its reduction rides along.  Ragged weighted bags, a hot row, a list length that
@@ -541,7 +541,7 @@ def test_444_shapes_shared_slices_and_matrix_cores(R, with_cache, path):
     t = W.TableShape(12 * 11 * 13, (12, 11, 13), (4, 4, 4), (1, R, R, 1))
     wl = dataclasses.replace(W.WORKLOADS["tiny"], tables=(t,), name="small444")
     rng = np.random.default_rng(40 + R)
-    lens = rng.integers(0, 9, 1500).astype(np.int64)
+    lens = rng.integers(0, 9, n_bags).astype(np.int64)           # 6000 bags: lists of > 512 entries per workgroup
     lens[7] = 431                                                   # one long bag
     off = np.zeros(lens.size + 1, dtype=np.int64)
     np.cumsum(lens, out=off[1:])
