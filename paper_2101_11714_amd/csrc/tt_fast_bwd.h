@@ -1005,30 +1005,45 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     if (!any && !fused && !pout) return;
 #endif
 
+    // The G2 owner's last phase: all old values are loaded before the first store (one round trip, not one per element).
+    const float *src2 = fused ? G2 : dG2;                              // x - lr * g to the second set of cores, or dG += g
+    float *dst2 = fused ? o2 : dG2;
+    const float mul2 = fused ? -lr : 1.f;
     if (MFMA && ROLE == 1) {
         // result registers of the 32 x 32 tiles: register r of lane (kh, ln) is row 32 rh + 8 (r / 4) + 4 kh + r % 4, column ln
+        constexpr int NR = MFMA ? RT * 16 : 1;
+        float prev[NR];
+        if (!pout) {
 #pragma unroll
-        for (int tc = 0; tc < (MFMA ? RT : 0); ++tc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int a = 32 * rh + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
-                const size_t i = (size_t)s * C::sB + (size_t)a * C::COLS + c;
-                const float g = accm[MFMA ? tc : 0][r];
-                if (pout) pout[a * C::COLS + c] = g;
-                else if (fused) o2[i] = fmaf(-lr, g, G2[i]);
-                else add_to(&dG2[i], g);
+            for (int j = 0; j < NR; ++j) {
+                const int tc = j / 16, r = j % 16, a = 32 * rh + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
+                prev[j] = src2[(size_t)s * C::sB + (size_t)a * C::COLS + c];
             }
+        }
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int tc = j / 16, r = j % 16, a = 32 * rh + 8 * (r / 4) + 4 * kh + r % 4, c = w * R + 32 * tc + ln;
+            const float g = accm[MFMA ? tc : 0][r];
+            if (pout) pout[a * C::COLS + c] = g;
+            else dst2[(size_t)s * C::sB + (size_t)a * C::COLS + c] = fmaf(mul2, g, prev[j]);
+        }
     } else if (!MFMA && ROLE == 1) {
         if (active) {
             const size_t at = (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
+            float prev[NACC2];
+            if (PREFETCH && fused) {
+#pragma unroll
+                for (int j = 0; j < NACC2; ++j) prev[j] = old[j];
+            } else {
+#pragma unroll
+                for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) prev[aa * V + v] = src2[at + aa * C::COLS + v];
+            }
 #pragma unroll
             for (int aa = 0; aa < RQ; ++aa)
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const size_t i = at + aa * C::COLS + v;
-                    if (fused) o2[i] = fmaf(-lr, acc[aa * V + v], PREFETCH ? old[aa * V + v] : G2[i]);
-                    else add_to(&dG2[i], acc[aa * V + v]);
-                }
+                for (int v = 0; v < V; ++v) dst2[at + aa * C::COLS + v] = fmaf(mul2, acc[aa * V + v], prev[aa * V + v]);
         }
     } else if (ROLE == 0) {
         float red[NACC1];
