@@ -112,11 +112,11 @@ int64_t tt_cache_table_capacity(int64_t K);
 
 /* Bytes of device workspace that is always enough for tt_emb_fwd / tt_emb_bwd with L
  * positions in n_bags bags and a cache of cache_rows rows (0 = no cache).  tt_emb_fwd needs
- * none.  tt_emb_bwd needs none for a short index stream without a cache; with a cache, from
- * 32768 positions on (16384 with a cache; it then groups the positions with a device sort first),
- * or for the column factorisation (4,4,4) from 4096 positions on (several workgroups then share
- * a slice and leave partial sums in the workspace), it reports TT_ERR_WORKSPACE if the workspace
- * is missing or too small.  Returns 0 on a bad shape. */
+ * none.  tt_emb_bwd needs none for a short index stream without a cache; with a cache, or from
+ * 4096 positions on (from there on, depending on the shape, several workgroups share a slice and
+ * leave partial sums in the workspace; from 32768 positions on, 16384 with a cache, the positions
+ * are grouped with a device sort first), it reports TT_ERR_WORKSPACE if the workspace is missing
+ * or too small.  Returns 0 on a bad shape. */
 size_t tt_emb_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows);
 
 /* Bytes of device workspace tt_cache_build needs for n_cand candidates. */
@@ -220,9 +220,8 @@ int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], floa
  *            is written, also in slices that no position touches.  Must not alias
  *            cores (other workgroups still read the old slices); a training loop
  *            swaps the two sets after each step.
- * workspace: tt_emb_bwd_sgd_workspace_bytes(...) bytes (none needed without a cache,
- *            below 32,768 positions (4,096 for the column factorisation (4,4,4)),
- *            for the shapes with a specialised kernel).
+ * workspace: tt_emb_bwd_sgd_workspace_bytes(...) bytes (none needed without a cache
+ *            below 4,096 positions, for the shapes with a specialised kernel).
  * L == 0 copies the cores.
  */
 int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],

@@ -76,10 +76,10 @@ typedef float mfma4_t __attribute__((ext_vector_type(4)));
 // a returned value, was measured and is slower here than load, add, store.)
 __device__ __forceinline__ void add_to(float *dst, float x) { *dst += x; }
 
-// Several workgroups may share one slice (only used for the (4,4,4) shapes, whose lists get long and
-// whose rows are expensive): ns[r] workgroups per slice of core r, each takes one part of the
-// positions and, where ns[r] > 1, stores its partial slice gradient at part[r] + (slice ns[r] +
-// part) * slice size instead of finishing the slice; bwd_split_finish_kernel adds the parts up.
+// Several workgroups may share one slice (from 4096 positions on: the lists get long, and one hot row can
+// fill a list): ns[r] workgroups per slice of core r, each takes one part of the positions and, where
+// ns[r] > 1, stores its partial slice gradient at part[r] + (slice ns[r] + part) * slice size instead of
+// finishing the slice; bwd_split_finish_kernel adds the parts up.
 struct FbSplit {
     int ns[3];
     float *part[3];
@@ -324,7 +324,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     constexpr int PFMAX = NACC2 > KEEP1 ? (NACC2 > PF3 ? NACC2 : PF3) : (KEEP1 > PF3 ? KEEP1 : PF3);
     constexpr bool PREFETCH = PFMAX <= 8;
     float old[PREFETCH ? PFMAX : 1];
-    if (PREFETCH && fused) {
+    if (PREFETCH && fused && !pout) {
         if (ROLE == 1) {
             const float *src = G2 + (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;    // inactive lanes: c0 = 0, in range
 #pragma unroll
@@ -1031,7 +1031,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         if (active) {
             const size_t at = (size_t)s * C::sB + (size_t)a0 * C::COLS + c0;
             float prev[NACC2];
-            if (PREFETCH && fused) {
+            if (pout) {
+                // a partial slice gradient: nothing to read
+            } else if (PREFETCH && fused) {
 #pragma unroll
                 for (int j = 0; j < NACC2; ++j) prev[j] = old[j];
             } else {
@@ -1040,10 +1042,17 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                     for (int v = 0; v < V; ++v) prev[aa * V + v] = src2[at + aa * C::COLS + v];
             }
+            if (pout) {
 #pragma unroll
-            for (int aa = 0; aa < RQ; ++aa)
+                for (int aa = 0; aa < RQ; ++aa)
 #pragma unroll
-                for (int v = 0; v < V; ++v) dst2[at + aa * C::COLS + v] = fmaf(mul2, acc[aa * V + v], prev[aa * V + v]);
+                    for (int v = 0; v < V; ++v) pout[(a0 + aa) * C::COLS + c0 + v] = acc[aa * V + v];
+            } else {
+#pragma unroll
+                for (int aa = 0; aa < RQ; ++aa)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) dst2[at + aa * C::COLS + v] = fmaf(mul2, acc[aa * V + v], prev[aa * V + v]);
+            }
         }
     } else if (ROLE == 0) {
         float red[NACC1];
@@ -1057,7 +1066,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 const int idx = base + i;                                  // = j1 * RQ + aa
                 const int j1 = idx / RQ, aa = idx % RQ;
                 const size_t at = (size_t)s * C::sA + j1 * R + a0 + aa;
-                if (MFMA && pout) pout[j1 * R + a0 + aa] = red[i];
+                if (pout) pout[j1 * R + a0 + aa] = red[i];
                 else if (fused) o1[at] = fmaf(-lr, red[i], PREFETCH ? old[i] : G1[at]);
                 else add_to(&dG1[at], red[i]);
             }
@@ -1084,7 +1093,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #pragma unroll
                     for (int jj = 0; jj < N2; ++jj) sum += part[(ww * C::COLS + jj * R + b) * N3 + j3];
                 const size_t at = (size_t)s * C::sC + e;
-                if (MFMA && pout) pout[e] = sum;
+                if (pout) pout[e] = sum;
                 else if (fused) o3[at] = fmaf(-lr, sum, PREFETCH ? old[i] : G3[at]);
                 else add_to(&dG3[at], sum);
             }
@@ -1095,7 +1104,9 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 #endif
 }
 
-template <typename C>
+// SPLIT: the launch may share slices between workgroups (FbSplit); without it the kernel takes no such argument
+// and its workgroups are the slice owners, nothing else (the small batches of the Criteo-shaped workloads).
+template <typename C, bool SPLIT>
 __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WAVES_PER_SIMD))) void bwd_fast_kernel(
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3,
     const int64_t *__restrict__ indices, int L, const int64_t *__restrict__ offsets, int n_bags,
@@ -1103,8 +1114,9 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     float *__restrict__ dG1, float *__restrict__ dG2, float *__restrict__ dG3,
     const uint32_t *__restrict__ gvals, const int *__restrict__ goff, const int *__restrict__ gend,
     float lr, float *__restrict__ o1, float *__restrict__ o2, float *__restrict__ o3, const float *__restrict__ t0,
-    typename FbSplitArg<FbCfg<C>::MFMA>::type sp)
+    typename FbSplitArg<SPLIT>::type sp)
 {
+    static_assert(SPLIT || !FbCfg<C>::MFMA, "the (4,4,4) shapes always take the split descriptor");
     __shared__ FbLds<C> lds;
 #if defined(TT_PROFILE)
     const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
@@ -1137,6 +1149,20 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
         else
         if (role == 1) fb_body<C>(lds, p, 1, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, sp.pbuf, sp.pflag, rh);
         else fb_body<C>(lds, p, 2, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, sp.pbuf, sp.pflag, rh);
+    } else if constexpr (SPLIT) {
+        // run-time role as below, but ns[role] workgroups share a slice, each with a part of the positions
+        const int g = blockIdx.x, n0 = p.m1 * sp.ns[0], n1 = p.m2 * sp.ns[1];
+        const int role = (g >= n0) + (g >= n0 + n1);
+        const int q = g - (role == 0 ? 0 : (role == 1 ? n0 : n0 + n1));
+        const int S = sp.ns[role], sl = q / S, part = q - sl * S;
+        float *pout = nullptr;
+        if (S > 1) pout = sp.part[role] + (size_t)q * (role == 0 ? C::sA : (role == 1 ? C::sB : C::sC));
+        if (!gvals) {
+            int lo = 0, end = L;
+            fb_part_range(part, S, FB_CAP, lo, end);
+            fb_load_rows(indices, slot, lo, min(end, lo + FB_SCAN), rowv);
+        }
+        fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, part, S, pout, nullptr, nullptr, 0);
     } else {
         // The index loads do not depend on the role: issue them before anything else.
         if (!gvals) fb_load_rows(indices, slot, 0, min(L, FB_SCAN), rowv);
@@ -1292,17 +1318,23 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
     }
 }
 
-// Split factors for a call: only the (4,4,4) shapes, from 4096 positions on (below that the extra pass does not
-// pay).  Two workgroups share a G2 or G3 slice: the longest lists decide the kernel time (without a cache one hot
-// row can fill a list).  With the grouping pre-pass the G2 owners also compute the G1 gradients (fb_with_p), so
+// Split factors for a call: from 4096 or 8192 positions on (below that the extra pass does not pay).  Two or four
+// workgroups share a slice: the longest lists decide the kernel time (without a cache one hot row can fill a
+// list), and a scan of a part of the positions takes fewer rounds.  With the grouping pre-pass the G2 owners also compute the G1 gradients (fb_with_p), so
 // there are no G1 owners; without it they exist and four of them share a slice (each streams a G2 slice per row).
 template <typename C>
 static inline void fb_choose_split(int L, int (&ns)[3])
 {
     ns[0] = ns[1] = ns[2] = 1;
-    if (FbCfg<C>::MFMA && L >= 4096) {
-        ns[0] = 4;
-        ns[1] = ns[2] = 2;
+    if (FbCfg<C>::MFMA) {
+        if (L >= 4096) {
+            ns[0] = 4;
+            ns[1] = ns[2] = 2;
+        }
+    } else if (L >= (C::R >= 64 ? 4096 : 8192)) {
+        // (2,2,4): at 4096 positions twice the workgroups no longer fit the chip at once and the extra pass costs
+        // more than the shorter lists save, except at R = 64 where a G1 owner has one G2 row in flight at a time
+        ns[0] = ns[1] = ns[2] = L >= 131072 ? 8 : (L >= 16384 ? 4 : 2);
     }
 }
 
@@ -1324,6 +1356,10 @@ static inline void fast_bwd_split(const Params &p, int L, int (&ns)[3])
 {
     ns[0] = ns[1] = ns[2] = 1;
     switch (fast_config(p)) {
+    case 0: fb_choose_split<Cfg224R8>(L, ns); break;
+    case 1: fb_choose_split<Cfg224R16>(L, ns); break;
+    case 2: fb_choose_split<Cfg224R32>(L, ns); break;
+    case 3: fb_choose_split<Cfg224R64>(L, ns); break;
     case 4: fb_choose_split<Cfg444R32>(L, ns); break;
     case 5: fb_choose_split<Cfg444R64>(L, ns); break;
     default: break;
@@ -1386,11 +1422,11 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
         sp.cw = *cw;
         grid += cw->blocks;
     }
-    if constexpr (MFMA)
-        hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+    if (MFMA || sp.ns[0] > 1 || sp.ns[1] > 1 || sp.ns[2] > 1)
+        hipLaunchKernelGGL((bwd_fast_kernel<C, true>), dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
                            n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, sp);
-    else
-        hipLaunchKernelGGL(bwd_fast_kernel<C>, dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
+    else if constexpr (!MFMA)
+        hipLaunchKernelGGL((bwd_fast_kernel<C, false>), dim3(grid), dim3(WG), 0, st, p, G1, G2, G3, idx, L, off,
                            n_bags, alpha, slot, go, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, FbNoSplit());
     if (with_p)
         hipLaunchKernelGGL(g1_from_p_kernel<C>, dim3(p.m1 + sp.cw.blocks), dim3(WG), 0, st, p, idx, L, slot, gvals, goff, gend,

@@ -121,13 +121,17 @@ def test_workspace_rules_of_the_backward():
     one = C.c_void_p(16)
     small = B.make_shape(10_131_227, (200, 220, 250), (2, 2, 4), (1, 32, 32, 1))
     big = B.make_shape(10_000_000, (200, 200, 250), (4, 4, 4), (1, 32, 32, 1))
-    # (2,2,4): no workspace below 32768 positions without a cache, one from there on
+    # every shape with a specialised kernel: none for a short stream without a cache; from 8192 positions on (4096 at
+    # rank 64 and for (4,4,4)) the slices are shared by several workgroups, which needs room for the partial sums;
+    # from 32768 positions on also for the lists
+    assert l.tt_emb_bwd(C.byref(small), arr, one, 9000, None, 9000, None, None, one, arr, None, None, 0, None) == -4
+    assert l.tt_emb_workspace_bytes(C.byref(small), 9000, 9000, 0) >= 2 * 4 * (200 * 64 + 220 * 2048 + 250 * 128)
     L = 40000
     need = l.tt_emb_workspace_bytes(C.byref(small), L, L, 0)
     assert need > 80 * L
     assert l.tt_emb_bwd(C.byref(small), arr, one, L, None, L, None, None, one, arr, None, None, 0, None) == -4
     assert l.tt_emb_bwd(C.byref(small), arr, one, L, None, L, None, None, one, arr, None, one, 1024, None) == -4
-    # (4,4,4): the slices are shared from 4096 positions on, which needs room for the partial sums
+    # (4,4,4): the same, with more parts
     for n in (5000, 40000):
         need = l.tt_emb_bwd_sgd_workspace_bytes(C.byref(big), n, n, 0)
         assert need >= 2 * 200 * 32 * 4 * 32 * 4                    # two partial copies of the second core at least
