@@ -227,7 +227,7 @@ static int fwd_common(const tt_shape_t *shape, const float *const cores[3],
     hipStream_t st = (hipStream_t)stream;
 
     if (g_fast_path || keep_t0) {
-        int frc = fast_fwd(p, cores[0], cores[1], cores[2], indices, offsets, (int)n_bags, alpha, cd, output,
+        int frc = fast_fwd(p, cores[0], cores[1], cores[2], indices, offsets, L, (int)n_bags, alpha, cd, output,
                            keep_t0 ? t0_out : nullptr, st);
         if (frc == 0) {
             hipError_t e = hipGetLastError();

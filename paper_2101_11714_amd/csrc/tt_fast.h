@@ -113,7 +113,9 @@ struct ReduceKeep {
 // the other positions go through the cores one after the other.  The partial products of
 // stage 1 are accumulated over the bag's lookups before one shuffle reduction per bag,
 // and the sum of the cached rows is added to the result at the end.
-template <typename C>
+// WGBAG: a whole workgroup per bag, for long bags: its four waves take a quarter of the bag's
+// positions each and their results are added through LDS, in wave order.
+template <typename C, bool WGBAG>
 __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__restrict__ G1,
                                                       const float *__restrict__ G2, const float *__restrict__ G3,
                                                       const int64_t *__restrict__ indices,
@@ -123,8 +125,9 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
 {
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V;
     const int lane = threadIdx.x & 63;
-    const int bag = __builtin_amdgcn_readfirstlane(blockIdx.x * NWAVE + (threadIdx.x >> 6));
-    if (bag >= n_bags) return;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int bag = WGBAG ? (int)blockIdx.x : (int)blockIdx.x * NWAVE + wv;
+    if (bag >= n_bags) return;                              // (uniform in the workgroup if WGBAG)
     const bool active = lane < C::LANES;
     const int c0 = active ? lane * V : 0;
     const int j2 = c0 / R, b0 = c0 % R;
@@ -174,8 +177,13 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
         }
     };
 
-    const int k0 = offsets ? (int)offsets[bag] : bag;
-    const int k1 = offsets ? (int)offsets[bag + 1] : bag + 1;
+    int k0 = offsets ? (int)offsets[bag] : bag;
+    int k1 = offsets ? (int)offsets[bag + 1] : bag + 1;
+    if (WGBAG) {                                            // this wave's quarter of the bag
+        const int per = (k1 - k0 + NWAVE - 1) / NWAVE;
+        k0 = min(k1, k0 + wv * per);
+        k1 = min(k1, k0 + per);
+    }
     int kb = k0;
     if (k1 - k0 == 1 && !cache.K) {
         // one index per bag and no cache (the Criteo-shaped workloads): the shortest chain from index to slices
@@ -240,7 +248,19 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
             acc[i] += j3 == 0 ? x : (j3 == 1 ? y : (j3 == 2 ? z : u));
         }
     }
-    if (active && lg < ReduceKeep<C::NV, C::LN>::writers) {
+    if constexpr (WGBAG) {
+        __shared__ float partial[NWAVE][C::N];
+        if (active && lg < ReduceKeep<C::NV, C::LN>::writers) {
+#pragma unroll
+            for (int i = 0; i < KEEP; ++i) {
+                const int idx = base + i, j1 = idx / N3, j3 = idx % N3;
+                partial[wv][(j1 * N2 + j2) * N3 + j3] = acc[i];
+            }
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < C::N; e += WG)
+            out[(size_t)bag * C::N + e] = (partial[0][e] + partial[1][e]) + (partial[2][e] + partial[3][e]);
+    } else if (active && lg < ReduceKeep<C::NV, C::LN>::writers) {
         float *o = out + (size_t)bag * C::N;
 #pragma unroll
         for (int i = 0; i < KEEP; ++i) {
@@ -253,13 +273,20 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
 
 // ---- dispatch ----------------------------------------------------------------------
 
+// L: number of positions; a workgroup per bag from an average of 32 positions per bag on (measured: at 20 positions
+// per bag, most of them cached, a wave per bag is faster; at 100 the workgroup is)
 template <typename C>
 static inline void launch_fwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
-                              const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd, float *out,
+                              const int64_t *off, int64_t L, int n_bags, const float *alpha, const CacheDev &cd, float *out,
                               float *t0_out, hipStream_t st)
 {
-    hipLaunchKernelGGL(fwd_fast_kernel<C>, dim3((n_bags + NWAVE - 1) / NWAVE), dim3(WG), 0, st, p, G1, G2, G3, idx, off,
-                       n_bags, alpha, cd, out, t0_out);
+    static_assert(NWAVE == 4, "the workgroup-per-bag variant adds four partial results");
+    if (off && L >= 32 * (int64_t)n_bags)
+        hipLaunchKernelGGL((fwd_fast_kernel<C, true>), dim3(n_bags), dim3(WG), 0, st, p, G1, G2, G3, idx, off, n_bags, alpha,
+                           cd, out, t0_out);
+    else
+        hipLaunchKernelGGL((fwd_fast_kernel<C, false>), dim3((n_bags + NWAVE - 1) / NWAVE), dim3(WG), 0, st, p, G1, G2, G3, idx,
+                           off, n_bags, alpha, cd, out, t0_out);
 }
 
 // id of the specialised configuration for this shape, or -1
@@ -289,16 +316,16 @@ using Cfg444R64 = FastCfg<4, 4, 4, 64, 4>;
 
 // Returns 0 if a specialised forward kernel was launched, -1 if the shape has none.
 static inline int fast_fwd(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
-                           const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd, float *out,
+                           const int64_t *off, int64_t L, int n_bags, const float *alpha, const CacheDev &cd, float *out,
                            float *t0_out, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 0: launch_fwd<Cfg224R8>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
-    case 1: launch_fwd<Cfg224R16>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
-    case 2: launch_fwd<Cfg224R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
-    case 3: launch_fwd<Cfg224R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
-    case 4: launch_fwd<Cfg444R32>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
-    case 5: launch_fwd<Cfg444R64>(p, G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 0: launch_fwd<Cfg224R8>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 1: launch_fwd<Cfg224R16>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 2: launch_fwd<Cfg224R32>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 3: launch_fwd<Cfg224R64>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 4: launch_fwd<Cfg444R32>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
+    case 5: launch_fwd<Cfg444R64>(p, G1, G2, G3, idx, off, L, n_bags, alpha, cd, out, t0_out, st); return 0;
     default: return -1;
     }
 }

@@ -530,6 +530,43 @@ def test_kept_t0_ragged_weighted_with_cache(path):
     assert_close(dc.cpu().numpy()[:K], rc, "kept T0 + cache dCache")
 
 
+@pytest.mark.parametrize("R", [32, 64])
+def test_forward_long_bags_take_a_workgroup_each(R, path):
+    """Bags of about 100 positions (the forward then gives every bag a whole workgroup), ragged, weighted, with a
+    cache and with empty bags, on a (4,4,4) shape; the kept T0 must match as well."""
+    import dataclasses
+    t = W.TableShape(12 * 11 * 13, (12, 11, 13), (4, 4, 4), (1, R, R, 1))
+    wl = dataclasses.replace(W.WORKLOADS["tiny"], tables=(t,), name="small444")
+    rng = np.random.default_rng(60 + R)
+    lens = rng.integers(60, 140, 40).astype(np.int64)
+    lens[[3, 17]] = 0
+    lens[5] = 1
+    off = np.zeros(lens.size + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    L = int(off[-1])
+    idx = rng.integers(0, t.num_rows, L)
+    idx[rng.random(L) < 0.3] = 17                                   # one hot row
+    batch = W.Batch(idx, off, rng.standard_normal((lens.size, t.dim)).astype(np.float32),
+                    (0.5 + rng.random(L)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    rows, counts = np.unique(idx, return_counts=True)
+    K = 25
+    cache, _, _ = d.build_cache(K, rows.astype(np.int64), counts.astype(np.int64))
+    keys = ora.cache_select(rows, counts, K)
+    crows = cache.rows.cpu().numpy()[:K]
+    ref = ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha, cache_keys=keys, cache_rows=crows)
+    assert_close(d.fwd(cache=cache), ref, "long bags forward")
+    out, t0 = d.fwd_keep_t0(cache=cache)
+    assert_close(out, ref, "long bags forward keeping T0")
+    got = t0.cpu().numpy()
+    cached = ora.cache_lookup(d.oshape, keys, idx) >= 0
+    assert np.isnan(got[cached]).all() and not np.isnan(got[~cached]).any()
+    pick = np.random.default_rng(3).choice(np.flatnonzero(~cached), 48, replace=False)
+    want = np.stack([ora.t0(d.oshape, d.cores, int(idx[k])).reshape(-1) for k in pick])
+    assert_close(got[pick], want, "kept T0 of long bags")
+    assert_close(d.fwd(), ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha), "long bags forward, no cache")
+
+
 @pytest.mark.parametrize("R,n_bags", [(32, 1500), (64, 1500), (32, 6000)])
 @pytest.mark.parametrize("with_cache", [False, True])
 def test_444_shapes_shared_slices_and_matrix_cores(R, n_bags, with_cache, path):
