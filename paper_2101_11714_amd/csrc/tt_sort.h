@@ -13,8 +13,10 @@ constexpr int SCAN_WG = 1024;
 
 static inline int rs_blocks(int64_t n) { return (int)((n + RS_TILE - 1) / RS_TILE); }
 
-// hist[bin * nblk + blk] = number of keys of tile blk whose digit is bin.
+// hist[bin * nblk + blk] = number of keys of tile blk whose digit is bin (BYBLK: hist[blk * nbins + bin], the
+// layout the scatter kernel reads when it does the scan itself).
 // A pass sorts by `db` <= 8 bits of the key, taken at `shift` (1 << db bins).
+template <bool BYBLK>
 __global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict__ keys, int n, int shift, int db,
                                                      uint32_t *__restrict__ hist, int nblk)
 {
@@ -24,13 +26,14 @@ __global__ __launch_bounds__(WG) void rs_hist_kernel(const uint64_t *__restrict_
     h[t] = 0;
     __syncthreads();
     const int base = blockIdx.x * RS_TILE;
+    uint64_t k[RS_SUB];                                             // all loads first (clamped: none is conditional)
 #pragma unroll
-    for (int s = 0; s < RS_SUB; ++s) {
-        int i = base + s * WG + t;
-        if (i < n) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & mask], 1u);
-    }
+    for (int s = 0; s < RS_SUB; ++s) k[s] = keys[min(base + s * WG + t, n - 1)];
+#pragma unroll
+    for (int s = 0; s < RS_SUB; ++s)
+        if (base + s * WG + t < n) atomicAdd(&h[(uint32_t)(k[s] >> shift) & mask], 1u);
     __syncthreads();
-    if (t <= (int)mask) hist[t * nblk + blockIdx.x] = h[t];
+    if (t <= (int)mask) hist[BYBLK ? blockIdx.x * (int)(mask + 1u) + t : t * nblk + blockIdx.x] = h[t];
 }
 
 // In-place exclusive scan of data[0..total); data[total] receives the sum.  One workgroup.
@@ -97,51 +100,163 @@ __global__ __launch_bounds__(SCAN_WG) void scan_kernel(uint32_t *__restrict__ da
 }
 
 // Stable scatter of one pass.  vin == nullptr means payload = position.
+// The tile is 8 rounds of 256 keys; a wave ranks its 64 keys of a round among themselves with ballots, all rounds
+// first, then thread t (= bin t) turns the 32 (round, wave) counts of its bin into starting positions, and every key
+// goes to start + rank, through LDS, where the tile is put in order first: a digit's keys of one tile are neighbours in
+// the output, and scattered 8-byte stores of single lanes cost several times the stores of whole runs.
+// OWNSCAN: `hist` holds the raw counts by tile (rs_hist_kernel<true>) and every workgroup derives its own starting
+// positions from them: the keys with smaller digits anywhere plus the keys with the same digit in earlier tiles.  That is
+// nblk * nbins / 1024 16-byte loads per thread, all independent, instead of a scan kernel of one workgroup between the
+// two launches; the host takes this form for up to RS_OWNSCAN_MAX tiles.
+constexpr int RS_OWNSCAN_MAX = 512;
+
+template <bool OWNSCAN>
 __global__ __launch_bounds__(WG) void rs_scatter_kernel(const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin,
                                                         uint64_t *__restrict__ kout, uint32_t *__restrict__ vout,
                                                         int n, int shift, int db, const uint32_t *__restrict__ hist, int nblk)
 {
-    __shared__ uint32_t base[256];
-    __shared__ uint32_t cnt[NWAVE][256];
+    __shared__ __align__(16) uint32_t cnt[RS_SUB * NWAVE * 256];    // [round][wave][bin]; first the partial sums below
+    __shared__ uint64_t sk[RS_TILE];                                // the tile in output order
+    __shared__ uint32_t sv[RS_TILE];
+    __shared__ uint32_t gofs[256];
+    __shared__ uint32_t wtot[NWAVE], wtot2[NWAVE];
     const int t = threadIdx.x, w = t >> 6;
     const uint32_t mask = (1u << db) - 1u;
-    base[t] = t <= (int)mask ? hist[t * nblk + blockIdx.x] : 0u;
     const int tile = blockIdx.x * RS_TILE;
+    // the keys and payloads of all rounds are loaded before anything else
+    uint64_t keys[RS_SUB];
+    uint32_t vals[RS_SUB];
+#pragma unroll
     for (int s = 0; s < RS_SUB; ++s) {
         const int i = tile + s * WG + t;
-        const bool valid = i < n;
-        const uint64_t key = valid ? kin[i] : 0ull;
-        const uint32_t dg = (uint32_t)(key >> shift) & mask;
+        keys[s] = i < n ? kin[i] : 0ull;
+        vals[s] = i < n && vin ? vin[i] : (uint32_t)i;
+    }
+    uint32_t start;                                                 // of bin t in the output
+    if constexpr (OWNSCAN) {
+        // thread t sums 4 neighbouring bins (one 16-byte load per tile) over every (256 / q4)-th tile; all loads are
+        // independent and the counts were written by workgroups anywhere on the chip, so they are issued together
+        const int nbins = (int)mask + 1;
+        uint32_t *ptot = cnt, *ppre = cnt + 4 * WG;                 // [row group][bin]: totals, earlier tiles
+        uint32_t tot = 0, pre = 0;
+        if (nbins >= 4) {
+            const int q4 = nbins >> 2, c = t & (q4 - 1), rg = t / q4, nrg = WG / q4;
+            const uint4 *h4 = reinterpret_cast<const uint4 *>(hist);
+            uint4 t4 = make_uint4(0u, 0u, 0u, 0u), p4 = t4;
+            for (int b0 = rg; b0 < nblk; b0 += 16 * nrg) {         // 16 loads in flight (clamped, so none is conditional)
+                uint4 v[16];
 #pragma unroll
-        for (int j = 0; j < NWAVE; ++j) cnt[j][t] = 0;
-        __syncthreads();
-        // lanes of this wave that hold the same digit
-        uint64_t same = __ballot(valid);
-        for (int b = 0; b < db; ++b) {                              // uniform
-            const bool bit = (dg >> b) & 1u;
-            const uint64_t bal = __ballot(bit);
-            same &= bit ? bal : ~bal;
-        }
-        const int rank = __popcll(same & lanemask_lt());
-        if (valid && rank == 0) cnt[w][dg] = (uint32_t)__popcll(same);
-        __syncthreads();
-        {   // thread t owns bin t: turn per-wave counts into starting positions
-            uint32_t r = base[t];
+                for (int q = 0; q < 16; ++q) v[q] = h4[min(b0 + q * nrg, nblk - 1) * q4 + c];
 #pragma unroll
-            for (int j = 0; j < NWAVE; ++j) {
-                uint32_t c = cnt[j][t];
-                cnt[j][t] = r;
-                r += c;
+                for (int q = 0; q < 16; ++q) {
+                    const int b = b0 + q * nrg;
+                    const uint32_t in = b < nblk ? 0xffffffffu : 0u;
+                    const uint32_t m = b < (int)blockIdx.x ? 0xffffffffu : 0u;      // blockIdx.x < nblk
+                    t4.x += v[q].x & in; t4.y += v[q].y & in; t4.z += v[q].z & in; t4.w += v[q].w & in;
+                    p4.x += v[q].x & m; p4.y += v[q].y & m; p4.z += v[q].z & m; p4.w += v[q].w & m;
+                }
             }
-            base[t] = r;
+            *reinterpret_cast<uint4 *>(&ptot[rg * nbins + 4 * c]) = t4;
+            *reinterpret_cast<uint4 *>(&ppre[rg * nbins + 4 * c]) = p4;
+            __syncthreads();
+            if (t < nbins)
+                for (int q = 0; q < nrg; ++q) { tot += ptot[q * nbins + t]; pre += ppre[q * nbins + t]; }
+        } else {
+            if (t < nbins)
+                for (int b = 0; b < nblk; ++b) {
+                    const uint32_t v = hist[b * nbins + t];
+                    tot += v;
+                    pre += b < (int)blockIdx.x ? v : 0u;
+                }
         }
+        // exclusive scan of the totals over the bins (thread t = bin t)
+        const int lane = t & 63;
+        uint32_t inc = tot;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wtot[w] = inc;
+        __syncthreads();                                            // also: ptot / ppre have been read
+        uint32_t before = inc - tot;
+        for (int j = 0; j < w; ++j) before += wtot[j];
+        start = before + pre;
+    } else {
+        start = t <= (int)mask ? hist[t * nblk + blockIdx.x] : 0u;
+    }
+    {   // clear the counts: 8192 values, 8 stores of 16 bytes per thread
+        uint4 *c4 = reinterpret_cast<uint4 *>(cnt);
+#pragma unroll
+        for (int q = 0; q < RS_SUB * NWAVE * 256 / 4 / WG; ++q) c4[q * WG + t] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    __syncthreads();
+    int rank[RS_SUB];
+    {   // lanes of this wave that hold the same digit, one bit at a time, the rounds side by side (independent chains)
+        uint64_t same[RS_SUB];
+#pragma unroll
+        for (int s = 0; s < RS_SUB; ++s) same[s] = __ballot(tile + s * WG + t < n);
+        for (int b = 0; b < db; ++b) {                              // uniform
+#pragma unroll
+            for (int s = 0; s < RS_SUB; ++s) {
+                const bool bit = (keys[s] >> (shift + b)) & 1ull;
+                const uint64_t bal = __ballot(bit);
+                same[s] &= bit ? bal : ~bal;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < RS_SUB; ++s) {
+            const uint32_t dg = (uint32_t)(keys[s] >> shift) & mask;
+            rank[s] = __popcll(same[s] & lanemask_lt());
+            if (tile + s * WG + t < n && rank[s] == 0) cnt[(s * NWAVE + w) * 256 + dg] = (uint32_t)__popcll(same[s]);
+        }
+    }
+    __syncthreads();
+    {   // thread t owns bin t: the counts per round and wave become positions within the tile sorted by digit
+        uint32_t c[RS_SUB * NWAVE];
+        uint32_t total = 0;
+#pragma unroll
+        for (int q = 0; q < RS_SUB * NWAVE; ++q) { c[q] = cnt[q * 256 + t]; total += c[q]; }
+        const int lane = t & 63;
+        uint32_t inc = total;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wtot2[w] = inc;
         __syncthreads();
-        if (valid) {
-            const uint32_t dst = cnt[w][dg] + (uint32_t)rank;
+        uint32_t r = inc - total;                                   // keys of the tile with a smaller digit
+        for (int j = 0; j < w; ++j) r += wtot2[j];
+        gofs[t] = start - r;                                        // output position minus position in the tile
+#pragma unroll
+        for (int q = 0; q < RS_SUB * NWAVE; ++q) {
+            cnt[q * 256 + t] = r;
+            r += c[q];
+        }
+    }
+    __syncthreads();
+    // the tile is put in order in LDS first, so that neighbouring lanes store to neighbouring addresses
+#pragma unroll
+    for (int s = 0; s < RS_SUB; ++s) {
+        if (tile + s * WG + t < n) {
+            const uint32_t dg = (uint32_t)(keys[s] >> shift) & mask;
+            const uint32_t lp = cnt[(s * NWAVE + w) * 256 + dg] + (uint32_t)rank[s];
+            sk[lp] = keys[s];
+            sv[lp] = vals[s];
+        }
+    }
+    __syncthreads();
+    const int nv = min(RS_TILE, n - tile);
+#pragma unroll
+    for (int s = 0; s < RS_SUB; ++s) {
+        const int lp = s * WG + t;
+        if (lp < nv) {
+            const uint64_t key = sk[lp];
+            const uint32_t dst = (uint32_t)lp + gofs[(uint32_t)(key >> shift) & mask];
             kout[dst] = key;
-            vout[dst] = vin ? vin[i] : (uint32_t)i;
+            vout[dst] = sv[lp];
         }
-        __syncthreads();
     }
 }
 
@@ -260,10 +375,16 @@ static inline hipError_t radix_sort(const SortWs &s, int n, int bits, hipStream_
     const int npass = (bits + 7) / 8;
     const int db = (bits + npass - 1) / npass;
     for (int shift = 0; shift < bits; shift += db) {
-        hipLaunchKernelGGL(rs_hist_kernel, dim3(nblk), dim3(WG), 0, st, kin, n, shift, db, s.hist, nblk);
-        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, s.hist, (1 << db) * nblk);
-        hipLaunchKernelGGL(rs_scatter_kernel, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift, db,
-                           s.hist, nblk);
+        if (nblk <= RS_OWNSCAN_MAX) {
+            hipLaunchKernelGGL(rs_hist_kernel<true>, dim3(nblk), dim3(WG), 0, st, kin, n, shift, db, s.hist, nblk);
+            hipLaunchKernelGGL(rs_scatter_kernel<true>, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift, db,
+                               s.hist, nblk);
+        } else {
+            hipLaunchKernelGGL(rs_hist_kernel<false>, dim3(nblk), dim3(WG), 0, st, kin, n, shift, db, s.hist, nblk);
+            hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(SCAN_WG), 0, st, s.hist, (1 << db) * nblk);
+            hipLaunchKernelGGL(rs_scatter_kernel<false>, dim3(nblk), dim3(WG), 0, st, kin, vin, kout, vout, n, shift, db,
+                               s.hist, nblk);
+        }
         uint64_t *tk = kin; kin = kout; kout = tk;
         if (first) { vin = s.v0; vout = s.v1; first = false; }
         else { uint32_t *tv = vin; vin = vout; vout = tv; }

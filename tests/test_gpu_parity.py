@@ -87,6 +87,21 @@ def test_dedup_all_equal_and_empty():
     assert gu.numel() == 0 and gc.numel() == 0 and gp.numel() == 0
 
 
+@pytest.mark.parametrize("L", [2048 * 512, 2048 * 512 + 1, 1_300_003])
+def test_dedup_long_lists_both_forms_of_the_sort(L):
+    """Up to 512 tiles of 2048 keys the scatter kernel of the sort derives its own offsets; beyond, a scan kernel does."""
+    t = W.WORKLOADS["terabyte_r64"].tables[0]
+    rng = np.random.default_rng(L)
+    idx = rng.integers(0, t.num_rows, L, dtype=np.int64)
+    idx[rng.random(L) < 0.3] = 12345                                                      # one very long run
+    idx[: L // 4] = idx[L // 2: L // 2 + L // 4]                                          # many pairs
+    ru, rc, rp = ora.dedup(idx)
+    gu, gc, gp = B.tt_emb_debug_dedup(B.shape_of(t), torch.from_numpy(idx).to(dev()), 0)
+    assert np.array_equal(gu.cpu().numpy(), ru)
+    assert np.array_equal(gc.cpu().numpy(), rc)
+    assert np.array_equal(gp.cpu().numpy(), rp)
+
+
 # ------------------------------------------------------------------ forward
 
 @pytest.mark.parametrize("name", SINGLE)
