@@ -371,11 +371,11 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         hipError_t es = radix_sort(g.sort, n, bits, st, &ks, &vs);
         if (es != hipSuccess) return hip_fail(es, "grouping sort");
         hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
-        GrpCacheWork cw{ks, vs, g.crange, g.end, g.part, grad_cache, cd.K ? cdiv(cdiv(L, GT), NWAVE) : 0};
+        GrpCacheWork cw{ks, vs, g.crange, g.end, g.part, grad_cache, cd.K ? cdiv(cdiv(L, GT), NWAVE) : 0, clear_gc};
         cache_merged = cd.K && fast_bwd_takes_cache_work(p, (int)L);     // the owner kernels do the cached rows as well
         if (cd.K && !cache_merged) {
             hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
-                               (int)n_bags, alpha, grad_output, grad_cache, g.part);
+                               (int)n_bags, alpha, grad_output, grad_cache, g.part, clear_gc);
             hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, g.crange, g.end, g.part,
                                grad_cache);
         }

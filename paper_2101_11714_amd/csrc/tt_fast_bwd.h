@@ -160,12 +160,14 @@ __device__ __forceinline__ void fb_load_rows(const int64_t *__restrict__ indices
         rowv[it] = ok ? (uint32_t)indices[k] : FB_NONE;
     }
     if (slot) {
+        int32_t sl[FB_ITER];                                    // all loads first: a load behind a condition is waited for there
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
-            const int k = wlo + it * WAVE + lane;
-            const bool ok = (it * WAVE < span) && (k < hi);
-            if (ok && slot[k] >= 0) rowv[it] = FB_NONE;
+            sl[it] = slot[max(min(wlo + it * WAVE + lane, hi - 1), 0)];   // clamped, not conditional
         }
+#pragma unroll
+        for (int it = 0; it < FB_ITER; ++it)
+            if (sl[it] >= 0) rowv[it] = FB_NONE;                  // a position past hi already has FB_NONE
     }
 }
 
@@ -951,10 +953,16 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         int pw[NWAVE] = {0, 0, 0, 0}, pn = 0;                              // the list to process in this turn, if any
         if (gvals) {
             pn = hi - lo;
-            for (int i = t; i < pn; i += WG) {
-                const uint32_t k = gvals[lo + i] - sub;
-                lds.klist[i] = k;
-                lds.rows[i] = (uint32_t)indices[k];
+            {   // two round trips for the whole list: all payloads, then all rows (clamped indices: no load is conditional)
+                constexpr int NL = FB_CAP / WG;
+                uint32_t kk[NL], rr[NL];
+#pragma unroll
+                for (int q = 0; q < NL; ++q) kk[q] = gvals[lo + min(q * WG + t, pn - 1)] - sub;
+#pragma unroll
+                for (int q = 0; q < NL; ++q) rr[q] = (uint32_t)indices[kk[q]];
+#pragma unroll
+                for (int q = 0; q < NL; ++q)
+                    if (q * WG + t < pn) { lds.klist[q * WG + t] = kk[q]; lds.rows[q * WG + t] = rr[q]; }
             }
             __syncthreads();
             pw[0] = pn;                                                    // one contiguous list
@@ -1125,7 +1133,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
     if constexpr (FbCfg<C>::MFMA) {
         if (sp.cw.blocks && (int)blockIdx.x >= sp.n_owner) {             // uniform: this workgroup sums cached-row gradients
             grp_cache_tile_body<(C::N + 63) / 64>(p, (int)blockIdx.x - sp.n_owner, sp.cw.ks, sp.cw.vs, sp.cw.crange, offsets, n_bags, alpha,
-                                grad_out, sp.cw.grad_cache, sp.cw.part);
+                                grad_out, sp.cw.grad_cache, sp.cw.part, sp.cw.fresh);
             return;
         }
         // Role, slice and part of this workgroup (see FbSplit); with sp.pbuf there are no G1 owners here (the G2
@@ -1184,6 +1192,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 
 // Sums the partial slice gradients of the split roles (FbSplit) and finishes their slices: adds the sum to dG
 // (out == nullptr) or writes x - lr * sum to out.  One thread per float4 of the split cores, all of them in one launch.
+constexpr int FB_MAX_PARTS = 8;                             // workgroups that may share one slice
 struct FbFinish {
     const float *part[4], *x[4];
     float *dG[4], *out[4];
@@ -1199,19 +1208,21 @@ __global__ __launch_bounds__(WG) void bwd_split_finish_kernel(FbFinish a, float 
         const int64_t j = i - (r ? a.end4[r - 1] : 0);
         const int64_t sl = j / a.slice4[r], e = j - sl * a.slice4[r];
         const float4 *src = reinterpret_cast<const float4 *>(a.part[r]) + sl * a.ns[r] * a.slice4[r] + e;
-        float4 sum = src[0];
-        for (int h = 1; h < a.ns[r]; ++h) {
-            const float4 v = src[(int64_t)h * a.slice4[r]];
-            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-        }
+        // all parts and the old value are loaded together (at most FB_MAX_PARTS parts; a part past the last repeats it)
+        const int ns = a.ns[r];
+        float4 v[FB_MAX_PARTS];
+#pragma unroll
+        for (int h = 0; h < FB_MAX_PARTS; ++h) v[h] = src[(int64_t)min(h, ns - 1) * a.slice4[r]];
+        const float4 x = a.out[r] ? reinterpret_cast<const float4 *>(a.x[r])[j] : reinterpret_cast<const float4 *>(a.dG[r])[j];
+        float4 sum = v[0];
+#pragma unroll
+        for (int h = 1; h < FB_MAX_PARTS; ++h)
+            if (h < ns) { sum.x += v[h].x; sum.y += v[h].y; sum.z += v[h].z; sum.w += v[h].w; }
         if (a.out[r]) {
-            const float4 x = reinterpret_cast<const float4 *>(a.x[r])[j];
             reinterpret_cast<float4 *>(a.out[r])[j] =
                 make_float4(fmaf(-lr, sum.x, x.x), fmaf(-lr, sum.y, x.y), fmaf(-lr, sum.z, x.z), fmaf(-lr, sum.w, x.w));
         } else {
-            float4 *d = reinterpret_cast<float4 *>(a.dG[r]) + j;
-            const float4 g = *d;
-            *d = make_float4(g.x + sum.x, g.y + sum.y, g.z + sum.z, g.w + sum.w);
+            reinterpret_cast<float4 *>(a.dG[r])[j] = make_float4(x.x + sum.x, x.y + sum.y, x.z + sum.z, x.w + sum.w);
         }
     }
 }
@@ -1233,7 +1244,7 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
         grp_cache_fix_body<(C::N + 63) / 64>(p, (int)blockIdx.x - p.m1, cw.ks, cw.crange, cw.gend, cw.part, cw.grad_cache);
         return;
     }
-    constexpr int PA = C::sA / 4, NG = WG / PA, UN = 4;
+    constexpr int PA = C::sA / 4, NG = WG / PA, UN = 16;                  // UN rows of P in flight per thread: a slice's list is one or two passes
     constexpr int ITER = 32, PER = ITER * WAVE;                           // candidates per lane / per wave and round
     __shared__ uint32_t list[NWAVE][PER];
     __shared__ int wcnt[NWAVE];
@@ -1265,8 +1276,12 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
                     take[it] = ok && i1 == s && !(slot && slot[c] >= 0);
                 }
             }
+            // (index 0 for the candidates that are out already: a load behind a condition would be waited for on the spot)
+            int pf[8];
 #pragma unroll
-            for (int it = 0; it < 8; ++it) take[it] = take[it] && pflag[kk[it]] != 0;
+            for (int it = 0; it < 8; ++it) pf[it] = pflag[take[it] ? kk[it] : 0u];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) take[it] = take[it] && pf[it] != 0;
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
                 const uint64_t m = __ballot(take[it]);
@@ -1283,16 +1298,16 @@ __global__ __launch_bounds__(WG) void g1_from_p_kernel(Params p, const int64_t *
             float4 v[UN];
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
-                const int j = j0 + u * NG;
+                const int j = min(j0 + u * NG, total - 1);                // past the end: the last row again, not added
                 int e = j, ww = 0;
 #pragma unroll
                 for (int x = 0; x + 1 < NWAVE; ++x)
                     if (e >= wc[x] && ww == x) { e -= wc[x]; ww = x + 1; }
-                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (j < total) v[u] = p4[(size_t)list[ww][e] * PA + f];
+                v[u] = p4[(size_t)list[ww][e] * PA + f];
             }
 #pragma unroll
-            for (int u = 0; u < UN; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+            for (int u = 0; u < UN; ++u)
+                if (j0 + u * NG < total) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
         }
         __syncthreads();                                                  // before the lists are reused
     }
@@ -1416,7 +1431,7 @@ static inline void launch_bwd(const Params &p, const float *G1, const float *G2,
     // the caller's cached-row work rides along (fast_bwd_takes_cache_work): tiles behind the owners, the runs that cross
     // tiles behind g1_from_p_kernel's workgroups, the SGD step of the cache lines in the finishing kernel
     const bool with_cw = cw != nullptr && cw->blocks > 0;
-    sp.cw = GrpCacheWork{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    sp.cw = GrpCacheWork{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, false};
     sp.n_owner = grid;
     if (with_cw) {
         sp.cw = *cw;

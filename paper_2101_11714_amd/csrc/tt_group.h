@@ -121,7 +121,7 @@ __device__ __forceinline__ void grp_cache_tile_body(const Params &p, int block, 
                                                     const uint32_t *__restrict__ vs, const int *__restrict__ crange,
                                                     const int64_t *__restrict__ offsets, int n_bags,
                                                     const float *__restrict__ alpha, const float *__restrict__ grad_out,
-                                                    float *__restrict__ grad_cache, float *__restrict__ part)
+                                                    float *__restrict__ grad_cache, float *__restrict__ part, bool fresh)
 {
     static_assert(GT == WAVE, "one item per lane");
     const int N = p.N, nb3 = p.m1 + p.m2 + p.m3;
@@ -156,10 +156,18 @@ __device__ __forceinline__ void grp_cache_tile_body(const Params &p, int block, 
             for (int c = 0; c < MAXC; ++c)
                 if (lane + 64 * c < N) dst[lane + 64 * c] = sum[c];
         } else {
+            // a run inside the tile is all there is for its slot: where the caller has just cleared the gradient
+            // (`fresh`) it is stored, not added, and the waves do not wait for a load per run
             float *dst = grad_cache + (size_t)(key - nb3) * N;
+            if (fresh) {
 #pragma unroll
-            for (int c = 0; c < MAXC; ++c)
-                if (lane + 64 * c < N) dst[lane + 64 * c] += sum[c];
+                for (int c = 0; c < MAXC; ++c)
+                    if (lane + 64 * c < N) dst[lane + 64 * c] = sum[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < MAXC; ++c)
+                    if (lane + 64 * c < N) dst[lane + 64 * c] += sum[c];
+            }
         }
         first = false;
 #pragma unroll
@@ -196,9 +204,9 @@ __global__ __launch_bounds__(WG) void grp_cache_tile_kernel(Params p, const uint
                                                             const int64_t *__restrict__ offsets, int n_bags,
                                                             const float *__restrict__ alpha,
                                                             const float *__restrict__ grad_out,
-                                                            float *__restrict__ grad_cache, float *__restrict__ part)
+                                                            float *__restrict__ grad_cache, float *__restrict__ part, bool fresh)
 {
-    grp_cache_tile_body<4>(p, blockIdx.x, ks, vs, crange, offsets, n_bags, alpha, grad_out, grad_cache, part);   // N <= 256
+    grp_cache_tile_body<4>(p, blockIdx.x, ks, vs, crange, offsets, n_bags, alpha, grad_out, grad_cache, part, fresh);   // N <= 256
 }
 
 // A run that crosses tile borders is finished where it begins.  Wave w of a workgroup looks at tile
@@ -225,9 +233,11 @@ __device__ __forceinline__ void grp_cache_fix_body(const Params &p, int block, c
         int key = -1, last_tile = 0;
         bool own = false;
         if (i0 < ce && i1 < ce) {                                  // else no tile here, or nothing to its right
-            key = (int)ks[i1 - 1];
-            own = (int)ks[i1] == key;                              // the last run goes on in the next tile
-            if (own && (int)ks[i0] == key && i0 > cb && (int)ks[i0 - 1] == key) own = false;   // it begins elsewhere
+            // the four keys that decide are loaded together (one round trip, not one per condition)
+            const int kl = (int)ks[i1 - 1], kn = (int)ks[i1], kf = (int)ks[i0], kb = (int)ks[max(i0 - 1, cb)];
+            key = kl;
+            own = kn == key;                                       // the last run goes on in the next tile
+            if (own && kf == key && i0 > cb && kb == key) own = false;                         // it begins elsewhere
             if (own) last_tile = (gend[key] - 1 - cb) / GT;        // tile that holds the run's last item
         }
         const bool is_long = own && last_tile - tile > SHORT;
@@ -312,6 +322,7 @@ struct GrpCacheWork {
     const int *crange, *gend;
     float *part, *grad_cache;
     int blocks;                                  // 0: nothing to do
+    bool fresh;                                  // grad_cache was cleared for this call (else the sums are added to it)
 };
 
 }  // namespace tt
