@@ -90,6 +90,9 @@ def main():
                     help="csr: bags given by an offsets array; none: the boundary's form for one index per bag "
                          "(offsets == NULL), for the workloads whose bags all hold one index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-call", action="store_true",
+                    help="fused step: the backward in one call on the step's stream, also where it has an index-only pre-pass "
+                         "(by default that runs on a second stream next to the forward pass)")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the steps are captured once in a HIP graph of POOL steps and replayed; "
                          "stream: every kernel is launched from Python")
@@ -166,13 +169,25 @@ def main():
 
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
+    # The index-only pre-pass of the backward (cache probe, grouping sort of long lists) runs on a second stream next to
+    # the forward pass of the same batch where there is one; the graph keeps the fork and the join.
+    two_calls = args.step == "fused" and not args.one_call and B.bwd_has_prepass(shape, max(Ls), K, keep_t0)
+    side = torch.cuda.Stream() if two_calls else None
+
     def step(i):
         j = i % POOL
         if args.step == "fused":
             cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
+            if two_calls:
+                main = torch.cuda.current_stream()
+                side.wait_stream(main)
+                with torch.cuda.stream(side):
+                    B.tt_emb_bwd_prepare(shape, idx[j], off[j], n_bags, cache=cache, workspace=ws, kept_t0=keep_t0)
             fwd_call(cur, j)
+            if two_calls:
+                torch.cuda.current_stream().wait_stream(side)
             B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
-                             workspace=ws, t0=t0_pool[j] if keep_t0 else None)
+                             workspace=ws, t0=t0_pool[j] if keep_t0 else None, prepared=two_calls)
         else:
             B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
             B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads, alpha=alpha[j], cache=cache,
@@ -293,7 +308,8 @@ def main():
                                                                 ", cache of %d rows" % K if K else "",
                                                                 ", weights: %s" % args.weights if args.weights != "none" else ""),
                    "table": tab,
-                   "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0), "wall_s_timed_region": round(wall, 3)},
+                   "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0),
+                   "prepass_on_second_stream": bool(two_calls), "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

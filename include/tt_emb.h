@@ -230,6 +230,31 @@ int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *
                    const float *grad_output, float lr,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The fused step in two calls.  Part of the backward pass of Alg. 2 depends on the
+ * indices and the cache's row map alone: which positions are cached (Section 4.2) and,
+ * for long index lists, the grouping of the positions by the core slices they touch.
+ * tt_emb_bwd_prepare runs that part into the workspace; tt_emb_bwd_sgd_prepared then
+ * does the rest and gives the result of tt_emb_bwd_sgd (t0 == NULL) or
+ * tt_emb_bwd_sgd_t0 (t0 != NULL), bit for bit.  A caller can enqueue the first call on
+ * another stream next to the forward pass of the same batch (it reads neither the cores
+ * nor the cache rows) and make the second wait for it.
+ * Both calls take the same shape, indices, L, offsets, n_bags, cache and workspace;
+ * kept_t0 != 0 says that the second call will pass a t0.  The workspace must not be
+ * used by anything else between the two calls, and one prepare serves one step.
+ * For a short list without a cache the first call has nothing to do and enqueues nothing.
+ */
+int tt_emb_bwd_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                       const int64_t *offsets, int64_t n_bags, const tt_cache_t *cache, int kept_t0,
+                       void *workspace, size_t workspace_bytes, void *stream);
+/* 1 if tt_emb_bwd_prepare enqueues work for such a call (worth a stream of its own), else 0. */
+int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0);
+int tt_emb_bwd_sgd_prepared(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                            const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                            const float *alpha, const tt_cache_t *cache,
+                            const float *grad_output, const float *t0, float lr,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Always-sufficient workspace size of tt_emb_bwd_sgd; 0 for an invalid shape. */
 size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows);
 

@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0",
+           "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -74,6 +74,9 @@ def lib():
         l.tt_emb_bwd_t0.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd_sgd_t0.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_bwd_sgd.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_prepare.argtypes = [vp, vp, i64, vp, i64, vp, C.c_int, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_has_prepass.argtypes = [vp, i64, i64, C.c_int]
+        l.tt_emb_bwd_sgd_prepared.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
         l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
         l.tt_cache_lookup.argtypes = [vp, vp, i64, vp, vp]
@@ -233,10 +236,25 @@ def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
                             _ptr(grad_cache), _ptr(workspace), wsb, _stream()))
 
 
+def bwd_has_prepass(shape: TTShape, L: int, cache_rows: int = 0, kept_t0: bool = False) -> bool:
+    return bool(lib().tt_emb_bwd_has_prepass(C.byref(shape), L, cache_rows, int(kept_t0)))
+
+
+def tt_emb_bwd_prepare(shape: TTShape, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,
+                       cache: Optional[Cache] = None, workspace: Optional[torch.Tensor] = None,
+                       kept_t0: bool = False) -> None:
+    """The index-only part of the fused step, on the current stream; tt_emb_bwd_sgd(..., prepared=True) does the rest."""
+    _dev(indices, torch.int64)
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_bwd_prepare(C.byref(shape), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                                    cache.ref() if cache else None, int(kept_t0), _ptr(workspace), wsb, _stream()))
+
+
 def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],
                    indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
                    lr: float, alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None,
-                   workspace: Optional[torch.Tensor] = None, t0: Optional[torch.Tensor] = None) -> None:
+                   workspace: Optional[torch.Tensor] = None, t0: Optional[torch.Tensor] = None,
+                   prepared: bool = False) -> None:
     _dev(indices, torch.int64)
     if offsets is not None:
         _dev(offsets, torch.int64)
@@ -247,6 +265,14 @@ def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Seq
     for k in range(3):
         assert cores_out[k].numel() == cores[k].numel()
     wsb = workspace.numel() if workspace is not None else 0
+    if prepared:
+        if t0 is not None:
+            _dev(t0, torch.float32)
+        _check(lib().tt_emb_bwd_sgd_prepared(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices),
+                                             indices.numel(), _ptr(offsets), n_bags, _ptr(alpha),
+                                             cache.ref() if cache else None, _ptr(grad_output), _ptr(t0), C.c_float(lr),
+                                             _ptr(workspace), wsb, _stream()))
+        return
     if t0 is not None:
         _dev(t0, torch.float32)
         _check(lib().tt_emb_bwd_sgd_t0(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices),

@@ -260,6 +260,8 @@ int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
     return fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, t0, true, stream);
 }
 
+enum BwdPhase { BWD_ALL, BWD_PREPARE, BWD_REST };
+
 // Backward pass behind tt_emb_bwd (cores_out == nullptr: gradients are added to grad_cores /
 // grad_cache) and tt_emb_bwd_sgd (cores_out != nullptr: the cores after the SGD step are written
 // to cores_out, the cached rows are updated in place; grad_cores / grad_cache are unused).
@@ -267,29 +269,34 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                       const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
                       const float *alpha, const tt_cache_t *cache, const float *grad_output,
                       float *const grad_cores[3], float *grad_cache, float lr, float *const cores_out[3],
-                      const float *t0, void *workspace, size_t workspace_bytes, void *stream)
+                      const float *t0, void *workspace, size_t workspace_bytes, void *stream, BwdPhase phase = BWD_ALL)
 {
-    const bool fused = cores_out != nullptr;
+    // BWD_PREPARE (fused step only): the part that needs the indices and the cache's row map alone, into the
+    // workspace; t0 != nullptr then only says that the later call will bring a kept T0.  BWD_REST: everything else.
+    const bool prep = phase == BWD_PREPARE;
+    const bool fused = cores_out != nullptr || prep;
     Params p;
     int rc = check_shape(shape, &p);
     if (rc) return rc;
     if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
-    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
-    if (fused) {
+    if (!prep && (!cores || !cores[0] || !cores[1] || !cores[2])) return fail(TT_ERR_NULL, "cores is NULL");
+    if (prep) {
+    } else if (fused) {
         if (!cores_out[0] || !cores_out[1] || !cores_out[2]) return fail(TT_ERR_NULL, "cores_out is NULL");
         for (int k = 0; k < 3; ++k)
             if (cores_out[k] == cores[k]) return fail(TT_ERR_BAD_ARG, "cores_out must not alias cores");
     } else if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2]) {
         return fail(TT_ERR_NULL, "grad_cores is NULL");
     }
-    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (!prep && n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
     CacheDev cd;
     if ((rc = check_cache(cache, &cd, fused))) return rc;
     if (!fused && cd.K && !grad_cache) return fail(TT_ERR_NULL, "grad_cache is NULL but a cache is given");
     if (t0 && !fast_bwd_supported(p)) return fail(TT_ERR_UNSUPPORTED, "no kernel uses a kept T0 for this shape");
-    if (misaligned({cores[0], cores[1], cores[2], grad_output, t0, cd.rows, workspace}) ||
-        (fused ? misaligned({cores_out[0], cores_out[1], cores_out[2]})
-               : misaligned({grad_cores[0], grad_cores[1], grad_cores[2], grad_cache})))
+    if (prep ? misaligned({cd.rows, workspace})
+             : (misaligned({cores[0], cores[1], cores[2], grad_output, t0, cd.rows, workspace}) ||
+                (fused ? misaligned({cores_out[0], cores_out[1], cores_out[2]})
+                       : misaligned({grad_cores[0], grad_cores[1], grad_cores[2], grad_cache}))))
         return fail(TT_ERR_BAD_ARG, "cores, gradients, t0, cache rows and workspace must be 16-byte aligned");
     const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
     const bool grouped = fast && (g_fast_path == 2 || L >= (cd.K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
@@ -327,21 +334,22 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             grad_cache = (float *)q;
             q += gc_bytes;
             const int64_t n = (int64_t)cd.K * p.N;
-            if (!(grouped && L > 0))                                      // the grouping pre-pass clears it itself
+            if (!(grouped && L > 0) && phase != BWD_REST)                 // the grouping pre-pass clears it itself
                 hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, grad_cache, n, 0.f);
         }
         if (!fast) {
             for (int k = 0; k < 3; ++k) {
                 gtmp[k] = (float *)q;
                 q += g_bytes[k];
-                hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(core_floats[k], WG) < 1024 ? cdiv(core_floats[k], WG) : 1024),
-                                   dim3(WG), 0, st, gtmp[k], core_floats[k], 0.f);
+                if (phase != BWD_REST)
+                    hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(core_floats[k], WG) < 1024 ? cdiv(core_floats[k], WG) : 1024),
+                                       dim3(WG), 0, st, gtmp[k], core_floats[k], 0.f);
             }
             grad_cores = gtmp;
         }
     }
-    float *o1 = fused && fast ? cores_out[0] : nullptr, *o2 = fused && fast ? cores_out[1] : nullptr,
-          *o3 = fused && fast ? cores_out[2] : nullptr;
+    const bool outs = fused && fast && !prep;                            // (the pre-pass has no cores)
+    float *o1 = outs ? cores_out[0] : nullptr, *o2 = outs ? cores_out[1] : nullptr, *o3 = outs ? cores_out[2] : nullptr;
     float *d1 = grad_cores ? grad_cores[0] : nullptr, *d2 = grad_cores ? grad_cores[1] : nullptr,
           *d3 = grad_cores ? grad_cores[2] : nullptr;
 
@@ -353,7 +361,8 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     int32_t *slot = nullptr;
     if (cd.K && L > 0 && !grouped) {                                      // the grouping pre-pass probes the cache itself
         slot = (int32_t *)workspace;
-        hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
+        if (phase != BWD_REST)
+            hipLaunchKernelGGL(cache_lookup_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, st, cd, indices, (int)L, slot);
     }
     if (grouped && L > 0) {
         // group the positions by the slices / cache slots they touch, then run the owners on their lists
@@ -362,15 +371,24 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         const int n = 3 * (int)L;
         const int64_t kthreads = L > nbins + 1 ? L : nbins + 1;
         const bool clear_gc = fused && cd.K;                                // N is a multiple of 4 for these shapes
-        hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(kthreads, WG)), dim3(WG), 0, st, p, indices, (int)L, cd, g.sort.k0, g.off,
-                           g.end, nbins, g.crange, clear_gc ? (float4 *)grad_cache : nullptr,
-                           clear_gc ? (int64_t)cd.K * p.N / 4 : (int64_t)0);
         int bits = 1;
         while ((1 << bits) <= nbins) ++bits;
         uint64_t *ks; uint32_t *vs;
-        hipError_t es = radix_sort(g.sort, n, bits, st, &ks, &vs);
-        if (es != hipSuccess) return hip_fail(es, "grouping sort");
-        hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
+        radix_sort_result(g.sort, bits, &ks, &vs);
+        if (phase != BWD_REST) {
+            hipLaunchKernelGGL(grp_keys_kernel, dim3(cdiv(kthreads, WG)), dim3(WG), 0, st, p, indices, (int)L, cd, g.sort.k0, g.off,
+                               g.end, nbins, g.crange, clear_gc ? (float4 *)grad_cache : nullptr,
+                               clear_gc ? (int64_t)cd.K * p.N / 4 : (int64_t)0);
+            uint64_t *ks2; uint32_t *vs2;
+            hipError_t es = radix_sort(g.sort, n, bits, st, &ks2, &vs2);
+            if (es != hipSuccess) return hip_fail(es, "grouping sort");
+            if (ks2 != ks || vs2 != vs) return fail(TT_ERR_BAD_ARG, "internal: the sort's result is not where it was expected");
+            hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
+        }
+        if (prep) {
+            hipError_t e = hipGetLastError();
+            return e == hipSuccess ? TT_OK : hip_fail(e, "backward pre-pass launch");
+        }
         GrpCacheWork cw{ks, vs, g.crange, g.end, g.part, grad_cache, cd.K ? cdiv(cdiv(L, GT), NWAVE) : 0, clear_gc};
         cache_merged = cd.K && fast_bwd_takes_cache_work(p, (int)L);     // the owner kernels do the cached rows as well
         if (cd.K && !cache_merged) {
@@ -383,6 +401,10 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                  d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, split_ws, cache_merged ? &cw : nullptr,
                  fused && cache_merged ? cache->rows : nullptr, (int64_t)cd.K * p.N, st);
     } else {
+        if (prep) {
+            hipError_t e = hipGetLastError();
+            return e == hipSuccess ? TT_OK : hip_fail(e, "backward pre-pass launch");
+        }
         if (cd.K && L > 0)
             hipLaunchKernelGGL(bwd_cache_kernel, dim3(cdiv(cd.K, G)), dim3(WG), lds_cache, st, p.N, cd.K, G, slot, (int)L,
                                offsets, (int)n_bags, alpha, grad_output, grad_cache);
@@ -454,6 +476,34 @@ int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], floa
     if (L > 0 && !t0) return fail(TT_ERR_NULL, "t0 is NULL");
     return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
                       lr, cores_out, t0, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_bwd_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                       const tt_cache_t *cache, int kept_t0, void *workspace, size_t workspace_bytes, void *stream)
+{
+    static const float marker = 0.f;                       // stands for "a kept T0 will be given": never dereferenced
+    return bwd_common(shape, nullptr, indices, L, offsets, n_bags, nullptr, cache, nullptr, nullptr, nullptr, 0.f,
+                      nullptr, kept_t0 ? &marker : nullptr, workspace, workspace_bytes, stream, BWD_PREPARE);
+}
+
+int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L <= 0 || cache_rows < 0) return 0;
+    const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
+    const bool grouped = fast && (g_fast_path == 2 || L >= (cache_rows ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+    return cache_rows > 0 || grouped;
+}
+
+int tt_emb_bwd_sgd_prepared(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                            const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                            const float *alpha, const tt_cache_t *cache,
+                            const float *grad_output, const float *t0, float lr,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
+    return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
+                      lr, cores_out, t0, workspace, workspace_bytes, stream, BWD_REST);
 }
 
 size_t tt_emb_bwd_sgd_workspace_bytes(const tt_shape_t *shape, int64_t L, int64_t n_bags, int64_t cache_rows)

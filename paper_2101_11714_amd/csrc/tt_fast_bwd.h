@@ -160,14 +160,20 @@ __device__ __forceinline__ void fb_load_rows(const int64_t *__restrict__ indices
         rowv[it] = ok ? (uint32_t)indices[k] : FB_NONE;
     }
     if (slot) {
-        int32_t sl[FB_ITER];                                    // all loads first: a load behind a condition is waited for there
+        // all loads first: the compiler would test each value where it is loaded, one round trip per value
+        // (the empty asm statements keep the eight loads ahead of the eight tests)
+        int32_t sl[FB_ITER];
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
-            sl[it] = slot[max(min(wlo + it * WAVE + lane, hi - 1), 0)];   // clamped, not conditional
+            const int k = wlo + it * WAVE + lane;
+            const bool ok = (it * WAVE < span) && (k < hi);
+            sl[it] = ok ? slot[k] : -1;
         }
 #pragma unroll
+        for (int it = 0; it < FB_ITER; ++it) asm volatile("" : "+v"(sl[it]));
+#pragma unroll
         for (int it = 0; it < FB_ITER; ++it)
-            if (sl[it] >= 0) rowv[it] = FB_NONE;                  // a position past hi already has FB_NONE
+            if (sl[it] >= 0) rowv[it] = FB_NONE;
     }
 }
 
@@ -1205,24 +1211,32 @@ __global__ __launch_bounds__(WG) void bwd_split_finish_kernel(FbFinish a, float 
 {
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < a.end4[a.n - 1]; i += (int64_t)gridDim.x * WG) {
         const int r = (i >= a.end4[0]) + (i >= a.end4[1]) + (i >= a.end4[2]);
-        const int64_t j = i - (r ? a.end4[r - 1] : 0);
-        const int64_t sl = j / a.slice4[r], e = j - sl * a.slice4[r];
-        const float4 *src = reinterpret_cast<const float4 *>(a.part[r]) + sl * a.ns[r] * a.slice4[r] + e;
-        // all parts and the old value are loaded together (at most FB_MAX_PARTS parts; a part past the last repeats it)
-        const int ns = a.ns[r];
-        float4 v[FB_MAX_PARTS];
+        // One copy of the body per array, so that its descriptor sits in scalar registers: an argument array indexed
+        // by a run-time number is read from memory, one more round trip before the first useful load.
 #pragma unroll
-        for (int h = 0; h < FB_MAX_PARTS; ++h) v[h] = src[(int64_t)min(h, ns - 1) * a.slice4[r]];
-        const float4 x = a.out[r] ? reinterpret_cast<const float4 *>(a.x[r])[j] : reinterpret_cast<const float4 *>(a.dG[r])[j];
-        float4 sum = v[0];
+        for (int rr = 0; rr < 4; ++rr) {
+            if (r != rr) continue;
+            const int ns = a.ns[rr], slice4 = a.slice4[rr];
+            float *out = a.out[rr];
+            const int64_t j = i - (rr ? a.end4[rr ? rr - 1 : 0] : 0);
+            const int64_t sl = j / slice4, e = j - sl * slice4;
+            const float4 *src = reinterpret_cast<const float4 *>(a.part[rr]) + sl * ns * slice4 + e;
+            // the old value and all parts (at most FB_MAX_PARTS) are loaded together
+            const float4 x = reinterpret_cast<const float4 *>(out ? a.x[rr] : a.dG[rr])[j];
+            float4 v[FB_MAX_PARTS];
 #pragma unroll
-        for (int h = 1; h < FB_MAX_PARTS; ++h)
-            if (h < ns) { sum.x += v[h].x; sum.y += v[h].y; sum.z += v[h].z; sum.w += v[h].w; }
-        if (a.out[r]) {
-            reinterpret_cast<float4 *>(a.out[r])[j] =
-                make_float4(fmaf(-lr, sum.x, x.x), fmaf(-lr, sum.y, x.y), fmaf(-lr, sum.z, x.z), fmaf(-lr, sum.w, x.w));
-        } else {
-            reinterpret_cast<float4 *>(a.dG[r])[j] = make_float4(x.x + sum.x, x.y + sum.y, x.z + sum.z, x.w + sum.w);
+            for (int h = 0; h < FB_MAX_PARTS; ++h)
+                v[h] = h < ns ? src[(int64_t)h * slice4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 sum = v[0];
+#pragma unroll
+            for (int h = 1; h < FB_MAX_PARTS; ++h)
+                if (h < ns) { sum.x += v[h].x; sum.y += v[h].y; sum.z += v[h].z; sum.w += v[h].w; }
+            if (out) {
+                reinterpret_cast<float4 *>(out)[j] =
+                    make_float4(fmaf(-lr, sum.x, x.x), fmaf(-lr, sum.y, x.y), fmaf(-lr, sum.z, x.z), fmaf(-lr, sum.w, x.w));
+            } else {
+                reinterpret_cast<float4 *>(a.dG[rr])[j] = make_float4(x.x + sum.x, x.y + sum.y, x.z + sum.z, x.w + sum.w);
+            }
         }
     }
 }

@@ -362,6 +362,16 @@ static inline SortWs sort_ws_layout(void *ws, int64_t n)
     return s;
 }
 
+// The buffers that hold the result of radix_sort(s, n, bits, ...): they depend on the number of passes only.
+static inline void radix_sort_result(const SortWs &s, int bits, uint64_t **kres, uint32_t **vres)
+{
+    const int npass = (bits + 7) / 8;
+    const int db = (bits + npass - 1) / npass;
+    const int count = (bits + db - 1) / db;                // passes that run
+    *kres = count % 2 ? s.k1 : s.k0;
+    *vres = count == 0 ? nullptr : (count % 2 ? s.v0 : s.v1);
+}
+
 // Sort keys in s.k0 (payload = original position) by their low `bits` bits.
 // Returns the buffers that hold the result in *kres / *vres.
 static inline hipError_t radix_sort(const SortWs &s, int n, int bits, hipStream_t st,

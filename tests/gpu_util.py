@@ -86,13 +86,21 @@ class DeviceTable:
         torch.cuda.synchronize()
         return grad_cores, grad_cache
 
-    def bwd_sgd(self, lr, cache=None, use_offsets=True, t0=None):
-        """Fused backward + SGD: returns the new cores (the cache lines are updated in place)."""
+    def bwd_sgd(self, lr, cache=None, use_offsets=True, t0=None, two_calls=False):
+        """Fused backward + SGD: returns the new cores (the cache lines are updated in place).
+        two_calls: the index-only pre-pass on a stream of its own, then the rest on the current stream."""
         out = [torch.full_like(x, float("nan")) for x in self.g]
         ws = torch.empty(B.bwd_sgd_workspace_bytes(self.shape, self.L, self.n_bags, cache.K if cache is not None else 0),
                          dtype=torch.uint8, device=dev())
-        B.tt_emb_bwd_sgd(self.shape, self.g, out, self.idx, self.off if use_offsets else None, self.n_bags, self.go,
-                         lr, alpha=self.alpha, cache=cache, workspace=ws, t0=t0)
+        off = self.off if use_offsets else None
+        if two_calls:
+            side, main = torch.cuda.Stream(), torch.cuda.current_stream()
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                B.tt_emb_bwd_prepare(self.shape, self.idx, off, self.n_bags, cache=cache, workspace=ws, kept_t0=t0 is not None)
+            main.wait_stream(side)
+        B.tt_emb_bwd_sgd(self.shape, self.g, out, self.idx, off, self.n_bags, self.go,
+                         lr, alpha=self.alpha, cache=cache, workspace=ws, t0=t0, prepared=two_calls)
         torch.cuda.synchronize()
         return out
 

@@ -113,6 +113,29 @@ def test_null_and_bad_arguments():
     assert l.tt_emb_debug_dedup(C.byref(s), one, 5, None, 7, one, one, one, one, one, 1 << 20, None) == -3
 
 
+def test_two_call_fused_step_checks_its_arguments():
+    """tt_emb_bwd_prepare / tt_emb_bwd_sgd_prepared refuse bad arguments before anything is enqueued."""
+    l = B.lib()
+    arr = (C.c_void_p * 3)(16, 16, 16)
+    out = (C.c_void_p * 3)(32, 32, 32)
+    one = C.c_void_p(16)
+    small = B.make_shape(10_131_227, (200, 220, 250), (2, 2, 4), (1, 32, 32, 1))
+    bad = B.make_shape(10, (1, 2, 3), (2, 2, 4), (1, 32, 32, 1))
+    f = C.c_float(0.1)
+    assert l.tt_emb_bwd_prepare(C.byref(bad), one, 1, None, 1, None, 0, None, 0, None) == -2
+    assert l.tt_emb_bwd_prepare(C.byref(small), None, 1, None, 1, None, 0, None, 0, None) == -1
+    assert l.tt_emb_bwd_prepare(C.byref(small), one, -1, None, 1, None, 0, None, 0, None) == -3
+    # a long list needs the workspace in both calls
+    L = 40000
+    assert l.tt_emb_bwd_prepare(C.byref(small), one, L, None, L, None, 1, None, 0, None) == -4
+    assert l.tt_emb_bwd_prepare(C.byref(small), one, L, None, L, None, 1, one, 1024, None) == -4
+    assert l.tt_emb_bwd_prepare(C.byref(small), one, L, None, L, None, 1, C.c_void_p(8), 1 << 30, None) == -3
+    assert l.tt_emb_bwd_sgd_prepared(C.byref(small), arr, out, one, L, None, L, None, None, one, one, f, None, 0, None) == -4
+    assert l.tt_emb_bwd_sgd_prepared(C.byref(small), arr, None, one, 1, None, 1, None, None, one, None, f, None, 0, None) == -1
+    assert l.tt_emb_bwd_sgd_prepared(C.byref(small), arr, arr, one, 1, None, 1, None, None, one, None, f, None, 0, None) == -3
+    assert l.tt_emb_bwd_sgd_prepared(C.byref(small), arr, out, one, 1, None, 1, None, None, None, None, f, None, 0, None) == -1
+
+
 def test_workspace_rules_of_the_backward():
     """Which calls need a workspace, and that a missing or short one is refused before anything is enqueued."""
     l = B.lib()

@@ -302,6 +302,37 @@ def test_fused_with_cache(name, table, path):
     assert_close(cache.rows.cpu().numpy()[:K], ora.sgd(crow, rc, wl.lr), "%s fused cache lines" % name)
 
 
+@pytest.mark.parametrize("name,table,with_cache", [("tiny", 0, True), ("kaggle_r32", 0, False), ("kaggle_r32", 0, True),
+                                                   ("terabyte_r64", 0, False), ("multihot_cache", 0, True),
+                                                   ("multihot_cache", 6, False)])
+@pytest.mark.parametrize("kept_t0", [False, True])
+def test_fused_step_in_two_calls_is_the_same_bit_for_bit(name, table, with_cache, kept_t0, path):
+    """tt_emb_bwd_prepare on another stream + tt_emb_bwd_sgd_prepared against the one call (itself checked against the
+    oracle above): short lists with and without a cache, grouped lists with and without one."""
+    if kept_t0 and path != 1:
+        pytest.skip("a kept T0 always takes the specialised kernels: one run is enough")
+    wl = W.WORKLOADS[name]
+    d = DeviceTable(wl, table=table)
+    cache = None
+    if with_cache:
+        if name == "multihot_cache":
+            cache, _, _ = d.build_cache(W.cache_size(wl, table))
+        else:
+            rows, counts = np.unique(d.batch.indices, return_counts=True)
+            cache, _, _ = d.build_cache(20 if name == "tiny" else 300, rows.astype(np.int64), counts.astype(np.int64))
+    t0 = d.fwd_keep_t0(cache)[1] if kept_t0 else None
+    lines = cache.rows.clone() if cache is not None else None
+    one = d.bwd_sgd(wl.lr, cache=cache, t0=t0)
+    if cache is not None:
+        lines_one = cache.rows.clone()
+        cache.rows.copy_(lines)
+    two = d.bwd_sgd(wl.lr, cache=cache, t0=t0, two_calls=True)
+    for k in range(3):
+        assert torch.equal(one[k], two[k]), "core %d" % (k + 1)
+    if cache is not None:
+        assert torch.equal(lines_one, cache.rows), "cache lines"
+
+
 # ------------------------------------------------------------------ cache
 
 def test_cache_on_tiny(path):
