@@ -664,6 +664,51 @@ def test_444_shapes_shared_slices_and_matrix_cores(R, n_bags, with_cache, path):
         assert_close(cache.rows.cpu().numpy()[:K], crows.astype(np.float64) - lr * rc, "fused cache lines")
 
 
+@pytest.mark.parametrize("n,R,n_bags", [((2, 2, 4), 8, 3000), ((4, 4, 4), 32, 500)])
+@pytest.mark.parametrize("with_cache", [False, True])
+def test_very_long_lists(n, R, n_bags, with_cache):
+    """Bags of 120 positions on a small table, so that every row occurs many times and every owner walks its list in
+    many pieces of 512 entries.  360,000 positions of the (2,2,4) shape: 3 L items are more than 512 tiles of the
+    grouping sort (its scan-kernel form) and eight workgroups share a slice; 60,000 of the (4,4,4) shape (the
+    oracle takes seconds per pass there)."""
+    import dataclasses
+    t = W.TableShape(12 * 11 * 13, (12, 11, 13), n, (1, R, R, 1))
+    wl = dataclasses.replace(W.WORKLOADS["tiny"], tables=(t,), name="long")
+    rng = np.random.default_rng(77 + R)
+    lens = np.full(n_bags, 120, dtype=np.int64)
+    lens[5] = 7
+    lens[6] = 233
+    off = np.zeros(n_bags + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    L = int(off[-1])
+    assert n_bags < 3000 or 3 * L > 2048 * 512
+    idx = rng.integers(0, t.num_rows, L)
+    idx[rng.random(L) < 0.05] = 777
+    batch = W.Batch(idx, off, rng.standard_normal((n_bags, t.dim)).astype(np.float32), (0.5 + rng.random(L)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    cache, keys, K = None, None, 0
+    if with_cache:
+        rows, counts = np.unique(idx, return_counts=True)
+        K = 50
+        cache, _, _ = d.build_cache(K, rows.astype(np.int64), counts.astype(np.int64))
+        keys = ora.cache_select(rows, counts, K)
+    crows = cache.rows.cpu().numpy()[:K].copy() if with_cache else None
+    out, t0 = d.fwd_keep_t0(cache=cache)
+    assert_close(out, ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha, cache_keys=keys, cache_rows=crows), "forward")
+    rg, rc = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha, cache_keys=keys)
+    lr = 1e-3
+    new = d.bwd_sgd(lr, cache=cache, t0=t0, two_calls=True)
+    for k in range(3):
+        assert_close((d.cores[k].astype(np.float64) - new[k].cpu().numpy()) / lr, rg[k], "gradient of core %d" % (k + 1))
+    if with_cache:
+        assert_close((crows.astype(np.float64) - cache.rows.cpu().numpy()[:K]) / lr, rc, "gradient of the cache lines")
+    dg, dc = d.bwd(cache=cache)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), rg[k], "dG%d" % (k + 1))
+    if with_cache:
+        assert_close(dc.cpu().numpy()[:K], rc, "dCache")
+
+
 # ------------------------------------------------------------------ the uncompressed comparison kernels
 
 @pytest.mark.parametrize("N,lens", [(16, (1, 1)), (16, (0, 7)), (64, (0, 30)), (256, (1, 3))])
