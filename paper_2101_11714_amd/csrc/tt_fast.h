@@ -108,6 +108,8 @@ struct ReduceKeep {
 };
 
 // ---- forward ---------------------------------------------------------------------
+constexpr int FWD_WAVE_PER_BAG = 0, FWD_WG_PER_BAG = 1, FWD_XCD_LOCAL = 2;
+constexpr int FWD_SEG = 32;                       // bags per segment of the XCD-local variant (8 workgroups, a bag per wave)
 // One wave per bag.  The wave reads the bag's positions 64 at a time and probes the cache
 // for all of them at once; cached rows are summed 64 / (N/4) at a time as float4 pieces,
 // the other positions go through the cores one after the other.  The partial products of
@@ -115,7 +117,7 @@ struct ReduceKeep {
 // and the sum of the cached rows is added to the result at the end.
 // WGBAG: a whole workgroup per bag, for long bags: its four waves take a quarter of the bag's
 // positions each and their results are added through LDS, in wave order.
-template <typename C, bool WGBAG>
+template <typename C, int MODE>
 __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__restrict__ G1,
                                                       const float *__restrict__ G2, const float *__restrict__ G3,
                                                       const int64_t *__restrict__ indices,
@@ -124,13 +126,15 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
                                                       float *__restrict__ out, float *__restrict__ t0_out)
 {
     constexpr int N1 = C::N1, N2 = C::N2, N3 = C::N3, R = C::R, V = C::V;
+    constexpr bool WGBAG = MODE == FWD_WG_PER_BAG;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int bag = WGBAG ? (int)blockIdx.x : (int)blockIdx.x * NWAVE + wv;
-    if (bag >= n_bags) return;                              // (uniform in the workgroup if WGBAG)
     const bool active = lane < C::LANES;
     const int c0 = active ? lane * V : 0;
     const int j2 = c0 / R, b0 = c0 % R;
+
+    // bounds: the bag's positions [bk0, bk1) and its first row if the caller has read them already (bk0 < 0: not)
+    auto do_bag = [&](const int bag, const int bk0, const int bk1, const uint32_t brow) __attribute__((always_inline)) {
     float acc[C::NV];
 #pragma unroll
     for (int i = 0; i < C::NV; ++i) acc[i] = 0.f;
@@ -177,8 +181,8 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
         }
     };
 
-    int k0 = offsets ? (int)offsets[bag] : bag;
-    int k1 = offsets ? (int)offsets[bag + 1] : bag + 1;
+    int k0 = bk0 >= 0 ? bk0 : (offsets ? (int)offsets[bag] : bag);
+    int k1 = bk0 >= 0 ? bk1 : (offsets ? (int)offsets[bag + 1] : bag + 1);
     if (WGBAG) {                                            // this wave's quarter of the bag
         const int per = (k1 - k0 + NWAVE - 1) / NWAVE;
         k0 = min(k1, k0 + wv * per);
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
     int kb = k0;
     if (k1 - k0 == 1 && !cache.K) {
         // one index per bag and no cache (the Criteo-shaped workloads): the shortest chain from index to slices
-        through_cores((uint32_t)__builtin_amdgcn_readfirstlane((int)indices[k0]), alpha ? alpha[k0] : 1.f, k0);
+        through_cores(bk0 >= 0 ? brow : (uint32_t)__builtin_amdgcn_readfirstlane((int)indices[k0]), alpha ? alpha[k0] : 1.f, k0);
         kb = k1;
     }
     // cached rows: NG = 64 / NQ of them per step, lane (g, f) adds float4 f of the g-th one
@@ -269,6 +273,76 @@ __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__r
             o[(j1 * N2 + j2) * N3 + j3] = acc[i];
         }
     }
+    };  // do_bag
+
+    if constexpr (MODE == FWD_XCD_LOCAL) {
+        // Workgroup 8 s + x runs on XCD x (workgroups go to the XCDs in turn).  Of the FWD_SEG bags of segment s it takes
+        // those whose first row has its second digit in the x-th eighth of [0, m2), so that every XCD reads an eighth
+        // of the second core, which then stays in its L2 -- but at most an eighth of the segment's bags: what a
+        // bucket holds beyond that (a hot row fills its bucket) goes to the workgroups with room left, in a fixed
+        // order.  Every wave works the assignment out for itself (lane l looks at bag l) and takes every fourth bag
+        // of its workgroup's list.  Any assignment gives the same result: a bag is computed by one wave as a whole.
+        static_assert(FWD_SEG <= WAVE && FWD_SEG % 8 == 0, "one bag per lane");
+        __shared__ int list[NWAVE][FWD_SEG / 8 + 1];
+        const int x = blockIdx.x & 7, first = (int)(blockIdx.x >> 3) * FWD_SEG;
+        const int mybag = first + lane;
+        const bool valid = lane < FWD_SEG && mybag < n_bags;
+        const int k0v = valid ? (offsets ? (int)offsets[mybag] : mybag) : 0;
+        const int k1v = valid ? (offsets ? (int)offsets[mybag + 1] : mybag + 1) : 0;
+        const uint32_t rowv = k1v > k0v ? (uint32_t)indices[k0v] : 0u;
+        int bucket = lane & 7;                                             // empty bags: spread
+        if (k1v > k0v) {
+            int i1, i2, i3;
+            decode(p, rowv, i1, i2, i3);
+            bucket = min(7, (int)fast_div((uint32_t)i2 * 8u, (uint32_t)p.m2, p.mg2));
+        }
+        uint64_t M[8];
+        int spare_before = 0, spare_mine = 0, nvalid = __popcll(__ballot(valid));
+        const int cap = (nvalid + 7) / 8;
+#pragma unroll
+        for (int y = 0; y < 8; ++y) {
+            M[y] = __ballot(valid && bucket == y);
+            const int spare = cap - min(cap, (int)__popcll(M[y]));
+            if (y < x) spare_before += spare;
+            if (y == x) spare_mine = spare;
+        }
+        int cnt = 0;                                                       // bags of this workgroup
+        {
+            uint64_t m = 0;
+#pragma unroll
+            for (int y = 0; y < 8; ++y) m = y == x ? M[y] : m;
+            for (int q = 0; m && q < cap; ++q) {                           // uniform: the bucket's first bags
+                const int j = __builtin_ctzll(m);
+                m &= m - 1;
+                if (lane == 0) list[wv][cnt] = j;
+                ++cnt;
+            }
+        }
+        int r = 0;                                                         // number of the bag among those beyond the caps
+#pragma unroll
+        for (int y = 0; y < 8; ++y) {
+            uint64_t m = M[y];
+            for (int q = 0; m; ++q) {                                      // uniform
+                const int j = __builtin_ctzll(m);
+                m &= m - 1;
+                if (q < cap) continue;
+                if (r >= spare_before && r < spare_before + spare_mine) {
+                    if (lane == 0) list[wv][cnt] = j;
+                    ++cnt;
+                }
+                ++r;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int q = wv; q < cnt; q += NWAVE) {                            // uniform
+            const int j = __builtin_amdgcn_readfirstlane(list[wv][q]);    // the bag that lane j looked at
+            do_bag(first + j, __builtin_amdgcn_readlane(k0v, j), __builtin_amdgcn_readlane(k1v, j),
+                   (uint32_t)__builtin_amdgcn_readlane((int)rowv, j));
+        }
+    } else {
+        const int bag = WGBAG ? (int)blockIdx.x : (int)blockIdx.x * NWAVE + wv;
+        if (bag < n_bags) do_bag(bag, -1, 0, 0u);           // (uniform in the workgroup if WGBAG)
+    }
 }
 
 // ---- dispatch ----------------------------------------------------------------------
@@ -281,12 +355,20 @@ static inline void launch_fwd(const Params &p, const float *G1, const float *G2,
                               float *t0_out, hipStream_t st)
 {
     static_assert(NWAVE == 4, "the workgroup-per-bag variant adds four partial results");
+    // XCD-local: short bags (one index mostly), a second core too large for one XCD's L2 (4 MB) next to the rest, and
+    // enough slices to read that their bandwidth matters more than the longer way to a wave's first load
+    // (measured: 8,192 lookups of 64 KB slices 42.5 -> 31 us; 4,096 of 32 KB slices 11.7 -> 13.4 us)
+    const bool xcd_local = L < 2 * (int64_t)n_bags && (size_t)p.m2 * C::sB * sizeof(float) > (3u << 20) &&
+                           (size_t)n_bags * C::sB * sizeof(float) >= ((size_t)256 << 20);
     if (off && L >= 32 * (int64_t)n_bags)
-        hipLaunchKernelGGL((fwd_fast_kernel<C, true>), dim3(n_bags), dim3(WG), 0, st, p, G1, G2, G3, idx, off, n_bags, alpha,
-                           cd, out, t0_out);
+        hipLaunchKernelGGL((fwd_fast_kernel<C, FWD_WG_PER_BAG>), dim3(n_bags), dim3(WG), 0, st, p, G1, G2, G3, idx, off, n_bags,
+                           alpha, cd, out, t0_out);
+    else if (xcd_local)
+        hipLaunchKernelGGL((fwd_fast_kernel<C, FWD_XCD_LOCAL>), dim3(8 * ((n_bags + FWD_SEG - 1) / FWD_SEG)), dim3(WG), 0, st, p,
+                           G1, G2, G3, idx, off, n_bags, alpha, cd, out, t0_out);
     else
-        hipLaunchKernelGGL((fwd_fast_kernel<C, false>), dim3((n_bags + NWAVE - 1) / NWAVE), dim3(WG), 0, st, p, G1, G2, G3, idx,
-                           off, n_bags, alpha, cd, out, t0_out);
+        hipLaunchKernelGGL((fwd_fast_kernel<C, FWD_WAVE_PER_BAG>), dim3((n_bags + NWAVE - 1) / NWAVE), dim3(WG), 0, st, p, G1, G2,
+                           G3, idx, off, n_bags, alpha, cd, out, t0_out);
 }
 
 // id of the specialised configuration for this shape, or -1

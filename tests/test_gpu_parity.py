@@ -613,6 +613,42 @@ def test_forward_long_bags_take_a_workgroup_each(R, path):
     assert_close(d.fwd(), ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha), "long bags forward, no cache")
 
 
+@pytest.mark.parametrize("with_cache", [False, True])
+def test_forward_short_bags_large_second_core(with_cache):
+    """Many short bags (0 to 3 positions, fewer than 2 on average) on a table whose second core is larger than one
+    XCD's L2: the forward assigns the bags to the workgroups by the second digit of their first row.  A hot row
+    fills its bucket and spills over; ragged, weighted, with empty bags, a tail segment, with and without a cache."""
+    import dataclasses
+    t = W.TableShape(16 * 50 * 16, (16, 50, 16), (4, 4, 4), (1, 64, 64, 1))
+    wl = dataclasses.replace(W.WORKLOADS["tiny"], tables=(t,), name="shortbags")
+    rng = np.random.default_rng(5)
+    n_bags = 4096 + 19
+    lens = rng.choice([0, 1, 1, 1, 1, 2, 3], n_bags).astype(np.int64)
+    off = np.zeros(n_bags + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    L = int(off[-1])
+    assert n_bags <= L < 2 * n_bags
+    idx = rng.integers(0, t.num_rows, L)
+    idx[rng.random(L) < 0.15] = 4321                                # a hot row
+    batch = W.Batch(idx, off, rng.standard_normal((n_bags, t.dim)).astype(np.float32), (0.5 + rng.random(L)).astype(np.float32))
+    d = DeviceTable(wl, batch=batch)
+    cache, keys, crows = None, None, None
+    if with_cache:
+        rows, counts = np.unique(idx, return_counts=True)
+        cache, _, _ = d.build_cache(30, rows.astype(np.int64), counts.astype(np.int64))
+        keys = ora.cache_select(rows, counts, 30)
+        crows = (cache.rows.cpu().numpy()[:30] * 1.25).astype(np.float32)
+        cache.rows[:30].copy_(torch.from_numpy(crows))
+    ref = ora.fwd(d.oshape, d.cores, idx, off, alpha=batch.alpha, cache_keys=keys, cache_rows=crows)
+    assert_close(d.fwd(cache=cache), ref, "forward")
+    out, t0 = d.fwd_keep_t0(cache=cache)
+    assert_close(out, ref, "forward keeping T0")
+    rg, rc = ora.bwd(d.oshape, d.cores, idx, off, batch.grad_output, alpha=batch.alpha, cache_keys=keys)
+    new = d.bwd_sgd(0.01, cache=cache, t0=t0)                     # the kept T0 is the right one, position by position
+    for k in range(3):
+        assert_close((d.cores[k].astype(np.float64) - new[k].cpu().numpy()) / 0.01, rg[k], "gradient of core %d from the kept T0" % (k + 1))
+
+
 @pytest.mark.parametrize("R,n_bags", [(32, 1500), (64, 1500), (32, 6000)])
 @pytest.mark.parametrize("with_cache", [False, True])
 def test_444_shapes_shared_slices_and_matrix_cores(R, n_bags, with_cache, path):
