@@ -115,8 +115,10 @@ constexpr int FWD_SEG = 32;                       // bags per segment of the XCD
 // the other positions go through the cores one after the other.  The partial products of
 // stage 1 are accumulated over the bag's lookups before one shuffle reduction per bag,
 // and the sum of the cached rows is added to the result at the end.
-// WGBAG: a whole workgroup per bag, for long bags: its four waves take a quarter of the bag's
+// MODE FWD_WG_PER_BAG: a whole workgroup per bag, for long bags: its four waves take a quarter of the bag's
 // positions each and their results are added through LDS, in wave order.
+// MODE FWD_XCD_LOCAL: still a wave per bag, but which bags a workgroup takes depends on their rows, so that each of
+// the 8 XCDs reads an eighth of the second core (see the end of the kernel).
 template <typename C, int MODE>
 __global__ __launch_bounds__(WG) void fwd_fast_kernel(Params p, const float *__restrict__ G1,
                                                       const float *__restrict__ G2, const float *__restrict__ G3,
