@@ -955,3 +955,71 @@ def test_graph_replays_of_the_benchmark_step_match_eager_calls():
         oc = [ora.sgd(oc[k], dg[k], lr) for k in range(3)]
     for k in range(3):
         assert_close(eager[0][k].cpu().numpy(), oc[k], "two benchmark steps, core %d" % (k + 1))
+
+
+def test_graph_replays_of_the_two_stream_step_match_eager_calls():
+    """The step as bench.py runs it where the backward has an index-only pre-pass (multi-hot table with its cache):
+    tt_emb_bwd_prepare on a second stream next to the forward, then tt_emb_bwd_sgd_prepared.  Replays of the
+    captured pair of steps (fork and join inside the graph) leave the same cores and cache lines, bit for bit,
+    as the one-call steps launched one by one."""
+    wl = W.WORKLOADS["multihot_cache"]
+    t = wl.tables[0]
+    shape = B.shape_of(t)
+    cores_h = W.make_cores(t, wl.init, wl.seed)
+    batches = [W.make_batch(wl, 0, j) for j in range(2)]
+    d = dev()
+    idx = [torch.from_numpy(b.indices).to(d) for b in batches]
+    off = [torch.from_numpy(b.offsets).to(d) for b in batches]
+    go = [torch.from_numpy(b.grad_output).to(d) for b in batches]
+    L, lr, K = idx[0].numel(), 0.01, W.cache_size(wl, 0)
+    rows_h, counts_h = W.warmup_counts(wl, 0)
+    assert B.bwd_has_prepass(shape, L, K, True)
+
+    def fresh():
+        a = [torch.from_numpy(c).to(d) for c in cores_h]
+        cache = B.Cache(K, t.dim, d)
+        B.tt_cache_build(shape, a, torch.from_numpy(rows_h).to(d), torch.from_numpy(counts_h).to(d), cache)
+        torch.cuda.synchronize()
+        return a, [torch.empty_like(x) for x in a], cache
+
+    out = torch.empty((wl.n_bags, t.dim), dtype=torch.float32, device=d)
+    t0 = [torch.empty((L, B.t0_floats(shape)), dtype=torch.float32, device=d) for _ in range(2)]
+    ws = torch.empty(B.bwd_sgd_workspace_bytes(shape, L, wl.n_bags, K), dtype=torch.uint8, device=d)
+    side = torch.cuda.Stream()
+
+    def two_steps(a, b, cache, two_calls):
+        for j in range(2):
+            cur, nxt = (a, b) if j == 0 else (b, a)
+            if two_calls:
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    B.tt_emb_bwd_prepare(shape, idx[j], off[j], wl.n_bags, cache=cache, workspace=ws, kept_t0=True)
+            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], wl.n_bags, out, t0[j], cache=cache)
+            if two_calls:
+                torch.cuda.current_stream().wait_stream(side)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], lr, cache=cache, workspace=ws, t0=t0[j],
+                             prepared=two_calls)
+
+    a, b, cache = fresh()
+    eager = []
+    for _ in range(3):
+        two_steps(a, b, cache, False)
+        torch.cuda.synchronize()
+        eager.append(([x.clone() for x in a], cache.rows.clone()))
+    ga, gb, gcache = fresh()
+    start_rows = gcache.rows.clone()
+    two_steps(ga, gb, gcache, True)                                # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        two_steps(ga, gb, gcache, True)
+    for k in range(3):
+        ga[k].copy_(torch.from_numpy(cores_h[k]))
+    gcache.rows.copy_(start_rows)
+    for rep in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        for k in range(3):
+            assert torch.equal(ga[k], eager[rep][0][k]), (rep, k)
+        assert torch.equal(gcache.rows, eager[rep][1]), rep
+        _ = (out * 2).sum().item()                                 # unrelated eager work between replays
