@@ -396,7 +396,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
     // gradients of entries [0, n_g / NQ) of the window that starts at list entry i0 (entry e goes
     // to its staged position lds.epos[e]), then the G1 slices of rows [sb0, sb0 + nb) (unless the
     // G1 owner), then their G3 slices (unless the G3 owner).
-    constexpr int IPT = N <= 16 ? 3 : 2;
+    constexpr int IPT = N <= 16 ? 4 : (MFMA ? (R == 64 ? 8 : 4) : 2);           // (as many as the registers allow)
     auto stage_items = [&](int i0, int n_g, int sb0, int nb, const int (&wc)[NWAVE]) __attribute__((always_inline)) {
         const int n_a = ROLE != 0 ? nb * PA : 0;
         const int n_c = ROLE != 2 ? nb * PC : 0;
