@@ -169,25 +169,38 @@ def main():
 
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
-    # The index-only pre-pass of the backward (cache probe, grouping sort of long lists) runs on a second stream next to
-    # the forward pass of the same batch where there is one; the graph keeps the fork and the join.
+    # The index-only pre-pass of the backward (cache probe, grouping sort of long lists) runs on a second stream where
+    # there is one.  Within a sequence of steps (the captured graph) the pre-pass of step i + 1 is enqueued when step i
+    # begins, so that it runs next to the whole of step i (the indices of the next batch are known, as with a data
+    # loader that is one batch ahead); it needs a workspace of its own, two alternate.  A step on its own (first = last
+    # = True) runs its pre-pass next to its forward pass.  The graph keeps the forks and the joins.
     two_calls = args.step == "fused" and not args.one_call and B.bwd_has_prepass(shape, max(Ls), K, keep_t0)
     side = torch.cuda.Stream() if two_calls else None
+    ws_pair = [ws, torch.empty_like(ws)] if two_calls else [ws, ws]
+    prepared_ev = [torch.cuda.Event(), torch.cuda.Event()] if two_calls else None
 
-    def step(i):
+    def prepare_on_side(i):
+        """Pre-pass of step i on the second stream, after everything enqueued on the current stream so far."""
+        j = i % POOL
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            B.tt_emb_bwd_prepare(shape, idx[j], off[j], n_bags, cache=cache, workspace=ws_pair[i % 2], kept_t0=keep_t0)
+            prepared_ev[i % 2].record(side)
+
+    def step(i, first=True, last=True):
         j = i % POOL
         if args.step == "fused":
             cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
             if two_calls:
-                main = torch.cuda.current_stream()
-                side.wait_stream(main)
-                with torch.cuda.stream(side):
-                    B.tt_emb_bwd_prepare(shape, idx[j], off[j], n_bags, cache=cache, workspace=ws, kept_t0=keep_t0)
+                if first:
+                    prepare_on_side(i)
+                if not last:
+                    prepare_on_side(i + 1)                  # its workspace was last read by step i - 1
             fwd_call(cur, j)
             if two_calls:
-                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
             B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
-                             workspace=ws, t0=t0_pool[j] if keep_t0 else None, prepared=two_calls)
+                             workspace=ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None, prepared=two_calls)
         else:
             B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
             B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads, alpha=alpha[j], cache=cache,
@@ -210,7 +223,10 @@ def main():
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for i in range(POOL):
-                fn(i)
+                if fn is step:
+                    fn(i, first=i == 0, last=i == POOL - 1)
+                else:
+                    fn(i)
         return g
 
     def timed_any(fn, count):
@@ -309,7 +325,7 @@ def main():
                                                                 ", weights: %s" % args.weights if args.weights != "none" else ""),
                    "table": tab,
                    "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0),
-                   "prepass_on_second_stream": bool(two_calls), "wall_s_timed_region": round(wall, 3)},
+                   "prepass_on_second_stream": bool(two_calls), "prepass_one_step_ahead": bool(two_calls and args.launch == "graph"), "wall_s_timed_region": round(wall, 3)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

@@ -958,9 +958,9 @@ def test_graph_replays_of_the_benchmark_step_match_eager_calls():
 
 
 def test_graph_replays_of_the_two_stream_step_match_eager_calls():
-    """The step as bench.py runs it where the backward has an index-only pre-pass (multi-hot table with its cache):
-    tt_emb_bwd_prepare on a second stream next to the forward, then tt_emb_bwd_sgd_prepared.  Replays of the
-    captured pair of steps (fork and join inside the graph) leave the same cores and cache lines, bit for bit,
+    """The steps as bench.py runs them where the backward has an index-only pre-pass (multi-hot table with its cache):
+    tt_emb_bwd_prepare on a second stream, one step ahead, then tt_emb_bwd_sgd_prepared.  Replays of the
+    captured pair of steps (forks and joins inside the graph) leave the same cores and cache lines, bit for bit,
     as the one-call steps launched one by one."""
     wl = W.WORKLOADS["multihot_cache"]
     t = wl.tables[0]
@@ -984,20 +984,28 @@ def test_graph_replays_of_the_two_stream_step_match_eager_calls():
 
     out = torch.empty((wl.n_bags, t.dim), dtype=torch.float32, device=d)
     t0 = [torch.empty((L, B.t0_floats(shape)), dtype=torch.float32, device=d) for _ in range(2)]
-    ws = torch.empty(B.bwd_sgd_workspace_bytes(shape, L, wl.n_bags, K), dtype=torch.uint8, device=d)
+    ws = [torch.empty(B.bwd_sgd_workspace_bytes(shape, L, wl.n_bags, K), dtype=torch.uint8, device=d) for _ in range(2)]
     side = torch.cuda.Stream()
+    done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def prepare_on_side(j, cache):
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            B.tt_emb_bwd_prepare(shape, idx[j], off[j], wl.n_bags, cache=cache, workspace=ws[j], kept_t0=True)
+            done[j].record(side)
 
     def two_steps(a, b, cache, two_calls):
+        # as in bench.py: the pre-pass of the first step next to its forward pass, the pre-pass of the second step
+        # (workspace of its own) enqueued right behind it, so that it runs next to the whole first step
         for j in range(2):
             cur, nxt = (a, b) if j == 0 else (b, a)
-            if two_calls:
-                side.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(side):
-                    B.tt_emb_bwd_prepare(shape, idx[j], off[j], wl.n_bags, cache=cache, workspace=ws, kept_t0=True)
+            if two_calls and j == 0:
+                prepare_on_side(0, cache)
+                prepare_on_side(1, cache)
             B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], wl.n_bags, out, t0[j], cache=cache)
             if two_calls:
-                torch.cuda.current_stream().wait_stream(side)
-            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], lr, cache=cache, workspace=ws, t0=t0[j],
+                torch.cuda.current_stream().wait_event(done[j])
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], lr, cache=cache, workspace=ws[j], t0=t0[j],
                              prepared=two_calls)
 
     a, b, cache = fresh()
