@@ -170,9 +170,9 @@ def main():
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
     # The index-only pre-pass of the backward (cache probe, grouping sort of long lists) runs on a second stream where
-    # there is one.  Within a sequence of steps (the captured graph) the pre-pass of step i + 1 is enqueued when step i
-    # begins, so that it runs next to the whole of step i (the indices of the next batch are known, as with a data
-    # loader that is one batch ahead); it needs a workspace of its own, two alternate.  A step on its own (first = last
+    # there is one.  Within a sequence of steps (the captured graph) the pre-pass of step i + 1 is enqueued behind the
+    # forward pass of step i, so that it runs next to the backward pass of step i (the indices of the next batch are
+    # known, as with a data loader that is one batch ahead); it needs a workspace of its own, two alternate.  A step on its own (first = last
     # = True) runs its pre-pass next to its forward pass.  The graph keeps the forks and the joins.
     two_calls = args.step == "fused" and not args.one_call and B.bwd_has_prepass(shape, max(Ls), K, keep_t0)
     side = torch.cuda.Stream() if two_calls else None
@@ -194,10 +194,10 @@ def main():
             if two_calls:
                 if first:
                     prepare_on_side(i)
-                if not last:
-                    prepare_on_side(i + 1)                  # its workspace was last read by step i - 1
             fwd_call(cur, j)
-            if two_calls:
+            if two_calls and not last:
+                prepare_on_side(i + 1)                      # next to this step's backward (measured: better than next to
+            if two_calls:                                   # its forward); its workspace was last read by step i - 1
                 torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
             B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
                              workspace=ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None, prepared=two_calls)

@@ -71,8 +71,8 @@ class _Table:
         ws = torch.empty(B.bwd_sgd_workspace_bytes(self.c, L, n_bags, cache.K if cache else 0), dtype=torch.uint8, device=dev)
 
         # The index-only part of the backward (cache probe, grouping of long lists) on a second stream, one step ahead:
-        # the pre-pass of step j + 1 is enqueued when step j begins (two workspaces alternate), the first one of a
-        # graph next to its own forward pass.
+        # the pre-pass of step j + 1 is enqueued behind the forward pass of step j (two workspaces alternate), the first
+        # one of a graph next to its own forward pass.
         two_calls = B.bwd_has_prepass(self.c, L, cache.K if cache else 0, True)
         side = torch.cuda.Stream() if two_calls else None
         wsp = [ws, torch.empty_like(ws)] if two_calls else [ws, ws]
@@ -86,13 +86,12 @@ class _Table:
 
         def tt_step(j):
             cur, nxt = (self.cores, self.cores2) if j % 2 == 0 else (self.cores2, self.cores)
-            if two_calls:
-                if j == 0:
-                    prepare_on_side(0)
-                if j + 1 < STEPS:
-                    prepare_on_side(j + 1)
+            if two_calls and j == 0:
+                prepare_on_side(0)
             B.tt_emb_fwd_keep_t0(self.c, cur, idx[j], off[j], n_bags, out, t0[j], cache=cache)
             if two_calls:
+                if j + 1 < STEPS:
+                    prepare_on_side(j + 1)                  # next to this step's backward pass
                 torch.cuda.current_stream().wait_event(done[j % 2])
             B.tt_emb_bwd_sgd(self.c, cur, nxt, idx[j], off[j], n_bags, go[j], lr, cache=cache, workspace=wsp[j % 2], t0=t0[j],
                              prepared=two_calls)

@@ -996,14 +996,15 @@ def test_graph_replays_of_the_two_stream_step_match_eager_calls():
 
     def two_steps(a, b, cache, two_calls):
         # as in bench.py: the pre-pass of the first step next to its forward pass, the pre-pass of the second step
-        # (workspace of its own) enqueued right behind it, so that it runs next to the whole first step
+        # (workspace of its own) enqueued behind that forward pass, so that it runs next to the first backward pass
         for j in range(2):
             cur, nxt = (a, b) if j == 0 else (b, a)
             if two_calls and j == 0:
                 prepare_on_side(0, cache)
-                prepare_on_side(1, cache)
             B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], wl.n_bags, out, t0[j], cache=cache)
             if two_calls:
+                if j == 0:
+                    prepare_on_side(1, cache)
                 torch.cuda.current_stream().wait_event(done[j])
             B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], lr, cache=cache, workspace=ws[j], t0=t0[j],
                              prepared=two_calls)
