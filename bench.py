@@ -218,22 +218,23 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / count
 
-    def captured(fn):
-        """A HIP graph of POOL consecutive calls fn(0..POOL-1); replay() launches all of them."""
+    def captured(fn, sequence=False):
+        """A HIP graph of POOL consecutive calls fn(0..POOL-1); replay() launches all of them.
+        sequence: fn is told which call is the first and which the last of the graph (see step)."""
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for i in range(POOL):
-                if fn is step:
+                if sequence:
                     fn(i, first=i == 0, last=i == POOL - 1)
                 else:
                     fn(i)
         return g
 
-    def timed_any(fn, count):
+    def timed_any(fn, count, sequence=False):
         """ms per call of fn, either launched call by call or as replays of a POOL-call graph."""
         if args.launch == "stream":
             return timed(fn, count)
-        g = captured(fn)
+        g = captured(fn, sequence)
         g.replay()
         reps = max(1, count // POOL)
         return timed(lambda i: g.replay(), reps) / POOL
@@ -243,7 +244,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_step = timed_any(step, steps)
+    ms_step = timed_any(step, steps, sequence=True)
     wall = time.perf_counter() - t0
     value = L / (ms_step * 1e-3)
 
