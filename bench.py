@@ -33,7 +33,10 @@ POOL = 16                      # distinct batches cycled through, so caches see 
 # are in profiles/hbm_traffic_bench_kaggle_r32.md.  Only valid for the workload they were taken on.
 MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 11.00e6, "bwd_sgd": 13.08e6},
                                    "recompute": {"fwd": 9.93e6, "bwd_sgd": 15.42e6},
-                                   "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}}}
+                                   "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}},
+                    # profiles/hbm_traffic_bench_terabyte_multihot.md (multihot_cache: table 0 only)
+                    "terabyte_r64": {"keep_t0": {"fwd": 128.6e6, "bwd_sgd": 330.4e6}},
+                    "multihot_cache": {"keep_t0": {"fwd": 153.4e6, "bwd_sgd": 190.1e6}}}
 
 
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published
@@ -283,7 +286,7 @@ def main():
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get(
+                "traffic": MEASURED_TRAFFIC.get(args.workload if tab == 0 else None, {}).get(
                     "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
                 "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
