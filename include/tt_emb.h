@@ -359,6 +359,17 @@ int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t
                         int32_t *i1, int32_t *i2, int32_t *i3, void *stream);
 
 /*
+ * The same digits from the other decoders inside the library, which all must agree with
+ * Section 3.1's digit map bit for bit.  mode 0: the integer decode (= tt_emb_debug_decode);
+ * mode 1: the multiply-free floating-point decode with which the backward's slice owners find
+ * the runs of equal rows;  mode 2: what the owners' selection of their positions decides:
+ * i2 and i3 from the digit arithmetic of that test, i1 = the slice whose row range holds the
+ * row (-1 if none of the neighbouring slices does, -2 if more than one does).
+ */
+int tt_emb_debug_decode_as(const tt_shape_t *shape, const int64_t *indices, int64_t L, int mode,
+                           int32_t *i1, int32_t *i2, int32_t *i3, void *stream);
+
+/*
  * Canonical duplicate-free form of a key stream derived from `indices`:
  *   which = 0: the row id itself;  which = 1,2,3: digit i1, i2 or i3.
  * Positions with slot[k] >= 0 are skipped (slot may be NULL: nothing skipped).

@@ -28,7 +28,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
            "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
-           "tt_emb_debug_decode", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
+           "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
 
 class TTShape(C.Structure):
@@ -93,6 +93,7 @@ def lib():
         l.tt_freq_update.argtypes = [vp, vp, i64, vp]
         l.tt_freq_export.argtypes = [vp, vp, vp, vp, vp]
         l.tt_emb_debug_decode.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+        l.tt_emb_debug_decode_as.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp, vp]
         l.tt_emb_debug_dedup.argtypes = [vp, vp, i64, vp, C.c_int, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_debug_set_fast_path.argtypes = [C.c_int]
         _lib = l
@@ -366,6 +367,14 @@ def tt_emb_debug_decode(shape: TTShape, indices: torch.Tensor) -> List[torch.Ten
     out = [torch.empty(indices.numel(), dtype=torch.int32, device=indices.device) for _ in range(3)]
     _check(lib().tt_emb_debug_decode(C.byref(shape), _ptr(indices), indices.numel(), _ptr(out[0]), _ptr(out[1]),
                                      _ptr(out[2]), _stream()))
+    return out
+
+
+def tt_emb_debug_decode_as(shape: TTShape, indices: torch.Tensor, mode: int) -> List[torch.Tensor]:
+    _dev(indices, torch.int64)
+    out = [torch.empty(indices.numel(), dtype=torch.int32, device=indices.device) for _ in range(3)]
+    _check(lib().tt_emb_debug_decode_as(C.byref(shape), _ptr(indices), indices.numel(), int(mode), _ptr(out[0]),
+                                        _ptr(out[1]), _ptr(out[2]), _stream()))
     return out
 
 

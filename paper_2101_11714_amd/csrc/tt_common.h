@@ -60,6 +60,40 @@ __device__ __forceinline__ void decode_f64(const Params &p, uint32_t row, int &i
     i1 = (int)q2;
 }
 
+// What an owner workgroup of the backward pass tests to find its positions (Section 3.1's digit
+// map, one digit at a time).  Cores 2 and 3: the digit of the row (given as a double) from the
+// same multiply-free arithmetic, compared with the slice number as doubles.  Core 1: the rows
+// with i1 = s are the contiguous range [s m2 m3, (s+1) m2 m3), clamped to the 31-bit row space.
+__device__ __forceinline__ double select_digit_f64(const Params &p, int role, double rd)
+{
+    const double q = floor(fma(rd, p.inv3, p.half3));
+    double d = fma(-q, p.m3d, rd);                                          // i3
+    if (role == 1) {
+        const double q2 = floor(fma(q, p.inv2, p.half2));
+        d = fma(-q2, p.m2d, q);                                             // i2
+    }
+    return d;
+}
+
+struct RowRange {
+    uint32_t lo, len;                                                       // rows lo <= row < lo + len
+};
+
+__device__ __forceinline__ RowRange rows_of_i1(const Params &p, int s)
+{
+    RowRange r{0u, 0u};
+    const uint64_t m23 = (uint64_t)p.m2 * (uint64_t)p.m3;
+    const uint64_t lo64 = (uint64_t)s * m23;
+    if (lo64 < (1ull << 31)) {
+        r.lo = (uint32_t)lo64;
+        const uint64_t hi64 = lo64 + m23 < (1ull << 31) ? lo64 + m23 : (1ull << 31);
+        r.len = (uint32_t)(hi64 - lo64);
+    }
+    return r;
+}
+
+__device__ __forceinline__ bool in_rows(const RowRange &r, uint32_t row) { return (row - r.lo) < r.len; }
+
 // ---- cache map: open addressing, linear probing -----------------------------
 // entry = (row << 32) | slot, empty = all ones.
 

@@ -899,6 +899,23 @@ int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t
     return e == hipSuccess ? TT_OK : hip_fail(e, "decode launch");
 }
 
+int tt_emb_debug_decode_as(const tt_shape_t *shape, const int64_t *indices, int64_t L, int mode,
+                           int32_t *i1, int32_t *i2, int32_t *i3, void *stream)
+{
+    if (mode == 0) return tt_emb_debug_decode(shape, indices, L, i1, i2, i3, stream);
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (mode != 1 && mode != 2) return fail(TT_ERR_BAD_ARG, "mode must be 0, 1 or 2");
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (L == 0) return TT_OK;
+    if (!indices || !i1 || !i2 || !i3) return fail(TT_ERR_NULL, "NULL array");
+    hipLaunchKernelGGL(decode_as_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, p, indices, (int)L, mode, i1, i2, i3);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "decode launch");
+}
+
 int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                        const int32_t *slot, int which,
                        int64_t *uniq, int32_t *count, int32_t *perm, int64_t *n_out,

@@ -201,17 +201,10 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
     uint64_t masks[FB_ITER];
     int cnt = 0;
     if (role == 0) {
-        uint32_t r0lo = 0, r0len = 0;
-        const uint64_t m23 = (uint64_t)p.m2 * (uint64_t)p.m3;
-        const uint64_t lo64 = (uint64_t)s * m23;
-        if (lo64 < (1ull << 31)) {
-            r0lo = (uint32_t)lo64;
-            const uint64_t hi64 = lo64 + m23 < (1ull << 31) ? lo64 + m23 : (1ull << 31);
-            r0len = (uint32_t)(hi64 - lo64);
-        }
+        const RowRange rr = rows_of_i1(p, s);
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
-            const bool hit = rowv[it] != FB_NONE && (rowv[it] - r0lo) < r0len;
+            const bool hit = rowv[it] != FB_NONE && in_rows(rr, rowv[it]);
             masks[it] = __ballot(hit);
             cnt += __popcll(masks[it]);
         }
@@ -219,14 +212,7 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
         const double sd = (double)s;
 #pragma unroll
         for (int it = 0; it < FB_ITER; ++it) {
-            const double rd = (double)rowv[it];
-            const double q = floor(fma(rd, p.inv3, p.half3));
-            double d = fma(-q, p.m3d, rd);                                  // i3
-            if (role == 1) {
-                const double q2 = floor(fma(q, p.inv2, p.half2));
-                d = fma(-q2, p.m2d, q);                                     // i2
-            }
-            const bool hit = rowv[it] != FB_NONE && d == sd;
+            const bool hit = rowv[it] != FB_NONE && select_digit_f64(p, role, (double)rowv[it]) == sd;
             masks[it] = __ballot(hit);
             cnt += __popcll(masks[it]);
         }

@@ -340,6 +340,32 @@ __global__ __launch_bounds__(WG) void decode_kernel(Params p, const int64_t *__r
     o1[k] = i1; o2[k] = i2; o3[k] = i3;
 }
 
+// The digits as the other decoders of the library produce them, for the bit-exact tests:
+// mode 1: decode_f64 (run detection of the backward's owners);  mode 2: what an owner's
+// selection decides: i2 and i3 from select_digit_f64, i1 = the slice s among (integer i1) - 1,
+// i1, i1 + 1 whose row range holds the row (-1: none does, -2: more than one does).
+__global__ __launch_bounds__(WG) void decode_as_kernel(Params p, const int64_t *__restrict__ indices, int L, int mode,
+                                                       int32_t *__restrict__ o1, int32_t *__restrict__ o2,
+                                                       int32_t *__restrict__ o3)
+{
+    const int k = blockIdx.x * WG + threadIdx.x;
+    if (k >= L) return;
+    const uint32_t row = (uint32_t)indices[k];
+    int i1, i2, i3;
+    if (mode == 1) {
+        decode_f64(p, row, i1, i2, i3);
+    } else {
+        int g1, g2, g3;
+        decode(p, row, g1, g2, g3);
+        i1 = -1;
+        for (int s = g1 - 1; s <= g1 + 1; ++s)
+            if (s >= 0 && s < p.m1 && in_rows(rows_of_i1(p, s), row)) i1 = i1 == -1 ? s : -2;
+        i2 = (int)select_digit_f64(p, 1, (double)row);
+        i3 = (int)select_digit_f64(p, 2, (double)row);
+    }
+    o1[k] = i1; o2[k] = i2; o3[k] = i3;
+}
+
 // keys[k] = row id (which = 0) or digit (which = 1..3) of indices[k]; skipped positions get `sentinel`.
 __global__ __launch_bounds__(WG) void dedup_keys_kernel(Params p, const int64_t *__restrict__ indices, int L,
                                                         const int32_t *__restrict__ slot, int which,

@@ -12,8 +12,12 @@ from paper_2101_11714_amd import workloads as W
 
 # Bar for floating point: max |gpu - ref| / max |ref| per tensor (the benchmark spec's 1e-4).
 REL_TOL = 1e-4
-# Elementwise companion check: |gpu - ref| <= 1e-4 |ref| + 1e-5 max|ref|.
-ELT_RTOL, ELT_ATOL_FRAC = 1e-4, 1e-5
+# Elementwise companion check: |gpu - ref| <= 1e-4 |ref| + 4e-6 max|ref|.  The absolute part is the
+# expected fp32 rounding error of a sum of up to R^2 = 4096 products accumulated in fp32 against the
+# tensor's scale, eps sqrt(4096) = 6e-8 x 64 = 3.8e-6; elements that cancel to nearly zero cannot do
+# better.  (1e-6, tried first, is at the two-sigma level of that error: it flags one element in
+# thousands of a gradient slice.)
+ELT_RTOL, ELT_ATOL_FRAC = 1e-4, 4e-6
 
 
 def dev():

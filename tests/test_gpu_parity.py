@@ -54,6 +54,49 @@ def test_decode_awkward_factors():
             assert np.array_equal(got[k].cpu().numpy(), ref[k]), m
 
 
+def _edge_rows(t):
+    """Rows at which a digit changes: multiples of m3 and of m2 m3 and their neighbours, the ends of the table."""
+    m1, m2, m3 = t.m
+    rng = np.random.default_rng(11)
+    k3 = rng.integers(0, max(1, t.num_rows // m3), 4096, dtype=np.int64) * m3
+    k23 = np.arange(0, m1 + 1, dtype=np.int64) * (m2 * m3)
+    e = np.concatenate([[0, 1, t.num_rows - 1, t.num_rows - 2], k3 - 1, k3, k3 + 1, k23 - 1, k23, k23 + 1])
+    return np.unique(e[(e >= 0) & (e < t.num_rows)])
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["run_detection_decode", "owner_selection"])
+@pytest.mark.parametrize("name", SINGLE + ["multihot_cache"])
+def test_backward_decoders_bit_exact(name, mode):
+    """The floating-point digit arithmetic that the backward's slice owners run (decode_f64 for the runs
+    of equal rows, select_digit_f64 / the row range of i1 for the selection) against the oracle's digits:
+    every table of every workload, 10^6 random rows, the rows where a digit changes, and the batch."""
+    wl = W.WORKLOADS[name]
+    for table, t in enumerate(wl.tables):
+        rng = np.random.default_rng(100 + table)
+        idx = np.concatenate([_edge_rows(t), rng.integers(0, t.num_rows, 1_000_000, dtype=np.int64),
+                              W.make_batch(wl, table).indices])
+        got = B.tt_emb_debug_decode_as(B.shape_of(t), torch.from_numpy(idx).to(dev()), mode)
+        ref = ora.decode(ora.Shape.of(t), idx)
+        for k in range(3):
+            assert np.array_equal(got[k].cpu().numpy(), ref[k]), (name, table, k)
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["run_detection_decode", "owner_selection"])
+def test_backward_decoders_awkward_factors(mode):
+    # divisors 1, 2, powers of two, primes, a large last factor, and tables that reach the 2^31 row limit
+    for m in [(1, 1, 7), (3, 1, 5), (2, 2, 2), (7, 1, 1), (13, 17, 19), (64, 128, 256), (5, 100003, 3), (2, 3, 300000007),
+              (1290, 1291, 1289), (46340, 46340, 1), (1, 2, 2 ** 30), (2 ** 15, 2 ** 15, 2), (3, 715827882, 1)]:
+        rows = min(m[0] * m[1] * m[2], 2 ** 31 - 1)
+        t = W.TableShape(rows, m, (2, 2, 4), (1, 8, 8, 1))
+        rng = np.random.default_rng(1)
+        idx = np.unique(np.concatenate([rng.integers(0, rows, 200000), rng.integers(max(0, rows - 5000), rows, 5000),
+                                        _edge_rows(t)]))
+        got = B.tt_emb_debug_decode_as(B.shape_of(t), torch.from_numpy(idx).to(dev()), mode)
+        ref = ora.decode(ora.Shape(rows, m, (2, 2, 4), (1, 8, 8, 1)), idx)
+        for k in range(3):
+            assert np.array_equal(got[k].cpu().numpy(), ref[k]), (m, k)
+
+
 @pytest.mark.parametrize("name", ["tiny", "kaggle_r32", "terabyte_r64", "multihot_cache"])
 @pytest.mark.parametrize("which", [0, 1, 2, 3])
 def test_dedup_bit_exact(name, which):
@@ -108,9 +151,8 @@ def test_dedup_long_lists_both_forms_of_the_sort(L):
 def test_forward_matches_oracle(name, path):
     d = DeviceTable(W.WORKLOADS[name])
     out = d.fwd()
-    pick, idx, off, alpha = sample_bags(d.batch, 2048)
-    ref = ora.fwd(d.oshape, d.cores, idx, off, alpha=alpha)
-    assert_close(out[pick], ref, name + " forward")
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, alpha=d.batch.alpha)     # every bag
+    assert_close(out, ref, name + " forward")
     if d.L == d.n_bags:                                   # one index per bag: offsets may be omitted
         assert np.array_equal(d.fwd(use_offsets=False), out)
 
@@ -369,8 +411,17 @@ def test_cache_on_tiny(path):
     assert float(dc.abs().max()) == 0.0
 
 
-@pytest.mark.parametrize("table", [0, 6])
-def test_multihot_with_cache(table, path):
+# every table with the specialised kernels; the shape-generic and the always-grouped path on the smallest and the largest
+@pytest.mark.parametrize("table,mode", [(tb, 1) for tb in range(7)] + [(0, 0), (6, 0), (0, 2), (6, 2)])
+def test_multihot_with_cache(table, mode):
+    old_mode = B.set_fast_path(mode)
+    try:
+        _multihot_with_cache(table)
+    finally:
+        B.set_fast_path(old_mode)
+
+
+def _multihot_with_cache(table):
     wl = W.WORKLOADS["multihot_cache"]
     d = DeviceTable(wl, table=table)
     K = W.cache_size(wl, table)
@@ -389,8 +440,8 @@ def test_multihot_with_cache(table, path):
     crow = (crow * 1.5).astype(np.float32)
     cache.rows.copy_(torch.from_numpy(crow))
     out = d.fwd(cache=cache)
-    pick, idx, off, _ = sample_bags(d.batch, 256)
-    assert_close(out[pick], ora.fwd(d.oshape, d.cores, idx, off, cache_keys=keys, cache_rows=crow), "multihot forward")
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, cache_keys=keys, cache_rows=crow)   # every bag
+    assert_close(out, ref, "multihot forward")
     dg, dc = d.bwd(cache=cache)
     rg, rc = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, cache_keys=keys)
     for k in range(3):
