@@ -231,6 +231,26 @@ int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * tt_emb_bwd_sgd for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
+ * Same arguments and same result, bit for bit, as tt_emb_bwd_sgd; the scratch memory is an
+ * array of tt_emb_static_scratch_bytes() (32 MiB) bytes inside the library's device image, of
+ * which every GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates and frees nothing.  A call that needs more scratch memory than that (long index
+ * lists, large caches: what tt_emb_bwd_sgd_workspace_bytes says, minus its allowance for
+ * shapes without a specialised kernel) fails with TT_ERR_WORKSPACE and enqueues nothing.
+ * The first call on a device also looks the array's address up (hipGetSymbolAddress): make
+ * that call outside a capture.  All calls on one GPU share the array, which keeps what the
+ * last call left in it (the kernels initialise what they read): calls that overlap on one GPU,
+ * on different streams or from different threads, race and give wrong results.
+ */
+int tt_emb_bwd_sgd_static(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                          const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                          const float *alpha, const tt_cache_t *cache,
+                          const float *grad_output, float lr, void *stream);
+size_t tt_emb_static_scratch_bytes(void);
+
+/*
  * The fused step in two calls.  Part of the backward pass of Alg. 2 depends on the
  * indices and the cache's row map alone: which positions are cached (Section 4.2) and,
  * for long index lists, the grouping of the positions by the core slices they touch.

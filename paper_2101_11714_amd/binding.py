@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -74,6 +74,9 @@ def lib():
         l.tt_emb_bwd_t0.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd_sgd_t0.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_bwd_sgd.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_sgd_static.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp]
+        l.tt_emb_static_scratch_bytes.restype = C.c_size_t
+        l.tt_emb_static_scratch_bytes.argtypes = []
         l.tt_emb_bwd_prepare.argtypes = [vp, vp, i64, vp, i64, vp, C.c_int, vp, C.c_size_t, vp]
         l.tt_emb_bwd_has_prepass.argtypes = [vp, i64, i64, C.c_int]
         l.tt_emb_bwd_sgd_prepared.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
@@ -249,6 +252,28 @@ def tt_emb_bwd_prepare(shape: TTShape, indices: torch.Tensor, offsets: Optional[
     wsb = workspace.numel() if workspace is not None else 0
     _check(lib().tt_emb_bwd_prepare(C.byref(shape), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
                                     cache.ref() if cache else None, int(kept_t0), _ptr(workspace), wsb, _stream()))
+
+
+def tt_emb_bwd_sgd_static(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],
+                          indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
+                          lr: float, alpha: Optional[torch.Tensor] = None, cache: Optional[Cache] = None) -> None:
+    """tt_emb_bwd_sgd with the library's own static scratch array instead of a workspace (allocates nothing)."""
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(grad_output, torch.float32)
+    for k in range(3):
+        assert cores_out[k].numel() == cores[k].numel()
+    _check(lib().tt_emb_bwd_sgd_static(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices),
+                                       indices.numel(), _ptr(offsets), n_bags, _ptr(alpha),
+                                       cache.ref() if cache else None, _ptr(grad_output), C.c_float(lr), _stream()))
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().tt_emb_static_scratch_bytes())
 
 
 def tt_emb_bwd_sgd(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],

@@ -6,6 +6,7 @@
 
 #include <stdarg.h>
 #include <initializer_list>
+#include <mutex>
 #include <stdio.h>
 #include <string.h>
 
@@ -22,6 +23,12 @@
 #include "tt_anyd.h"
 
 using namespace tt;
+
+// Scratch memory of tt_emb_bwd_sgd_static, the entry point for callers that cannot allocate: every GPU
+// the library runs on holds its own copy of this array until the process ends.  In host code the name
+// is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -464,6 +471,50 @@ int tt_emb_bwd_sgd(const tt_shape_t *shape, const float *const cores[3], float *
     if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
     return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
                       lr, cores_out, nullptr, workspace, workspace_bytes, stream);
+}
+
+// Address of this device's copy of scratch[], looked up once per device.
+static int static_scratch_ptr(void **out)
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void *ptrs[MAX_DEV] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEV) return fail(TT_ERR_UNSUPPORTED, "device number %d beyond %d", dev, MAX_DEV - 1);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!q) return fail(TT_ERR_HIP, "hipGetSymbolAddress(scratch) returned no address");
+        ptrs[dev] = q;
+    }
+    *out = ptrs[dev];
+    return TT_OK;
+}
+
+size_t tt_emb_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int tt_emb_bwd_sgd_static(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                          const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                          const float *alpha, const tt_cache_t *cache,
+                          const float *grad_output, float lr, void *stream)
+{
+    if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
+    void *ws = nullptr;
+    int rc = static_scratch_ptr(&ws);
+    if (rc) return rc;
+    // (the kernels initialise every part of the workspace that they read: nothing is left to clear here)
+    rc = bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
+                    lr, cores_out, nullptr, ws, STATIC_SCRATCH_BYTES, stream);
+    if (rc == TT_ERR_WORKSPACE)
+        return fail(TT_ERR_WORKSPACE, "this call needs more scratch memory than the %zu bytes of the static array "
+                    "(%zu positions, cache of %lld rows): use tt_emb_bwd_sgd with a workspace of "
+                    "tt_emb_bwd_sgd_workspace_bytes() bytes", STATIC_SCRATCH_BYTES, (size_t)L,
+                    (long long)(cache ? cache->K : 0));
+    return rc;
 }
 
 int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
