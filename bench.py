@@ -210,64 +210,94 @@ def main():
                          grad_cache=grad_cache, workspace=ws)
             B.tt_emb_sgd_update(shape, cores, grads, lr, cache=cache, grad_cache=grad_cache, zero_grad=True)
 
-    def timed(fn, count):
-        """ms per call of fn(i), count calls enqueued back to back between two events on the current stream."""
+    REPS = 5                                            # repetitions of every timed region: the median is reported
+
+    def sync_time(fn):
+        """ms between two events on the current stream around fn(), bracketed by synchronize() on both sides."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
-        for i in range(count):
-            fn(i)
+        fn()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / count
+        return e0.elapsed_time(e1)
 
-    def captured(fn, sequence=False):
-        """A HIP graph of POOL consecutive calls fn(0..POOL-1); replay() launches all of them.
+    def captured(fn, count, sequence=False):
+        """A HIP graph of the consecutive calls fn(0..count-1); replay() launches all of them.
         sequence: fn is told which call is the first and which the last of the graph (see step)."""
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for i in range(POOL):
+            for i in range(count):
                 if sequence:
-                    fn(i, first=i == 0, last=i == POOL - 1)
+                    fn(i, first=i == 0, last=i == count - 1)
                 else:
                     fn(i)
         return g
 
-    def timed_any(fn, count, sequence=False):
-        """ms per call of fn, either launched call by call or as replays of a POOL-call graph."""
+    def runner(fn, count, sequence=False):
+        """A function that enqueues EXACTLY count consecutive calls of fn: call by call, or as replays of a graph of
+        POOL calls plus one replay of a graph of the count % POOL calls that remain."""
         if args.launch == "stream":
-            return timed(fn, count)
-        g = captured(fn, sequence)
-        g.replay()
-        reps = max(1, count // POOL)
-        return timed(lambda i: g.replay(), reps) / POOL
+            def run():
+                for i in range(count):
+                    fn(i)
+            return run
+        whole, rest = divmod(count, POOL)
+        g_pool = captured(fn, POOL, sequence) if whole else None
+        g_rest = captured(fn, rest, sequence) if rest else None
+        for g in (g_pool, g_rest):
+            if g is not None:
+                g.replay()                                  # first replay: untimed
 
-    steps = max(POOL, (args.steps // POOL) * POOL)
+        def run():
+            for _ in range(whole):
+                g_pool.replay()
+            if g_rest is not None:
+                g_rest.replay()
+        return run
+
+    def timed_ms(fn, count, sequence=False):
+        """ms per call: REPS repetitions of exactly count calls each; returns (median, min, max)."""
+        run = runner(fn, count, sequence)
+        per = sorted(sync_time(run) / count for _ in range(REPS))
+        return per[REPS // 2], per[0], per[-1]
+
+    steps = max(1, args.steps)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_step = timed_any(step, steps, sequence=True)
+    ms_step, ms_step_min, ms_step_max = timed_ms(step, steps, sequence=True)
     wall = time.perf_counter() - t0
     value = L / (ms_step * 1e-3)
 
-    # per-kernel durations: each stage alone, launched back to back on the same stream
+    # per-kernel durations: each stage alone, launched back to back on the stream the step runs on
     reps = max(POOL * 16, min(steps, 4096))
-    ms_fwd = timed_any(lambda i: fwd_call(cores, i % POOL), reps)
+    ms_fwd = timed_ms(lambda i: fwd_call(cores, i % POOL), reps)[0]
     if args.step == "fused":
         # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
-        ms_bs = timed_any(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
-                                                     go[i % POOL], lr, alpha=alpha[i % POOL], cache=cache, workspace=ws,
-                                                     t0=t0_pool[i % POOL] if keep_t0 else None), reps)
+        ms_bs = timed_ms(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
+                                                    go[i % POOL], lr, alpha=alpha[i % POOL], cache=cache, workspace=ws,
+                                                    t0=t0_pool[i % POOL] if keep_t0 else None), reps)[0]
         stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
     else:
-        ms_bwd = timed_any(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads,
-                                                  alpha=alpha[i % POOL], cache=cache, grad_cache=grad_cache, workspace=ws), reps)
+        ms_bwd = timed_ms(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads,
+                                                 alpha=alpha[i % POOL], cache=cache, grad_cache=grad_cache, workspace=ws), reps)[0]
         for g in grads:
             g.zero_()
-        ms_sgd = timed_any(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, cache=cache, grad_cache=grad_cache,
-                                                         zero_grad=True), reps)
+        ms_sgd = timed_ms(lambda i: B.tt_emb_sgd_update(shape, cores, grads, 0.0, cache=cache, grad_cache=grad_cache,
+                                                        zero_grad=True), reps)[0]
         stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
+
+    # the same step with Alg. 2's recomputation instead of the stored intermediate, beside the headline
+    ms_recompute = None
+    if keep_t0:
+        def step_recompute(i):
+            j = i % POOL
+            cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
+            B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache, workspace=ws)
+        ms_recompute = timed_ms(step_recompute, min(steps, 20 * POOL))[0]
 
     # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
     b0 = batches_h[0].indices
@@ -278,17 +308,17 @@ def main():
     n_cached = int(np.isin(b0, keys_h).sum()) if keys_h is not None else 0
     ab = algorithmic_bytes(t, Ls[0], n_bags, touched, n_cached)
     af = algorithmic_flops(t, Ls[0] - n_cached, keep_t0)
-    if keep_t0:                                          # T0 is written once and read once per lookup
-        t0_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape)
-        ab["fwd"] += t0_bytes
-        ab["bwd_sgd"] += t0_bytes
+    # the stored intermediate is written once and read once per uncached lookup: an intermediate, not part of the
+    # method's algorithmic bytes, reported beside them
+    kept_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape) if keep_t0 else 0
     dominant = max(stage_ms, key=stage_ms.get)
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(args.workload if tab == 0 else None, {}).get(
                     "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
-                "algorithmic_bytes": ab[dominant], "avg_us": round(stage_ms[dominant] * 1e3, 3),
+                "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes,
+                "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms},
                 "fp32_tflops": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12, 3),
@@ -320,7 +350,8 @@ def main():
     print(json.dumps({
         "metric": "TT-EmbeddingBag fwd+bwd lookups/sec; % of HBM/fp32 roofline at R=32",
         "value": round(value, 1), "unit": "lookups/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_step, 6), "ms_per_step_min_max": [round(ms_step_min, 6), round(ms_step_max, 6)],
+        "repetitions": REPS, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d rows as %dx%dx%d, dim %d as %dx%dx%d, ranks (1,%d,%d,1), %d bags x %d index, "
                                "Zipf(%.2f)%s%s, fwd+bwd+SGD" % (wl.name, t.num_rows, *t.m, t.dim, *t.n, t.r[1], t.r[2],
@@ -329,7 +360,8 @@ def main():
                                                                 ", weights: %s" % args.weights if args.weights != "none" else ""),
                    "table": tab,
                    "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0),
-                   "prepass_on_second_stream": bool(two_calls), "prepass_one_step_ahead": bool(two_calls and args.launch == "graph"), "wall_s_timed_region": round(wall, 3)},
+                   "prepass_on_second_stream": bool(two_calls), "prepass_one_step_ahead": bool(two_calls and args.launch == "graph"), "wall_s_timed_region": round(wall, 3),
+                   "ms_per_step_recompute": None if ms_recompute is None else round(ms_recompute, 6)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 
