@@ -5,12 +5,15 @@ forward, backward and the SGD update of the cores, at the Kaggle-shaped R = 32
 configuration (10,131,227 rows as 200x220x250, dimension 16 as 2x2x4, 2048 bags
 of one index, Zipf(1.05) indices).  All inputs are resident in HBM before the
 timed region.  By default the backward pass and the SGD update are one call
-(two sets of cores used in turn) and the forward pass keeps its intermediate T0
-for the backward pass (tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0); --recompute
-uses tt_emb_fwd + tt_emb_bwd_sgd, --step separate times tt_emb_fwd + tt_emb_bwd
-+ tt_emb_sgd_update.  Prints ONE JSON line.
+(two sets of cores used in turn), the forward pass keeps its intermediate T0 for
+the backward pass, and where the library keeps per-slice position lists (short
+index lists of the (2,2,4) shapes) the lists of batch i + 1 are filed by riders
+of the backward launch of batch i (tt_emb_fwd_keep + tt_emb_bwd_sgd_kept);
+--no-lists uses tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0, --recompute tt_emb_fwd +
+tt_emb_bwd_sgd, --step separate tt_emb_fwd + tt_emb_bwd + tt_emb_sgd_update.
+Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32] [--step fused|separate] [--recompute]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload kaggle_r32] [--step fused|separate] [--recompute] [--no-lists]
 """
 
 from __future__ import annotations
@@ -89,6 +92,9 @@ def main():
                     help="the backward pass recomputes the forward's intermediate T0 (tt_emb_fwd / tt_emb_bwd_sgd) "
                          "instead of reading the copy that the forward pass stored "
                          "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0, the default of the fused step)")
+    ap.add_argument("--no-lists", action="store_true",
+                    help="fused step with the stored T0 but without the per-slice position lists filed ahead "
+                         "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0): every slice owner scans the index array itself")
     ap.add_argument("--offsets", choices=["csr", "none"], default="csr",
                     help="csr: bags given by an offsets array; none: the boundary's form for one index per bag "
                          "(offsets == NULL), for the workloads whose bags all hold one index")
@@ -164,11 +170,26 @@ def main():
     # one stored intermediate per batch of the pool (1 MB each at Kaggle R = 32)
     t0_pool = [torch.empty((max(Ls[j], 1), B.t0_floats(shape)), dtype=torch.float32, device=dev) for j in range(POOL)] if keep_t0 else None
 
+    # per-slice position lists filed ahead of the backward pass, where the library keeps them
+    use_lists = keep_t0 and not args.no_lists and K == 0 and all(B.kept_has_lists(shape, x) for x in Ls)
+    kept_pool = [torch.empty(B.kept_bytes(shape, Ls[j]), dtype=torch.uint8, device=dev) for j in range(POOL)] if use_lists else None
+
     def fwd_call(cur, j):
-        if keep_t0:
+        if use_lists:
+            B.tt_emb_fwd_keep(shape, cur, idx[j], off[j], n_bags, out, kept_pool[j], alpha=alpha[j], lists_ready=True)
+        elif keep_t0:
             B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], n_bags, out, t0_pool[j], alpha=alpha[j], cache=cache)
         else:
             B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
+
+    def bwd_sgd_call(cur, nxt, j, jn):
+        """Backward + SGD of batch j; with lists, riders of the launch file the lists of batch jn (the next one)."""
+        if use_lists:
+            B.tt_emb_bwd_sgd_kept(shape, cur, nxt, idx[j], off[j], n_bags, go[j], kept_pool[j], lr, alpha=alpha[j],
+                                  workspace=ws, next_batch=(idx[jn], kept_pool[jn]))
+        else:
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
+                             workspace=ws, t0=t0_pool[j] if keep_t0 else None)
 
     assert POOL % 2 == 0                                # so that every graph replay starts on the same set
 
@@ -202,8 +223,11 @@ def main():
                 prepare_on_side(i + 1)                      # next to this step's backward (measured: better than next to
             if two_calls:                                   # its forward); its workspace was last read by step i - 1
                 torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
-            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
-                             workspace=ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None, prepared=two_calls)
+                B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
+                                 workspace=ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None, prepared=True)
+            else:
+                # (a graph starts with batch 0 again: its last step files the lists of batch 0)
+                bwd_sgd_call(cur, nxt, j, 0 if last else (j + 1) % POOL)
         else:
             B.tt_emb_fwd(shape, cores, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
             B.tt_emb_bwd(shape, cores, idx[j], off[j], n_bags, go[j], grads, alpha=alpha[j], cache=cache,
@@ -263,8 +287,12 @@ def main():
         return per[REPS // 2], per[0], per[-1]
 
     steps = max(1, args.steps)
+    if use_lists:
+        B.tt_emb_kept_prepare(shape, idx[0], kept_pool[0])
     for i in range(args.warmup):
-        step(i)
+        step(i, last=False)
+    if use_lists:
+        B.tt_emb_kept_prepare(shape, idx[0], kept_pool[0])  # every timed graph starts with batch 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ms_step, ms_step_min, ms_step_max = timed_ms(step, steps, sequence=True)
@@ -276,9 +304,7 @@ def main():
     ms_fwd = timed_ms(lambda i: fwd_call(cores, i % POOL), reps)[0]
     if args.step == "fused":
         # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
-        ms_bs = timed_ms(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags,
-                                                    go[i % POOL], lr, alpha=alpha[i % POOL], cache=cache, workspace=ws,
-                                                    t0=t0_pool[i % POOL] if keep_t0 else None), reps)[0]
+        ms_bs = timed_ms(lambda i: bwd_sgd_call(cores, cores2, i % POOL, (i + 1) % POOL), reps)[0]
         stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
     else:
         ms_bwd = timed_ms(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads,
@@ -290,7 +316,7 @@ def main():
         stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
 
     # the same step with Alg. 2's recomputation instead of the stored intermediate, beside the headline
-    ms_recompute = None
+    ms_recompute, ms_stored_t0 = None, None
     if keep_t0:
         def step_recompute(i):
             j = i % POOL
@@ -298,6 +324,15 @@ def main():
             B.tt_emb_fwd(shape, cur, idx[j], off[j], n_bags, out, alpha=alpha[j], cache=cache)
             B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache, workspace=ws)
         ms_recompute = timed_ms(step_recompute, min(steps, 20 * POOL))[0]
+    if use_lists:
+        # ... and with the stored T0 but every slice owner scanning the index array itself (no lists filed ahead)
+        def step_stored_t0(i):
+            j = i % POOL
+            cur, nxt = (cores, cores2) if i % 2 == 0 else (cores2, cores)
+            B.tt_emb_fwd_keep_t0(shape, cur, idx[j], off[j], n_bags, out, t0_pool[j], alpha=alpha[j], cache=cache)
+            B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache, workspace=ws,
+                             t0=t0_pool[j])
+        ms_stored_t0 = timed_ms(step_stored_t0, min(steps, 20 * POOL))[0]
 
     # touched slices of one batch (host arithmetic on the synthetic indices, for the byte model only)
     b0 = batches_h[0].indices
@@ -311,13 +346,14 @@ def main():
     # the stored intermediate is written once and read once per uncached lookup: an intermediate, not part of the
     # method's algorithmic bytes, reported beside them
     kept_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape) if keep_t0 else 0
+    list_bytes = 3 * Ls[0] * 16 if use_lists else 0      # one 16-byte list entry per position and core
     dominant = max(stage_ms, key=stage_ms.get)
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(args.workload if tab == 0 else None, {}).get(
                     "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
-                "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes,
+                "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes, "kept_list_bytes": list_bytes,
                 "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms},
@@ -361,7 +397,9 @@ def main():
                    "table": tab,
                    "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0),
                    "prepass_on_second_stream": bool(two_calls), "prepass_one_step_ahead": bool(two_calls and args.launch == "graph"), "wall_s_timed_region": round(wall, 3),
-                   "ms_per_step_recompute": None if ms_recompute is None else round(ms_recompute, 6)},
+                   "lists_filed_ahead": bool(use_lists),
+                   "ms_per_step_recompute": None if ms_recompute is None else round(ms_recompute, 6),
+                   "ms_per_step_stored_t0_without_lists": None if ms_stored_t0 is None else round(ms_stored_t0, 6)},
         "roofline": roofline, "cpu_baseline": cpu}))
 
 

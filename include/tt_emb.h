@@ -211,6 +211,71 @@ int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], floa
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The stored-intermediate variant with the index work done ahead (Section 4.2, first paragraph;
+ * Eq. 4; Alg. 2).  tt_emb_fwd_keep is tt_emb_fwd that also leaves in `kept`, for the backward pass of
+ * the SAME batch (same shape, indices, L, offsets, n_bags, cache),
+ *   - T0 = G1[i1] G2[i2] of every position whose row is not cached, exactly as tt_emb_fwd_keep_t0
+ *     does (it sits at the start of the buffer), and
+ *   - for every core slice the list of the positions that touch it, in position order, with the
+ *     runs of equal rows marked (integer work on the indices; the encoding is private).
+ * With these a slice owner of the backward pass loads its list instead of scanning and decoding the
+ * whole index array, and the owners of the third core's slices read T0 instead of recomputing it.
+ * tt_emb_bwd_kept and tt_emb_bwd_sgd_kept are tt_emb_bwd and tt_emb_bwd_sgd given that buffer;
+ * results agree with theirs to rounding (sums are taken in another fixed order) and are
+ * bit-identical from run to run.
+ * kept:  device buffer of tt_emb_kept_bytes(shape, L) bytes, 16-byte aligned; written by the
+ *        forward call (and by whoever files the lists, see below), read by the backward call,
+ *        otherwise the caller's.  It begins with T0, fp32 [L][n1 n2][r[2]] (entries of cached
+ *        positions are not written); the rest (the lists) is private.
+ * Coverage: the lists exist for n = (2,2,4), equal ranks in {8,16,32}, L <= 8192 and
+ * m1 + m2 + m3 <= 1536, without cached positions in the backward; any other call with a
+ * specialised kernel keeps and uses T0 alone (exactly tt_emb_fwd_keep_t0 / tt_emb_bwd_t0 /
+ * tt_emb_bwd_sgd_t0, workspace rules included); TT_ERR_UNSUPPORTED for shapes without one.
+ * tt_emb_kept_bytes returns 0 for such shapes.  workspace: as for tt_emb_bwd / tt_emb_bwd_sgd
+ * (none is needed where the lists exist).
+ */
+size_t tt_emb_kept_bytes(const tt_shape_t *shape, int64_t L);
+/* 1 if lists are kept for such a call (see the coverage above), 0 if T0 alone or nothing is. */
+int tt_emb_kept_has_lists(const tt_shape_t *shape, int64_t L);
+int tt_emb_fwd_keep(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    const float *alpha, const tt_cache_t *cache,
+                    float *output, void *kept, size_t kept_bytes, int lists_ready, void *stream);
+
+/*
+ * The lists depend on the indices (and the cache's row map) alone, so they can be filed before the
+ * batch's forward pass: by tt_emb_kept_prepare (a small launch of its own), or by the backward call of
+ * the batch BEFORE, whose launch has room for the few workgroups that do it (`next`, below; a loader
+ * that is one batch ahead knows the indices).  lists_ready != 0 tells tt_emb_fwd_keep that `kept`
+ * already holds the lists of exactly these indices (same L, same cache); it then only adds T0.
+ * With lists_ready == 0 the call files them itself, in a second small launch behind the forward's.
+ * indices / L / kept / kept_bytes of tt_next_batch_t: as for tt_emb_fwd_keep (host struct; the kept
+ * buffer must differ from the current batch's).  Where no lists are kept for the next batch (see the
+ * coverage above) nothing is done for it.
+ */
+typedef struct tt_next_batch_t {
+    const int64_t *indices;
+    int64_t L;
+    void *kept;
+    size_t kept_bytes;
+} tt_next_batch_t;
+
+int tt_emb_kept_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t L, const tt_cache_t *cache,
+                        void *kept, size_t kept_bytes, void *stream);
+/* next == NULL: no next batch.  Otherwise its lists are in next->kept when the call's work is done. */
+int tt_emb_bwd_kept(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    const float *alpha, const tt_cache_t *cache,
+                    const float *grad_output, const void *kept, size_t kept_bytes,
+                    float *const grad_cores[3], float *grad_cache, const tt_next_batch_t *next,
+                    void *workspace, size_t workspace_bytes, void *stream);
+int tt_emb_bwd_sgd_kept(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                        const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                        const float *alpha, const tt_cache_t *cache,
+                        const float *grad_output, const void *kept, size_t kept_bytes, float lr,
+                        const tt_next_batch_t *next, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Backward pass and SGD step in one call (Section 3.1, Eq. 4; Alg. 2; Section 5):
  * cores_out = cores - lr * (gradient of <output, grad_output> for this batch), and,
  * with a cache, cache->rows -= lr * (gradient of the cached rows), in place
@@ -388,6 +453,19 @@ int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t
  */
 int tt_emb_debug_decode_as(const tt_shape_t *shape, const int64_t *indices, int64_t L, int mode,
                            int32_t *i1, int32_t *i2, int32_t *i3, void *stream);
+
+/*
+ * What the lists that tt_emb_fwd_keep left in `kept` say, for the bit-exact tests of that
+ * integer work (Section 3.1's digit map; the grouping that Alg. 2's "+=" implies).  For core
+ * r = 0, 1, 2 and position k (arrays int32 [3][L], device):
+ *   slice[r][k]: the slice of core r+1 whose list holds k (-1: none, a cached position),
+ *   rep[r][k]:   the entry's run marker resolved to a position: the first position with the same
+ *                row among the 256 positions [256 g, 256 (g+1)) that hold k,
+ *   times[r][k]: in how many lists of core r+1 position k was found (must be 1, or 0 if cached).
+ * TT_ERR_UNSUPPORTED where tt_emb_fwd_keep keeps no lists (see its coverage).
+ */
+int tt_emb_debug_kept_lists(const tt_shape_t *shape, const void *kept, size_t kept_bytes, int64_t L,
+                            int32_t *slice, int32_t *rep, int32_t *times, void *stream);
 
 /*
  * Canonical duplicate-free form of a key stream derived from `indices`:

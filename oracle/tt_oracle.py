@@ -247,6 +247,33 @@ def t0(shape: Shape, cores, row_id: int) -> np.ndarray:
     return (A @ Bm).reshape(n1 * n2, R2)
 
 
+def kept_lists(shape: Shape, indices, cached=None, chunk: Optional[int] = None):
+    """What the per-slice lists of a forward pass that keeps them must say about every position k (the grouping
+    that Alg. 2's "+=" into core slices implies, Section 3.1's digits): slice[r][k] = digit r of indices[k], and
+    rep[k] = the first position k' <= k of the same chunk of `chunk` consecutive positions with indices[k'] ==
+    indices[k] (cached positions, cached[k] true, are in no list: -1 and never a rep).  chunk defaults to
+    256.  Returns (slice int32 [3][L], rep int32 [L])."""
+    idx = np.asarray(indices, dtype=np.int64)
+    L = idx.size
+    if chunk is None:
+        chunk = 256
+    digits = decode(shape, idx)
+    sl = np.stack([np.asarray(d, dtype=np.int32) for d in digits])
+    rep = np.full(L, -1, dtype=np.int32)
+    for lo in range(0, L, chunk):
+        first = {}
+        for k in range(lo, min(L, lo + chunk)):
+            if cached is not None and cached[k]:
+                continue
+            r = int(idx[k])
+            if r not in first:
+                first[r] = k
+            rep[k] = first[r]
+    if cached is not None:
+        sl[:, np.asarray(cached, dtype=bool)] = -1
+    return sl, rep
+
+
 # ---- mean pooling (Section 4.1: a bag is pooled by summation or by averaging) --------------
 
 def mean_weights(offsets, alpha=None) -> np.ndarray:

@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -77,6 +77,14 @@ def lib():
         l.tt_emb_bwd_sgd_static.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, f32, vp]
         l.tt_emb_static_scratch_bytes.restype = C.c_size_t
         l.tt_emb_static_scratch_bytes.argtypes = []
+        l.tt_emb_kept_bytes.restype = C.c_size_t
+        l.tt_emb_kept_bytes.argtypes = [vp, i64]
+        l.tt_emb_kept_has_lists.argtypes = [vp, i64]
+        l.tt_emb_fwd_keep.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
+        l.tt_emb_kept_prepare.argtypes = [vp, vp, i64, vp, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_kept.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, vp, vp, vp, vp, C.c_size_t, vp]
+        l.tt_emb_bwd_sgd_kept.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, f32, vp, vp, C.c_size_t, vp]
+        l.tt_emb_debug_kept_lists.argtypes = [vp, vp, C.c_size_t, i64, vp, vp, vp, vp]
         l.tt_emb_bwd_prepare.argtypes = [vp, vp, i64, vp, i64, vp, C.c_int, vp, C.c_size_t, vp]
         l.tt_emb_bwd_has_prepass.argtypes = [vp, i64, i64, C.c_int]
         l.tt_emb_bwd_sgd_prepared.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
@@ -252,6 +260,89 @@ def tt_emb_bwd_prepare(shape: TTShape, indices: torch.Tensor, offsets: Optional[
     wsb = workspace.numel() if workspace is not None else 0
     _check(lib().tt_emb_bwd_prepare(C.byref(shape), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
                                     cache.ref() if cache else None, int(kept_t0), _ptr(workspace), wsb, _stream()))
+
+
+def kept_bytes(shape: TTShape, L: int) -> int:
+    return int(lib().tt_emb_kept_bytes(C.byref(shape), int(L)))
+
+
+def kept_has_lists(shape: TTShape, L: int) -> bool:
+    return bool(lib().tt_emb_kept_has_lists(C.byref(shape), int(L)))
+
+
+class TTNextBatch(C.Structure):
+    _fields_ = [("indices", C.c_void_p), ("L", C.c_int64), ("kept", C.c_void_p), ("kept_bytes", C.c_size_t)]
+
+
+def _next(next_batch):
+    """next_batch: None or (indices, kept) of the batch whose lists the call files as well."""
+    if next_batch is None:
+        return None
+    indices, kept = next_batch
+    _dev(indices, torch.int64)
+    _dev(kept, torch.uint8)
+    return C.byref(TTNextBatch(indices.data_ptr(), indices.numel(), kept.data_ptr(), kept.numel()))
+
+
+def tt_emb_kept_prepare(shape: TTShape, indices: torch.Tensor, kept: torch.Tensor, cache: Optional["Cache"] = None) -> None:
+    _dev(indices, torch.int64)
+    _dev(kept, torch.uint8)
+    _check(lib().tt_emb_kept_prepare(C.byref(shape), _ptr(indices), indices.numel(), cache.ref() if cache else None,
+                                     _ptr(kept), kept.numel(), _stream()))
+
+
+def tt_emb_fwd_keep(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                    n_bags: int, output: torch.Tensor, kept: torch.Tensor, alpha: Optional[torch.Tensor] = None,
+                    cache: Optional["Cache"] = None, lists_ready: bool = False) -> None:
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(output, torch.float32)
+    _dev(kept, torch.uint8)
+    _check(lib().tt_emb_fwd_keep(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                                 _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(kept), kept.numel(),
+                                 1 if lists_ready else 0, _stream()))
+
+
+def tt_emb_bwd_kept(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor, offsets: Optional[torch.Tensor],
+                    n_bags: int, grad_output: torch.Tensor, kept: torch.Tensor, grad_cores: Sequence[torch.Tensor],
+                    alpha: Optional[torch.Tensor] = None, cache: Optional["Cache"] = None,
+                    grad_cache: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                    next_batch=None) -> None:
+    _dev(indices, torch.int64)
+    _dev(grad_output, torch.float32)
+    _dev(kept, torch.uint8)
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_bwd_kept(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
+                                 _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output), _ptr(kept), kept.numel(),
+                                 _ptr_array(grad_cores), _ptr(grad_cache), _next(next_batch), _ptr(workspace), wsb, _stream()))
+
+
+def tt_emb_bwd_sgd_kept(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],
+                        indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int, grad_output: torch.Tensor,
+                        kept: torch.Tensor, lr: float, alpha: Optional[torch.Tensor] = None, cache: Optional["Cache"] = None,
+                        workspace: Optional[torch.Tensor] = None, next_batch=None) -> None:
+    _dev(indices, torch.int64)
+    _dev(grad_output, torch.float32)
+    _dev(kept, torch.uint8)
+    for k in range(3):
+        assert cores_out[k].numel() == cores[k].numel()
+    wsb = workspace.numel() if workspace is not None else 0
+    _check(lib().tt_emb_bwd_sgd_kept(C.byref(shape), _ptr_array(cores), _ptr_array(cores_out), _ptr(indices), indices.numel(),
+                                     _ptr(offsets), n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(grad_output),
+                                     _ptr(kept), kept.numel(), C.c_float(lr), _next(next_batch), _ptr(workspace), wsb,
+                                     _stream()))
+
+
+def tt_emb_debug_kept_lists(shape: TTShape, kept: torch.Tensor, L: int):
+    """(slice, rep, times), each int32 [3][L]."""
+    out = [torch.empty((3, L), dtype=torch.int32, device=kept.device) for _ in range(3)]
+    _check(lib().tt_emb_debug_kept_lists(C.byref(shape), _ptr(kept), kept.numel(), int(L), _ptr(out[0]), _ptr(out[1]),
+                                         _ptr(out[2]), _stream()))
+    return out
 
 
 def tt_emb_bwd_sgd_static(shape: TTShape, cores: Sequence[torch.Tensor], cores_out: Sequence[torch.Tensor],

@@ -16,6 +16,7 @@
 #include "tt_generic.h"
 #include "tt_fast.h"
 #include "tt_fast_bwd.h"
+#include "tt_kept.h"
 #include "tt_group.h"
 #include "tt_freq.h"
 #include "tt_dense.h"
@@ -527,6 +528,187 @@ int tt_emb_bwd_sgd_t0(const tt_shape_t *shape, const float *const cores[3], floa
     if (L > 0 && !t0) return fail(TT_ERR_NULL, "t0 is NULL");
     return bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, nullptr, nullptr,
                       lr, cores_out, t0, workspace, workspace_bytes, stream);
+}
+
+// ---- forward and backward with the kept partial products and lists (tt_kept.h) ----
+
+size_t tt_emb_kept_bytes(const tt_shape_t *shape, int64_t L)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L < 0 || L >= (1ll << 31) || fast_config(p) < 0) return 0;
+    if (kept_supported(p, L)) return kept_layout(p, L).bytes;
+    return align256((size_t)(L > 0 ? L : 1) * p.n1 * p.cols * sizeof(float));       // T0 alone
+}
+
+int tt_emb_kept_has_lists(const tt_shape_t *shape, int64_t L)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L < 0) return 0;
+    return kept_supported(p, L) ? 1 : 0;
+}
+
+int tt_emb_fwd_keep(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    const float *alpha, const tt_cache_t *cache,
+                    float *output, void *kept, size_t kept_bytes, int lists_ready, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps intermediates for this shape");
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    const size_t need = tt_emb_kept_bytes(shape, L);
+    if (L > 0 && (!kept || kept_bytes < need))
+        return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", need, kept_bytes);
+    // T0 at the start of the buffer, by the forward kernel that keeps it
+    rc = fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, (float *)kept, true, stream);
+    if (rc || !kept_supported(p, L) || lists_ready) return rc;
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, false))) return rc;
+    kept_sort(p, indices, (int)L, cd, kept_dev(kept, kept_layout(p, L)), (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "list launch");
+}
+
+// Checks the description of a batch whose lists are to be filed; *kd_out gets its layout if lists exist for it
+// (*has = true), else nothing is to be done for it.
+static int check_next(const Params &p, const int64_t *indices, int64_t L, void *kept, size_t kept_bytes, const tt_shape_t *shape,
+                      KeptDev *kd_out, bool *has)
+{
+    *has = false;
+    if (L < 0) return fail(TT_ERR_BAD_ARG, "negative L");
+    if (L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L >= 2^31");
+    if (!kept_supported(p, L)) return TT_OK;
+    if (!indices) return fail(TT_ERR_NULL, "indices is NULL");
+    const size_t need = tt_emb_kept_bytes(shape, L);
+    if (!kept || kept_bytes < need) return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", need, kept_bytes);
+    if (misaligned({kept})) return fail(TT_ERR_BAD_ARG, "the kept buffer must be 16-byte aligned");
+    *kd_out = kept_dev(kept, kept_layout(p, L));
+    *has = true;
+    return TT_OK;
+}
+
+int tt_emb_kept_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t L, const tt_cache_t *cache,
+                        void *kept, size_t kept_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps intermediates for this shape");
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, false))) return rc;
+    KeptDev kd;
+    bool has;
+    if ((rc = check_next(p, indices, L, kept, kept_bytes, shape, &kd, &has))) return rc;
+    if (!has) return TT_OK;
+    kept_sort(p, indices, (int)L, cd, kd, (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "list launch");
+}
+
+// tt_emb_bwd_kept (cores_out == nullptr) and tt_emb_bwd_sgd_kept
+static int bwd_kept_common(const tt_shape_t *shape, const float *const cores[3], const int64_t *indices, int64_t L,
+                           const int64_t *offsets, int64_t n_bags, const float *alpha, const tt_cache_t *cache,
+                           const float *grad_output, const void *kept, size_t kept_bytes, float *const grad_cores[3],
+                           float *grad_cache, float lr, float *const cores_out[3], const tt_next_batch_t *next,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel uses kept intermediates for this shape");
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    const size_t need = tt_emb_kept_bytes(shape, L);
+    if (L > 0 && (!kept || kept_bytes < need))
+        return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", need, kept_bytes);
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, false))) return rc;
+    KpNext nx{nullptr, 0, 0, KeptDev{}};
+    if (next) {
+        bool has;
+        if ((rc = check_next(p, next->indices, next->L, next->kept, next->kept_bytes, shape, &nx.kd, &has))) return rc;
+        if (has) {
+            nx.indices = next->indices;
+            nx.L = (int)next->L;
+            nx.n_sort = nx.kd.G;
+        }
+    }
+    const bool fused = cores_out != nullptr;
+    if (!kept_supported(p, L) || cd.K) {                                    // the kept T0 sits at the start of the buffer
+        rc = bwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, grad_cores, grad_cache, lr,
+                        cores_out, L > 0 ? (const float *)kept : nullptr, workspace, workspace_bytes, stream);
+        if (rc || !nx.n_sort) return rc;
+        kept_sort(p, nx.indices, nx.L, cd, nx.kd, (hipStream_t)stream);     // no launch to ride along with: one of their own
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? TT_OK : hip_fail(e, "list launch");
+    }
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (fused) {
+        if (!cores_out[0] || !cores_out[1] || !cores_out[2]) return fail(TT_ERR_NULL, "cores_out is NULL");
+        for (int k = 0; k < 3; ++k)
+            if (cores_out[k] == cores[k]) return fail(TT_ERR_BAD_ARG, "cores_out must not alias cores");
+    } else if (!grad_cores || !grad_cores[0] || !grad_cores[1] || !grad_cores[2]) {
+        return fail(TT_ERR_NULL, "grad_cores is NULL");
+    }
+    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (misaligned({cores[0], cores[1], cores[2], grad_output, kept}) ||
+        (fused ? misaligned({cores_out[0], cores_out[1], cores_out[2]})
+               : misaligned({grad_cores[0], grad_cores[1], grad_cores[2]})))
+        return fail(TT_ERR_BAD_ARG, "cores, gradients and kept buffer must be 16-byte aligned");
+    if (offsets && n_bags > 0 && L % n_bags == 0) {                         // a guess for the bag of a position
+        p.bagP = (uint32_t)(L / n_bags);
+        p.mgP = p.bagP > 1 ? (uint32_t)(((1ull << 32) + p.bagP - 1) / (uint64_t)p.bagP) : 0u;
+    }
+    const KeptDev kd = kept_dev(const_cast<void *>(kept), kept_layout(p, L));
+    kept_bwd(p, cores[0], cores[1], cores[2], (int)L, offsets, (int)n_bags, alpha, grad_output,
+             fused ? nullptr : grad_cores[0], fused ? nullptr : grad_cores[1], fused ? nullptr : grad_cores[2], lr,
+             fused ? cores_out[0] : nullptr, fused ? cores_out[1] : nullptr, fused ? cores_out[2] : nullptr, kd, cd, nx,
+             (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "backward launch");
+}
+
+int tt_emb_bwd_kept(const tt_shape_t *shape, const float *const cores[3],
+                    const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    const float *alpha, const tt_cache_t *cache,
+                    const float *grad_output, const void *kept, size_t kept_bytes,
+                    float *const grad_cores[3], float *grad_cache, const tt_next_batch_t *next,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_kept_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, kept, kept_bytes, grad_cores,
+                           grad_cache, 0.f, nullptr, next, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_bwd_sgd_kept(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
+                        const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                        const float *alpha, const tt_cache_t *cache,
+                        const float *grad_output, const void *kept, size_t kept_bytes, float lr,
+                        const tt_next_batch_t *next, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cores_out) return fail(TT_ERR_NULL, "cores_out is NULL");
+    return bwd_kept_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, grad_output, kept, kept_bytes, nullptr,
+                           nullptr, lr, cores_out, next, workspace, workspace_bytes, stream);
+}
+
+int tt_emb_debug_kept_lists(const tt_shape_t *shape, const void *kept, size_t kept_bytes, int64_t L,
+                            int32_t *slice, int32_t *rep, int32_t *times, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if (!kept_supported(p, L)) return fail(TT_ERR_UNSUPPORTED, "no lists are kept for this shape and length");
+    if (!kept || !slice || !rep || !times) return fail(TT_ERR_NULL, "NULL array");
+    const KeptLayout kl = kept_layout(p, L);
+    if (kept_bytes < kl.bytes) return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", kl.bytes, kept_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = 3 * L;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, slice, n, -1);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, rep, n, -1);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(cdiv(n, WG) < 1024 ? cdiv(n, WG) : 1024), dim3(WG), 0, st, times, n, 0);
+    hipLaunchKernelGGL(kept_lists_export_kernel, dim3(kl.nbins), dim3(WG), 0, st, p, kept_dev(const_cast<void *>(kept), kl), (int)L,
+                       slice, rep, times);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "list export launch");
 }
 
 int tt_emb_bwd_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,

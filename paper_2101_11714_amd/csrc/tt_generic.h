@@ -270,6 +270,11 @@ __global__ __launch_bounds__(WG) void sgd_kernel(SgdArgs a, float lr, int zero_g
     }
 }
 
+__global__ __launch_bounds__(WG) void fill_i32_kernel(int32_t *__restrict__ p, int64_t n, int32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;
+}
+
 __global__ __launch_bounds__(WG) void fill_f32_kernel(float *__restrict__ p, int64_t n, float v)
 {
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;

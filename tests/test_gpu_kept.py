@@ -1,0 +1,269 @@
+"""GPU parity of the path that keeps T0 from the forward pass and files per-slice lists ahead of the backward pass
+(tt_emb_fwd_keep, tt_emb_bwd_kept, tt_emb_bwd_sgd_kept), through the C ABI, against the CPU oracle."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tt_oracle as ora
+from paper_2101_11714_amd import binding as B
+from paper_2101_11714_amd import workloads as W
+from gpu_util import DeviceTable, assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+KEPT = ["tiny", "kaggle_r32", "sweep_r8", "sweep_r16", "sweep_r32", "sweep_r64"]     # (sweep_r64: the stored-T0 fallback)
+LISTS = KEPT[:-1]
+
+
+class Kept:
+    """One forward pass that keeps, and views of what it kept."""
+
+    def __init__(self, d: DeviceTable, cache=None, use_offsets=True, poison=True):
+        self.d = d
+        nbytes = B.kept_bytes(d.shape, d.L)
+        self.buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev())
+        if poison:
+            self.buf.fill_(0xFF)                                    # stale bits everywhere: NaNs, huge counts
+        self.out = torch.full((d.n_bags, d.t.dim), float("nan"), dtype=torch.float32, device=dev())
+        self.off = d.off if use_offsets else None
+        B.tt_emb_fwd_keep(d.shape, d.g, d.idx, self.off, d.n_bags, self.out, self.buf, alpha=d.alpha, cache=cache)
+        torch.cuda.synchronize()
+
+    def t0(self):
+        n = B.t0_floats(self.d.shape)
+        return self.buf[: self.d.L * n * 4].view(torch.float32).view(self.d.L, n)
+
+    def bwd(self, cache=None):
+        d = self.d
+        grads = [torch.zeros_like(x) for x in d.g]
+        gc = torch.zeros_like(cache.rows) if cache is not None else None
+        ws = torch.empty(max(256, B.workspace_bytes(d.shape, d.L, d.n_bags, cache.K if cache is not None else 0)),
+                         dtype=torch.uint8, device=dev())
+        B.tt_emb_bwd_kept(d.shape, d.g, d.idx, self.off, d.n_bags, d.go, self.buf, grads, alpha=d.alpha, cache=cache,
+                          grad_cache=gc, workspace=ws)
+        torch.cuda.synchronize()
+        return grads, gc
+
+    def bwd_sgd(self, lr, cache=None):
+        d = self.d
+        out = [torch.full_like(x, float("nan")) for x in d.g]
+        ws = torch.empty(max(256, B.bwd_sgd_workspace_bytes(d.shape, d.L, d.n_bags, cache.K if cache is not None else 0)),
+                         dtype=torch.uint8, device=dev())
+        B.tt_emb_bwd_sgd_kept(d.shape, d.g, out, d.idx, self.off, d.n_bags, d.go, self.buf, lr, alpha=d.alpha, cache=cache,
+                              workspace=ws)
+        torch.cuda.synchronize()
+        return out
+
+
+def _check_backward(d, kp, what, lr=0.1):
+    rg, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    grads, _ = kp.bwd()
+    for k in range(3):
+        assert_close(grads[k].cpu().numpy(), rg[k], "%s dG%d" % (what, k + 1))
+    new = kp.bwd_sgd(lr)
+    for k in range(3):
+        ref = ora.sgd(d.cores[k], rg[k].astype(np.float32), lr)
+        assert_close(new[k].cpu().numpy(), ref, "%s cores after the fused step, core %d" % (what, k + 1))
+        # the fused step is the same arithmetic as the gradient followed by x - lr g
+        two = (d.g[k].double() - lr * grads[k].double()).float()
+        assert_close(new[k].cpu().numpy(), two.cpu().numpy(), "%s fused vs separate, core %d" % (what, k + 1))
+    return grads, new
+
+
+@pytest.mark.parametrize("name", KEPT)
+def test_kept_forward_output_and_t0(name):
+    d = DeviceTable(W.WORKLOADS[name])
+    kp = Kept(d)
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, alpha=d.batch.alpha)
+    assert_close(kp.out.cpu().numpy(), ref, name + " forward that keeps")
+    rng = np.random.default_rng(7)
+    pick = np.unique(np.concatenate([[0, d.L - 1], rng.integers(0, d.L, 200)]))
+    t0 = kp.t0().cpu().numpy()[pick]
+    want_t0 = np.stack([ora.t0(d.oshape, d.cores, int(d.batch.indices[k])).reshape(-1) for k in pick])
+    assert_close(t0, want_t0, name + " kept T0")
+
+
+@pytest.mark.parametrize("name", LISTS)
+def test_kept_lists_bit_exact(name):
+    d = DeviceTable(W.WORKLOADS[name])
+    kp = Kept(d)
+    sl, rep, times = (x.cpu().numpy() for x in B.tt_emb_debug_kept_lists(d.shape, kp.buf, d.L))
+    want_sl, want_rep = ora.kept_lists(d.oshape, d.batch.indices)
+    assert np.all(times == 1)
+    assert np.array_equal(sl, want_sl)
+    for r in range(3):
+        assert np.array_equal(rep[r], want_rep)
+
+
+@pytest.mark.parametrize("name", KEPT)
+def test_kept_backward_and_fused_step_match_oracle(name):
+    d = DeviceTable(W.WORKLOADS[name])
+    kp = Kept(d)
+    grads, new = _check_backward(d, kp, name, W.WORKLOADS[name].lr)
+    # a second forward files the lists in another order (atomics); the results must not change by a bit
+    for _ in range(2):
+        kp2 = Kept(d, poison=False)
+        g2, _ = kp2.bwd()
+        n2 = kp2.bwd_sgd(W.WORKLOADS[name].lr)
+        for k in range(3):
+            assert torch.equal(g2[k], grads[k]) and torch.equal(n2[k], new[k])
+    if d.L == d.n_bags:                                              # one index per bag: offsets may be omitted
+        kp3 = Kept(d, use_offsets=False)
+        g3, _ = kp3.bwd()
+        for k in range(3):
+            assert torch.equal(g3[k], grads[k])
+
+
+def _custom(wl, idx, lens, seed, with_alpha=True):
+    t = wl.tables[0]
+    rng = np.random.default_rng(seed)
+    off = np.zeros(len(lens) + 1, dtype=np.int64)
+    np.cumsum(np.asarray(lens, dtype=np.int64), out=off[1:])
+    assert off[-1] == idx.size
+    alpha = (0.5 + rng.random(idx.size)).astype(np.float32) if with_alpha else None
+    return W.Batch(np.asarray(idx, dtype=np.int64), off, rng.standard_normal((len(lens), t.dim)).astype(np.float32), alpha)
+
+
+def test_kept_ragged_weighted_empty_bags_and_long_runs():
+    wl = W.WORKLOADS["tiny"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(5)
+    lens = [0, 3, 0, 0, 1, 70, 2, 0, 300, 1, 0, 130]
+    idx = rng.integers(0, t.num_rows, sum(lens))
+    idx[10:60] = 77                                        # a long run of one row
+    idx[100:400:2] = 512                                   # a run of 150 spread over the positions: long-list path
+    d = DeviceTable(wl, batch=_custom(wl, idx, lens, 6))
+    kp = Kept(d)
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, alpha=d.batch.alpha)
+    assert_close(kp.out.cpu().numpy(), ref, "ragged forward that keeps")
+    assert np.all(kp.out.cpu().numpy()[np.asarray(lens) == 0] == 0)
+    _check_backward(d, kp, "ragged")
+    sl, rep, times = (x.cpu().numpy() for x in B.tt_emb_debug_kept_lists(d.shape, kp.buf, d.L))
+    want_sl, want_rep = ora.kept_lists(d.oshape, d.batch.indices)
+    assert np.all(times == 1) and np.array_equal(sl, want_sl) and np.array_equal(rep[0], want_rep)
+
+
+@pytest.mark.parametrize("name,L", [("kaggle_r32", 8192), ("kaggle_r32", 5000), ("sweep_r64", 1), ("sweep_r8", 257),
+                                    ("kaggle_r32", 2049)])
+def test_kept_sizes_up_to_the_limit(name, L):
+    wl = W.WORKLOADS[name]
+    t = wl.tables[0]
+    rng = np.random.default_rng(L)
+    base = W.make_batch(wl, 0, 3).indices
+    idx = base[rng.integers(0, base.size, L)]              # the workload's row popularity
+    d = DeviceTable(wl, batch=_custom(wl, idx, [1] * L, L, with_alpha=False))
+    kp = Kept(d)
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets)
+    assert_close(kp.out.cpu().numpy(), ref, "forward that keeps, L = %d" % L)
+    _check_backward(d, kp, "L = %d" % L)
+
+
+def test_kept_adversarial_identity_map_and_one_row():
+    """All hot rows share their first two digits (lists of hundreds of entries, several rounds), and a
+    batch of one single row (every list is the whole batch)."""
+    wl = W.WORKLOADS["kaggle_r32"]
+    t = wl.tables[0]
+    rng = np.random.default_rng(9)
+    zipf = np.minimum((rng.pareto(0.3, 3000)).astype(np.int64), t.num_rows - 1)     # many small row ids
+    d = DeviceTable(wl, batch=_custom(wl, zipf, [1] * zipf.size, 10))
+    _check_backward(d, Kept(d), "identity map")
+    one = np.full(1500, 4242421, dtype=np.int64)
+    d = DeviceTable(wl, batch=_custom(wl, one, [1] * one.size, 11))
+    _check_backward(d, Kept(d), "one row")
+
+
+@pytest.mark.parametrize("name,L", [("kaggle_r32", 2048), ("sweep_r16", 4096), ("kaggle_r32", 7000)])
+def test_kept_lists_filed_ahead_by_prepare_or_by_the_previous_backward(name, L):
+    wl = W.WORKLOADS[name]
+    rng = np.random.default_rng(L + 1)
+    base = np.concatenate([W.make_batch(wl, 0, s).indices for s in range(4)])
+    mk = lambda seed: DeviceTable(wl, batch=_custom(wl, base[np.random.default_rng(seed).integers(0, base.size, L)], [1] * L, seed,
+                                                    with_alpha=False))
+    d1, d2 = mk(1), mk(2)
+    ref = Kept(d2)                                                   # batch 2 on its own: the forward files its lists itself
+    ref_lists = [x.cpu() for x in B.tt_emb_debug_kept_lists(d2.shape, ref.buf, d2.L)]
+    ref_new = ref.bwd_sgd(0.05)
+    for how in ("prepare", "previous_backward"):
+        buf2 = torch.empty(B.kept_bytes(d2.shape, d2.L), dtype=torch.uint8, device=dev())
+        buf2.fill_(0xFF)
+        if how == "prepare":
+            B.tt_emb_kept_prepare(d2.shape, d2.idx, buf2)
+        else:
+            k1 = Kept(d1)
+            alone = k1.bwd_sgd(0.05)
+            out1 = [torch.full_like(x, float("nan")) for x in d1.g]
+            B.tt_emb_bwd_sgd_kept(d1.shape, d1.g, out1, d1.idx, d1.off, d1.n_bags, d1.go, k1.buf, 0.05, next_batch=(d2.idx, buf2))
+            torch.cuda.synchronize()
+            for k in range(3):
+                assert torch.equal(out1[k], alone[k])                 # the riders change nothing of the call's own result
+        lists = [x.cpu() for x in B.tt_emb_debug_kept_lists(d2.shape, buf2, d2.L)]
+        for a, b in zip(lists, ref_lists):
+            assert torch.equal(a, b), how
+        out = torch.full((d2.n_bags, d2.t.dim), float("nan"), dtype=torch.float32, device=dev())
+        B.tt_emb_fwd_keep(d2.shape, d2.g, d2.idx, d2.off, d2.n_bags, out, buf2, lists_ready=True)
+        assert torch.equal(out, ref.out)
+        new = [torch.full_like(x, float("nan")) for x in d2.g]
+        B.tt_emb_bwd_sgd_kept(d2.shape, d2.g, new, d2.idx, d2.off, d2.n_bags, d2.go, buf2, 0.05)
+        torch.cuda.synchronize()
+        for k in range(3):
+            assert torch.equal(new[k], ref_new[k]), how
+
+
+def test_kept_with_cache_falls_back_for_the_backward():
+    wl = W.WORKLOADS["tiny"]
+    d = DeviceTable(wl)
+    rows = np.arange(0, 1000, 7, dtype=np.int64)
+    counts = np.arange(rows.size, 0, -1, dtype=np.int64)
+    K = 60
+    cache, _, _ = d.build_cache(K, rows, counts)
+    keys = ora.cache_select(rows, counts, K)
+    crow = (cache.rows.cpu().numpy() * 1.5).astype(np.float32)       # lines that differ from the cores
+    cache.rows.copy_(torch.from_numpy(crow))
+    kp = Kept(d, cache=cache)
+    ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, cache_keys=keys, cache_rows=crow)
+    assert_close(kp.out.cpu().numpy(), ref, "cached forward that keeps")
+    cached = ora.cache_lookup(d.oshape, keys, d.batch.indices) >= 0
+    assert cached.any() and not cached.all()
+    sl, rep, times = (x.cpu().numpy() for x in B.tt_emb_debug_kept_lists(d.shape, kp.buf, d.L))
+    want_sl, want_rep = ora.kept_lists(d.oshape, d.batch.indices, cached=cached)
+    assert np.array_equal(times[0], (~cached).astype(np.int32)) and np.array_equal(sl, want_sl)
+    assert np.array_equal(rep[1], want_rep)
+    grads, gc = kp.bwd(cache=cache)
+    rg, rc = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, cache_keys=keys)
+    for k in range(3):
+        assert_close(grads[k].cpu().numpy(), rg[k], "cached dG%d" % (k + 1))
+    assert_close(gc.cpu().numpy()[:K], rc, "dCache")
+
+
+def test_kept_falls_back_to_the_stored_t0_for_other_shapes():
+    wl = W.WORKLOADS["terabyte_r64"]
+    d = DeviceTable(wl)
+    kp = Kept(d, poison=False)
+    out0, t0 = d.fwd_keep_t0()
+    assert np.array_equal(kp.out.cpu().numpy(), out0)
+    assert torch.equal(kp.t0(), t0)
+    a = kp.bwd_sgd(0.05)
+    b = d.bwd_sgd(0.05, t0=t0)
+    for k in range(3):
+        assert torch.equal(a[k], b[k])
+
+
+def test_kept_rejects_bad_arguments():
+    wl = W.WORKLOADS["kaggle_r32"]
+    d = DeviceTable(wl)
+    out = torch.empty((d.n_bags, d.t.dim), dtype=torch.float32, device=dev())
+    small = torch.empty(1024, dtype=torch.uint8, device=dev())
+    with pytest.raises(B.TTError) as e:
+        B.tt_emb_fwd_keep(d.shape, d.g, d.idx, d.off, d.n_bags, out, small)
+    assert e.value.code == -4
+    odd = B.make_shape(1000, (10, 10, 10), (2, 3, 4), (1, 5, 5, 1))
+    assert B.kept_bytes(odd, 100) == 0
+    # no positions at all: the fused step copies the cores
+    empty = W.Batch(np.zeros(0, np.int64), np.zeros(4, np.int64), np.zeros((3, d.t.dim), np.float32), None)
+    d0 = DeviceTable(wl, batch=empty)
+    kp = Kept(d0)
+    assert float(kp.out.abs().max()) == 0.0
+    new = kp.bwd_sgd(0.1)
+    for k in range(3):
+        assert torch.equal(new[k], d0.g[k])

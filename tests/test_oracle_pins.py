@@ -443,6 +443,27 @@ def test_stored_intermediate_times_last_core_is_the_row():
         assert np.allclose(T0, ref, rtol=1e-13, atol=1e-13)
 
 
+def test_kept_lists_against_brute_force():
+    shape = ora.Shape(1000, (10, 10, 10), (2, 2, 4), (1, 8, 8, 1))
+    rng = np.random.default_rng(53)
+    idx = rng.integers(0, 40, 700).astype(np.int64) * 25 + 3          # many repeats
+    cached = rng.random(700) < 0.2
+    sl, rep = ora.kept_lists(shape, idx, cached=cached, chunk=256)
+    for k in range(700):
+        if cached[k]:
+            assert rep[k] == -1 and (sl[:, k] == -1).all()
+            continue
+        assert sl[0, k] * 100 + sl[1, k] * 10 + sl[2, k] == idx[k]      # decimal digits of the row
+        lo = (k // 256) * 256
+        same = [q for q in range(lo, k + 1) if idx[q] == idx[k] and not cached[q]]
+        assert rep[k] == same[0]
+    sl2, rep2 = ora.kept_lists(shape, idx)                               # default chunk for 700 positions: 256; nothing cached
+    assert np.array_equal(sl2, np.stack(ora.decode(shape, idx)).astype(np.int32))
+    _, first = np.unique(idx[:256], return_index=True)
+    assert np.array_equal(np.flatnonzero(rep2[:256] == np.arange(256)), np.sort(first))   # the reps are the first occurrences
+    assert np.array_equal(idx[rep2], idx) and np.all(rep2 <= np.arange(700)) and np.all(rep2 // 256 == np.arange(700) // 256)
+
+
 def test_mean_pooling_matches_library_mean_mode():
     wl, shape, cores, batch = tiny()
     w = torch.from_numpy(dense_table(shape, cores))
