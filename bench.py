@@ -31,15 +31,39 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 POOL = 16                      # distinct batches cycled through, so caches see a stream
 
-# HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
-# scaled by what the counter reads for a 256 MiB copy (factors 2.000 and 1.000); the runs and figures
-# are in profiles/hbm_traffic_bench_kaggle_r32.md.  Only valid for the workload they were taken on.
-MEASURED_TRAFFIC = {"kaggle_r32": {"keep_t0": {"fwd": 11.00e6, "bwd_sgd": 13.08e6},
-                                   "recompute": {"fwd": 9.93e6, "bwd_sgd": 15.42e6},
-                                   "separate": {"fwd": 9.93e6, "bwd": 16.84e6, "sgd": 7.96e6}},
-                    # profiles/hbm_traffic_bench_terabyte_multihot.md (multihot_cache: table 0 only)
-                    "terabyte_r64": {"keep_t0": {"fwd": 128.6e6, "bwd_sgd": 330.4e6}},
-                    "multihot_cache": {"keep_t0": {"fwd": 153.4e6, "bwd_sgd": 190.1e6}}}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.md")
+
+
+def measured_traffic(workload, table, variant, stage):
+    """HBM bytes per launch (read + written) of one stage, from the tracked table of rocprofv3 counter runs
+    (FETCH_SIZE / WRITE_SIZE, each scaled by what the counter reads for a copy of known size).  The table names the
+    commit and the commands it was taken with; a figure is only valid for the workload and variant of its row.
+    None if the table has no such row."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 7 and cells[0] == workload and cells[1] == str(table) and cells[2] == variant and cells[3] == stage:
+                    return float(cells[6]) * 1e6
+    except OSError:
+        pass
+    return None
+
+
+def pmc_means(dirs):
+    """Mean counter value per kernel from rocprofv3 --pmc csv output (the figures the traffic table is made of)."""
+    import collections, csv, glob
+    for d in dirs:
+        for path in sorted(glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)):
+            acc = collections.defaultdict(lambda: [0.0, 0])
+            with open(path) as f:
+                for r in csv.DictReader(f):
+                    k = (r["Kernel_Name"][:90], r["Counter_Name"])
+                    acc[k][0] += float(r["Counter_Value"])
+                    acc[k][1] += 1
+            print(path)
+            for k, (tot, n) in sorted(acc.items(), key=lambda kv: -kv[1][0]):
+                print("  %-90s %-12s dispatches=%5d mean=%12.1f" % (k[0], k[1], n, tot / n))
 
 
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published
@@ -92,6 +116,9 @@ def main():
                     help="the backward pass recomputes the forward's intermediate T0 (tt_emb_fwd / tt_emb_bwd_sgd) "
                          "instead of reading the copy that the forward pass stored "
                          "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0, the default of the fused step)")
+    ap.add_argument("--pmc-means", nargs="+", metavar="DIR",
+                    help="no benchmark: print the mean counter value per kernel from rocprofv3 --pmc csv output under "
+                         "the given folders")
     ap.add_argument("--no-lists", action="store_true",
                     help="fused step with the stored T0 but without the per-slice position lists filed ahead "
                          "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0): every slice owner scans the index array itself")
@@ -118,6 +145,9 @@ def main():
     from paper_2101_11714_amd import binding as B
     from paper_2101_11714_amd import workloads as W
 
+    if args.pmc_means:
+        pmc_means(args.pmc_means)
+        return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     if args.copy_calibration:
@@ -348,11 +378,12 @@ def main():
     kept_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape) if keep_t0 else 0
     list_bytes = 3 * Ls[0] * 16 if use_lists else 0      # one 16-byte list entry per position and core
     dominant = max(stage_ms, key=stage_ms.get)
+    variant = "lists" if use_lists else ("keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"))
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get(args.workload if tab == 0 else None, {}).get(
-                    "keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"), {}).get(dominant),
+                "traffic": measured_traffic(args.workload, tab, variant, dominant),
+                "traffic_source": "profiles/hbm_traffic_table.md, row (%s, %d, %s, %s)" % (args.workload, tab, variant, dominant),
                 "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes, "kept_list_bytes": list_bytes,
                 "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
@@ -382,6 +413,30 @@ def main():
         cpu = {"value": round(done * L / spent, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
                "sample": "%d whole steps (fwd+bwd+sgd) over the same pool of %d-lookup batches, %.1f s, single thread, fp64"
                          % (done, L, spent)}
+        # secondary figure: the forward pass alone, on one thread and with the bags shared out among the host threads
+        # this process may use (the backward keeps its one defined accumulation order, so it stays on one thread)
+        want = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+
+        def fwd_rate(threads):
+            n, t_spent, ran = 0, 0.0, 1
+            while n < 1 or (t_spent < 3.0 and n < 256 * POOL):
+                b = batches_h[n % POOL]
+                s0 = time.perf_counter()
+                if threads == 1:
+                    ora.fwd(oshape, oc, b.indices, b.offsets, alpha=al_h[n % POOL], cache_keys=keys_h, cache_rows=crow)
+                else:
+                    ran = ora.fwd_threads(oshape, oc, b.indices, b.offsets, threads, alpha=al_h[n % POOL], cache_keys=keys_h,
+                                          cache_rows=crow)[1]
+                t_spent += time.perf_counter() - s0
+                n += 1
+            return round(n * L / t_spent, 1), ran, n
+
+        f1, _, n1 = fwd_rate(1)
+        fn, ran, nn = fwd_rate(want)
+        cpu["forward_only"] = {"value": f1, "unit": "lookups/s", "cores": 1, "sample": "%d forward passes, single thread" % n1}
+        cpu["forward_only_openmp"] = {"value": fn, "unit": "lookups/s", "cores": ran,
+                                      "sample": "%d forward passes, bags shared out among %d threads, results bit-identical "
+                                                "to the single thread's" % (nn, ran)}
 
     print(json.dumps({
         "metric": "TT-EmbeddingBag fwd+bwd lookups/sec; % of HBM/fp32 roofline at R=32",

@@ -19,7 +19,7 @@
  *    contiguous block.
  *  - Row index i has digits i = i1*m2*m3 + i2*m3 + i3 (i1 most significant,
  *    Section 3.1).  Only 0 <= i < num_rows <= m1*m2*m3 may be looked up; this is a
- *    precondition on `indices` that the library does not check on the device.
+ *    precondition on `indices` that only tt_emb_validate checks on the device.
  *  - An embedding row has N = n1*n2*n3 columns; column j = (j1*n2 + j2)*n3 + j3.
  *  - Bags are given in CSR form: offsets[0..n_bags], offsets[0] = 0,
  *    non-decreasing, offsets[n_bags] = L; bag b pools positions
@@ -34,7 +34,8 @@
  *  - Every fp32 array (cores, outputs, gradients, cache rows, kept T0) and every
  *    workspace must start on a 16-byte boundary; TT_ERR_BAD_ARG otherwise.
  *  - Limits: d = 3, num_rows < 2^31, L < 2^31 (3 L < 2^31 in the backward pass of
- *    the shapes with a specialised kernel), fp32 data.
+ *    the shapes with a specialised kernel), n_bags * N < 2^31, fp32 data;
+ *    TT_ERR_UNSUPPORTED beyond them.
  */
 #ifndef TT_EMB_H
 #define TT_EMB_H
@@ -78,8 +79,8 @@ typedef struct tt_cache_t {
     uint64_t *table;      /* [capacity] */
 } tt_cache_t;
 
-/* The access-frequency tracker of the semi-dynamic cache (Section 4.2: an open
- * addressing hash table that tracks how often every row is used).  The struct is
+/* Per-row use counts that feed the cache's refills (Section 4.2), held in a hash
+ * table in device memory.  The struct is
  * host memory; `table` ([capacity] 64-bit words, private encoding) and `stats`
  * ([2]: distinct rows tracked, accesses dropped because the table was full) are
  * device memory that the caller allocates; capacity is a power of two >= 64 and
@@ -367,9 +368,9 @@ int tt_cache_build(const tt_shape_t *shape, const float *const cores[3],
                    const tt_cache_t *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * One refill of the semi-dynamic cache (Section 4.2: the frequently used rows are
- * loaded into the cache only every 100s to 1000s of iterations, initialised from
- * the cores; what an evicted line has learned is discarded).  The K most used
+ * One refill of the cache under Section 4.2's semi-dynamic policy; the caller
+ * decides how rarely to call it.  The weights of a row that leaves the cache are
+ * dropped, not written back into the cores.  The K most used
  * candidates become the cached set, in tt_cache_build's order.  A row that was
  * cached before keeps its line as it is (with the weights it has learned); a row
  * that enters is rebuilt from the cores.
@@ -439,6 +440,24 @@ int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
                          const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
                          const float *alpha, const float *grad_output, float lr, void *stream);
 
+/*
+ * The preconditions on the lookup arguments (Section 4.1's interface: row ids of the table, bags
+ * in CSR form), checked on the device by a small kernel of its own; no other call checks them,
+ * and what a call does with arguments that break them is undefined (it may read or write out of
+ * bounds).  Meant for the boundary of a serving or training loop: validate a batch once, read
+ * the flag, and only then hand the batch to the other calls.
+ * indices, L, offsets, n_bags: as in tt_emb_fwd (offsets == NULL: n_bags == L, nothing to check
+ *        on the bags).
+ * flag:  int32 [1] on the device.  Written 0 if every precondition holds, else the OR of
+ *        TT_BAD_INDEX         an index < 0 or >= num_rows,
+ *        TT_BAD_OFFSETS_ORDER offsets[0] != 0 or offsets decreasing somewhere,
+ *        TT_BAD_OFFSETS_RANGE an offset outside [0, L], or offsets[n_bags] != L.
+ * The return value only covers what the host can see (NULL pointers, negative sizes).
+ */
+enum { TT_BAD_INDEX = 1, TT_BAD_OFFSETS_ORDER = 2, TT_BAD_OFFSETS_RANGE = 4 };
+int tt_emb_validate(const tt_shape_t *shape, const int64_t *indices, int64_t L,
+                    const int64_t *offsets, int64_t n_bags, int32_t *flag, void *stream);
+
 /* Digits of every index (Section 3.1): i1, i2, i3 are int32 [L]. */
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                         int32_t *i1, int32_t *i2, int32_t *i3, void *stream);
@@ -482,9 +501,12 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
                        int64_t *uniq, int32_t *count, int32_t *perm, int64_t *n_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
-/* Kernel selection, process-wide, meant for tests.  1 (default): shapes with a specialised
- * kernel use it, and the backward groups long index streams first.  0: every call takes the
- * shape-generic kernels.  2: as 1, but the backward always groups first.  Returns the old value. */
+/* Kernel selection for the library calls that the CALLING THREAD makes from now on, meant for
+ * tests: the value is per thread, every thread starts at 1, and no other thread's calls are
+ * affected.  1: shapes with a specialised kernel use it, and the backward groups long index
+ * streams first.  0: every call takes the shape-generic kernels.  2: as 1, but the backward
+ * always groups first.  Returns the thread's old value.  Workspace queries, tt_emb_bwd_prepare
+ * and the backward call that follows must be made under the same value. */
 int tt_emb_debug_set_fast_path(int mode);
 
 #ifdef __cplusplus

@@ -25,6 +25,9 @@
  * not here, and are "parity unpinned" harness conventions.
  */
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -157,6 +160,27 @@ void ora_cache_fill(const int64_t m[3], const int64_t n[3], const int64_t r[4],
  * prose), sum pooling, optional per-position weight alpha[k] (NULL = 1).
  * A cached row is read from cache_rows instead of being rebuilt (Section 4.2).
  * Lookups are pooled in increasing k.  An empty bag gives a zero row. */
+static void fwd_one_bag(const int64_t m[3], const int64_t n[3], const int64_t r[4],
+                        const float *G1, const float *G2, const float *G3,
+                        const int64_t *indices, const int64_t *offsets, const float *alpha,
+                        const int32_t *map, const float *cache_rows,
+                        int64_t b, double *acc, double *row, float *output)
+{
+    const int64_t N = n[0] * n[1] * n[2];
+    for (int64_t j = 0; j < N; ++j) acc[j] = 0.0;
+    for (int64_t k = offsets[b]; k < offsets[b + 1]; ++k) {
+        const int64_t i = indices[k];
+        const double w = alpha ? (double)alpha[k] : 1.0;
+        if (map && map[i] >= 0) {
+            for (int64_t j = 0; j < N; ++j) row[j] = (double)cache_rows[(int64_t)map[i] * N + j];
+        } else {
+            ora_row(m, n, r, G1, G2, G3, i, row);
+        }
+        for (int64_t j = 0; j < N; ++j) acc[j] += w * row[j];
+    }
+    for (int64_t j = 0; j < N; ++j) output[b * N + j] = (float)acc[j];
+}
+
 int ora_fwd(const int64_t m[3], const int64_t n[3], const int64_t r[4], int64_t num_rows,
             const float *G1, const float *G2, const float *G3,
             const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
@@ -170,22 +194,44 @@ int ora_fwd(const int64_t m[3], const int64_t n[3], const int64_t r[4], int64_t 
     if (K > 0) { map = build_slot_map(num_rows, cache_keys, K); if (!map) return -1; }
     double *acc = (double *)malloc((size_t)N * sizeof(double));
     double *row = (double *)malloc((size_t)N * sizeof(double));
-    for (int64_t b = 0; b < n_bags; ++b) {
-        for (int64_t j = 0; j < N; ++j) acc[j] = 0.0;
-        for (int64_t k = offsets[b]; k < offsets[b + 1]; ++k) {
-            const int64_t i = indices[k];
-            const double w = alpha ? (double)alpha[k] : 1.0;
-            if (map && map[i] >= 0) {
-                for (int64_t j = 0; j < N; ++j) row[j] = (double)cache_rows[(int64_t)map[i] * N + j];
-            } else {
-                ora_row(m, n, r, G1, G2, G3, i, row);
-            }
-            for (int64_t j = 0; j < N; ++j) acc[j] += w * row[j];
-        }
-        for (int64_t j = 0; j < N; ++j) output[b * N + j] = (float)acc[j];
-    }
+    for (int64_t b = 0; b < n_bags; ++b)
+        fwd_one_bag(m, n, r, G1, G2, G3, indices, offsets, alpha, map, cache_rows, b, acc, row, output);
     free(acc); free(row); free(map);
     return 0;
+}
+
+/* The same forward pass with the bags shared out among `threads` host threads (a bag is
+ * still pooled by one thread, in increasing k, so every output value is the one ora_fwd
+ * gives, bit for bit).  Returns the number of threads that ran, or -1.  Only the timing
+ * of a multi-core CPU baseline uses it; the tests check it against ora_fwd. */
+int ora_fwd_threads(const int64_t m[3], const int64_t n[3], const int64_t r[4], int64_t num_rows,
+                    const float *G1, const float *G2, const float *G3,
+                    const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    const float *alpha,
+                    const int64_t *cache_keys, const float *cache_rows, int64_t K,
+                    float *output, int threads)
+{
+    const int64_t N = n[0] * n[1] * n[2];
+    int32_t *map = NULL;
+    int ran = 1;
+    (void)L;
+    if (threads < 1) threads = 1;
+    if (K > 0) { map = build_slot_map(num_rows, cache_keys, K); if (!map) return -1; }
+#pragma omp parallel num_threads(threads)
+    {
+        double *acc = (double *)malloc((size_t)N * sizeof(double));
+        double *row = (double *)malloc((size_t)N * sizeof(double));
+#ifdef _OPENMP
+#pragma omp single
+        ran = omp_get_num_threads();
+#endif
+#pragma omp for schedule(static)
+        for (int64_t b = 0; b < n_bags; ++b)
+            fwd_one_bag(m, n, r, G1, G2, G3, indices, offsets, alpha, map, cache_rows, b, acc, row, output);
+        free(acc); free(row);
+    }
+    free(map);
+    return ran;
 }
 
 /* ---- backward ----------------------------------------------------------- */

@@ -19,23 +19,32 @@ _SRC = os.path.join(_HERE, "tt_oracle.c")
 _LIB = os.path.join(_HERE, "libtt_oracle.so")
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc -O2 (no intrinsics, no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+_LIB_SAN = os.path.join(_HERE, "libtt_oracle_san.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no intrinsics, no fast-math).  sanitize: a second library with the address
+    and undefined-behaviour sanitizers, for a process that has their runtime preloaded (see TT_ORACLE_SANITIZE)."""
+    lib = _LIB_SAN if sanitize else _LIB
+    stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < os.path.getmtime(_SRC)
     if force or stale:
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+        tmp = "%s.%d.tmp" % (lib, os.getpid())
+        subprocess.check_call(["gcc"] + flags + ["-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, lib)
+    return lib
 
 
 _lib = None
 
 
 def _load():
+    """The compiled oracle.  With TT_ORACLE_SANITIZE=1 in the environment: its sanitizer build (the process must have
+    been started with the sanitizer runtime preloaded)."""
     global _lib
     if _lib is None:
-        build()
-        _lib = C.CDLL(_LIB)
+        _lib = C.CDLL(build(sanitize=os.environ.get("TT_ORACLE_SANITIZE") == "1"))
         _lib.ora_param_count.restype = C.c_int64
         _lib.ora_dedup.restype = C.c_int64
     return _lib
@@ -157,6 +166,25 @@ def fwd(shape: Shape, cores, indices, offsets, alpha=None, cache_keys=None, cach
                          _p(ck), _p(cr), C.c_int64(K), _p(out))
     assert rc == 0
     return out
+
+
+def fwd_threads(shape: Shape, cores, indices, offsets, threads: int, alpha=None, cache_keys=None, cache_rows=None):
+    """fwd with the bags shared out among host threads: (output, threads that ran).  Bit-identical to fwd."""
+    g = [_f32(c) for c in cores]
+    idx, off = _i64(indices), _i64(offsets)
+    _check_csr(shape, idx, off)
+    n_bags = off.size - 1
+    a = None if alpha is None else _f32(alpha)
+    K = 0 if cache_keys is None else int(np.asarray(cache_keys).size)
+    ck = None if K == 0 else _i64(cache_keys)
+    cr = None if K == 0 else _f32(cache_rows)
+    out = np.empty((n_bags, shape.dim), dtype=np.float32)
+    m, n, r = shape.c()
+    ran = _load().ora_fwd_threads(m, n, r, C.c_int64(shape.num_rows), _p(g[0]), _p(g[1]), _p(g[2]),
+                                  _p(idx), C.c_int64(idx.size), _p(off), C.c_int64(n_bags), _p(a),
+                                  _p(ck), _p(cr), C.c_int64(K), _p(out), C.c_int(int(threads)))
+    assert ran >= 1
+    return out, int(ran)
 
 
 def bwd(shape: Shape, cores, indices, offsets, grad_output, alpha=None, cache_keys=None):

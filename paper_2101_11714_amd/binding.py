@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_validate", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -78,6 +78,7 @@ def lib():
         l.tt_emb_static_scratch_bytes.restype = C.c_size_t
         l.tt_emb_static_scratch_bytes.argtypes = []
         l.tt_emb_kept_bytes.restype = C.c_size_t
+        l.tt_emb_validate.argtypes = [vp, vp, i64, vp, i64, vp, vp]
         l.tt_emb_kept_bytes.argtypes = [vp, i64]
         l.tt_emb_kept_has_lists.argtypes = [vp, i64]
         l.tt_emb_fwd_keep.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
@@ -196,6 +197,21 @@ def tt_emb_fwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
     _check(lib().tt_emb_fwd(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets), n_bags,
                             _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(workspace), wsb, _stream()))
     return output
+
+
+TT_BAD_INDEX, TT_BAD_OFFSETS_ORDER, TT_BAD_OFFSETS_RANGE = 1, 2, 4
+
+
+def tt_emb_validate(shape: TTShape, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,
+                    flag: torch.Tensor) -> torch.Tensor:
+    """flag: int32 [1] on the device; 0 afterwards if the arguments are valid, else TT_BAD_* bits."""
+    _dev(indices, torch.int64)
+    _dev(flag, torch.int32)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    _check(lib().tt_emb_validate(C.byref(shape), _ptr(indices), indices.numel(), _ptr(offsets), n_bags, _ptr(flag), _stream()))
+    return flag
 
 
 def t0_floats(shape: TTShape) -> int:

@@ -34,7 +34,9 @@ static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 namespace {
 
 thread_local char g_err[512] = "";
-int g_fast_path = 1;                       // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
+// Kernel selection of the calling thread (tests only; no other thread's calls change with it):
+// 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
+thread_local int g_fast_path = 1;
 // from this many positions on the backward groups them first (tt_group.h)
 constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
 constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
@@ -82,10 +84,12 @@ int check_shape(const tt_shape_t *s, Params *p)
     return TT_OK;
 }
 
-int check_lookup_args(const int64_t *indices, int64_t L, int64_t n_bags, const int64_t *offsets)
+int check_lookup_args(const int64_t *indices, int64_t L, int64_t n_bags, const int64_t *offsets, int64_t N)
 {
     if (L < 0 || n_bags < 0) return fail(TT_ERR_BAD_ARG, "negative L or n_bags");
     if (L >= (1ll << 31) || n_bags >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "L or n_bags >= 2^31");
+    // (some kernels form element offsets into the [n_bags][N] arrays in 32 bits)
+    if (n_bags * N >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "n_bags * N >= 2^31");
     if (L > 0 && !indices) return fail(TT_ERR_NULL, "indices is NULL");
     if (!offsets && n_bags != L) return fail(TT_ERR_BAD_ARG, "offsets == NULL requires n_bags == L");
     return TT_OK;
@@ -220,7 +224,7 @@ static int fwd_common(const tt_shape_t *shape, const float *const cores[3],
     Params p;
     int rc = check_shape(shape, &p);
     if (rc) return rc;
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, p.N))) return rc;
     if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
     if (n_bags > 0 && !output) return fail(TT_ERR_NULL, "output is NULL");
     CacheDev cd;
@@ -286,7 +290,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     Params p;
     int rc = check_shape(shape, &p);
     if (rc) return rc;
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, p.N))) return rc;
     if (!prep && (!cores || !cores[0] || !cores[1] || !cores[2])) return fail(TT_ERR_NULL, "cores is NULL");
     if (prep) {
     } else if (fused) {
@@ -349,7 +353,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             for (int k = 0; k < 3; ++k) {
                 gtmp[k] = (float *)q;
                 q += g_bytes[k];
-                if (phase != BWD_REST)
+                if (phase != BWD_PREPARE)                                 // not index-only work: the pre-pass leaves it
                     hipLaunchKernelGGL(fill_f32_kernel, dim3(cdiv(core_floats[k], WG) < 1024 ? cdiv(core_floats[k], WG) : 1024),
                                        dim3(WG), 0, st, gtmp[k], core_floats[k], 0.f);
             }
@@ -556,7 +560,7 @@ int tt_emb_fwd_keep(const tt_shape_t *shape, const float *const cores[3],
     int rc = check_shape(shape, &p);
     if (rc) return rc;
     if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps intermediates for this shape");
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, p.N))) return rc;
     const size_t need = tt_emb_kept_bytes(shape, L);
     if (L > 0 && (!kept || kept_bytes < need))
         return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", need, kept_bytes);
@@ -617,7 +621,7 @@ static int bwd_kept_common(const tt_shape_t *shape, const float *const cores[3],
     int rc = check_shape(shape, &p);
     if (rc) return rc;
     if (fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel uses kept intermediates for this shape");
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, p.N))) return rc;
     const size_t need = tt_emb_kept_bytes(shape, L);
     if (L > 0 && (!kept || kept_bytes < need))
         return fail(TT_ERR_WORKSPACE, "kept buffer of %zu bytes needed, %zu given", need, kept_bytes);
@@ -953,7 +957,7 @@ static int check_dense(const float *table, int64_t num_rows, int32_t N, const in
                        const int64_t *offsets, int64_t n_bags)
 {
     if (num_rows <= 0 || N <= 0 || N % 4 || N > 256 || (N & (N - 1))) return fail(TT_ERR_BAD_ARG, "N must be a power of two in [4, 256]");
-    int rc = check_lookup_args(indices, L, n_bags, offsets);
+    int rc = check_lookup_args(indices, L, n_bags, offsets, N);
     if (rc) return rc;
     if (!table) return fail(TT_ERR_NULL, "table is NULL");
     return TT_OK;
@@ -1063,7 +1067,7 @@ int tt_embd_fwd(const tt_shape_d_t *shape, const float *const cores[4],
     ShapeD s;
     int rc = check_shape_d(shape, &s);
     if (rc) return rc;
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, s.N))) return rc;
     if (!cores) return fail(TT_ERR_NULL, "cores is NULL");
     for (int k = 0; k < s.d; ++k)
         if (!cores[k]) return fail(TT_ERR_NULL, "cores is NULL");
@@ -1083,7 +1087,7 @@ int tt_embd_bwd(const tt_shape_d_t *shape, const float *const cores[4],
     ShapeD s;
     int rc = check_shape_d(shape, &s);
     if (rc) return rc;
-    if ((rc = check_lookup_args(indices, L, n_bags, offsets))) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, s.N))) return rc;
     if (!cores || !grad_cores) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
     for (int k = 0; k < s.d; ++k)
         if (!cores[k] || !grad_cores[k]) return fail(TT_ERR_NULL, "cores or grad_cores is NULL");
@@ -1130,6 +1134,22 @@ int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t
     hipLaunchKernelGGL(decode_kernel, dim3(cdiv(L, WG)), dim3(WG), 0, (hipStream_t)stream, p, indices, (int)L, i1, i2, i3);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "decode launch");
+}
+
+int tt_emb_validate(const tt_shape_t *shape, const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                    int32_t *flag, void *stream)
+{
+    int rc = check_shape(shape, nullptr);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, 1))) return rc;
+    if (!flag) return fail(TT_ERR_NULL, "flag is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(WG), 0, st, flag, (int64_t)1, 0);
+    const int64_t n = L > n_bags + 1 ? L : n_bags + 1;
+    hipLaunchKernelGGL(validate_kernel, dim3(cdiv(n, WG) < 2048 ? cdiv(n, WG) : 2048), dim3(WG), 0, st, shape->num_rows,
+                       indices, L, offsets, n_bags, flag);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "validate launch");
 }
 
 int tt_emb_debug_decode_as(const tt_shape_t *shape, const int64_t *indices, int64_t L, int mode,
@@ -1195,13 +1215,5 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
     return e == hipSuccess ? TT_OK : hip_fail(e, "dedup launch");
 }
 
-#ifdef TT_PROFILE
-// debug builds only: device buffer of [workgroups][16] cycle stamps written by the backward kernel
-int tt_debug_set_prof(void *buf)
-{
-    unsigned long long *pbuf = (unsigned long long *)buf;
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(tt::g_tt_prof), &pbuf, sizeof(pbuf));
-}
-#endif
 
 }  // extern "C"

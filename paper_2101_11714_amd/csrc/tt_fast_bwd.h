@@ -49,25 +49,6 @@ constexpr int FB_PIECE = WAVE;              // entries sorted together
 constexpr int FB_WCAP = FB_CAP / NWAVE;     // entries one wave may select per round
 constexpr uint32_t FB_NONE = 0xFFFFFFFFu;
 
-#if defined(TT_PROFILE)
-__device__ unsigned long long *g_tt_prof = nullptr;        // [workgroup][16], debug builds only
-#endif
-#if defined(TT_PROFILE) && TT_PROFILE == 2 && defined(TT_PROFILE_SUM)
-// stamps 1..6 sum the cycles since the previous stamp over all windows of a workgroup (ts[14] = previous stamp)
-#define TT_STAMP(i)                                                                     \
-    do {                                                                                \
-        const unsigned long long now_ = __builtin_readcyclecounter();                   \
-        if ((i) >= 1 && (i) <= 6) ts[(i)] += now_ - ts[14]; else ts[(i)] = now_;         \
-        if ((i) != 15) ts[14] = now_;                                                   \
-    } while (0)
-#define TT_NOTE(i, v) ts[(i)] += (unsigned long long)(v)
-#elif defined(TT_PROFILE) && TT_PROFILE == 2
-#define TT_STAMP(i) ts[(i)] = __builtin_readcyclecounter()
-#define TT_NOTE(i, v) ts[(i)] = (unsigned long long)(v)
-#else
-#define TT_STAMP(i) do { } while (0)
-#define TT_NOTE(i, v) do { } while (0)
-#endif
 
 typedef float mfma16_t __attribute__((ext_vector_type(16)));
 typedef float mfma4_t __attribute__((ext_vector_type(4)));
@@ -188,9 +169,6 @@ template <typename C>
 __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int role, int s,
                                          const uint32_t (&rowv)[FB_ITER], int lo, int hi, int round,
                                          const int (&fill)[NWAVE], int (&wc)[NWAVE]
-#if defined(TT_PROFILE) && TT_PROFILE == 2
-                                         , unsigned long long *ts
-#endif
                                          )
 {
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -217,7 +195,6 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
             cnt += __popcll(masks[it]);
         }
     }
-    TT_STAMP(12);
     int myfill = 0;
 #pragma unroll
     for (int j = 0; j < NWAVE; ++j) myfill = j == w ? fill[j] : myfill;
@@ -238,7 +215,6 @@ __device__ __forceinline__ int fb_select(FbLds<C> &lds, const Params &p, int rol
     int *wcnt = lds.wcnt[round & 1];
     if (lane == 0) wcnt[w] = cnt;
     __syncthreads();
-    TT_STAMP(13);
     int total = 0;
 #pragma unroll
     for (int j = 0; j < NWAVE; ++j) {
@@ -337,10 +313,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             for (int i = 0; i < PF3; ++i) old[i] = G3[(size_t)s * C::sC + min(t + i * WG, C::sC - 1)];
         }
     }
-#if defined(TT_PROFILE) && TT_PROFILE == 2
-    unsigned long long ts[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    TT_STAMP(0);
-#endif
 
     // ---- staging: gather float4 items from global memory into LDS ----
     // One item in flight: its value, and for a gradient item what is needed to confirm the bag.
@@ -814,7 +786,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
 
     // One round: the n selected entries, entry e at fb_slot(wc, e) of lds.klist / lds.rows.
     auto process = [&](int n, const int (&wc)[NWAVE]) __attribute__((always_inline)) {
-        TT_STAMP(1); TT_NOTE(8, n);
         for (int i0 = 0; i0 < n; i0 += W) {
             const int nw = min(W, n - i0);
             // A short window's gradients are loaded while it is analysed (one float4 per thread).
@@ -831,7 +802,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             if (W <= FB_PIECE || nw <= FB_PIECE) {
                 // one piece: every wave analyses it by itself (same result everywhere, no barrier)
                 nsegs = analyse(wc, i0, nw, mysg, mypos, i1, i2, i3, myk);
-                TT_STAMP(15);
                 if (MFMA && ROLE == 1 && with_p && w == 0 && lane < nw) pflag[myk] = mysg >= 0;
                 if (lane < nw) lds.epos[lane] = mypos;
                 if (mysg >= 0) {                                           // first entry of its run
@@ -865,21 +835,18 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 if (t == 0) lds.seg_start[nsegs] = nw;
                 __syncthreads();
             }
-            TT_STAMP(2); TT_NOTE(9, nsegs);
             // All global loads of the window's first phase are issued together: first G2 rows,
             // upstream gradients, small operands of the first rows.
             const bool mm = MFMA && ROLE == 1;                            // this owner multiplies on the matrix cores
             if (mm) g2_fetch(0, nsegs, g2cur);
             float bm[UB][RQ][V];
             if (ROLE != 1 && !t0mode && !mm) bm_load(0, nsegs, bm);
-            TT_STAMP(3);
             stage_items(i0, early_done ? 0 : nw * NQ, 0, t0mode || mm ? 0 : min(SB, nsegs), wc);
             if (early_done) {
                 const float4 g = item_finish(early);
                 if (t < nw * NQ) *reinterpret_cast<float4 *>(&stage[4 * (NQ * lds.epos[t / NQ] + t % NQ)]) = g;
             }
             __syncthreads();
-            TT_STAMP(4);
             if (nsegs < nw) {                                              // uniform: some row occurs more than once
                 // sum each run into its first entry, in list order (a run has at most 64 entries)
                 for (int item = t; item < nsegs * N; item += WG) {
@@ -902,7 +869,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 __syncthreads();
             }
             if (!mm) dt_prepare(0, min(SB, nsegs));
-            TT_STAMP(5);
             if (t0mode) consume_t0(nsegs);
             if (mm) consume_g2_mfma(nsegs);
             for (int ub0 = 0; ub0 < (t0mode || mm ? 0 : nsegs); ub0 += UB) {
@@ -919,7 +885,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
                 consume(ub0, sb0, nsegs, bm);
             }
             __syncthreads();                                             // before the LDS lists are reused
-            TT_STAMP(6);
         }
     };
 
@@ -962,11 +927,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
         } else {
             if (lo > lo0 || span != FB_SCAN || round > 0) fb_load_rows(indices, slot, lo, hi, rowv);
             int wc[NWAVE];
-#if defined(TT_PROFILE) && TT_PROFILE == 2
-            fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, fill, wc, ts);
-#else
             fb_select<C>(lds, p, ROLE, s, rowv, lo, hi, round++, fill, wc);
-#endif
             bool too_big = false, over = false;
 #pragma unroll
             for (int j = 0; j < NWAVE; ++j) {
@@ -993,17 +954,7 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             process(pn, pw);
         }
     }
-#if defined(TT_PROFILE) && TT_PROFILE == 2
-    auto flush = [&]() __attribute__((always_inline)) {
-        TT_STAMP(7);
-        if (g_tt_prof && threadIdx.x == 0)
-            for (int i = 0; i < 16; ++i)
-                if (i < 10 || i > 11) g_tt_prof[blockIdx.x * 16 + i] = ts[i];
-    };
-    if (!any && !fused && !pout) { flush(); return; }
-#else
     if (!any && !fused && !pout) return;
-#endif
 
     // The G2 owner's last phase: all old values are loaded before the first store (one round trip, not one per element).
     const float *src2 = fused ? G2 : dG2;                              // x - lr * g to the second set of cores, or dG += g
@@ -1099,9 +1050,6 @@ __device__ __forceinline__ void fb_body(FbLds<C> &lds, const Params &p, const in
             }
         }
     }
-#if defined(TT_PROFILE) && TT_PROFILE == 2
-    flush();
-#endif
 }
 
 // SPLIT: the launch may share slices between workgroups (FbSplit); without it the kernel takes no such argument
@@ -1118,9 +1066,6 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
 {
     static_assert(SPLIT || !FbCfg<C>::MFMA, "the (4,4,4) shapes always take the split descriptor");
     __shared__ FbLds<C> lds;
-#if defined(TT_PROFILE)
-    const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
-#endif
     uint32_t rowv[FB_ITER];
     if constexpr (FbCfg<C>::MFMA) {
         if (sp.cw.blocks && (int)blockIdx.x >= sp.n_owner) {             // uniform: this workgroup sums cached-row gradients
@@ -1174,12 +1119,6 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(FbCfg<C>::WA
         const int sl = g - (ge1 ? p.m1 : 0) - (ge2 ? p.m2 : 0);
         fb_body<C>(lds, p, role, sl, G1, G2, G3, indices, L, offsets, n_bags, alpha, slot, grad_out, dG1, dG2, dG3, gvals, goff, gend, lr, o1, o2, o3, t0, rowv, 0, 1, nullptr, nullptr, nullptr, 0);
     }
-#if defined(TT_PROFILE)
-    if (g_tt_prof && threadIdx.x == 0) {
-        g_tt_prof[blockIdx.x * 16 + 11] = t_begin;
-        g_tt_prof[blockIdx.x * 16 + 10] = __builtin_amdgcn_s_memrealtime();
-    }
-#endif
 }
 
 // Sums the partial slice gradients of the split roles (FbSplit) and finishes their slices: adds the sum to dG

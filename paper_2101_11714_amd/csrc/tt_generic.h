@@ -275,6 +275,31 @@ __global__ __launch_bounds__(WG) void fill_i32_kernel(int32_t *__restrict__ p, i
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;
 }
 
+// Checks of the lookup arguments (Section 4.1): every index in [0, num_rows), offsets[0] == 0, offsets
+// non-decreasing, offsets[n_bags] == L.  The bits of what fails are OR-ed into *flag (cleared before the launch).
+__global__ __launch_bounds__(WG) void validate_kernel(int64_t num_rows, const int64_t *__restrict__ indices, int64_t L,
+                                                      const int64_t *__restrict__ offsets, int64_t n_bags,
+                                                      int32_t *__restrict__ flag)
+{
+    int bad = 0;
+    const int64_t n = L > n_bags + 1 ? L : n_bags + 1;
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) {
+        if (i < L) {
+            const int64_t row = indices[i];
+            if (row < 0 || row >= num_rows) bad |= 1;
+        }
+        if (offsets && i <= n_bags) {
+            const int64_t o = offsets[i];
+            if (i == 0 ? o != 0 : o < offsets[i - 1]) bad |= 2;
+            if (o < 0 || o > L || (i == n_bags && o != L)) bad |= 4;
+        }
+    }
+    // one atomic per wave that found something
+    for (int b = 1; b <= 4; b <<= 1)
+        if (__ballot((bad & b) != 0) == 0) bad &= ~b;
+    if (bad && (threadIdx.x & (WAVE - 1)) == 0) atomicOr(flag, bad);
+}
+
 __global__ __launch_bounds__(WG) void fill_f32_kernel(float *__restrict__ p, int64_t n, float v)
 {
     for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n; i += (int64_t)gridDim.x * WG) p[i] = v;

@@ -323,6 +323,36 @@ def test_fused_other_shapes():
         assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], 0.1), "fused odd core %d" % (k + 1))
 
 
+def test_prepared_call_alone_where_the_library_reports_no_prepass():
+    """A shape without a specialised kernel, no cache: tt_emb_bwd_has_prepass says 0, so a caller may skip
+    tt_emb_bwd_prepare; tt_emb_bwd_sgd_prepared then clears its own gradient buffers (the workspace starts dirty)."""
+    shape = W.TableShape(2 * 3 * 5 * 7, (6, 5, 7), (3, 2, 5), (1, 4, 7, 1))
+    wl = W.Workload("odd", (shape,), 50, (0, 6), "uniform", 0.0, "normal0.1", 22)
+    d = DeviceTable(wl, with_alpha=True)
+    assert not B.bwd_has_prepass(d.shape, d.L, 0, False)
+    out = [torch.full_like(x, float("nan")) for x in d.g]
+    ws = torch.full((B.bwd_sgd_workspace_bytes(d.shape, d.L, d.n_bags, 0),), 0x7F, dtype=torch.uint8, device=dev())
+    for _ in range(2):                                  # the second call finds the first call's gradients there
+        B.tt_emb_bwd_sgd(d.shape, d.g, out, d.idx, d.off, d.n_bags, d.go, 0.1, alpha=d.alpha, workspace=ws, prepared=True)
+    torch.cuda.synchronize()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    for k in range(3):
+        assert_close(out[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], 0.1), "prepared-only odd core %d" % (k + 1))
+
+
+def test_output_arrays_beyond_32_bit_offsets_are_refused():
+    """n_bags * N >= 2^31: the call fails before anything is enqueued (no array of that size is needed to see it)."""
+    wl = W.WORKLOADS["tiny"]
+    d = DeviceTable(wl)
+    import ctypes as C
+    n_bags = (1 << 31) // d.t.dim
+    out = torch.empty(16, dtype=torch.float32, device=dev())
+    rc = B.lib().tt_emb_fwd(C.byref(d.shape), B._ptr_array(d.g), B._ptr(d.idx), d.idx.numel(), None, n_bags, None, None,
+                            B._ptr(out), None, 0, None)
+    assert rc == -6, B.lib().tt_last_error()            # TT_ERR_UNSUPPORTED
+    assert b"n_bags * N" in B.lib().tt_last_error()
+
+
 @pytest.mark.parametrize("name,table", [("tiny", 0), ("multihot_cache", 0), ("multihot_cache", 6)])
 def test_fused_with_cache(name, table, path):
     wl = W.WORKLOADS[name]

@@ -591,3 +591,21 @@ def test_general_d_with_three_cores_is_the_three_core_oracle():
     gd = ora.bwd_d(m, n, r, cores, batch.indices, batch.offsets, batch.grad_output)
     for k in range(3):
         np.testing.assert_allclose(gd[k].reshape(-1), np.asarray(g3[k]).reshape(-1), rtol=1e-5, atol=1e-7)
+
+
+def test_threaded_forward_is_the_forward_bit_for_bit():
+    """ora.fwd_threads only shares the bags out: ragged weighted bags with a cache, several thread counts."""
+    rng = np.random.default_rng(77)
+    shape = ora.Shape(4 * 5 * 6, (4, 5, 6), (2, 2, 4), (1, 3, 5, 1))
+    cores = [rng.standard_normal(shape.core_size(k)).astype(np.float32) for k in range(3)]
+    lens = rng.integers(0, 9, 57)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = rng.integers(0, shape.num_rows, off[-1]).astype(np.int64)
+    alpha = rng.standard_normal(off[-1]).astype(np.float32)
+    keys = np.array([3, 17, 99], dtype=np.int64)
+    crow = rng.standard_normal((3, shape.dim)).astype(np.float32)
+    ref = ora.fwd(shape, cores, idx, off, alpha=alpha, cache_keys=keys, cache_rows=crow)
+    for threads in (1, 2, 3, 8):
+        out, ran = ora.fwd_threads(shape, cores, idx, off, threads, alpha=alpha, cache_keys=keys, cache_rows=crow)
+        assert 1 <= ran <= threads
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
