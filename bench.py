@@ -66,6 +66,30 @@ def pmc_means(dirs):
                 print("  %-90s %-12s dispatches=%5d mean=%12.1f" % (k[0], k[1], n, tot / n))
 
 
+def trace_context(dirs):
+    """From rocprofv3 --kernel-trace csv output: duration of every kernel by the kernel that ran before it, and the idle
+    time between the two (a kernel that follows another one finds different lines in the caches than one that follows
+    itself, which is how the per-stage timings of this script and a trace of whole steps differ)."""
+    import collections, csv, glob, statistics
+    for d in dirs:
+        for path in sorted(glob.glob(os.path.join(d, "**", "*kernel_trace.csv"), recursive=True)):
+            with open(path) as f:
+                rows = sorted(((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), r["Kernel_Name"]) for r in csv.DictReader(f)))
+            acc = collections.defaultdict(list)
+            for (s0, e0, k0), (s1, e1, k1) in zip(rows, rows[1:]):
+                name = lambda k: k.split("(")[0].split("<")[0].split("::")[-1].replace("void ", "")
+                acc[(name(k0), name(k1))].append((e1 - s1, s1 - e0))
+            print(path)
+            for key, v in sorted(acc.items(), key=lambda kv: -len(kv[1])):
+                if len(v) < 50:
+                    continue
+                dur, gap = sorted(x[0] for x in v), sorted(x[1] for x in v)
+                q = lambda a, f: a[min(len(a) - 1, int(len(a) * f))]
+                print("  %-22s after %-22s n=%6d  duration ns p10 %6d p50 %6d p90 %6d mean %8.1f | idle before ns p50 %6d mean %8.1f"
+                      % (key[1], key[0], len(v), q(dur, .1), q(dur, .5), q(dur, .9), statistics.mean(dur), q(gap, .5),
+                         statistics.mean(gap)))
+
+
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published
 
 
@@ -119,6 +143,9 @@ def main():
     ap.add_argument("--pmc-means", nargs="+", metavar="DIR",
                     help="no benchmark: print the mean counter value per kernel from rocprofv3 --pmc csv output under "
                          "the given folders")
+    ap.add_argument("--trace-context", nargs="+", metavar="DIR",
+                    help="no benchmark: from rocprofv3 --kernel-trace csv output under the given folders, print every "
+                         "kernel's duration by the kernel that ran before it")
     ap.add_argument("--no-lists", action="store_true",
                     help="fused step with the stored T0 but without the per-slice position lists filed ahead "
                          "(tt_emb_fwd_keep_t0 / tt_emb_bwd_sgd_t0): every slice owner scans the index array itself")
@@ -147,6 +174,9 @@ def main():
 
     if args.pmc_means:
         pmc_means(args.pmc_means)
+        return
+    if args.trace_context:
+        trace_context(args.trace_context)
         return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
@@ -345,6 +375,12 @@ def main():
                                                         zero_grad=True), reps)[0]
         stage_ms = {"fwd": ms_fwd, "bwd": ms_bwd, "sgd": ms_sgd}
 
+    # what a launch costs before it computes anything: kernels that do nothing, one workgroup and as many as the backward
+    # pass starts, in the same kind of sequence (the floor under every stage's time above)
+    n_wg = t.m[0] + t.m[1] + t.m[2]
+    launch_floor = {"1_workgroup": round(timed_ms(lambda i: B.tt_emb_debug_launch_probe(1), reps)[0] * 1e3, 3),
+                    "%d_workgroups" % n_wg: round(timed_ms(lambda i: B.tt_emb_debug_launch_probe(n_wg), reps)[0] * 1e3, 3)}
+
     # the same step with Alg. 2's recomputation instead of the stored intermediate, beside the headline
     ms_recompute, ms_stored_t0 = None, None
     if keep_t0:
@@ -387,6 +423,7 @@ def main():
                 "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes, "kept_list_bytes": list_bytes,
                 "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
+                "launch_floor_us": launch_floor,
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms},
                 "fp32_tflops": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12, 3),
                 "fp32_frac": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 5),

@@ -458,6 +458,11 @@ enum { TT_BAD_INDEX = 1, TT_BAD_OFFSETS_ORDER = 2, TT_BAD_OFFSETS_RANGE = 4 };
 int tt_emb_validate(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                     const int64_t *offsets, int64_t n_bags, int32_t *flag, void *stream);
 
+/* For measurements: enqueues a kernel of `blocks` workgroups of 256 threads that does nothing
+ * (if sink != NULL, device int32 [1], one thread stores 1 there).  Timed in a sequence of such
+ * launches it gives the cost of a launch of that size, the floor under every kernel's time. */
+int tt_emb_debug_launch_probe(int32_t blocks, int32_t *sink, void *stream);
+
 /* Digits of every index (Section 3.1): i1, i2, i3 are int32 [L]. */
 int tt_emb_debug_decode(const tt_shape_t *shape, const int64_t *indices, int64_t L,
                         int32_t *i1, int32_t *i2, int32_t *i3, void *stream);

@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_validate", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_validate", "tt_emb_debug_launch_probe", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -79,6 +79,7 @@ def lib():
         l.tt_emb_static_scratch_bytes.argtypes = []
         l.tt_emb_kept_bytes.restype = C.c_size_t
         l.tt_emb_validate.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+        l.tt_emb_debug_launch_probe.argtypes = [C.c_int32, vp, vp]
         l.tt_emb_kept_bytes.argtypes = [vp, i64]
         l.tt_emb_kept_has_lists.argtypes = [vp, i64]
         l.tt_emb_fwd_keep.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, C.c_int, vp]
@@ -212,6 +213,10 @@ def tt_emb_validate(shape: TTShape, indices: torch.Tensor, offsets: Optional[tor
         assert offsets.numel() == n_bags + 1
     _check(lib().tt_emb_validate(C.byref(shape), _ptr(indices), indices.numel(), _ptr(offsets), n_bags, _ptr(flag), _stream()))
     return flag
+
+
+def tt_emb_debug_launch_probe(blocks: int, sink: Optional[torch.Tensor] = None) -> None:
+    _check(lib().tt_emb_debug_launch_probe(int(blocks), _ptr(sink), _stream()))
 
 
 def t0_floats(shape: TTShape) -> int:

@@ -1152,6 +1152,14 @@ int tt_emb_validate(const tt_shape_t *shape, const int64_t *indices, int64_t L, 
     return e == hipSuccess ? TT_OK : hip_fail(e, "validate launch");
 }
 
+int tt_emb_debug_launch_probe(int32_t blocks, int32_t *sink, void *stream)
+{
+    if (blocks < 1 || blocks > (1 << 20)) return fail(TT_ERR_BAD_ARG, "blocks must be in [1, 2^20]");
+    hipLaunchKernelGGL(launch_probe_kernel, dim3(blocks), dim3(WG), 0, (hipStream_t)stream, sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "probe launch");
+}
+
 int tt_emb_debug_decode_as(const tt_shape_t *shape, const int64_t *indices, int64_t L, int mode,
                            int32_t *i1, int32_t *i2, int32_t *i3, void *stream)
 {
