@@ -259,6 +259,7 @@ def main():
     # known, as with a data loader that is one batch ahead); it needs a workspace of its own, two alternate.  A step on its own (first = last
     # = True) runs its pre-pass next to its forward pass.  The graph keeps the forks and the joins.
     two_calls = args.step == "fused" and not args.one_call and B.bwd_has_prepass(shape, max(Ls), K, keep_t0)
+    fwd_lists = two_calls and all(B.fwd_uses_lists(shape, x, K, keep_t0) for x in Ls)
     side = torch.cuda.Stream() if two_calls else None
     ws_pair = [ws, torch.empty_like(ws)] if two_calls else [ws, ws]
     prepared_ev = [torch.cuda.Event(), torch.cuda.Event()] if two_calls else None
@@ -278,11 +279,18 @@ def main():
             if two_calls:
                 if first:
                     prepare_on_side(i)
-            fwd_call(cur, j)
+            if fwd_lists:
+                # the forward pass works from the pre-pass's lists where the library has such a kernel (long streams)
+                torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
+                B.tt_emb_fwd_prepared(shape, cur, idx[j], off[j], n_bags, out, ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None,
+                                      alpha=alpha[j], cache=cache)
+            else:
+                fwd_call(cur, j)
             if two_calls and not last:
                 prepare_on_side(i + 1)                      # next to this step's backward (measured: better than next to
             if two_calls:                                   # its forward); its workspace was last read by step i - 1
-                torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
+                if not fwd_lists:
+                    torch.cuda.current_stream().wait_event(prepared_ev[i % 2])
                 B.tt_emb_bwd_sgd(shape, cur, nxt, idx[j], off[j], n_bags, go[j], lr, alpha=alpha[j], cache=cache,
                                  workspace=ws_pair[i % 2], t0=t0_pool[j] if keep_t0 else None, prepared=True)
             else:
@@ -361,7 +369,17 @@ def main():
 
     # per-kernel durations: each stage alone, launched back to back on the stream the step runs on
     reps = max(POOL * 16, min(steps, 4096))
-    ms_fwd = timed_ms(lambda i: fwd_call(cores, i % POOL), reps)[0]
+    if fwd_lists:
+        # the forward pass of the step works from the lists of the pre-pass: one prepared workspace per batch of the pool
+        ws_stage = [torch.empty_like(ws) for _ in range(POOL)]
+        for j in range(POOL):
+            B.tt_emb_bwd_prepare(shape, idx[j], off[j], n_bags, cache=cache, workspace=ws_stage[j], kept_t0=keep_t0)
+        ms_fwd = timed_ms(lambda i: B.tt_emb_fwd_prepared(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out, ws_stage[i % POOL],
+                                                          t0=t0_pool[i % POOL] if keep_t0 else None, alpha=alpha[i % POOL],
+                                                          cache=cache), reps)[0]
+        del ws_stage
+    else:
+        ms_fwd = timed_ms(lambda i: fwd_call(cores, i % POOL), reps)[0]
     if args.step == "fused":
         # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
         ms_bs = timed_ms(lambda i: bwd_sgd_call(cores, cores2, i % POOL, (i + 1) % POOL), reps)[0]
@@ -489,7 +507,7 @@ def main():
                    "table": tab,
                    "lookups_per_step": L, "launch": args.launch, "step": args.step, "keep_t0": bool(keep_t0),
                    "prepass_on_second_stream": bool(two_calls), "prepass_one_step_ahead": bool(two_calls and args.launch == "graph"), "wall_s_timed_region": round(wall, 3),
-                   "lists_filed_ahead": bool(use_lists),
+                   "lists_filed_ahead": bool(use_lists), "forward_from_prepass_lists": bool(fwd_lists),
                    "ms_per_step_recompute": None if ms_recompute is None else round(ms_recompute, 6),
                    "ms_per_step_stored_t0_without_lists": None if ms_stored_t0 is None else round(ms_stored_t0, 6)},
         "roofline": roofline, "cpu_baseline": cpu}))

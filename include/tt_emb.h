@@ -335,6 +335,27 @@ int tt_emb_bwd_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t 
                        void *workspace, size_t workspace_bytes, void *stream);
 /* 1 if tt_emb_bwd_prepare enqueues work for such a call (worth a stream of its own), else 0. */
 int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0);
+
+/*
+ * The forward pass of a call whose index-only pre-pass has run: tt_emb_fwd / tt_emb_fwd_keep_t0
+ * (t0 != NULL) for a caller that has enqueued tt_emb_bwd_prepare with the same shape, indices,
+ * offsets, cache and workspace (and kept_t0 = (t0 != NULL)) before it.  Where that pre-pass
+ * groups the positions by the slices they touch (long index streams, tt_emb_bwd_has_prepass)
+ * and the shape has such a kernel, the forward pass works from the lists: a workgroup takes
+ * positions of one slice of the second core, multiplies their stacked first-core rows with
+ * the slice on the matrix cores (Eq. 3, first product), and the rows of each bag are pooled
+ * afterwards in position order.  Otherwise the call is tt_emb_fwd / tt_emb_fwd_keep_t0.
+ * The workspace is read (lists) and written (one row per position, in a part of it that the
+ * backward calls do not use); the backward call that follows takes the same workspace.
+ * Same results as tt_emb_fwd up to the order of the fp32 sums over the rank indices.
+ */
+/* 1 if tt_emb_fwd_prepared works from the pre-pass's lists for such a call (then the forward pass has to
+ * wait for tt_emb_bwd_prepare), 0 if it is tt_emb_fwd / tt_emb_fwd_keep_t0 and needs no pre-pass. */
+int tt_emb_fwd_uses_lists(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0);
+int tt_emb_fwd_prepared(const tt_shape_t *shape, const float *const cores[3],
+                        const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                        const float *alpha, const tt_cache_t *cache,
+                        float *output, float *t0, void *workspace, size_t workspace_bytes, void *stream);
 int tt_emb_bwd_sgd_prepared(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
                             const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
                             const float *alpha, const tt_cache_t *cache,
@@ -432,6 +453,11 @@ int tt_embd_sgd_update(const tt_shape_d_t *shape, float *const cores[4], float *
  * tt_dense_bag_bwd_sgd:  table[indices[k]] -= lr * alpha[k] * grad_output[bag(k)] for
  *                        every position (sparse SGD with floating-point atomics: the
  *                        order in which duplicates are applied is not fixed).
+ * tt_dense_bag_bwd_sgd_merged: the same update with duplicates merged first: positions sorted by
+ *                        row, each row's gradients added in position order, every distinct row
+ *                        written once.  No floating-point atomics, the result is the same in every
+ *                        run; workspace of tt_dense_bag_bwd_workspace_bytes(L, N) bytes.  The
+ *                        faster of the two stands for the uncompressed table in a comparison.
  */
 int tt_dense_bag_fwd(const float *table, int64_t num_rows, int32_t N,
                      const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
@@ -439,6 +465,11 @@ int tt_dense_bag_fwd(const float *table, int64_t num_rows, int32_t N,
 int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
                          const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
                          const float *alpha, const float *grad_output, float lr, void *stream);
+size_t tt_dense_bag_bwd_workspace_bytes(int64_t L, int32_t N);
+int tt_dense_bag_bwd_sgd_merged(float *table, int64_t num_rows, int32_t N,
+                                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                                const float *alpha, const float *grad_output, float lr,
+                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * The preconditions on the lookup arguments (Section 4.1's interface: row ids of the table, bags

@@ -25,8 +25,8 @@ ERR_NAMES = {0: "TT_OK", -1: "TT_ERR_NULL", -2: "TT_ERR_BAD_SHAPE", -3: "TT_ERR_
 EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
-           "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd",
-           "tt_emb_validate", "tt_emb_debug_launch_probe", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd", "tt_dense_bag_bwd_sgd_merged", "tt_dense_bag_bwd_workspace_bytes",
+           "tt_emb_validate", "tt_emb_debug_launch_probe", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_fwd_prepared", "tt_emb_fwd_uses_lists", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -88,6 +88,8 @@ def lib():
         l.tt_emb_bwd_sgd_kept.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, C.c_size_t, f32, vp, vp, C.c_size_t, vp]
         l.tt_emb_debug_kept_lists.argtypes = [vp, vp, C.c_size_t, i64, vp, vp, vp, vp]
         l.tt_emb_bwd_prepare.argtypes = [vp, vp, i64, vp, i64, vp, C.c_int, vp, C.c_size_t, vp]
+        l.tt_emb_fwd_uses_lists.argtypes = [vp, i64, i64, C.c_int]
+        l.tt_emb_fwd_prepared.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd_has_prepass.argtypes = [vp, i64, i64, C.c_int]
         l.tt_emb_bwd_sgd_prepared.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
@@ -97,6 +99,9 @@ def lib():
         l.tt_cache_refill_workspace_bytes.argtypes = [vp, i64, i64]
         l.tt_dense_bag_fwd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, vp]
         l.tt_dense_bag_bwd_sgd.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp]
+        l.tt_dense_bag_bwd_sgd_merged.argtypes = [vp, i64, C.c_int32, vp, i64, vp, i64, vp, vp, f32, vp, C.c_size_t, vp]
+        l.tt_dense_bag_bwd_workspace_bytes.argtypes = [i64, C.c_int32]
+        l.tt_dense_bag_bwd_workspace_bytes.restype = C.c_size_t
         l.tt_embd_fwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp]
         l.tt_embd_bwd.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp]
         l.tt_embd_sgd_update.argtypes = [vp, vp, vp, f32, C.c_int, vp]
@@ -238,6 +243,33 @@ def tt_emb_fwd_keep_t0(shape: TTShape, cores: Sequence[torch.Tensor], indices: t
     assert t0.numel() >= indices.numel() * t0_floats(shape)
     _check(lib().tt_emb_fwd_keep_t0(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets),
                                     n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(t0), _stream()))
+    return output
+
+
+def fwd_uses_lists(shape: TTShape, L: int, cache_rows: int = 0, kept_t0: bool = False) -> bool:
+    return bool(lib().tt_emb_fwd_uses_lists(C.byref(shape), int(L), int(cache_rows), int(kept_t0)))
+
+
+def tt_emb_fwd_prepared(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Tensor,
+                        offsets: Optional[torch.Tensor], n_bags: int, output: torch.Tensor, workspace: torch.Tensor,
+                        t0: Optional[torch.Tensor] = None, alpha: Optional[torch.Tensor] = None,
+                        cache: Optional[Cache] = None) -> torch.Tensor:
+    """The forward pass after tt_emb_bwd_prepare into the same workspace (t0: keep the intermediate there)."""
+    _dev(indices, torch.int64)
+    if offsets is not None:
+        _dev(offsets, torch.int64)
+        assert offsets.numel() == n_bags + 1
+    if alpha is not None:
+        _dev(alpha, torch.float32)
+    _dev(output, torch.float32)
+    _dev(workspace, torch.uint8)
+    if t0 is not None:
+        _dev(t0, torch.float32)
+        assert t0.numel() >= indices.numel() * t0_floats(shape)
+    assert output.numel() == n_bags * shape.n[0] * shape.n[1] * shape.n[2]
+    _check(lib().tt_emb_fwd_prepared(C.byref(shape), _ptr_array(cores), _ptr(indices), indices.numel(), _ptr(offsets),
+                                     n_bags, _ptr(alpha), cache.ref() if cache else None, _ptr(output), _ptr(t0),
+                                     _ptr(workspace), workspace.numel(), _stream()))
     return output
 
 
@@ -553,6 +585,24 @@ def tt_dense_bag_bwd_sgd(table: torch.Tensor, indices: torch.Tensor, offsets: Op
     _dev(grad_output, torch.float32)
     _check(lib().tt_dense_bag_bwd_sgd(_ptr(table), table.shape[0], table.shape[1], _ptr(indices), indices.numel(),
                                       _ptr(offsets), n_bags, _ptr(alpha), _ptr(grad_output), C.c_float(lr), _stream()))
+
+
+def dense_bwd_workspace_bytes(L: int, N: int) -> int:
+    return int(lib().tt_dense_bag_bwd_workspace_bytes(int(L), int(N)))
+
+
+def tt_dense_bag_bwd_sgd_merged(table: torch.Tensor, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,
+                                grad_output: torch.Tensor, lr: float, alpha: Optional[torch.Tensor] = None,
+                                workspace: Optional[torch.Tensor] = None) -> None:
+    _dev(table, torch.float32)
+    _dev(indices, torch.int64)
+    _dev(grad_output, torch.float32)
+    if workspace is None:
+        workspace = torch.empty(max(dense_bwd_workspace_bytes(indices.numel(), table.shape[1]), 256), dtype=torch.uint8,
+                                device=table.device)
+    _check(lib().tt_dense_bag_bwd_sgd_merged(_ptr(table), table.shape[0], table.shape[1], _ptr(indices), indices.numel(),
+                                             _ptr(offsets), n_bags, _ptr(alpha), _ptr(grad_output), C.c_float(lr),
+                                             _ptr(workspace), workspace.numel(), _stream()))
 
 
 def tt_emb_mean_weights(offsets: torch.Tensor, n_bags: int, L: int, weights: torch.Tensor,

@@ -18,6 +18,7 @@
 #include "tt_fast_bwd.h"
 #include "tt_kept.h"
 #include "tt_group.h"
+#include "tt_fwd_owner.h"
 #include "tt_freq.h"
 #include "tt_dense.h"
 #include "tt_init.h"
@@ -272,6 +273,62 @@ int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
     return fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, t0, true, stream);
 }
 
+// does the backward of such a call group the positions first (tt_group.h)?
+static bool bwd_groups(const Params &p, int64_t L, int64_t K, bool kept_t0)
+{
+    const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
+    return fast && (g_fast_path == 2 || L >= (K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+}
+
+// does tt_emb_fwd_prepared work from the pre-pass's lists for such a call?
+static bool fwd_from_lists(const Params &p, int64_t L, int64_t K, bool kept_t0)
+{
+    // (measured: with a cache that takes most positions the wave-per-bag kernel is as fast at rank 32: 49 against 51 us
+    // for 163,840 positions of which a fifth go through the cores)
+    const bool pays = K == 0 || p.R1 >= 64;
+    return L > 0 && fwd_owner_supported(p) && pays && bwd_groups(p, L, K, kept_t0) && 3 * L < (1ll << 31);
+}
+
+int tt_emb_fwd_uses_lists(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L <= 0 || cache_rows < 0) return 0;
+    return fwd_from_lists(p, L, cache_rows, kept_t0 != 0) ? 1 : 0;
+}
+
+int tt_emb_fwd_prepared(const tt_shape_t *shape, const float *const cores[3],
+                        const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                        const float *alpha, const tt_cache_t *cache,
+                        float *output, float *t0, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Params p;
+    int rc = check_shape(shape, &p);
+    if (rc) return rc;
+    if ((rc = check_lookup_args(indices, L, n_bags, offsets, p.N))) return rc;
+    CacheDev cd;
+    if ((rc = check_cache(cache, &cd, true))) return rc;
+    if (t0 && fast_config(p) < 0) return fail(TT_ERR_UNSUPPORTED, "no kernel keeps T0 for this shape");
+    // the lists exist if the backward of this call groups its positions; else the forward needs none
+    if (!(n_bags > 0 && fwd_from_lists(p, L, cd.K, t0 != nullptr)))
+        return fwd_common(shape, cores, indices, L, offsets, n_bags, alpha, cache, output, t0, t0 != nullptr, stream);
+    if (!cores || !cores[0] || !cores[1] || !cores[2]) return fail(TT_ERR_NULL, "cores is NULL");
+    if (!output) return fail(TT_ERR_NULL, "output is NULL");
+    const size_t need = fwd_bwd_ws_bytes(p, L, cd.K);
+    if (!workspace || workspace_bytes < need)
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    if (misaligned({cores[0], cores[1], cores[2], output, t0, cd.rows, workspace}))
+        return fail(TT_ERR_BAD_ARG, "cores, output, t0, cache rows and workspace must be 16-byte aligned");
+    const int nbins = p.m1 + p.m2 + p.m3 + cd.K;
+    GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
+    int bits = 1;
+    while ((1 << bits) <= nbins) ++bits;
+    uint64_t *ks; uint32_t *vs;
+    radix_sort_result(g.sort, bits, &ks, &vs);
+    hipError_t e = fwd_owner(p, cores[0], cores[1], cores[2], indices, L, offsets, (int)n_bags, alpha, cd, vs, g.tiles,
+                             g.rows, output, t0, (hipStream_t)stream);
+    return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
+}
+
 enum BwdPhase { BWD_ALL, BWD_PREPARE, BWD_REST };
 
 // Backward pass behind tt_emb_bwd (cores_out == nullptr: gradients are added to grad_cores /
@@ -396,6 +453,11 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             if (es != hipSuccess) return hip_fail(es, "grouping sort");
             if (ks2 != ks || vs2 != vs) return fail(TT_ERR_BAD_ARG, "internal: the sort's result is not where it was expected");
             hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
+            if (fwd_from_lists(p, L, cd.K, t0 != nullptr)) {                // for tt_emb_fwd_prepared
+                const int ntiles = fwd_owner_tiles(p, L);
+                hipLaunchKernelGGL(grp_tiles_kernel, dim3(cdiv(ntiles, WG)), dim3(WG), 0, st, p.m1, p.m2, (int)L, fwd_owner_tp(p),
+                                   g.off, g.end, g.tiles, ntiles);
+            }
         }
         if (prep) {
             hipError_t e = hipGetLastError();
@@ -990,6 +1052,47 @@ int tt_dense_bag_bwd_sgd(float *table, int64_t num_rows, int32_t N,
     hipLaunchKernelGGL(dense_bwd_sgd_kernel, dim3(cdiv(n_bags, NWAVE)), dim3(WG), 0, (hipStream_t)stream, table, (int)N,
                        indices, offsets, (int)n_bags, alpha, grad_output, lr);
     hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TT_OK : hip_fail(e, "dense backward launch");
+}
+
+size_t tt_dense_bag_bwd_workspace_bytes(int64_t L, int32_t N)
+{
+    if (L < 0 || L >= (1ll << 31) || N <= 0 || N > 256) return 0;
+    return dense_ws_layout(nullptr, L > 0 ? L : 1, N).bytes;
+}
+
+int tt_dense_bag_bwd_sgd_merged(float *table, int64_t num_rows, int32_t N,
+                                const int64_t *indices, int64_t L, const int64_t *offsets, int64_t n_bags,
+                                const float *alpha, const float *grad_output, float lr,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_dense(table, num_rows, N, indices, L, offsets, n_bags);
+    if (rc) return rc;
+    if (n_bags > 0 && !grad_output) return fail(TT_ERR_NULL, "grad_output is NULL");
+    if (misaligned({table, grad_output, workspace})) return fail(TT_ERR_BAD_ARG, "table, grad_output and workspace must be 16-byte aligned");
+    if (n_bags == 0 || L == 0) return TT_OK;
+    const size_t need = tt_dense_bag_bwd_workspace_bytes(L, N);
+    if (!workspace || workspace_bytes < need)
+        return fail(TT_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    DenseWs ws = dense_ws_layout(workspace, L, N);
+    const int n = (int)L;
+    int bits = 1;
+    while (bits < 63 && (1ull << bits) <= (uint64_t)num_rows - 1) ++bits;
+    hipLaunchKernelGGL(dense_keys_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, indices, n, ws.sort.k0);
+    uint64_t *ks; uint32_t *vs;
+    hipError_t e = radix_sort(ws.sort, n, bits, st, &ks, &vs);
+    if (e != hipSuccess) return hip_fail(e, "dense backward sort");
+    const int tiles = (int)cdiv(n, DT);
+    const int bag_len = offsets && L % n_bags == 0 ? (int)(L / n_bags) : 0;     // a guess that the kernel checks
+    if (N <= 64)
+        hipLaunchKernelGGL((dense_seg_kernel<1, 16>), dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, table, (int)N, ks, vs, n,
+                           offsets, (int)n_bags, bag_len, alpha, grad_output, lr, ws.part);
+    else
+        hipLaunchKernelGGL((dense_seg_kernel<4, 8>), dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, table, (int)N, ks, vs, n,
+                           offsets, (int)n_bags, bag_len, alpha, grad_output, lr, ws.part);
+    hipLaunchKernelGGL(dense_fix_kernel, dim3(cdiv(tiles, NWAVE)), dim3(WG), 0, st, table, (int)N, ks, n, lr, ws.part);
+    e = hipGetLastError();
     return e == hipSuccess ? TT_OK : hip_fail(e, "dense backward launch");
 }
 

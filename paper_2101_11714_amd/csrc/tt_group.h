@@ -30,6 +30,8 @@ struct GroupWs {
     int *off, *end;                         // [nbins + 1] list bounds per key, in the sorted arrays
     int *crange;                            // [2] first and one-past-last sorted position of the cached items
     float *part;                            // [tiles][2][N] partial sums of runs that cross tile borders
+    float *rows;                            // [L][N] rows of the positions, for the forward pass that works from the lists
+    int4 *tiles;                            // [L / 32 + m2 + 1] tiles of that forward pass: {slice of G2, first item, items, 0}
     size_t bytes;
 };
 
@@ -46,6 +48,8 @@ static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
     g.crange = (int *)take(16);
     const int64_t tiles = (L + GT - 1) / GT + 1;
     g.part = (float *)take((size_t)tiles * 2 * N * 4);
+    g.rows = (float *)take((size_t)(L > 0 ? L : 1) * N * 4);
+    g.tiles = (int4 *)take(((size_t)L / 32 + (size_t)nbins + 1) * sizeof(int4));
     g.bytes = off + 256;
     return g;
 }
@@ -97,6 +101,46 @@ __global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restri
         if (prev < nb3) crange[0] = i;
         if (next >= nbins) crange[1] = i + 1;
     }
+}
+
+// Tiles of the forward pass that works from the lists: the list of every slice of the second core cut into pieces
+// of tp items, numbered slice after slice.  tiles[i] = {slice, first sorted item, items, 0}; entries past the last
+// tile get 0 items.  Every workgroup works the numbering out for itself (m2 <= 4 x 256 slices, four per thread)
+// and its threads then look their own tiles up.
+__global__ __launch_bounds__(WG) void grp_tiles_kernel(int m1, int m2, int L, int tp, const int *__restrict__ off,
+                                                       const int *__restrict__ end, int4 *__restrict__ tiles, int ntiles)
+{
+    __shared__ int s_tmp[NWAVE + 1];
+    __shared__ int s_base[4 * WG + 1];
+    const int t = threadIdx.x;
+    int cnt[4], v = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int b = 4 * t + q;
+        int len = b < m2 ? end[m1 + b] - off[m1 + b] : 0;
+        len = len < 0 ? 0 : (len > L ? L : len);
+        cnt[q] = (len + tp - 1) / tp;
+        v += cnt[q];
+    }
+    int total;
+    int base = block_excl_scan(v, s_tmp, &total);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { s_base[4 * t + q] = base; base += cnt[q]; }
+    if (t == WG - 1) s_base[4 * WG] = total;
+    __syncthreads();
+    const int tile = blockIdx.x * WG + t;
+    if (tile >= ntiles) return;
+    int4 out = make_int4(0, 0, 0, 0);
+    if (tile < total) {
+        int lo = 0, hi = 4 * WG;                                           // last b with s_base[b] <= tile
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_base[mid] <= tile) lo = mid; else hi = mid;
+        }
+        const int first = off[m1 + lo] + (tile - s_base[lo]) * tp;
+        out = make_int4(lo, first, min(tp, end[m1 + lo] - first), 0);
+    }
+    tiles[tile] = out;
 }
 
 // bag of position k: fixed bag length if the caller found one, else a search

@@ -9,9 +9,12 @@ same GPU (the studies of Sections 6.6 and 6.7 of the paper, on synthetic inputs)
   tables  : the seven independent tables of the multi-hot workload (8192 samples x 20 indices each,
             caches of 0.01 %), one after the other on one stream against one stream per table.
 
-A step is forward + backward + SGD.  TT: tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0; dense:
-tt_dense_bag_fwd + tt_dense_bag_bwd_sgd.  Every step sequence is captured in a HIP graph, so
-the figures are GPU times.  Prints a markdown table.
+A step is forward + backward + SGD.  TT: tt_emb_fwd_keep_t0 + tt_emb_bwd_sgd_t0 (tt_emb_fwd_keep +
+tt_emb_bwd_sgd_kept where the library keeps position lists; tt_emb_bwd_prepare one step ahead on a second stream,
+tt_emb_fwd_prepared and tt_emb_bwd_sgd_prepared where the backward has an index-only pre-pass); dense: tt_dense_bag_fwd + the faster
+of tt_dense_bag_bwd_sgd (one float atomic per position and column) and tt_dense_bag_bwd_sgd_merged
+(positions sorted by row, duplicates added up first, one write per distinct row), both reported.
+Every step sequence is captured in a HIP graph, so the figures are GPU times.  Prints a markdown table.
 
     python -m paper_2101_11714_amd.microbench [pooling] [hitrate] [tables]
 """
@@ -74,6 +77,7 @@ class _Table:
         # the pre-pass of step j + 1 is enqueued behind the forward pass of step j (two workspaces alternate), the first
         # one of a graph next to its own forward pass.
         two_calls = B.bwd_has_prepass(self.c, L, cache.K if cache else 0, True)
+        fwd_lists = two_calls and B.fwd_uses_lists(self.c, L, cache.K if cache else 0, True)
         side = torch.cuda.Stream() if two_calls else None
         wsp = [ws, torch.empty_like(ws)] if two_calls else [ws, ws]
         done = [torch.cuda.Event(), torch.cuda.Event()] if two_calls else None
@@ -88,34 +92,58 @@ class _Table:
             cur, nxt = (self.cores, self.cores2) if j % 2 == 0 else (self.cores2, self.cores)
             if two_calls and j == 0:
                 prepare_on_side(0)
-            B.tt_emb_fwd_keep_t0(self.c, cur, idx[j], off[j], n_bags, out, t0[j], cache=cache)
-            if two_calls:
-                if j + 1 < STEPS:
-                    prepare_on_side(j + 1)                  # next to this step's backward pass
+            if fwd_lists:                                   # the forward pass works from the pre-pass's lists where it can
+                torch.cuda.current_stream().wait_event(done[j % 2])
+                B.tt_emb_fwd_prepared(self.c, cur, idx[j], off[j], n_bags, out, wsp[j % 2], t0=t0[j], cache=cache)
+            else:
+                B.tt_emb_fwd_keep_t0(self.c, cur, idx[j], off[j], n_bags, out, t0[j], cache=cache)
+            if two_calls and j + 1 < STEPS:
+                prepare_on_side(j + 1)                      # next to this step's backward pass
+            if two_calls and not fwd_lists:
                 torch.cuda.current_stream().wait_event(done[j % 2])
             B.tt_emb_bwd_sgd(self.c, cur, nxt, idx[j], off[j], n_bags, go[j], lr, cache=cache, workspace=wsp[j % 2], t0=t0[j],
                              prepared=two_calls)
 
-        def dense_step(j):
+        # short lists of the (2,2,4) shapes: per-slice position lists, filed for batch j + 1 by riders of batch j's backward
+        lists = cache is None and B.kept_has_lists(self.c, L)
+        if lists:
+            kept = [torch.empty(B.kept_bytes(self.c, L), dtype=torch.uint8, device=dev) for _ in batches]
+            B.tt_emb_kept_prepare(self.c, idx[0], kept[0])
+
+            def tt_step(j):                                                  # noqa: F811
+                cur, nxt = (self.cores, self.cores2) if j % 2 == 0 else (self.cores2, self.cores)
+                jn = (j + 1) % STEPS
+                B.tt_emb_fwd_keep(self.c, cur, idx[j], off[j], n_bags, out, kept[j], lists_ready=True)
+                B.tt_emb_bwd_sgd_kept(self.c, cur, nxt, idx[j], off[j], n_bags, go[j], kept[j], lr, workspace=ws,
+                                      next_batch=(idx[jn], kept[jn]))
+
+        wsd = torch.empty(max(B.dense_bwd_workspace_bytes(L, self.shape.dim), 256), dtype=torch.uint8, device=dev)
+
+        def dense_step_atomic(j):
             B.tt_dense_bag_fwd(self.dense, idx[j], off[j], n_bags, out)
             B.tt_dense_bag_bwd_sgd(self.dense, idx[j], off[j], n_bags, go[j], lr)
 
-        return _graph_us(tt_step), _graph_us(dense_step)
+        def dense_step_merged(j):
+            B.tt_dense_bag_fwd(self.dense, idx[j], off[j], n_bags, out)
+            B.tt_dense_bag_bwd_sgd_merged(self.dense, idx[j], off[j], n_bags, go[j], lr, workspace=wsd)
+
+        return _graph_us(tt_step), _graph_us(dense_step_atomic), _graph_us(dense_step_merged)
 
 
 def pooling(dev):
     print("## Pooling factor x TT rank (Kaggle-shaped table, %d samples per step, no cache)\n" % N_BAGS)
-    print("| P | lookups/step | R | TT step us | dense step us | TT / dense | TT us per sample | TT M lookups/s |")
-    print("|---|---|---|---|---|---|---|---|")
+    print("| P | lookups/step | R | TT step us | dense us, atomics | dense us, merged | TT / faster dense | TT us per sample | TT M lookups/s |")
+    print("|---|---|---|---|---|---|---|---|---|")
     for R in (8, 16, 32, 64):
         base = W.WORKLOADS["sweep_r%d" % R]
         tab = _Table(base.tables[0], base.init, base.seed, dev)
         for P in (1, 10, 100):
             wl = dataclasses.replace(base, n_bags=N_BAGS, bag_len=(P, P))
             batches = [W.make_batch(wl, 0, j) for j in range(STEPS)]
-            tt, dn = tab.time(batches)
+            tt, da, dm = tab.time(batches)
             L = N_BAGS * P
-            print("| %d | %d | %d | %.1f | %.1f | %.1f | %.4f | %.1f |" % (P, L, R, tt, dn, tt / dn, tt / N_BAGS, L / tt), flush=True)
+            print("| %d | %d | %d | %.1f | %.1f | %.1f | %.1f | %.4f | %.1f |"
+                  % (P, L, R, tt, da, dm, tt / min(da, dm), tt / N_BAGS, L / tt), flush=True)
         del tab
         torch.cuda.empty_cache()
 
@@ -126,8 +154,8 @@ def hitrate(dev):
     K = W.cache_size(wl, 0)
     print("\n## Cache hit rate (table of %d rows, dimension %d, R = %d, cache of %d rows, %d samples per step)\n"
           % (shape.num_rows, shape.dim, shape.r[1], K, N_BAGS))
-    print("| P | hit rate | TT+cache step us | dense step us | TT / dense | TT M lookups/s |")
-    print("|---|---|---|---|---|---|")
+    print("| P | hit rate | TT+cache step us | dense us, atomics | dense us, merged | TT / faster dense | TT M lookups/s |")
+    print("|---|---|---|---|---|---|---|")
     tab = _Table(shape, wl.init, wl.seed, dev)
     rng = np.random.default_rng(77)
     cached = np.sort(rng.choice(shape.num_rows, K, replace=False)).astype(np.int64)
@@ -137,9 +165,10 @@ def hitrate(dev):
     for P in (10, 100):
         for h in (0.0, 0.5, 0.75, 0.9, 0.95, 0.99):
             batches = [W.make_hit_rate_batch(shape, cached, N_BAGS, P, h, 100 + j) for j in range(STEPS)]
-            tt, dn = tab.time(batches, cache=cache)
+            tt, da, dm = tab.time(batches, cache=cache)
             L = N_BAGS * P
-            print("| %d | %.0f %% | %.1f | %.1f | %.1f | %.1f |" % (P, 100 * h, tt, dn, tt / dn, L / tt), flush=True)
+            print("| %d | %.0f %% | %.1f | %.1f | %.1f | %.1f | %.1f |" % (P, 100 * h, tt, da, dm, tt / min(da, dm), L / tt),
+                  flush=True)
 
 
 def tables(dev):

@@ -857,6 +857,43 @@ def test_dense_embedding_bag_matches_its_definition(N, lens):
                            alpha=torch.from_numpy(alpha).to(d))
     torch.cuda.synchronize()
     assert_close(tb.cpu().numpy(), ref_tab, "dense sparse SGD")
+    # the same update with duplicates merged first: same definition, and the same bits in every run
+    results = []
+    for _ in range(2):
+        tm = torch.from_numpy(table).to(d)
+        B.tt_dense_bag_bwd_sgd_merged(tm, torch.from_numpy(idx).to(d), torch.from_numpy(off).to(d), n_bags,
+                                      torch.from_numpy(go).to(d), lr, alpha=torch.from_numpy(alpha).to(d))
+        torch.cuda.synchronize()
+        results.append(tm)
+    assert_close(results[0].cpu().numpy(), ref_tab, "dense merged SGD")
+    assert torch.equal(results[0], results[1])
+
+
+@pytest.mark.parametrize("N", [16, 64])
+def test_dense_merged_update_runs_over_many_tiles(N):
+    """Runs of equal rows of every kind for the tiled sum: one row that fills dozens of tiles, runs that begin or end
+    on a tile border, a run over exactly one tile, single positions, one index per bag without an offsets array."""
+    rng = np.random.default_rng(62)
+    rows = 100000
+    pieces = [np.full(64 * 70 + 5, 99999), np.full(64, 5), np.full(59, 7), np.full(128, 8), np.full(1, 9),
+              rng.integers(10, 5000, 3000), np.full(64 * 65, 6000), rng.integers(7000, rows - 1, 777)]
+    idx = np.concatenate(pieces).astype(np.int64)
+    rng.shuffle(idx)
+    L = idx.size
+    table = rng.standard_normal((rows, N)).astype(np.float32)
+    go = rng.standard_normal((L, N)).astype(np.float32)
+    lr = 0.01
+    ref = table.astype(np.float64)
+    np.add.at(ref, idx, -lr * go.astype(np.float64))
+    d = dev()
+    tm = torch.from_numpy(table).to(d)
+    B.tt_dense_bag_bwd_sgd_merged(tm, torch.from_numpy(idx).to(d), None, L, torch.from_numpy(go).to(d), lr)
+    torch.cuda.synchronize()
+    got = tm.cpu().numpy()
+    touched = np.unique(idx)
+    assert_close(got[touched], ref[touched], "dense merged SGD, long runs")
+    untouched = np.setdiff1d(np.arange(rows), touched)
+    assert np.array_equal(got[untouched], table[untouched])
 
 
 # ------------------------------------------------------------------ mean pooling
