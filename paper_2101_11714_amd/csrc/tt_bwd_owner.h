@@ -1,0 +1,492 @@
+// Backward pass for long index streams on the matrix cores (Eq. 4 / Alg. 2), after the grouping
+// pre-pass of tt_group.h and with the intermediate T0 kept by the forward pass.
+//
+// The positions that share a slice of the second core share the operand Bm = G2[i2], so the
+// two large products of Eq. 4 become matrix products over a tile of such positions.  With
+// dT0'[(e,j1)][(j2,b)] = sum_j3 dY_e[(j1,j2)][j3] C_e[b][j3] (the rows (e,j1) of up to TP
+// positions stacked: 128 rows):
+//     dG2[i2][a][(j2,b)] += sum_rows A[(e,j1)][a] dT0'[(e,j1)][(j2,b)]        (A = stacked rows of G1)
+//     P[(e,j1)][a]        = sum_(j2,b) dT0'[(e,j1)][(j2,b)] Bm[a][(j2,b)]     (the G1 gradient of position e)
+// both as fp32 MFMA 32x32x2 products with operands in LDS, one j2 at a time.  A tile leaves
+// its part of the slice gradient in part2[tile] and the rows P in pbuf[k]; three small kernels
+// finish the cores in a fixed order of summation (no atomics):
+//   * the parts of every G2 slice are added tile after tile,
+//   * the G1 gradient is a segmented sum of the rows P over the sorted items of the first
+//     core (one wave per 64 items; runs over tile borders are finished by the wave where the
+//     run begins, as in the cached-row reduction of tt_group.h),
+//   * the G3 gradient dG3[i3][b][j3] += sum_(j1,j2) T0_k[(j1,j2)][b] dY_k[(j1,j2)][j3] is the same
+//     kind of segmented sum over the sorted items of the third core, the row of an item being
+//     computed from the kept T0 on the way.
+// Every finish either adds to the gradient arrays or writes x - lr * gradient to the second
+// set of cores (slices that no position touches are copied).
+#pragma once
+
+#include "tt_common.h"
+#include "tt_fast.h"
+#include "tt_fast_bwd.h"
+#include "tt_group.h"
+
+namespace tt {
+
+constexpr int BO_MAX_CH = 4;                        // consecutive tiles that one workgroup takes at most: their parts of a slice gradient are added in registers
+
+template <typename C>
+struct BoCfg {
+    static constexpr int ROWS = 128, TP = ROWS / C::N1;
+    static constexpr int RB = C::R / 32;                       // 32-wide blocks of a rank index
+    static constexpr int LDA = C::R + 1, LDT = C::R + 2, LDB = C::R + 1;
+    static constexpr int NBQ = WG / TP, BQ = C::R / NBQ;       // threads per position / values of b per thread in dT0'
+    static constexpr int DY_FLOATS = TP * C::N;
+    static constexpr int LDS_FLOATS = DY_FLOATS + ROWS * LDA + ROWS * LDT + C::R * LDB;
+    static_assert(C::R % 32 == 0 && RB * RB <= NWAVE && WG % TP == 0 && NBQ <= 8, "tile layout");
+};
+
+template <typename C>
+static inline size_t bo_lds_bytes() { return (size_t)BoCfg<C>::LDS_FLOATS * sizeof(float); }
+
+// One workgroup per ch consecutive tiles of the tile table (tt_group.h), going on to later ones while there are
+// any.  The part of a slice gradient that the workgroup has added up goes to part2[first tile of that stretch]: a
+// stretch begins with the workgroup's first tile and wherever the slice changes.
+template <typename C>
+__global__ __launch_bounds__(WG) void bo_tile_kernel(Params p, const float *__restrict__ G1, const float *__restrict__ G2,
+                                                     const float *__restrict__ G3, const int64_t *__restrict__ indices, int L,
+                                                     const int64_t *__restrict__ offsets, int n_bags,
+                                                     const float *__restrict__ alpha, const float *__restrict__ grad_out,
+                                                     const int4 *__restrict__ info, const int4 *__restrict__ tiles, int ntiles,
+                                                     int ch, float *__restrict__ part2, float *__restrict__ pbuf)
+{
+    using F = BoCfg<C>;
+    constexpr int N1 = C::N1, N2 = C::N2, R = C::R, N = C::N, COLS = C::COLS, TP = F::TP;
+    constexpr int LDA = F::LDA, LDT = F::LDT, LDB = F::LDB;
+    constexpr bool KEEP_C = F::BQ <= 8;               // the third core's rows stay in registers over the j2 (else: fetched again)
+    extern __shared__ __align__(16) float bo_lds[];
+    float *dyl = bo_lds;                              // [TP][N]      alpha_k dY of the positions
+    float *As = dyl + F::DY_FLOATS;                   // [128][LDA]   stacked rows of G1
+    float *dT = As + F::ROWS * LDA;                   // [128][LDT]   dT0' for the current j2
+    float *Bl = dT + F::ROWS * LDT;                   // [R][LDB]     Bm[a][(j2, .)]
+    __shared__ int s_k[TP], s_i3[TP], s_bag[TP];
+    __shared__ int s_i1[TP];
+    __shared__ float s_w[TP];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int ln = lane & 31, kh = lane >> 5;
+    const bool g2wave = w < F::RB * F::RB;            // this wave holds block (ab, bb) of the R x R slice gradient per j2
+    const int ab1 = w / F::RB, bb1 = w % F::RB;
+
+    for (int chunk = blockIdx.x; chunk * ch < ntiles; chunk += gridDim.x) {
+        mfma16_t acc1[N2];
+        int cur = -1, slot = 0;
+        auto flush1 = [&]() __attribute__((always_inline)) {
+            if (cur >= 0 && g2wave) {
+#pragma unroll
+                for (int j2 = 0; j2 < N2; ++j2) {
+                    float *dst = part2 + (size_t)slot * C::sB + j2 * R + 32 * bb1 + ln;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) dst[(size_t)(32 * ab1 + 8 * (r / 4) + 4 * kh + r % 4) * COLS] = acc1[j2][r];
+                }
+            }
+        };
+        for (int tile = chunk * ch; tile < min(ntiles, (chunk + 1) * ch); ++tile) {
+            const int4 td = tiles[tile];
+            const int i2 = td.x, lo = td.y, n = td.z;
+            // (uniform: the tiles in use come first; the second test guards against a table that no pre-pass wrote)
+            if (n <= 0 || (unsigned)i2 >= (unsigned)p.m2 || lo < 0 || n > TP || lo + n > 3 * L) break;
+            if (i2 != cur) {
+                flush1();
+                cur = i2; slot = tile;
+#pragma unroll
+                for (int j2 = 0; j2 < N2; ++j2)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc1[j2][r] = 0.f;
+            }
+
+            // 1. the positions
+            if (t < TP) {
+                int k = 0, i1 = 0, i3 = 0, bag = 0;
+                float wgt = 0.f;
+                if (t < n) {
+                    const int4 pi = info[lo + t];
+                    k = (unsigned)pi.x < (unsigned)L ? pi.x : 0;
+                    i1 = pi.y; i3 = pi.z; bag = pi.w;
+                    wgt = alpha ? alpha[k] : 1.f;
+                }
+                s_k[t] = k; s_i1[t] = i1; s_i3[t] = i3; s_bag[t] = bag; s_w[t] = wgt;
+            }
+            __syncthreads();
+            // 2. dY to LDS (positions past the end: zeros)
+            for (int i = t; i < TP * N / 4; i += WG) {
+                const int e = i / (N / 4), f = i % (N / 4);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < n) {
+                    v = *reinterpret_cast<const float4 *>(grad_out + (size_t)s_bag[e] * N + 4 * f);
+                    const float wgt = s_w[e];
+                    v.x *= wgt; v.y *= wgt; v.z *= wgt; v.w *= wgt;
+                }
+                *reinterpret_cast<float4 *>(dyl + e * N + 4 * f) = v;
+            }
+            // thread (position ee, bq) of the dT0' product: its rows b = NBQ i + bq of G3[i3]
+            const int ee = t / F::NBQ, bq = t % F::NBQ;
+            const bool on = ee < n;
+            const float4 *Cp = reinterpret_cast<const float4 *>(G3 + (size_t)s_i3[ee] * C::sC) + bq;
+            float4 cv[F::BQ];
+            if constexpr (KEEP_C) {
+#pragma unroll
+                for (int i = 0; i < F::BQ; ++i) cv[i] = on ? Cp[i * F::NBQ] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            // the stacked rows of G1 to LDS
+            for (int i = t; i < F::ROWS * R / 4; i += WG) {
+                const int row = i / (R / 4), a4 = 4 * (i % (R / 4)), e = row / N1, j1 = row % N1;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < n) v = *reinterpret_cast<const float4 *>(G1 + (size_t)s_i1[e] * C::sA + j1 * R + a4);
+                float *d = As + row * LDA + a4;
+                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+            }
+            __syncthreads();
+
+            mfma16_t accp[F::RB];                                          // P: rows 32 w .. 32 w + 31, all a
+#pragma unroll
+            for (int ab = 0; ab < F::RB; ++ab)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accp[ab][r] = 0.f;
+
+#pragma unroll
+            for (int j2 = 0; j2 < N2; ++j2) {
+                // 3. Bm[a][(j2, b)] to LDS
+                {
+                    const float *src = G2 + (size_t)i2 * C::sB + j2 * R;
+                    for (int i = t; i < R * R / 4; i += WG) {
+                        const int a = i / (R / 4), b4 = 4 * (i % (R / 4));
+                        const float4 v = *reinterpret_cast<const float4 *>(src + a * COLS + b4);
+                        float *d = Bl + a * LDB + b4;
+                        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+                    }
+                }
+                // 4. dT0'[(ee, j1)][b] for this j2
+                if constexpr (!KEEP_C) {
+#pragma unroll
+                    for (int i = 0; i < F::BQ; ++i) cv[i] = on ? Cp[i * F::NBQ] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int j1 = 0; j1 < N1; ++j1) {
+                    const float4 dy = *reinterpret_cast<const float4 *>(dyl + ee * N + (j1 * N2 + j2) * 4);
+#pragma unroll
+                    for (int i = 0; i < F::BQ; ++i) {
+                        const float4 c = cv[i];
+                        dT[(ee * N1 + j1) * LDT + i * F::NBQ + bq] = fmaf(dy.x, c.x, fmaf(dy.y, c.y, fmaf(dy.z, c.z, dy.w * c.w)));
+                    }
+                }
+                __syncthreads();
+                // 5. the part of dG2: block (ab, bb) of the R x R result for this j2, over all 128 rows
+                if (g2wave) {
+#pragma unroll 8
+                    for (int s = 0; s < F::ROWS / 2; ++s) {
+                        const int row = kh * (F::ROWS / 2) + s;
+                        acc1[j2] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[row * LDA + 32 * ab1 + ln], dT[row * LDT + 32 * bb1 + ln],
+                                                                       acc1[j2], 0, 0, 0);
+                    }
+                }
+                // 6. P += dT0' Bm^T over the columns of this j2
+#pragma unroll 4
+                for (int s = 0; s < R / 2; ++s) {
+                    const float av = dT[(32 * w + ln) * LDT + kh * (R / 2) + s];
+#pragma unroll
+                    for (int ab = 0; ab < F::RB; ++ab)
+                        accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * ab + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
+                }
+                __syncthreads();                                           // dT0' and Bm are rewritten for the next j2
+            }
+            // 7. the rows P of the positions: pbuf[k][j1][a]
+#pragma unroll
+            for (int ab = 0; ab < F::RB; ++ab)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 32 * w + 8 * (r / 4) + 4 * kh + r % 4, e = row / N1, j1 = row % N1;
+                    if (e < n) pbuf[((size_t)s_k[e] * N1 + j1) * R + 32 * ab + ln] = accp[ab][r];
+                }
+            __syncthreads();                                               // the position arrays are rewritten for the next tile
+        }
+        flush1();
+    }
+}
+
+// dst[i2] = src[i2] + mul * (sum of the parts of slice i2, in the order of their tiles); a slice without tiles is copied
+// if dst is another array.  One thread per float4 of a slice; tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles.
+__global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, int ch, const int *__restrict__ tile_base,
+                                                          const float4 *__restrict__ part2, const float4 *__restrict__ src,
+                                                          float4 *__restrict__ dst, float mul)
+{
+    const int per = (slice4 + WG - 1) / WG;                                 // workgroups per slice
+    const int i2 = blockIdx.x / per, e = (blockIdx.x % per) * WG + threadIdx.x;
+    if (i2 >= m2 || e >= slice4) return;
+    const int t0 = tile_base[i2], t1 = tile_base[i2 + 1];
+    const size_t at = (size_t)i2 * slice4 + e;
+    if (t1 <= t0) {
+        if (dst != src) dst[at] = src[at];
+        return;
+    }
+    const float4 old = src[at];
+    float4 sum = part2[(size_t)t0 * slice4 + e];                             // the stretch that begins with the slice
+    // ... and those that begin with a workgroup's first tile (every ch-th tile of the table)
+    for (int u0 = (t0 / ch + 1) * ch; u0 < t1; u0 += 16 * ch) {
+        float4 x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int u = u0 + j * ch;
+            x[j] = u < t1 ? part2[(size_t)u * slice4 + e] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+    }
+    dst[at] = make_float4(fmaf(mul, sum.x, old.x), fmaf(mul, sum.y, old.y), fmaf(mul, sum.z, old.z), fmaf(mul, sum.w, old.w));
+}
+
+// ---- segmented sums over the sorted items of the first and of the third core ----------------------
+//
+// Items [range[0], range[1]) of the sorted arrays have keys klo .. klo + slices - 1; the row of an item (ROW4 float4,
+// lane l < ROW4 holds float4 l) comes from the producer.  One wave per tile of 64 items: runs of equal keys inside
+// the tile are applied at once (dst[key] = src[key] + mul * sum), the part of a run that goes on in the next tile is
+// left in part[tile][1], the part of a run that began in an earlier tile in part[tile][0] (a tile that is one run
+// throughout: [0]); bo_seg_fix_kernel finishes the runs that cross tile borders.
+constexpr int BO_ST = 64;
+
+// row of an item of the first core: the G1 gradient of its position, from pbuf
+struct BoRowP {
+    const float *pbuf;
+    int row_floats;
+    __device__ __forceinline__ float4 operator()(int k, int /*bag*/, float /*w*/, int lane, bool active) const
+    {
+        return active ? *reinterpret_cast<const float4 *>(pbuf + (size_t)k * row_floats + 4 * lane) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+};
+
+// row of an item of the third core: lane b holds sum_(j1,j2) T0_k[(j1,j2)][b] w dY[bag][(j1,j2)][0..3]
+template <typename C>
+struct BoRowT0 {
+    const float *t0, *grad_out;
+    __device__ __forceinline__ float4 operator()(int k, int bag, float w, int lane, bool active) const
+    {
+        constexpr int NJ = C::N1 * C::N2;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!active) return o;
+        const float *T = t0 + (size_t)k * NJ * C::R + lane;
+        const float4 *dy = reinterpret_cast<const float4 *>(grad_out + (size_t)bag * C::N);
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const float tv = w * T[jj * C::R];
+            const float4 d = dy[jj];
+            o.x = fmaf(tv, d.x, o.x); o.y = fmaf(tv, d.y, o.y); o.z = fmaf(tv, d.z, o.z); o.w = fmaf(tv, d.w, o.w);
+        }
+        return o;
+    }
+};
+
+template <int NBATCH, typename Producer>
+__global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int klo, int L,
+                                                    const uint64_t *__restrict__ ks, const int4 *__restrict__ info,
+                                                    const int *__restrict__ range, const float *__restrict__ alpha, const float *__restrict__ src,
+                                                    float *__restrict__ dst, float mul, float *__restrict__ part)
+{
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int r0 = range[0], r1 = range[1];
+    const int i0 = r0 + tile * BO_ST;
+    if (i0 >= r1) return;
+    const int cnt = min(BO_ST, r1 - i0);
+    const bool active = lane < row4;
+    int my_key = -1, my_k = 0, my_bag = 0;
+    float my_w = 0.f;
+    if (lane < cnt) {
+        my_key = (int)ks[i0 + lane];
+        const int4 pi = info[i0 + lane];
+        my_k = (unsigned)pi.x < (unsigned)L ? pi.x : 0;
+        my_bag = pi.w;
+        my_w = alpha ? alpha[my_k] : 1.f;
+    }
+    const int key_prev = i0 > r0 ? (int)ks[i0 - 1] : -1;
+    const int key_next = i0 + cnt < r1 ? (int)ks[i0 + cnt] : -1;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f), old_last = sum;
+    int cur = __builtin_amdgcn_readfirstlane(my_key);
+    bool first = cur == key_prev;                                          // the first run began in an earlier tile
+    auto flush = [&](int key, bool goes_on) {
+        if (active) {
+            if (first) *reinterpret_cast<float4 *>(part + ((size_t)tile * 2 + 0) * 256 + 4 * lane) = sum;
+            else if (goes_on) *reinterpret_cast<float4 *>(part + ((size_t)tile * 2 + 1) * 256 + 4 * lane) = sum;
+            else
+                *reinterpret_cast<float4 *>(dst + (size_t)(key - klo) * (4 * row4) + 4 * lane) =
+                    make_float4(fmaf(mul, sum.x, old_last.x), fmaf(mul, sum.y, old_last.y), fmaf(mul, sum.z, old_last.z),
+                                fmaf(mul, sum.w, old_last.w));
+        }
+        first = false;
+        sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    };
+    for (int e0 = 0; e0 < cnt; e0 += NBATCH) {
+        float4 g[NBATCH], old[NBATCH];
+#pragma unroll
+        for (int q = 0; q < NBATCH; ++q) {
+            const int e = min(e0 + q, cnt - 1);
+            const int key = __builtin_amdgcn_readlane(my_key, e), k = __builtin_amdgcn_readlane(my_k, e);
+            const int bag = __builtin_amdgcn_readlane(my_bag, e);
+            const float wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), e));
+            g[q] = prod(k, bag, wgt, lane, active);
+            old[q] = active ? *reinterpret_cast<const float4 *>(src + (size_t)(key - klo) * (4 * row4) + 4 * lane)
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < NBATCH; ++q) {
+            const int e = e0 + q;
+            if (e < cnt) {                                                   // uniform
+                const int key = __builtin_amdgcn_readlane(my_key, e);
+                if (key != cur) { flush(cur, false); cur = key; }
+                sum.x += g[q].x; sum.y += g[q].y; sum.z += g[q].z; sum.w += g[q].w;
+                old_last = old[q];
+            }
+        }
+    }
+    if (first || cur == key_next) flush(cur, true); else flush(cur, false);
+}
+
+// A run that crosses tile borders is applied by the wave of the tile where it begins: its own part[t][1], then
+// part[u][0] of the later tiles that the run reaches (a later tile is reached if its first item still has the run's
+// key), in tile order; the wave looks at 64 later tiles at a time.
+__global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const uint64_t *__restrict__ ks,
+                                                        const int *__restrict__ range, const float *__restrict__ src,
+                                                        float *__restrict__ dst, float mul, const float *__restrict__ part)
+{
+    constexpr int NB = 32;
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int r0 = range[0], r1 = range[1];
+    const int ntiles = (r1 - r0 + BO_ST - 1) / BO_ST;
+    const int i0 = r0 + tile * BO_ST, i1 = i0 + BO_ST;
+    if (i1 >= r1) return;                                                    // no tile here, or nothing to its right
+    const int key = (int)ks[i1 - 1];
+    if ((int)ks[i1] != key) return;                                          // the last run ends with the tile
+    if ((int)ks[i0] == key && i0 > r0 && (int)ks[i0 - 1] == key) return;     // it began in an earlier tile
+    int last = tile;
+    for (int base = tile + 1; base < ntiles; base += WAVE) {
+        const int u = base + lane;
+        const bool in = u < ntiles && (int)ks[r0 + (size_t)u * BO_ST] == key;
+        const unsigned long long b = __ballot(in);
+        const int reach = b == ~0ull ? WAVE : __builtin_ctzll(~b);
+        last = base + reach - 1;
+        if (reach < WAVE) break;
+    }
+    const bool active = lane < row4;
+    float4 sum = active ? *reinterpret_cast<const float4 *>(part + ((size_t)tile * 2 + 1) * 256 + 4 * lane) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u0 = tile + 1; u0 <= last; u0 += NB) {
+        float4 x[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            x[j] = active ? *reinterpret_cast<const float4 *>(part + ((size_t)min(u0 + j, last) * 2 + 0) * 256 + 4 * lane)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            if (u0 + j <= last) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+    }
+    if (active) {
+        const size_t at = (size_t)(key - klo) * (4 * row4) + 4 * lane;
+        const float4 old = *reinterpret_cast<const float4 *>(src + at);
+        *reinterpret_cast<float4 *>(dst + at) =
+            make_float4(fmaf(mul, sum.x, old.x), fmaf(mul, sum.y, old.y), fmaf(mul, sum.z, old.z), fmaf(mul, sum.w, old.w));
+    }
+}
+
+__global__ __launch_bounds__(WG) void bo_copy_kernel(const float4 *__restrict__ a, float4 *__restrict__ b, int64_t n4)
+{
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n4; i += (int64_t)gridDim.x * WG) b[i] = a[i];
+}
+
+// ---- host side -------------------------------------------------------------------------------------
+
+static inline bool bwd_owner_supported(const Params &p)
+{
+    const int cfg = fast_config(p);
+    return (cfg == 2 || cfg == 3 || cfg == 4 || cfg == 5) && p.m2 <= 4 * WG;
+}
+
+struct BoWs {
+    float *part2;        // [tiles][sB]
+    float *pbuf;         // [L][sA]
+    float *seg1, *seg3;  // [L / 64 + 1][2][256] each
+    size_t bytes;
+};
+
+static inline int bo_tiles(const Params &p, int64_t L) { return (int)((L + 128 / p.n1 - 1) / (128 / p.n1)) + p.m2; }
+
+static inline BoWs bo_ws_layout(void *ws, const Params &p, int64_t L)
+{
+    BoWs b;
+    char *base = (char *)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *q = base ? base + off : nullptr; off += (bytes + 255) & ~(size_t)255; return q; };
+    const int64_t Lp = L > 0 ? L : 1;
+    b.part2 = (float *)take((size_t)bo_tiles(p, Lp) * p.sB * 4);
+    b.pbuf = (float *)take((size_t)Lp * p.sA * 4);
+    const size_t seg = (size_t)(Lp / BO_ST + 2) * 2 * 256 * 4;
+    b.seg1 = (float *)take(seg);
+    b.seg3 = (float *)take(seg);
+    b.bytes = off;
+    return b;
+}
+
+// dst (o1..o3, or the gradient arrays if they are null) as described at the top.  crange[2..3]: the sorted range of
+// the third core's items; the first core's items start the sorted arrays.
+template <typename C>
+static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
+                                          int64_t L, const int64_t *off, int n_bags, const float *alpha, const float *go,
+                                          const float *t0, float *dG1, float *dG2, float *dG3, float lr, float *o1, float *o2,
+                                          float *o3, const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b,
+                                          hipStream_t st)
+{
+    const size_t lds = bo_lds_bytes<C>();
+    static bool allowed = false;                                             // (one device per process)
+    if (!allowed) {
+        hipError_t e = hipFuncSetAttribute((const void *)bo_tile_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        allowed = true;
+    }
+    const bool fused = o1 != nullptr;
+    const float mul = fused ? -lr : 1.f;
+    const int ntiles = bo_tiles(p, L);
+    // tiles per workgroup: as many as leave a few workgroups for every compute unit (the table's size is an upper
+    // bound of the tiles in use)
+    // (measured: one tile per workgroup is fastest; more only pay once a tile's chain of dependent loads is hidden)
+    const int ch = 1;
+    const int nchunks = (ntiles + ch - 1) / ch;
+    hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nchunks < 8192 ? nchunks : 8192), dim3(WG), lds, st, p, G1, G2, G3, idx, (int)L, off,
+                       n_bags, alpha, go, g.info, g.tiles, ntiles, ch, b.part2, b.pbuf);
+    const int slice4 = C::sB / 4, per = (slice4 + WG - 1) / WG;
+    hipLaunchKernelGGL(bo_g2_finish_kernel, dim3(p.m2 * per), dim3(WG), 0, st, p.m2, slice4, ch, g.tile_base, (const float4 *)b.part2,
+                       (const float4 *)(fused ? G2 : dG2), (float4 *)(fused ? o2 : dG2), mul);
+    if (fused) {
+        hipLaunchKernelGGL(bo_copy_kernel, dim3(64), dim3(WG), 0, st, (const float4 *)G1, (float4 *)o1, (int64_t)p.m1 * C::sA / 4);
+        hipLaunchKernelGGL(bo_copy_kernel, dim3(256), dim3(WG), 0, st, (const float4 *)G3, (float4 *)o3, (int64_t)p.m3 * C::sC / 4);
+    }
+    const int seg_tiles = (int)(L / BO_ST + 1), seg_grid = (seg_tiles + NWAVE - 1) / NWAVE;
+    // first core: items [crange[4], crange[5]) = [0, number of items of the first core)
+    hipLaunchKernelGGL((bo_seg_kernel<8, BoRowP>), dim3(seg_grid), dim3(WG), 0, st, BoRowP{b.pbuf, C::sA}, C::sA / 4, 0, (int)L,
+                       ks, g.info, g.crange + 4, alpha, fused ? G1 : dG1, fused ? o1 : dG1, mul, b.seg1);
+    hipLaunchKernelGGL(bo_seg_fix_kernel, dim3(seg_grid), dim3(WG), 0, st, C::sA / 4, 0, ks, g.crange + 4, fused ? G1 : dG1,
+                       fused ? o1 : dG1, mul, b.seg1);
+    hipLaunchKernelGGL((bo_seg_kernel<(C::N1 * C::N2 > 4 ? 4 : 8), BoRowT0<C>>), dim3(seg_grid), dim3(WG), 0, st,
+                       BoRowT0<C>{t0, go}, C::sC / 4, p.m1 + p.m2, (int)L, ks, g.info, g.crange + 2, alpha,
+                       fused ? G3 : dG3, fused ? o3 : dG3, mul, b.seg3);
+    hipLaunchKernelGGL(bo_seg_fix_kernel, dim3(seg_grid), dim3(WG), 0, st, C::sC / 4, p.m1 + p.m2, ks, g.crange + 2,
+                       fused ? G3 : dG3, fused ? o3 : dG3, mul, b.seg3);
+    return hipGetLastError();
+}
+
+static inline hipError_t bwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
+                                   int64_t L, const int64_t *off, int n_bags, const float *alpha, const float *go, const float *t0,
+                                   float *dG1, float *dG2, float *dG3, float lr, float *o1, float *o2, float *o3,
+                                   const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b, hipStream_t st)
+{
+    switch (fast_config(p)) {
+    case 2: return launch_bwd_owner<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
+    case 3: return launch_bwd_owner<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
+    case 4: return launch_bwd_owner<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
+    case 5: return launch_bwd_owner<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tt

@@ -19,6 +19,7 @@
 #include "tt_kept.h"
 #include "tt_group.h"
 #include "tt_fwd_owner.h"
+#include "tt_bwd_owner.h"
 #include "tt_freq.h"
 #include "tt_dense.h"
 #include "tt_init.h"
@@ -38,6 +39,7 @@ thread_local char g_err[512] = "";
 // Kernel selection of the calling thread (tests only; no other thread's calls change with it):
 // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
 thread_local int g_fast_path = 1;
+thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h where they apply
 // from this many positions on the backward groups them first (tt_group.h)
 constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
 constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
@@ -172,7 +174,12 @@ size_t split_ws_bytes_max(const Params &p, int64_t L)
 size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
 {
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
-    return n ? align256(n * sizeof(float)) : 0;
+    size_t bytes = n ? align256(n * sizeof(float)) : 0;
+    if (grouped && bwd_owner_supported(p)) {                            // the tiled backward's buffers instead
+        const size_t b = align256(bo_ws_layout(nullptr, p, L).bytes);
+        bytes = b > bytes ? b : bytes;
+    }
+    return bytes;
 }
 
 }  // namespace
@@ -183,7 +190,8 @@ const char *tt_last_error(void) { return g_err; }
 
 int tt_emb_debug_set_fast_path(int mode)
 {
-    int old = g_fast_path;
+    int old = g_bwd_tiles ? 3 : g_fast_path;
+    g_bwd_tiles = mode == 3;
     g_fast_path = mode < 0 ? 0 : (mode > 2 ? 2 : mode);
     return old;
 }
@@ -378,6 +386,8 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     size_t g_bytes[3] = {0, 0, 0};
     if (fused && !fast)
         for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
+    // long streams with a kept T0: the products of Eq. 4 over tiles of positions, on the matrix cores (tt_bwd_owner.h)
+    const bool tiled = grouped && t0 && g_bwd_tiles && bwd_owner_supported(p);
     const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped) : 0;
     const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
     const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
@@ -452,11 +462,14 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             hipError_t es = radix_sort(g.sort, n, bits, st, &ks2, &vs2);
             if (es != hipSuccess) return hip_fail(es, "grouping sort");
             if (ks2 != ks || vs2 != vs) return fail(TT_ERR_BAD_ARG, "internal: the sort's result is not where it was expected");
-            hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, nb3, nbins, g.off, g.end, g.crange);
-            if (fwd_from_lists(p, L, cd.K, t0 != nullptr)) {                // for tt_emb_fwd_prepared
+            hipLaunchKernelGGL(grp_bounds_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, ks, n, p.m1, p.m1 + p.m2, nb3, nbins, g.off, g.end, g.crange);
+            if (tiled)
+                hipLaunchKernelGGL(grp_info_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, p, indices, (int)L, offsets, (int)n_bags, ks, vs,
+                                   nb3, g.info);
+            if (fwd_from_lists(p, L, cd.K, t0 != nullptr) || tiled) {       // for tt_emb_fwd_prepared and the tiled backward
                 const int ntiles = fwd_owner_tiles(p, L);
                 hipLaunchKernelGGL(grp_tiles_kernel, dim3(cdiv(ntiles, WG)), dim3(WG), 0, st, p.m1, p.m2, (int)L, fwd_owner_tp(p),
-                                   g.off, g.end, g.tiles, ntiles);
+                                   g.off, g.end, g.tiles, ntiles, g.tile_base);
             }
         }
         if (prep) {
@@ -464,13 +477,19 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
             return e == hipSuccess ? TT_OK : hip_fail(e, "backward pre-pass launch");
         }
         GrpCacheWork cw{ks, vs, g.crange, g.end, g.part, grad_cache, cd.K ? cdiv(cdiv(L, GT), NWAVE) : 0, clear_gc};
-        cache_merged = cd.K && fast_bwd_takes_cache_work(p, (int)L);     // the owner kernels do the cached rows as well
+        cache_merged = !tiled && cd.K && fast_bwd_takes_cache_work(p, (int)L);     // the owner kernels do the cached rows as well
         if (cd.K && !cache_merged) {
             hipLaunchKernelGGL(grp_cache_tile_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, vs, g.crange, offsets,
                                (int)n_bags, alpha, grad_output, grad_cache, g.part, clear_gc);
             hipLaunchKernelGGL(grp_cache_fix_kernel, dim3(cw.blocks), dim3(WG), 0, st, p, ks, g.crange, g.end, g.part,
                                grad_cache);
         }
+        if (tiled) {
+            const BoWs bw = bo_ws_layout(split_ws, p, L);
+            hipError_t eb = bwd_owner(p, cores[0], cores[1], cores[2], indices, L, offsets, (int)n_bags, alpha, grad_output, t0,
+                                      d1, d2, d3, lr, o1, o2, o3, ks, vs, g, bw, st);
+            if (eb != hipSuccess) return hip_fail(eb, "backward launch");
+        } else
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,
                  d1, d2, d3, vs, g.off, g.end, lr, o1, o2, o3, t0, split_ws, cache_merged ? &cw : nullptr,
                  fused && cache_merged ? cache->rows : nullptr, (int64_t)cd.K * p.N, st);

@@ -28,10 +28,12 @@ constexpr int GT = 64;                      // sorted items per tile of the cach
 struct GroupWs {
     SortWs sort;                            // for 3 L items
     int *off, *end;                         // [nbins + 1] list bounds per key, in the sorted arrays
-    int *crange;                            // [2] first and one-past-last sorted position of the cached items
+    int *crange;                            // [6] sorted ranges [first, one past last): [0..1] cached items, [2..3] items of the third core, [4..5] of the first
     float *part;                            // [tiles][2][N] partial sums of runs that cross tile borders
     float *rows;                            // [L][N] rows of the positions, for the forward pass that works from the lists
-    int4 *tiles;                            // [L / 32 + m2 + 1] tiles of that forward pass: {slice of G2, first item, items, 0}
+    int4 *tiles;                            // [L / 32 + m2 + 1] tiles of the passes that work from the lists: {slice of G2, first item, items, 0}
+    int *tile_base;                         // [m2 + 1] first tile of every slice of G2
+    int4 *info;                             // [3 L] per sorted item: {position k, i1, i3, bag} (unused items: k = -1)
     size_t bytes;
 };
 
@@ -45,11 +47,13 @@ static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
     auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += align256(bytes); return q; };
     g.off = (int *)take(((size_t)nbins + 1) * 4);
     g.end = (int *)take(((size_t)nbins + 1) * 4);
-    g.crange = (int *)take(16);
+    g.crange = (int *)take(32);
     const int64_t tiles = (L + GT - 1) / GT + 1;
     g.part = (float *)take((size_t)tiles * 2 * N * 4);
     g.rows = (float *)take((size_t)(L > 0 ? L : 1) * N * 4);
     g.tiles = (int4 *)take(((size_t)L / 32 + (size_t)nbins + 1) * sizeof(int4));
+    g.tile_base = (int *)take(((size_t)nbins + 2) * 4);
+    g.info = (int4 *)take((size_t)n * sizeof(int4));
     g.bytes = off + 256;
     return g;
 }
@@ -64,7 +68,7 @@ __global__ __launch_bounds__(WG) void grp_keys_kernel(Params p, const int64_t *_
 {
     const int k = blockIdx.x * WG + threadIdx.x;
     if (k <= nbins) { off[k] = 0; end[k] = 0; }
-    if (k < 2) crange[k] = 0;
+    if (k < 6) crange[k] = 0;
     for (int64_t i = k; i < nzero4; i += (int64_t)gridDim.x * WG) zero[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (k >= L) return;
     const int nb3 = p.m1 + p.m2 + p.m3;
@@ -85,7 +89,7 @@ __global__ __launch_bounds__(WG) void grp_keys_kernel(Params p, const int64_t *_
 }
 
 // list bounds of every key that occurs, and the range of the cached items
-__global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restrict__ ks, int n, int nb3, int nbins,
+__global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restrict__ ks, int n, int m1, int m12, int nb3, int nbins,
                                                         int *__restrict__ off, int *__restrict__ end,
                                                         int *__restrict__ crange)
 {
@@ -100,6 +104,11 @@ __global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restri
     if (key >= nb3) {
         if (prev < nb3) crange[0] = i;
         if (next >= nbins) crange[1] = i + 1;
+    } else if (key >= m12) {
+        if (prev < m12) crange[2] = i;
+        if (next >= nb3) crange[3] = i + 1;
+    } else if (key < m1) {
+        if (next >= m1) crange[5] = i + 1;                        // (the items of the first core start the sorted arrays)
     }
 }
 
@@ -108,7 +117,8 @@ __global__ __launch_bounds__(WG) void grp_bounds_kernel(const uint64_t *__restri
 // tile get 0 items.  Every workgroup works the numbering out for itself (m2 <= 4 x 256 slices, four per thread)
 // and its threads then look their own tiles up.
 __global__ __launch_bounds__(WG) void grp_tiles_kernel(int m1, int m2, int L, int tp, const int *__restrict__ off,
-                                                       const int *__restrict__ end, int4 *__restrict__ tiles, int ntiles)
+                                                       const int *__restrict__ end, int4 *__restrict__ tiles, int ntiles,
+                                                       int *__restrict__ tile_base)
 {
     __shared__ int s_tmp[NWAVE + 1];
     __shared__ int s_base[4 * WG + 1];
@@ -128,6 +138,8 @@ __global__ __launch_bounds__(WG) void grp_tiles_kernel(int m1, int m2, int L, in
     for (int q = 0; q < 4; ++q) { s_base[4 * t + q] = base; base += cnt[q]; }
     if (t == WG - 1) s_base[4 * WG] = total;
     __syncthreads();
+    if (blockIdx.x == 0)
+        for (int b = t; b <= m2; b += WG) tile_base[b] = s_base[b < 4 * WG ? b : 4 * WG];
     const int tile = blockIdx.x * WG + t;
     if (tile >= ntiles) return;
     int4 out = make_int4(0, 0, 0, 0);
@@ -144,6 +156,31 @@ __global__ __launch_bounds__(WG) void grp_tiles_kernel(int m1, int m2, int L, in
 }
 
 // bag of position k: fixed bag length if the caller found one, else a search
+__device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restrict__ offsets, int n_bags, int k);
+
+// What the kernels that work from the sorted items need of every item, in sorted order, so that they fetch it in one
+// go: the position k the item belongs to (payload r L + k), the digits of its row and its bag.
+__global__ __launch_bounds__(WG) void grp_info_kernel(Params p, const int64_t *__restrict__ indices, int L,
+                                                      const int64_t *__restrict__ offsets, int n_bags,
+                                                      const uint64_t *__restrict__ ks, const uint32_t *__restrict__ vs, int nb3,
+                                                      int4 *__restrict__ info)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i >= 3 * L) return;
+    int4 out = make_int4(-1, 0, 0, 0);
+    if ((int)ks[i] < nb3) {                                      // an item of one of the cores
+        uint32_t v = vs[i];
+        const int k = (int)(v >= 2u * (uint32_t)L ? v - 2u * (uint32_t)L : (v >= (uint32_t)L ? v - (uint32_t)L : v));
+        if (k < L) {
+            int i1, i2, i3;
+            decode(p, (uint32_t)indices[k], i1, i2, i3);
+            out = make_int4(k, i1, i3, grp_bag(p, offsets, n_bags, k));
+        }
+    }
+    info[i] = out;
+}
+
+
 __device__ __forceinline__ int grp_bag(const Params &p, const int64_t *__restrict__ offsets, int n_bags, int k)
 {
     if (!offsets) return k;
