@@ -155,9 +155,15 @@ inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // workspace of tt_emb_bwd: slot of every position (with a cache) | grouping pre-pass
 size_t slot_ws_bytes(int64_t L, int with_cache) { return with_cache ? align256((size_t)(L > 0 ? L : 1) * 4) : 0; }
 
+// Does the forward pass that works from the pre-pass's lists pay for such a table (tt_fwd_owner.h)?  (Measured: with a
+// cache that takes most positions the wave-per-bag kernel is as fast at rank 32: 49 against 51 us for 163,840 positions
+// of which a fifth go through the cores.)  If so the workspace has room for one row per position.
+static inline bool fwd_lists_pay(const Params &p, int64_t K) { return fwd_owner_supported(p) && (K == 0 || p.R1 >= 64); }
+static inline int fwd_rows_n(const Params &p, int64_t K) { return fwd_lists_pay(p, K) ? p.N : 0; }
+
 size_t fwd_bwd_ws_bytes(const Params &p, int64_t L, int64_t K)
 {
-    return 256 + slot_ws_bytes(L, K != 0) + group_ws_layout(nullptr, L, p.m1 + p.m2 + p.m3 + (int)K, p.N).bytes;
+    return 256 + slot_ws_bytes(L, K != 0) + group_ws_layout(nullptr, L, p.m1 + p.m2 + p.m3 + (int)K, p.N, fwd_rows_n(p, K)).bytes;
 }
 
 // what the specialised backward kernel needs beyond the lists: partial slice gradients of the roles it splits over
@@ -175,7 +181,7 @@ size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
 {
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
     size_t bytes = n ? align256(n * sizeof(float)) : 0;
-    if (grouped && bwd_owner_supported(p)) {                            // the tiled backward's buffers instead
+    if (grouped && g_bwd_tiles && bwd_owner_supported(p)) {             // the tiled backward's buffers instead
         const size_t b = align256(bo_ws_layout(nullptr, p, L).bytes);
         bytes = b > bytes ? b : bytes;
     }
@@ -291,10 +297,7 @@ static bool bwd_groups(const Params &p, int64_t L, int64_t K, bool kept_t0)
 // does tt_emb_fwd_prepared work from the pre-pass's lists for such a call?
 static bool fwd_from_lists(const Params &p, int64_t L, int64_t K, bool kept_t0)
 {
-    // (measured: with a cache that takes most positions the wave-per-bag kernel is as fast at rank 32: 49 against 51 us
-    // for 163,840 positions of which a fifth go through the cores)
-    const bool pays = K == 0 || p.R1 >= 64;
-    return L > 0 && fwd_owner_supported(p) && pays && bwd_groups(p, L, K, kept_t0) && 3 * L < (1ll << 31);
+    return L > 0 && fwd_lists_pay(p, K) && bwd_groups(p, L, K, kept_t0) && 3 * L < (1ll << 31);
 }
 
 int tt_emb_fwd_uses_lists(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0)
@@ -327,7 +330,7 @@ int tt_emb_fwd_prepared(const tt_shape_t *shape, const float *const cores[3],
     if (misaligned({cores[0], cores[1], cores[2], output, t0, cd.rows, workspace}))
         return fail(TT_ERR_BAD_ARG, "cores, output, t0, cache rows and workspace must be 16-byte aligned");
     const int nbins = p.m1 + p.m2 + p.m3 + cd.K;
-    GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
+    GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N, fwd_rows_n(p, cd.K));
     int bits = 1;
     while ((1 << bits) <= nbins) ++bits;
     uint64_t *ks; uint32_t *vs;
@@ -446,7 +449,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if (grouped && L > 0) {
         // group the positions by the slices / cache slots they touch, then run the owners on their lists
         const int nb3 = p.m1 + p.m2 + p.m3, nbins = nb3 + cd.K;
-        GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N);
+        GroupWs g = group_ws_layout((char *)workspace + slot_ws_bytes(L, cd.K != 0), L, nbins, p.N, fwd_rows_n(p, cd.K));
         const int n = 3 * (int)L;
         const int64_t kthreads = L > nbins + 1 ? L : nbins + 1;
         const bool clear_gc = fused && cd.K;                                // N is a multiple of 4 for these shapes

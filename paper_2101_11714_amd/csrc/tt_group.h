@@ -37,7 +37,8 @@ struct GroupWs {
     size_t bytes;
 };
 
-static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
+// rowsN: N if a forward pass may work from the lists of this workspace (it then leaves one row per position there), else 0
+static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N, int rowsN)
 {
     GroupWs g;
     const int64_t n = 3 * (L > 0 ? L : 1);
@@ -50,7 +51,7 @@ static inline GroupWs group_ws_layout(void *ws, int64_t L, int nbins, int N)
     g.crange = (int *)take(32);
     const int64_t tiles = (L + GT - 1) / GT + 1;
     g.part = (float *)take((size_t)tiles * 2 * N * 4);
-    g.rows = (float *)take((size_t)(L > 0 ? L : 1) * N * 4);
+    g.rows = (float *)take(rowsN ? (size_t)(L > 0 ? L : 1) * rowsN * 4 : 16);
     g.tiles = (int4 *)take(((size_t)L / 32 + (size_t)nbins + 1) * sizeof(int4));
     g.tile_base = (int *)take(((size_t)nbins + 2) * 4);
     g.info = (int4 *)take((size_t)n * sizeof(int4));

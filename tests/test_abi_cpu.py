@@ -160,11 +160,13 @@ def test_workspace_rules_of_the_backward():
         assert need >= 2 * 200 * 32 * 4 * 32 * 4                    # two partial copies of the second core at least
         assert l.tt_emb_bwd(C.byref(big), arr, one, n, None, n, None, None, one, arr, None, None, 0, None) == -4
         assert l.tt_emb_bwd_sgd(C.byref(big), arr, out, one, n, None, n, None, None, one, C.c_float(0.1), one, 4096, None) == -4
-    # the query grows with the number of positions and with the cache
+    # the query grows with the number of positions, with and without a cache (with one, the forward pass of this
+    # shape does not work from the lists and the room for its rows is left out: not comparable across the two)
     a = l.tt_emb_workspace_bytes(C.byref(big), 40000, 2000, 0)
     b = l.tt_emb_workspace_bytes(C.byref(big), 80000, 2000, 0)
-    c = l.tt_emb_workspace_bytes(C.byref(big), 80000, 2000, 1000)
-    assert a < b < c
+    c = l.tt_emb_workspace_bytes(C.byref(big), 40000, 2000, 1000)
+    d = l.tt_emb_workspace_bytes(C.byref(big), 80000, 2000, 1000)
+    assert a < b and c < d and c > 1000 * 64 * 4
     # a workspace that does not start on a 16-byte boundary
     odd = C.c_void_p(24)
     assert l.tt_emb_bwd(C.byref(big), arr, one, 5000, None, 5000, None, None, one, arr, None, odd, 1 << 30, None) == -3
