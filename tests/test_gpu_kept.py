@@ -267,3 +267,62 @@ def test_kept_rejects_bad_arguments():
     new = kp.bwd_sgd(0.1)
     for k in range(3):
         assert torch.equal(new[k], d0.g[k])
+
+
+def test_graph_replays_of_the_default_benchmark_step_match_eager_calls():
+    """bench.py's default step replayed from a HIP graph: forward keeping T0 on lists that the riders of the previous
+    backward launch have filed, backward + SGD into the other set of cores with riders for the next batch.  Every replay
+    leaves the same cores as the same steps launched one by one (and the lists that the next replay starts from), and
+    the first pair of steps matches the oracle."""
+    wl = W.WORKLOADS["kaggle_r32"]
+    t = wl.tables[0]
+    shape, oshape = B.shape_of(t), ora.Shape.of(t)
+    cores_h = W.make_cores(t, wl.init, wl.seed)
+    batches = [W.make_batch(wl, 0, j) for j in range(2)]
+    d = dev()
+    idx = [torch.from_numpy(b.indices).to(d) for b in batches]
+    off = [torch.from_numpy(b.offsets).to(d) for b in batches]
+    go = [torch.from_numpy(b.grad_output).to(d) for b in batches]
+    lr = 0.01
+
+    def fresh():
+        a = [torch.from_numpy(c).to(d) for c in cores_h]
+        kept = [torch.zeros(B.kept_bytes(shape, idx[j].numel()), dtype=torch.uint8, device=d) for j in range(2)]
+        B.tt_emb_kept_prepare(shape, idx[0], kept[0])              # the lists of the first batch; the riders file the rest
+        return a, [torch.empty_like(x) for x in a], kept, torch.empty((wl.n_bags, t.dim), dtype=torch.float32, device=d)
+
+    def two_steps(a, b, kept, out):
+        for j in range(2):
+            cur, nxt = (a, b) if j == 0 else (b, a)
+            B.tt_emb_fwd_keep(shape, cur, idx[j], off[j], wl.n_bags, out, kept[j], lists_ready=True)
+            B.tt_emb_bwd_sgd_kept(shape, cur, nxt, idx[j], off[j], wl.n_bags, go[j], kept[j], lr,
+                                  next_batch=(idx[1 - j], kept[1 - j]))
+
+    a, b, kept, out = fresh()
+    eager = []
+    for _ in range(3):
+        two_steps(a, b, kept, out)
+        torch.cuda.synchronize()
+        eager.append([x.clone() for x in a])
+    ga, gb, gkept, gout = fresh()
+    two_steps(ga, gb, gkept, gout)                                 # warm-up outside the capture
+    for k in range(3):
+        ga[k].copy_(torch.from_numpy(cores_h[k]))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        two_steps(ga, gb, gkept, gout)
+    for k in range(3):
+        ga[k].copy_(torch.from_numpy(cores_h[k]))                  # the capture does not run anything
+    for rep in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        for k in range(3):
+            assert torch.equal(ga[k], eager[rep][k]), (rep, k)
+        _ = (gout * 2).sum().item()                                # unrelated eager work between replays
+    oc = [c.copy() for c in cores_h]
+    for j in range(2):
+        dg, _ = ora.bwd(oshape, oc, batches[j].indices, batches[j].offsets, batches[j].grad_output)
+        oc = [ora.sgd(oc[k], dg[k], lr) for k in range(3)]
+    for k in range(3):
+        assert_close(eager[0][k].cpu().numpy(), oc[k], "two default benchmark steps, core %d" % (k + 1))
