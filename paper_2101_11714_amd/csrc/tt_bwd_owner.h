@@ -58,7 +58,7 @@ __global__ __launch_bounds__(WG) void bo_tile_kernel(Params p, const float *__re
     using F = BoCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, R = C::R, N = C::N, COLS = C::COLS, TP = F::TP;
     constexpr int LDA = F::LDA, LDT = F::LDT, LDB = F::LDB;
-    constexpr bool KEEP_C = F::BQ <= 8;               // the third core's rows stay in registers over the j2 (else: fetched again)
+    constexpr bool KEEP_C = true;                     // the third core's rows stay in registers over the j2 (one workgroup per CU: registers are plenty)
     extern __shared__ __align__(16) float bo_lds[];
     float *dyl = bo_lds;                              // [TP][N]      alpha_k dY of the positions
     float *As = dyl + F::DY_FLOATS;                   // [128][LDA]   stacked rows of G1
@@ -148,18 +148,28 @@ __global__ __launch_bounds__(WG) void bo_tile_kernel(Params p, const float *__re
 #pragma unroll
                 for (int r = 0; r < 16; ++r) accp[ab][r] = 0.f;
 
+            // Bm[a][(j2, b)] goes through registers: the part for j2 + 1 is fetched while the products of j2 run
+            constexpr int NB4 = R * R / 4 / WG;
+            float4 bm[NB4];
+            auto fetch_bm = [&](int j2) __attribute__((always_inline)) {
+                const float *src = G2 + (size_t)i2 * C::sB + j2 * R;
+#pragma unroll
+                for (int q = 0; q < NB4; ++q) {
+                    const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
+                    bm[q] = *reinterpret_cast<const float4 *>(src + a * COLS + b4);
+                }
+            };
+            fetch_bm(0);
 #pragma unroll
             for (int j2 = 0; j2 < N2; ++j2) {
                 // 3. Bm[a][(j2, b)] to LDS
-                {
-                    const float *src = G2 + (size_t)i2 * C::sB + j2 * R;
-                    for (int i = t; i < R * R / 4; i += WG) {
-                        const int a = i / (R / 4), b4 = 4 * (i % (R / 4));
-                        const float4 v = *reinterpret_cast<const float4 *>(src + a * COLS + b4);
-                        float *d = Bl + a * LDB + b4;
-                        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-                    }
+#pragma unroll
+                for (int q = 0; q < NB4; ++q) {
+                    const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
+                    float *d = Bl + a * LDB + b4;
+                    d[0] = bm[q].x; d[1] = bm[q].y; d[2] = bm[q].z; d[3] = bm[q].w;
                 }
+                if (j2 + 1 < N2) fetch_bm(j2 + 1);
                 // 4. dT0'[(ee, j1)][b] for this j2
                 if constexpr (!KEEP_C) {
 #pragma unroll
@@ -209,34 +219,51 @@ __global__ __launch_bounds__(WG) void bo_tile_kernel(Params p, const float *__re
 }
 
 // dst[i2] = src[i2] + mul * (sum of the parts of slice i2, in the order of their tiles); a slice without tiles is copied
-// if dst is another array.  One thread per float4 of a slice; tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles.
+// if dst is another array.  A workgroup takes 64 float4 of a slice; wave q adds the q-th quarter of the slice's parts,
+// 16 in flight, and the four sums are added in wave order.  tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles;
+// only those that begin a stretch hold a part (the slice's first tile and every ch-th tile of the table).
 __global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, int ch, const int *__restrict__ tile_base,
                                                           const float4 *__restrict__ part2, const float4 *__restrict__ src,
                                                           float4 *__restrict__ dst, float mul)
 {
-    const int per = (slice4 + WG - 1) / WG;                                 // workgroups per slice
-    const int i2 = blockIdx.x / per, e = (blockIdx.x % per) * WG + threadIdx.x;
-    if (i2 >= m2 || e >= slice4) return;
+    __shared__ float4 s_red[NWAVE][WAVE];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int per = (slice4 + WAVE - 1) / WAVE;                             // workgroups per slice
+    const int i2 = blockIdx.x / per, e = (blockIdx.x % per) * WAVE + lane;
+    if (i2 >= m2) return;
+    const bool on = e < slice4;
     const int t0 = tile_base[i2], t1 = tile_base[i2 + 1];
     const size_t at = (size_t)i2 * slice4 + e;
-    if (t1 <= t0) {
-        if (dst != src) dst[at] = src[at];
+    if (t1 <= t0) {                                                          // uniform
+        if (dst != src && on && q == 0) dst[at] = src[at];
         return;
     }
-    const float4 old = src[at];
-    float4 sum = part2[(size_t)t0 * slice4 + e];                             // the stretch that begins with the slice
-    // ... and those that begin with a workgroup's first tile (every ch-th tile of the table)
-    for (int u0 = (t0 / ch + 1) * ch; u0 < t1; u0 += 16 * ch) {
+    // the parts: the stretch that begins with the slice, then those that begin at multiples of ch
+    const int first_u = (t0 / ch + 1) * ch;
+    const int nparts = first_u < t1 ? (t1 - first_u + ch - 1) / ch : 0;      // beyond the first one
+    const int pq = (nparts + NWAVE - 1) / NWAVE, j0 = q * pq, j1 = min(nparts, j0 + pq);
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q == 0 && on) sum = part2[(size_t)t0 * slice4 + e];
+    for (int jb = j0; jb < j1; jb += 16) {
         float4 x[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int u = u0 + j * ch;
-            x[j] = u < t1 ? part2[(size_t)u * slice4 + e] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int u = first_u + min(jb + j, j1 - 1) * ch;
+            x[j] = on ? part2[(size_t)u * slice4 + e] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+        for (int j = 0; j < 16; ++j)
+            if (jb + j < j1) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
     }
-    dst[at] = make_float4(fmaf(mul, sum.x, old.x), fmaf(mul, sum.y, old.y), fmaf(mul, sum.z, old.z), fmaf(mul, sum.w, old.w));
+    s_red[q][lane] = sum;
+    __syncthreads();
+    if (q == 0 && on) {
+        float4 tot = s_red[0][lane];
+#pragma unroll
+        for (int ww = 1; ww < NWAVE; ++ww) { tot.x += s_red[ww][lane].x; tot.y += s_red[ww][lane].y; tot.z += s_red[ww][lane].z; tot.w += s_red[ww][lane].w; }
+        const float4 old = src[at];
+        dst[at] = make_float4(fmaf(mul, tot.x, old.x), fmaf(mul, tot.y, old.y), fmaf(mul, tot.z, old.z), fmaf(mul, tot.w, old.w));
+    }
 }
 
 // ---- segmented sums over the sorted items of the first and of the third core ----------------------
@@ -303,6 +330,8 @@ __global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int
     }
     const int key_prev = i0 > r0 ? (int)ks[i0 - 1] : -1;
     const int key_next = i0 + cnt < r1 ? (int)ks[i0 + cnt] : -1;
+    // the old value of a slice is only needed where a run ends
+    const int my_end = (lane + 1 >= cnt || __shfl_down(my_key, 1) != my_key) ? 1 : 0;
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f), old_last = sum;
     int cur = __builtin_amdgcn_readfirstlane(my_key);
     bool first = cur == key_prev;                                          // the first run began in an earlier tile
@@ -327,8 +356,9 @@ __global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int
             const int bag = __builtin_amdgcn_readlane(my_bag, e);
             const float wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), e));
             g[q] = prod(k, bag, wgt, lane, active);
-            old[q] = active ? *reinterpret_cast<const float4 *>(src + (size_t)(key - klo) * (4 * row4) + 4 * lane)
-                            : make_float4(0.f, 0.f, 0.f, 0.f);
+            old[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (__builtin_amdgcn_readlane(my_end, e) && active)                // (uniform but for `active`)
+                old[q] = *reinterpret_cast<const float4 *>(src + (size_t)(key - klo) * (4 * row4) + 4 * lane);
         }
 #pragma unroll
         for (int q = 0; q < NBATCH; ++q) {
@@ -337,62 +367,106 @@ __global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int
                 const int key = __builtin_amdgcn_readlane(my_key, e);
                 if (key != cur) { flush(cur, false); cur = key; }
                 sum.x += g[q].x; sum.y += g[q].y; sum.z += g[q].z; sum.w += g[q].w;
-                old_last = old[q];
+                if (__builtin_amdgcn_readlane(my_end, e)) old_last = old[q];
             }
         }
     }
     if (first || cur == key_next) flush(cur, true); else flush(cur, false);
 }
 
-// A run that crosses tile borders is applied by the wave of the tile where it begins: its own part[t][1], then
+// A run that crosses tile borders is applied by the workgroup of the tile where it begins: its own part[t][1], then
 // part[u][0] of the later tiles that the run reaches (a later tile is reached if its first item still has the run's
-// key), in tile order; the wave looks at 64 later tiles at a time.
+// key), in tile order; a wave looks at 64 later tiles at a time.  A run over up to 16 later tiles is finished by its
+// wave alone; a longer one (a hot row) by the four waves together, wave w adding every fourth part, 16 in flight, and
+// the four sums are added in wave order.
 __global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const uint64_t *__restrict__ ks,
                                                         const int *__restrict__ range, const float *__restrict__ src,
                                                         float *__restrict__ dst, float mul, const float *__restrict__ part)
 {
-    constexpr int NB = 32;
-    const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    constexpr int NB = 16, SHORT = 16;
+    __shared__ int s_long[NWAVE][2];                                         // key (-1: none) and last tile of a long run
+    __shared__ float4 s_red[NWAVE][WAVE];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int tile = blockIdx.x * NWAVE + w;
     const int r0 = range[0], r1 = range[1];
     const int ntiles = (r1 - r0 + BO_ST - 1) / BO_ST;
     const int i0 = r0 + tile * BO_ST, i1 = i0 + BO_ST;
-    if (i1 >= r1) return;                                                    // no tile here, or nothing to its right
-    const int key = (int)ks[i1 - 1];
-    if ((int)ks[i1] != key) return;                                          // the last run ends with the tile
-    if ((int)ks[i0] == key && i0 > r0 && (int)ks[i0 - 1] == key) return;     // it began in an earlier tile
-    int last = tile;
-    for (int base = tile + 1; base < ntiles; base += WAVE) {
-        const int u = base + lane;
-        const bool in = u < ntiles && (int)ks[r0 + (size_t)u * BO_ST] == key;
-        const unsigned long long b = __ballot(in);
-        const int reach = b == ~0ull ? WAVE : __builtin_ctzll(~b);
-        last = base + reach - 1;
-        if (reach < WAVE) break;
-    }
     const bool active = lane < row4;
-    float4 sum = active ? *reinterpret_cast<const float4 *>(part + ((size_t)tile * 2 + 1) * 256 + 4 * lane) : make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int u0 = tile + 1; u0 <= last; u0 += NB) {
-        float4 x[NB];
+    int key = -1, last = tile;
+    bool own = false;
+    if (i1 < r1) {                                                           // else no tile here, or nothing to its right
+        key = (int)ks[i1 - 1];
+        own = (int)ks[i1] == key;                                            // the last run goes on in the next tile
+        if (own && (int)ks[i0] == key && i0 > r0 && (int)ks[i0 - 1] == key) own = false;   // it began in an earlier tile
+    }
+    if (own) {                                                               // uniform in the wave
+        for (int base = tile + 1; base < ntiles; base += WAVE) {
+            const int u = base + lane;
+            const bool in = u < ntiles && (int)ks[r0 + (size_t)u * BO_ST] == key;
+            const unsigned long long b = __ballot(in);
+            const int reach = b == ~0ull ? WAVE : __builtin_ctzll(~b);
+            last = base + reach - 1;
+            if (reach < WAVE) break;
+        }
+    }
+    const bool is_long = own && last - tile > SHORT;
+    if (lane == 0) { s_long[w][0] = is_long ? key : -1; s_long[w][1] = last; }
+    if (own && !is_long) {
+        float4 sum = active ? *reinterpret_cast<const float4 *>(part + ((size_t)tile * 2 + 1) * 256 + 4 * lane) : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 x[SHORT];
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            x[j] = active ? *reinterpret_cast<const float4 *>(part + ((size_t)min(u0 + j, last) * 2 + 0) * 256 + 4 * lane)
+        for (int j = 0; j < SHORT; ++j)
+            x[j] = active ? *reinterpret_cast<const float4 *>(part + ((size_t)min(tile + 1 + j, last) * 2 + 0) * 256 + 4 * lane)
                           : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            if (u0 + j <= last) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+        for (int j = 0; j < SHORT; ++j)
+            if (tile + 1 + j <= last) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+        if (active) {
+            const size_t at = (size_t)(key - klo) * (4 * row4) + 4 * lane;
+            const float4 old = *reinterpret_cast<const float4 *>(src + at);
+            *reinterpret_cast<float4 *>(dst + at) =
+                make_float4(fmaf(mul, sum.x, old.x), fmaf(mul, sum.y, old.y), fmaf(mul, sum.z, old.z), fmaf(mul, sum.w, old.w));
+        }
     }
-    if (active) {
-        const size_t at = (size_t)(key - klo) * (4 * row4) + 4 * lane;
-        const float4 old = *reinterpret_cast<const float4 *>(src + at);
-        *reinterpret_cast<float4 *>(dst + at) =
-            make_float4(fmaf(mul, sum.x, old.x), fmaf(mul, sum.y, old.y), fmaf(mul, sum.z, old.z), fmaf(mul, sum.w, old.w));
+    __syncthreads();
+    for (int q = 0; q < NWAVE; ++q) {                                        // long runs: uniform in the workgroup
+        const int lkey = s_long[q][0];
+        if (lkey < 0) continue;
+        const int ltile = blockIdx.x * NWAVE + q, llast = s_long[q][1];
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (w == 0 && active) sum = *reinterpret_cast<const float4 *>(part + ((size_t)ltile * 2 + 1) * 256 + 4 * lane);
+        for (int u0 = ltile + 1 + w; u0 <= llast; u0 += NB * NWAVE) {
+            float4 x[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                x[j] = active ? *reinterpret_cast<const float4 *>(part + ((size_t)min(u0 + j * NWAVE, llast) * 2 + 0) * 256 + 4 * lane)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                if (u0 + j * NWAVE <= llast) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
+        }
+        s_red[w][lane] = sum;
+        __syncthreads();
+        if (w == 0 && active) {
+            float4 tot = s_red[0][lane];
+#pragma unroll
+            for (int ww = 1; ww < NWAVE; ++ww) { tot.x += s_red[ww][lane].x; tot.y += s_red[ww][lane].y; tot.z += s_red[ww][lane].z; tot.w += s_red[ww][lane].w; }
+            const size_t at = (size_t)(lkey - klo) * (4 * row4) + 4 * lane;
+            const float4 old = *reinterpret_cast<const float4 *>(src + at);
+            *reinterpret_cast<float4 *>(dst + at) =
+                make_float4(fmaf(mul, tot.x, old.x), fmaf(mul, tot.y, old.y), fmaf(mul, tot.z, old.z), fmaf(mul, tot.w, old.w));
+        }
+        __syncthreads();                                                     // s_red is written again for the next long run
     }
 }
 
-__global__ __launch_bounds__(WG) void bo_copy_kernel(const float4 *__restrict__ a, float4 *__restrict__ b, int64_t n4)
+__global__ __launch_bounds__(WG) void bo_copy_kernel(const float4 *__restrict__ a, float4 *__restrict__ b, int64_t n4,
+                                                     const float4 *__restrict__ a2, float4 *__restrict__ b2, int64_t n42)
 {
-    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n4; i += (int64_t)gridDim.x * WG) b[i] = a[i];
+    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n4 + n42; i += (int64_t)gridDim.x * WG) {
+        if (i < n4) b[i] = a[i];
+        else b2[i - n4] = a2[i - n4];
+    }
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -454,12 +528,12 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
     const int nchunks = (ntiles + ch - 1) / ch;
     hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nchunks < 8192 ? nchunks : 8192), dim3(WG), lds, st, p, G1, G2, G3, idx, (int)L, off,
                        n_bags, alpha, go, g.info, g.tiles, ntiles, ch, b.part2, b.pbuf);
-    const int slice4 = C::sB / 4, per = (slice4 + WG - 1) / WG;
+    const int slice4 = C::sB / 4, per = (slice4 + WAVE - 1) / WAVE;
     hipLaunchKernelGGL(bo_g2_finish_kernel, dim3(p.m2 * per), dim3(WG), 0, st, p.m2, slice4, ch, g.tile_base, (const float4 *)b.part2,
                        (const float4 *)(fused ? G2 : dG2), (float4 *)(fused ? o2 : dG2), mul);
     if (fused) {
-        hipLaunchKernelGGL(bo_copy_kernel, dim3(64), dim3(WG), 0, st, (const float4 *)G1, (float4 *)o1, (int64_t)p.m1 * C::sA / 4);
-        hipLaunchKernelGGL(bo_copy_kernel, dim3(256), dim3(WG), 0, st, (const float4 *)G3, (float4 *)o3, (int64_t)p.m3 * C::sC / 4);
+        hipLaunchKernelGGL(bo_copy_kernel, dim3(256), dim3(WG), 0, st, (const float4 *)G1, (float4 *)o1, (int64_t)p.m1 * C::sA / 4,
+                           (const float4 *)G3, (float4 *)o3, (int64_t)p.m3 * C::sC / 4);
     }
     const int seg_tiles = (int)(L / BO_ST + 1), seg_grid = (seg_tiles + NWAVE - 1) / NWAVE;
     // first core: items [crange[4], crange[5]) = [0, number of items of the first core)
