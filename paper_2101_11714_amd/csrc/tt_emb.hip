@@ -39,7 +39,18 @@ thread_local char g_err[512] = "";
 // Kernel selection of the calling thread (tests only; no other thread's calls change with it):
 // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
 thread_local int g_fast_path = 1;
-thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h where they apply
+thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h wherever they apply
+// Without that switch the tile kernels run where they were measured faster than the list owners: the (2,2,4) shape at
+// rank 64 from 65,536 positions on (P = 100, 2048 bags: 357 against 429 us; at rank 32 and for the (4,4,4) shapes the
+// two are level or the list owners ahead).
+constexpr int64_t TILES_MIN_L = 65536;
+
+bool bwd_tiles_wanted(const Params &p, int64_t L)
+{
+    if (!bwd_owner_supported(p)) return false;
+    if (g_bwd_tiles) return true;
+    return g_fast_path == 1 && p.n1 == 2 && p.n2 == 2 && p.n3 == 4 && p.R1 == 64 && L >= TILES_MIN_L;
+}
 // from this many positions on the backward groups them first (tt_group.h)
 constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
 constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
@@ -181,7 +192,7 @@ size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
 {
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
     size_t bytes = n ? align256(n * sizeof(float)) : 0;
-    if (grouped && g_bwd_tiles && bwd_owner_supported(p)) {             // the tiled backward's buffers instead
+    if (grouped && bwd_tiles_wanted(p, L)) {                            // the tiled backward's buffers instead
         const size_t b = align256(bo_ws_layout(nullptr, p, L).bytes);
         bytes = b > bytes ? b : bytes;
     }
@@ -390,7 +401,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if (fused && !fast)
         for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
     // long streams with a kept T0: the products of Eq. 4 over tiles of positions, on the matrix cores (tt_bwd_owner.h)
-    const bool tiled = grouped && t0 && g_bwd_tiles && bwd_owner_supported(p);
+    const bool tiled = grouped && t0 && bwd_tiles_wanted(p, L);
     const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped) : 0;
     const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
     const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
