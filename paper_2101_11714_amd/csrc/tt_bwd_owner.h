@@ -28,204 +28,293 @@
 
 namespace tt {
 
-constexpr int BO_MAX_CH = 4;                        // consecutive tiles that one workgroup takes at most: their parts of a slice gradient are added in registers
+constexpr int BO_MAX_CHUNK = 64;                    // tiles that one workgroup takes at most (their descriptors sit in LDS)
 
 template <typename C>
 struct BoCfg {
     static constexpr int ROWS = 128, TP = ROWS / C::N1;
     static constexpr int RB = C::R / 32;                       // 32-wide blocks of a rank index
+    static constexpr int NB = RB * RB;                         // 32 x 32 blocks of the R x R slice gradient of one j2
+    static constexpr int KS = NWAVE / NB;                      // waves that share a block: each takes ROWS / KS of the stacked rows
     static constexpr int LDA = C::R + 1, LDT = C::R + 2, LDB = C::R + 1;
     static constexpr int NBQ = WG / TP, BQ = C::R / NBQ;       // threads per position / values of b per thread in dT0'
     static constexpr int DY_FLOATS = TP * C::N;
     static constexpr int LDS_FLOATS = DY_FLOATS + ROWS * LDA + ROWS * LDT + C::R * LDB;
-    static_assert(C::R % 32 == 0 && RB * RB <= NWAVE && WG % TP == 0 && NBQ <= 8, "tile layout");
+    static constexpr int NDY = TP * C::N / 4 / WG;             // float4 of dY per thread and tile
+    static constexpr int NA4 = ROWS * C::R / 4 / WG;           // float4 of the stacked G1 rows per thread and tile
+    static constexpr int WGS_PER_CU = C::R >= 64 ? 1 : 2;      // what the LDS of a tile leaves room for
+    static_assert(C::R % 32 == 0 && NB <= NWAVE && NWAVE % NB == 0 && WG % TP == 0 && NBQ <= 8, "tile layout");
+    static_assert(TP * C::N % (4 * WG) == 0 && ROWS * C::R % (4 * WG) == 0, "whole float4 per thread");
+    static_assert(NWAVE * 1024 <= ROWS * LDT, "the partial blocks of a slice gradient fit the dT0' area");
 };
 
 template <typename C>
 static inline size_t bo_lds_bytes() { return (size_t)BoCfg<C>::LDS_FLOATS * sizeof(float); }
 
-// One workgroup per ch consecutive tiles of the tile table (tt_group.h), going on to later ones while there are
-// any.  The part of a slice gradient that the workgroup has added up goes to part2[first tile of that stretch]: a
-// stretch begins with the workgroup's first tile and wherever the slice changes.
+// tiles per workgroup: the tiles in use (the first `used` of the table) shared out evenly among the workgroups
+__host__ __device__ static inline int bo_chunk(int used, int nwg) { return used > 0 ? (used + nwg - 1) / nwg : 1; }
+
+// One workgroup takes ch = bo_chunk(tiles in use, workgroups) consecutive tiles of the tile table (tt_group.h) and
+// works through them as a pipeline: while the products of a tile run on the matrix cores, the operands of the next
+// one (its upstream gradients, stacked G1 rows and G3 rows, looked up through the position records that were fetched
+// a tile earlier) are on their way into registers, and they are written to LDS when the tile is done, so that the
+// chain record -> operands -> products of a tile is not waited for.  The part of a slice gradient that the workgroup
+// has added up goes to part2[first tile of that stretch]: a stretch begins with the workgroup's first tile and
+// wherever the slice changes.  Where the R x R block structure leaves waves without a block of their own (R = 32),
+// the waves split the stacked rows of a block among them and their partial blocks are added, in wave order, when
+// the stretch is written.
 template <typename C>
-__global__ __launch_bounds__(WG) void bo_tile_kernel(Params p, const float *__restrict__ G1, const float *__restrict__ G2,
-                                                     const float *__restrict__ G3, const int64_t *__restrict__ indices, int L,
-                                                     const int64_t *__restrict__ offsets, int n_bags,
-                                                     const float *__restrict__ alpha, const float *__restrict__ grad_out,
-                                                     const int4 *__restrict__ info, const int4 *__restrict__ tiles, int ntiles,
-                                                     int ch, float *__restrict__ part2, float *__restrict__ pbuf)
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>::WGS_PER_CU))) void bo_tile_kernel(
+    Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3, int L, int n_bags,
+    const float *__restrict__ alpha, const float *__restrict__ grad_out, const int4 *__restrict__ info,
+    const int4 *__restrict__ tiles, int ntiles, const int *__restrict__ tile_base, float *__restrict__ part2,
+    float *__restrict__ pbuf)
 {
     using F = BoCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, R = C::R, N = C::N, COLS = C::COLS, TP = F::TP;
-    constexpr int LDA = F::LDA, LDT = F::LDT, LDB = F::LDB;
-    constexpr bool KEEP_C = true;                     // the third core's rows stay in registers over the j2 (one workgroup per CU: registers are plenty)
+    constexpr int LDA = F::LDA, LDT = F::LDT, LDB = F::LDB, NQ = N / 4;
     extern __shared__ __align__(16) float bo_lds[];
     float *dyl = bo_lds;                              // [TP][N]      alpha_k dY of the positions
     float *As = dyl + F::DY_FLOATS;                   // [128][LDA]   stacked rows of G1
     float *dT = As + F::ROWS * LDA;                   // [128][LDT]   dT0' for the current j2
     float *Bl = dT + F::ROWS * LDT;                   // [R][LDB]     Bm[a][(j2, .)]
-    __shared__ int s_k[TP], s_i3[TP], s_bag[TP];
-    __shared__ int s_i1[TP];
-    __shared__ float s_w[TP];
+    __shared__ int s_ti2[BO_MAX_CHUNK], s_tlo[BO_MAX_CHUNK], s_tn[BO_MAX_CHUNK];   // the workgroup's tiles: slice, first item, items
+    __shared__ int s_k[2][TP], s_i1[2][TP], s_i3[2][TP], s_bag[2][TP];   // the positions of this tile and of the next one
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int ln = lane & 31, kh = lane >> 5;
-    const bool g2wave = w < F::RB * F::RB;            // this wave holds block (ab, bb) of the R x R slice gradient per j2
-    const int ab1 = w / F::RB, bb1 = w % F::RB;
+    const int blk = w % F::NB, ks = w / F::NB;        // this wave adds rows [ks ROWS / KS, (ks + 1) ROWS / KS) into block blk
+    const int ab1 = blk / F::RB, bb1 = blk % F::RB;
 
-    for (int chunk = blockIdx.x; chunk * ch < ntiles; chunk += gridDim.x) {
-        mfma16_t acc1[N2];
-        int cur = -1, slot = 0;
-        auto flush1 = [&]() __attribute__((always_inline)) {
-            if (cur >= 0 && g2wave) {
-#pragma unroll
-                for (int j2 = 0; j2 < N2; ++j2) {
-                    float *dst = part2 + (size_t)slot * C::sB + j2 * R + 32 * bb1 + ln;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) dst[(size_t)(32 * ab1 + 8 * (r / 4) + 4 * kh + r % 4) * COLS] = acc1[j2][r];
-                }
-            }
-        };
-        for (int tile = chunk * ch; tile < min(ntiles, (chunk + 1) * ch); ++tile) {
-            const int4 td = tiles[tile];
-            const int i2 = td.x, lo = td.y, n = td.z;
-            // (uniform: the tiles in use come first; the second test guards against a table that no pre-pass wrote)
-            if (n <= 0 || (unsigned)i2 >= (unsigned)p.m2 || lo < 0 || n > TP || lo + n > 3 * L) break;
-            if (i2 != cur) {
-                flush1();
-                cur = i2; slot = tile;
-#pragma unroll
-                for (int j2 = 0; j2 < N2; ++j2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc1[j2][r] = 0.f;
-            }
+    const int used = min(ntiles, tile_base[p.m2]);
+    const int ch = bo_chunk(used, gridDim.x);
+    const int tbeg = blockIdx.x * ch, tend = min(used, tbeg + min(ch, BO_MAX_CHUNK));
+    if (tbeg >= tend) return;                         // uniform
+    if (t < tend - tbeg) {
+        const int4 td = tiles[tbeg + t];
+        // (guards against a table that no pre-pass wrote: such a tile ends the workgroup's work)
+        const bool ok = td.z > 0 && (unsigned)td.x < (unsigned)p.m2 && td.y >= 0 && td.z <= TP && td.y + td.z <= 3 * L;
+        s_ti2[t] = ok ? td.x : -1; s_tlo[t] = ok ? td.y : 0; s_tn[t] = ok ? td.z : 0;
+    }
+    __syncthreads();
 
-            // 1. the positions
-            if (t < TP) {
-                int k = 0, i1 = 0, i3 = 0, bag = 0;
-                float wgt = 0.f;
-                if (t < n) {
-                    const int4 pi = info[lo + t];
-                    k = (unsigned)pi.x < (unsigned)L ? pi.x : 0;
-                    i1 = pi.y; i3 = pi.z; bag = pi.w;
-                    wgt = alpha ? alpha[k] : 1.f;
-                }
-                s_k[t] = k; s_i1[t] = i1; s_i3[t] = i3; s_bag[t] = bag; s_w[t] = wgt;
-            }
-            __syncthreads();
-            // 2. dY to LDS (positions past the end: zeros)
-            for (int i = t; i < TP * N / 4; i += WG) {
-                const int e = i / (N / 4), f = i % (N / 4);
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < n) {
-                    v = *reinterpret_cast<const float4 *>(grad_out + (size_t)s_bag[e] * N + 4 * f);
-                    const float wgt = s_w[e];
-                    v.x *= wgt; v.y *= wgt; v.z *= wgt; v.w *= wgt;
-                }
-                *reinterpret_cast<float4 *>(dyl + e * N + 4 * f) = v;
-            }
-            // thread (position ee, bq) of the dT0' product: its rows b = NBQ i + bq of G3[i3]
-            const int ee = t / F::NBQ, bq = t % F::NBQ;
-            const bool on = ee < n;
-            const float4 *Cp = reinterpret_cast<const float4 *>(G3 + (size_t)s_i3[ee] * C::sC) + bq;
-            float4 cv[F::BQ];
-            if constexpr (KEEP_C) {
-#pragma unroll
-                for (int i = 0; i < F::BQ; ++i) cv[i] = on ? Cp[i * F::NBQ] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-            // the stacked rows of G1 to LDS
-            for (int i = t; i < F::ROWS * R / 4; i += WG) {
-                const int row = i / (R / 4), a4 = 4 * (i % (R / 4)), e = row / N1, j1 = row % N1;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < n) v = *reinterpret_cast<const float4 *>(G1 + (size_t)s_i1[e] * C::sA + j1 * R + a4);
-                float *d = As + row * LDA + a4;
-                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-            }
-            __syncthreads();
+    // ---- the pipeline's registers: records of the tile after next, operands of the next tile ----
+    // (plain floats and ints: arrays of vector types that lambdas take by reference end up in scratch memory)
+    int pin_k = 0, pin_i1 = 0, pin_i3 = 0, pin_bag = 0;
+    float nxt_dy[F::NDY][4], nxt_a[F::NA4][4], nxt_cv[F::BQ][4], cv[F::BQ][4];
+    float nxt_w[F::NDY];
+    constexpr int NB4 = R * R / 4 / WG;
+    float bm[NB4][4];
+    auto ld4 = [](const float *src, float (&d)[4]) __attribute__((always_inline)) {
+        const float4 v = *reinterpret_cast<const float4 *>(src);
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    };
+    const int ee = t / F::NBQ, bq = t % F::NBQ;        // thread (position ee, bq) of the dT0' product: rows b = NBQ i + bq of G3[i3]
 
-            mfma16_t accp[F::RB];                                          // P: rows 32 w .. 32 w + 31, all a
+    auto load_records = [&](int lo) __attribute__((always_inline)) {
+        if (t < TP) {
+            const int4 pi = info[min(lo + t, 3 * L - 1)];
+            pin_k = pi.x; pin_i1 = pi.y; pin_i3 = pi.z; pin_bag = pi.w;
+        }
+    };
+    auto publish_records = [&](int n, int set) __attribute__((always_inline)) {
+        if (t < TP) {
+            const bool on = t < n;
+            s_k[set][t] = on && (unsigned)pin_k < (unsigned)L ? pin_k : 0;
+            s_i1[set][t] = on ? min(max(pin_i1, 0), p.m1 - 1) : 0;
+            s_i3[set][t] = on ? min(max(pin_i3, 0), p.m3 - 1) : 0;
+            s_bag[set][t] = on ? min(max(pin_bag, 0), n_bags - 1) : 0;
+        }
+    };
+    auto fetch_bm = [&](int i2, int j2) __attribute__((always_inline)) {
+        const float *src = G2 + (size_t)i2 * C::sB + j2 * R;
 #pragma unroll
-            for (int ab = 0; ab < F::RB; ++ab)
+        for (int q = 0; q < NB4; ++q) {
+            const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
+            ld4(src + a * COLS + b4, bm[q]);
+        }
+    };
+    auto issue_operands = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) accp[ab][r] = 0.f;
+        for (int q = 0; q < F::NDY; ++q) {
+            const int i = q * WG + t, e = i / NQ, f = i % NQ;
+            ld4(grad_out + (size_t)s_bag[set][e] * N + 4 * f, nxt_dy[q]);
+            nxt_w[q] = alpha ? alpha[s_k[set][e]] : 1.f;
+        }
+#pragma unroll
+        for (int q = 0; q < F::NA4; ++q) {
+            const int i = q * WG + t, row = i / (R / 4), a4 = 4 * (i % (R / 4)), e = row / N1, j1 = row % N1;
+            ld4(G1 + (size_t)s_i1[set][e] * C::sA + j1 * R + a4, nxt_a[q]);
+        }
+        const float *Cp = G3 + (size_t)s_i3[set][ee] * C::sC + 4 * bq;
+#pragma unroll
+        for (int i = 0; i < F::BQ; ++i) ld4(Cp + 4 * i * F::NBQ, nxt_cv[i]);
+    };
+    // the operands of a tile of n positions to LDS and to cv[] (positions past the end: zeros)
+    auto commit_operands = [&](int n) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < F::NDY; ++q) {
+            const int i = q * WG + t, e = i / NQ, f = i % NQ;
+            const float wgt = e < n ? nxt_w[q] : 0.f;                        // (selected per component: a select of float4s goes through memory)
+            *reinterpret_cast<float4 *>(dyl + e * N + 4 * f) =
+                make_float4(e < n ? nxt_dy[q][0] * wgt : 0.f, e < n ? nxt_dy[q][1] * wgt : 0.f, e < n ? nxt_dy[q][2] * wgt : 0.f,
+                            e < n ? nxt_dy[q][3] * wgt : 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < F::NA4; ++q) {
+            const int i = q * WG + t, row = i / (R / 4), a4 = 4 * (i % (R / 4)), e = row / N1;
+            const bool on = e < n;
+            float *d = As + row * LDA + a4;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) d[x] = on ? nxt_a[q][x] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < F::BQ; ++i)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) cv[i][x] = ee < n ? nxt_cv[i][x] : 0.f;
+    };
 
-            // Bm[a][(j2, b)] goes through registers: the part for j2 + 1 is fetched while the products of j2 run
-            constexpr int NB4 = R * R / 4 / WG;
-            float4 bm[NB4];
-            auto fetch_bm = [&](int j2) __attribute__((always_inline)) {
-                const float *src = G2 + (size_t)i2 * C::sB + j2 * R;
-#pragma unroll
-                for (int q = 0; q < NB4; ++q) {
-                    const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
-                    bm[q] = *reinterpret_cast<const float4 *>(src + a * COLS + b4);
-                }
-            };
-            fetch_bm(0);
+    mfma16_t acc1[N2];
+    int cur = -1, slot = 0;
+    auto flush1 = [&]() __attribute__((always_inline)) {                       // (uniform)
+        if (cur < 0) return;
+        if constexpr (F::KS == 1) {
 #pragma unroll
             for (int j2 = 0; j2 < N2; ++j2) {
-                // 3. Bm[a][(j2, b)] to LDS
+                float *dst = part2 + (size_t)slot * C::sB + j2 * R + 32 * bb1 + ln;
 #pragma unroll
-                for (int q = 0; q < NB4; ++q) {
-                    const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
-                    float *d = Bl + a * LDB + b4;
-                    d[0] = bm[q].x; d[1] = bm[q].y; d[2] = bm[q].z; d[3] = bm[q].w;
-                }
-                if (j2 + 1 < N2) fetch_bm(j2 + 1);
-                // 4. dT0'[(ee, j1)][b] for this j2
-                if constexpr (!KEEP_C) {
+                for (int r = 0; r < 16; ++r) dst[(size_t)(32 * ab1 + 8 * (r / 4) + 4 * kh + r % 4) * COLS] = acc1[j2][r];
+            }
+        } else {
+            // the waves' partial blocks through the dT0' area (free between tiles): element (row, col) of wave w's block is
+            // value r = 4 (row / 8) + row % 4 of lane 32 ((row / 4) % 2) + col; thread (row, four columns) adds the KS partials
+            // of a block in wave order and stores a float4
 #pragma unroll
-                    for (int i = 0; i < F::BQ; ++i) cv[i] = on ? Cp[i * F::NBQ] : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
+            for (int j2 = 0; j2 < N2; ++j2) {
 #pragma unroll
-                for (int j1 = 0; j1 < N1; ++j1) {
-                    const float4 dy = *reinterpret_cast<const float4 *>(dyl + ee * N + (j1 * N2 + j2) * 4);
+                for (int r = 0; r < 16; ++r) dT[w * 1024 + r * 64 + lane] = acc1[j2][r];
+                __syncthreads();
+                for (int x = t; x < F::NB * 256; x += WG) {
+                    const int b = x / 256, row = (x % 256) / 8, c4 = 4 * (x % 8);
+                    const int at = (4 * (row / 8) + row % 4) * 64 + 32 * ((row / 4) % 2) + c4;
+                    float4 sum = *reinterpret_cast<const float4 *>(&dT[b * 1024 + at]);
 #pragma unroll
-                    for (int i = 0; i < F::BQ; ++i) {
-                        const float4 c = cv[i];
-                        dT[(ee * N1 + j1) * LDT + i * F::NBQ + bq] = fmaf(dy.x, c.x, fmaf(dy.y, c.y, fmaf(dy.z, c.z, dy.w * c.w)));
+                    for (int q = 1; q < F::KS; ++q) {
+                        const float4 v = *reinterpret_cast<const float4 *>(&dT[(b + F::NB * q) * 1024 + at]);
+                        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
                     }
+                    *reinterpret_cast<float4 *>(part2 + (size_t)slot * C::sB + (size_t)(32 * (b / F::RB) + row) * COLS + j2 * R +
+                                                32 * (b % F::RB) + c4) = sum;
                 }
                 __syncthreads();
-                // 5. the part of dG2: block (ab, bb) of the R x R result for this j2, over all 128 rows
-                if (g2wave) {
-#pragma unroll 8
-                    for (int s = 0; s < F::ROWS / 2; ++s) {
-                        const int row = kh * (F::ROWS / 2) + s;
-                        acc1[j2] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[row * LDA + 32 * ab1 + ln], dT[row * LDT + 32 * bb1 + ln],
-                                                                       acc1[j2], 0, 0, 0);
-                    }
-                }
-                // 6. P += dT0' Bm^T over the columns of this j2
-#pragma unroll 4
-                for (int s = 0; s < R / 2; ++s) {
-                    const float av = dT[(32 * w + ln) * LDT + kh * (R / 2) + s];
-#pragma unroll
-                    for (int ab = 0; ab < F::RB; ++ab)
-                        accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * ab + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
-                }
-                __syncthreads();                                           // dT0' and Bm are rewritten for the next j2
             }
-            // 7. the rows P of the positions: pbuf[k][j1][a]
-#pragma unroll
-            for (int ab = 0; ab < F::RB; ++ab)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 32 * w + 8 * (r / 4) + 4 * kh + r % 4, e = row / N1, j1 = row % N1;
-                    if (e < n) pbuf[((size_t)s_k[e] * N1 + j1) * R + 32 * ab + ln] = accp[ab][r];
-                }
-            __syncthreads();                                               // the position arrays are rewritten for the next tile
         }
-        flush1();
+    };
+
+    // ---- prologue: the first tile's operands, the second tile's records ----
+    {
+        load_records(s_tlo[0]);
+        publish_records(s_tn[0], 0);
+        __syncthreads();
+        issue_operands(0);
+        if (s_ti2[0] >= 0) fetch_bm(s_ti2[0], 0);
+        if (tbeg + 1 < tend) load_records(s_tlo[1]);
+        commit_operands(s_tn[0]);
+        __syncthreads();
     }
+    int sc = 0;
+    for (int tile = tbeg; tile < tend; ++tile, sc ^= 1) {
+        const int i2 = s_ti2[tile - tbeg], n = s_tn[tile - tbeg];
+        if (i2 < 0) break;                                                 // uniform
+        const bool has_next = tile + 1 < tend;
+        const int i2n = has_next ? s_ti2[tile + 1 - tbeg] : -1, nn = has_next ? s_tn[tile + 1 - tbeg] : 0;
+        if (i2 != cur) {
+            flush1();
+            cur = i2; slot = tile;
+#pragma unroll
+            for (int j2 = 0; j2 < N2; ++j2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[j2][r] = 0.f;
+        }
+        // the next tile: its records to LDS, its operands on their way, the records of the one after it too
+        if (has_next) {
+            publish_records(nn, sc ^ 1);
+            __syncthreads();
+            issue_operands(sc ^ 1);
+            if (tile + 2 < tend) load_records(s_tlo[tile + 2 - tbeg]);
+        }
+
+        mfma16_t accp[F::RB];                                              // P: rows 32 w .. 32 w + 31, all a
+#pragma unroll
+        for (int ab = 0; ab < F::RB; ++ab)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accp[ab][r] = 0.f;
+
+#pragma unroll
+        for (int j2 = 0; j2 < N2; ++j2) {
+            // Bm[a][(j2, b)] to LDS (it came through registers: the part for the next j2, or for the next tile, is fetched
+            // while the products of this one run)
+#pragma unroll
+            for (int q = 0; q < NB4; ++q) {
+                const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
+                float *d = Bl + a * LDB + b4;
+                d[0] = bm[q][0]; d[1] = bm[q][1]; d[2] = bm[q][2]; d[3] = bm[q][3];
+            }
+            if (j2 + 1 < N2) fetch_bm(i2, j2 + 1);
+            else if (i2n >= 0) fetch_bm(i2n, 0);
+            // dT0'[(ee, j1)][b] for this j2
+#pragma unroll
+            for (int j1 = 0; j1 < N1; ++j1) {
+                const float4 dy = *reinterpret_cast<const float4 *>(dyl + ee * N + (j1 * N2 + j2) * 4);
+#pragma unroll
+                for (int i = 0; i < F::BQ; ++i) {
+                    dT[(ee * N1 + j1) * LDT + i * F::NBQ + bq] = fmaf(dy.x, cv[i][0], fmaf(dy.y, cv[i][1], fmaf(dy.z, cv[i][2], dy.w * cv[i][3])));
+                }
+            }
+            __syncthreads();
+            // the part of dG2: block blk of the R x R result for this j2, over this wave's share of the 128 rows
+            {
+                constexpr int RW = F::ROWS / F::KS;
+#pragma unroll 8
+                for (int s = 0; s < RW / 2; ++s) {
+                    const int row = ks * RW + kh * (RW / 2) + s;
+                    acc1[j2] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[row * LDA + 32 * ab1 + ln], dT[row * LDT + 32 * bb1 + ln],
+                                                                   acc1[j2], 0, 0, 0);
+                }
+            }
+            // P += dT0' Bm^T over the columns of this j2
+#pragma unroll 4
+            for (int s = 0; s < R / 2; ++s) {
+                const float av = dT[(32 * w + ln) * LDT + kh * (R / 2) + s];
+#pragma unroll
+                for (int ab = 0; ab < F::RB; ++ab)
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * ab + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
+            }
+            __syncthreads();                                               // dT0' and Bm are rewritten for the next j2
+        }
+        // the rows P of the positions: pbuf[k][j1][a]
+#pragma unroll
+        for (int ab = 0; ab < F::RB; ++ab)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 32 * w + 8 * (r / 4) + 4 * kh + r % 4, e = row / N1, j1 = row % N1;
+                if (e < n) pbuf[((size_t)s_k[sc][e] * N1 + j1) * R + 32 * ab + ln] = accp[ab][r];
+            }
+        if (has_next) commit_operands(nn);
+        __syncthreads();                                                   // the next tile's operands are in place; this tile's records are free
+    }
+    flush1();
 }
 
 // dst[i2] = src[i2] + mul * (sum of the parts of slice i2, in the order of their tiles); a slice without tiles is copied
 // if dst is another array.  A workgroup takes 64 float4 of a slice; wave q adds the q-th quarter of the slice's parts,
 // 16 in flight, and the four sums are added in wave order.  tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles;
-// only those that begin a stretch hold a part (the slice's first tile and every ch-th tile of the table).
-__global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, int ch, const int *__restrict__ tile_base,
+// only those that begin a stretch hold a part (the slice's first tile and every ch-th tile of the table, ch being the
+// tiles per workgroup of bo_tile_kernel, which ran with nwg workgroups).
+__global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, int ntiles, int nwg, const int *__restrict__ tile_base,
                                                           const float4 *__restrict__ part2, const float4 *__restrict__ src,
                                                           float4 *__restrict__ dst, float mul)
 {
+    const int ch = bo_chunk(min(ntiles, tile_base[m2]), nwg);                // as in bo_tile_kernel
     __shared__ float4 s_red[NWAVE][WAVE];
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int per = (slice4 + WAVE - 1) / WAVE;                             // workgroups per slice
@@ -471,6 +560,18 @@ __global__ __launch_bounds__(WG) void bo_copy_kernel(const float4 *__restrict__ 
 
 // ---- host side -------------------------------------------------------------------------------------
 
+// compute units of the current device (asked once)
+static inline int bo_compute_units()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else cus = 256;
+    }
+    return cus;
+}
+
 static inline bool bwd_owner_supported(const Params &p)
 {
     const int cfg = fast_config(p);
@@ -521,16 +622,15 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
     const bool fused = o1 != nullptr;
     const float mul = fused ? -lr : 1.f;
     const int ntiles = bo_tiles(p, L);
-    // tiles per workgroup: as many as leave a few workgroups for every compute unit (the table's size is an upper
-    // bound of the tiles in use)
-    // (measured: one tile per workgroup is fastest; more only pay once a tile's chain of dependent loads is hidden)
-    const int ch = 1;
-    const int nchunks = (ntiles + ch - 1) / ch;
-    hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nchunks < 8192 ? nchunks : 8192), dim3(WG), lds, st, p, G1, G2, G3, idx, (int)L, off,
-                       n_bags, alpha, go, g.info, g.tiles, ntiles, ch, b.part2, b.pbuf);
+    // one or two workgroups per compute unit (what the tile's LDS allows), more only where a workgroup would get more
+    // tiles than it can hold descriptors of (the table's size is an upper bound of the tiles in use)
+    int nwg = BoCfg<C>::WGS_PER_CU * bo_compute_units();
+    if ((ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK > nwg) nwg = (ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK;
+    hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nwg), dim3(WG), lds, st, p, G1, G2, G3, (int)L, n_bags, alpha, go, g.info, g.tiles,
+                       ntiles, g.tile_base, b.part2, b.pbuf);
     const int slice4 = C::sB / 4, per = (slice4 + WAVE - 1) / WAVE;
-    hipLaunchKernelGGL(bo_g2_finish_kernel, dim3(p.m2 * per), dim3(WG), 0, st, p.m2, slice4, ch, g.tile_base, (const float4 *)b.part2,
-                       (const float4 *)(fused ? G2 : dG2), (float4 *)(fused ? o2 : dG2), mul);
+    hipLaunchKernelGGL(bo_g2_finish_kernel, dim3(p.m2 * per), dim3(WG), 0, st, p.m2, slice4, ntiles, nwg, g.tile_base,
+                       (const float4 *)b.part2, (const float4 *)(fused ? G2 : dG2), (float4 *)(fused ? o2 : dG2), mul);
     if (fused) {
         hipLaunchKernelGGL(bo_copy_kernel, dim3(256), dim3(WG), 0, st, (const float4 *)G1, (float4 *)o1, (int64_t)p.m1 * C::sA / 4,
                            (const float4 *)G3, (float4 *)o3, (int64_t)p.m3 * C::sC / 4);
