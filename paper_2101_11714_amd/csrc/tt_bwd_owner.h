@@ -63,6 +63,11 @@ __host__ __device__ static inline int bo_chunk(int used, int nwg) { return used 
 // wherever the slice changes.  Where the R x R block structure leaves waves without a block of their own (R = 32),
 // the waves split the stacked rows of a block among them and their partial blocks are added, in wave order, when
 // the stretch is written.
+// A barrier for data exchanged through LDS only.  __syncthreads() also waits for the workgroup's global stores, and on
+// this hardware stores and loads share a counter, so it would drain the global loads that are fetched ahead; nothing
+// that the tile kernel stores to global memory is read again by it.
+__device__ __forceinline__ void bo_lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <typename C>
 __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>::WGS_PER_CU))) void bo_tile_kernel(
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3, int L, int n_bags,
@@ -95,7 +100,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
         const bool ok = td.z > 0 && (unsigned)td.x < (unsigned)p.m2 && td.y >= 0 && td.z <= TP && td.y + td.z <= 3 * L;
         s_ti2[t] = ok ? td.x : -1; s_tlo[t] = ok ? td.y : 0; s_tn[t] = ok ? td.z : 0;
     }
-    __syncthreads();
+    bo_lds_barrier();
 
     // ---- the pipeline's registers: records of the tile after next, operands of the next tile ----
     // (plain floats and ints: arrays of vector types that lambdas take by reference end up in scratch memory)
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
             for (int j2 = 0; j2 < N2; ++j2) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) dT[w * 1024 + r * 64 + lane] = acc1[j2][r];
-                __syncthreads();
+                bo_lds_barrier();
                 for (int x = t; x < F::NB * 256; x += WG) {
                     const int b = x / 256, row = (x % 256) / 8, c4 = 4 * (x % 8);
                     const int at = (4 * (row / 8) + row % 4) * 64 + 32 * ((row / 4) % 2) + c4;
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
                     *reinterpret_cast<float4 *>(part2 + (size_t)slot * C::sB + (size_t)(32 * (b / F::RB) + row) * COLS + j2 * R +
                                                 32 * (b % F::RB) + c4) = sum;
                 }
-                __syncthreads();
+                bo_lds_barrier();
             }
         }
     };
@@ -214,12 +219,12 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
     {
         load_records(s_tlo[0]);
         publish_records(s_tn[0], 0);
-        __syncthreads();
+        bo_lds_barrier();
         issue_operands(0);
         if (s_ti2[0] >= 0) fetch_bm(s_ti2[0], 0);
         if (tbeg + 1 < tend) load_records(s_tlo[1]);
         commit_operands(s_tn[0]);
-        __syncthreads();
+        bo_lds_barrier();
     }
     int sc = 0;
     for (int tile = tbeg; tile < tend; ++tile, sc ^= 1) {
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
         // the next tile: its records to LDS, its operands on their way, the records of the one after it too
         if (has_next) {
             publish_records(nn, sc ^ 1);
-            __syncthreads();
+            bo_lds_barrier();
             issue_operands(sc ^ 1);
             if (tile + 2 < tend) load_records(s_tlo[tile + 2 - tbeg]);
         }
@@ -270,7 +275,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
                     dT[(ee * N1 + j1) * LDT + i * F::NBQ + bq] = fmaf(dy.x, cv[i][0], fmaf(dy.y, cv[i][1], fmaf(dy.z, cv[i][2], dy.w * cv[i][3])));
                 }
             }
-            __syncthreads();
+            bo_lds_barrier();
             // the part of dG2: block blk of the R x R result for this j2, over this wave's share of the 128 rows
             {
                 constexpr int RW = F::ROWS / F::KS;
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
                 for (int ab = 0; ab < F::RB; ++ab)
                     accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * ab + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
             }
-            __syncthreads();                                               // dT0' and Bm are rewritten for the next j2
+            bo_lds_barrier();                                               // dT0' and Bm are rewritten for the next j2
         }
         // the rows P of the positions: pbuf[k][j1][a]
 #pragma unroll
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
                 if (e < n) pbuf[((size_t)s_k[sc][e] * N1 + j1) * R + 32 * ab + ln] = accp[ab][r];
             }
         if (has_next) commit_operands(nn);
-        __syncthreads();                                                   // the next tile's operands are in place; this tile's records are free
+        bo_lds_barrier();                                                   // the next tile's operands are in place; this tile's records are free
     }
     flush1();
 }
