@@ -69,7 +69,7 @@ __host__ __device__ static inline int bo_chunk(int used, int nwg) { return used 
 __device__ __forceinline__ void bo_lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <typename C>
-__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>::WGS_PER_CU))) void bo_tile_kernel(
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WGS_PER_CU, BoCfg<C>::WGS_PER_CU))) void bo_tile_kernel(
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3, int L, int n_bags,
     const float *__restrict__ alpha, const float *__restrict__ grad_out, const int4 *__restrict__ info,
     const int4 *__restrict__ tiles, int ntiles, const int *__restrict__ tile_base, float *__restrict__ part2,
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
             // the part of dG2: block blk of the R x R result for this j2, over this wave's share of the 128 rows
             {
                 constexpr int RW = F::ROWS / F::KS;
-#pragma unroll 8
+#pragma unroll
                 for (int s = 0; s < RW / 2; ++s) {
                     const int row = ks * RW + kh * (RW / 2) + s;
                     acc1[j2] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[row * LDA + 32 * ab1 + ln], dT[row * LDT + 32 * bb1 + ln],
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(1, BoCfg<C>:
                 }
             }
             // P += dT0' Bm^T over the columns of this j2
-#pragma unroll 4
+#pragma unroll
             for (int s = 0; s < R / 2; ++s) {
                 const float av = dT[(32 * w + ln) * LDT + kh * (R / 2) + s];
 #pragma unroll
