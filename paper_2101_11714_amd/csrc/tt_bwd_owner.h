@@ -73,9 +73,19 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WG
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3, int L, int n_bags,
     const float *__restrict__ alpha, const float *__restrict__ grad_out, const int4 *__restrict__ info,
     const int4 *__restrict__ tiles, int ntiles, const int *__restrict__ tile_base, float *__restrict__ part2,
-    float *__restrict__ pbuf)
+    float *__restrict__ pbuf, float4 *__restrict__ o1, float4 *__restrict__ o3)
 {
     using F = BoCfg<C>;
+    if (o1) {
+        // the fused step: the first and the third core are copied to the second set here, all workgroups together; the
+        // kernels that follow overwrite the slices that the batch touches
+        const int64_t n1 = (int64_t)p.m1 * C::sA / 4, n3 = (int64_t)p.m3 * C::sC / 4;
+        const float4 *a1 = reinterpret_cast<const float4 *>(G1), *a3 = reinterpret_cast<const float4 *>(G3);
+        for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n1 + n3; i += (int64_t)gridDim.x * WG) {
+            if (i < n1) o1[i] = a1[i];
+            else o3[i - n1] = a3[i - n1];
+        }
+    }
     constexpr int N1 = C::N1, N2 = C::N2, R = C::R, N = C::N, COLS = C::COLS, TP = F::TP;
     constexpr int LDA = F::LDA, LDT = F::LDT, LDB = F::LDB, NQ = N / 4;
     extern __shared__ __align__(16) float bo_lds[];
@@ -315,15 +325,24 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WG
 // 16 in flight, and the four sums are added in wave order.  tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles;
 // only those that begin a stretch hold a part (the slice's first tile and every ch-th tile of the table, ch being the
 // tiles per workgroup of bo_tile_kernel, which ran with nwg workgroups).
-__global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, int ntiles, int nwg, const int *__restrict__ tile_base,
-                                                          const float4 *__restrict__ part2, const float4 *__restrict__ src,
-                                                          float4 *__restrict__ dst, float mul)
+struct BoFinishArgs {
+    int m2, slice4, ntiles, nwg;
+    const int *tile_base;
+    const float4 *part2, *src;
+    float4 *dst;
+};
+
+__device__ __forceinline__ void bo_g2_finish_body(int vblock, const BoFinishArgs &a, float mul)
 {
-    const int ch = bo_chunk(min(ntiles, tile_base[m2]), nwg);                // as in bo_tile_kernel
+    const int m2 = a.m2, slice4 = a.slice4;
+    const int *__restrict__ tile_base = a.tile_base;
+    const float4 *__restrict__ part2 = a.part2, *__restrict__ src = a.src;
+    float4 *__restrict__ dst = a.dst;
+    const int ch = bo_chunk(min(a.ntiles, tile_base[m2]), a.nwg);            // as in bo_tile_kernel
     __shared__ float4 s_red[NWAVE][WAVE];
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int per = (slice4 + WAVE - 1) / WAVE;                             // workgroups per slice
-    const int i2 = blockIdx.x / per, e = (blockIdx.x % per) * WAVE + lane;
+    const int i2 = vblock / per, e = (vblock % per) * WAVE + lane;
     if (i2 >= m2) return;
     const bool on = e < slice4;
     const int t0 = tile_base[i2], t1 = tile_base[i2 + 1];
@@ -363,11 +382,14 @@ __global__ __launch_bounds__(WG) void bo_g2_finish_kernel(int m2, int slice4, in
 // ---- segmented sums over the sorted items of the first and of the third core ----------------------
 //
 // Items [range[0], range[1]) of the sorted arrays have keys klo .. klo + slices - 1; the row of an item (ROW4 float4,
-// lane l < ROW4 holds float4 l) comes from the producer.  One wave per tile of 64 items: runs of equal keys inside
+// lane l < ROW4 holds float4 l) comes from the producer.  One wave per tile of st items (bo_seg_st): runs of equal keys inside
 // the tile are applied at once (dst[key] = src[key] + mul * sum), the part of a run that goes on in the next tile is
 // left in part[tile][1], the part of a run that began in an earlier tile in part[tile][0] (a tile that is one run
 // throughout: [0]); bo_seg_fix_kernel finishes the runs that cross tile borders.
-constexpr int BO_ST = 64;
+// Items per wave: fewer for shorter streams, so that there are thousands of waves and each one's chain of dependent
+// loads (a round trip per batch of items) stays short.
+// (measured: 8,192 positions of the (4,4,4) shape at rank 64, 64 -> 8 items: 77 -> 27 us; 204,800 positions: 64 is best)
+static inline int bo_seg_st(int64_t L) { return L >= 131072 ? 64 : (L >= 65536 ? 32 : (L >= 32768 ? 16 : 8)); }
 
 // row of an item of the first core: the G1 gradient of its position, from pbuf
 struct BoRowP {
@@ -400,18 +422,27 @@ struct BoRowT0 {
     }
 };
 
+struct BoSegArgs {
+    int row4, klo, st;                                                       // st: items per wave, a power of two up to 64
+    const int *range;
+    const float *src;
+    float *dst, *part;
+};
+
 template <int NBATCH, typename Producer>
-__global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int klo, int L,
-                                                    const uint64_t *__restrict__ ks, const int4 *__restrict__ info,
-                                                    const int *__restrict__ range, const float *__restrict__ alpha, const float *__restrict__ src,
-                                                    float *__restrict__ dst, float mul, float *__restrict__ part)
+__device__ __forceinline__ void bo_seg_body(int vblock, const Producer &prod, const BoSegArgs &a, int L, const uint64_t *__restrict__ ks,
+                                            const int4 *__restrict__ info, const float *__restrict__ alpha, float mul)
 {
+    const int row4 = a.row4, klo = a.klo;
+    const int *__restrict__ range = a.range;
+    const float *__restrict__ src = a.src;
+    float *__restrict__ dst = a.dst, *__restrict__ part = a.part;
     const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    const int tile = vblock * NWAVE + (threadIdx.x >> 6);
     const int r0 = range[0], r1 = range[1];
-    const int i0 = r0 + tile * BO_ST;
+    const int i0 = r0 + tile * a.st;
     if (i0 >= r1) return;
-    const int cnt = min(BO_ST, r1 - i0);
+    const int cnt = min(a.st, r1 - i0);
     const bool active = lane < row4;
     int my_key = -1, my_k = 0, my_bag = 0;
     float my_w = 0.f;
@@ -473,18 +504,21 @@ __global__ __launch_bounds__(WG) void bo_seg_kernel(Producer prod, int row4, int
 // key), in tile order; a wave looks at 64 later tiles at a time.  A run over up to 16 later tiles is finished by its
 // wave alone; a longer one (a hot row) by the four waves together, wave w adding every fourth part, 16 in flight, and
 // the four sums are added in wave order.
-__global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const uint64_t *__restrict__ ks,
-                                                        const int *__restrict__ range, const float *__restrict__ src,
-                                                        float *__restrict__ dst, float mul, const float *__restrict__ part)
+__device__ __forceinline__ void bo_seg_fix_body(int vblock, const BoSegArgs &a, const uint64_t *__restrict__ ks, float mul)
 {
+    const int row4 = a.row4, klo = a.klo;
+    const int *__restrict__ range = a.range;
+    const float *__restrict__ src = a.src;
+    float *__restrict__ dst = a.dst;
+    const float *__restrict__ part = a.part;
     constexpr int NB = 16, SHORT = 16;
     __shared__ int s_long[NWAVE][2];                                         // key (-1: none) and last tile of a long run
     __shared__ float4 s_red[NWAVE][WAVE];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int tile = blockIdx.x * NWAVE + w;
+    const int tile = vblock * NWAVE + w;
     const int r0 = range[0], r1 = range[1];
-    const int ntiles = (r1 - r0 + BO_ST - 1) / BO_ST;
-    const int i0 = r0 + tile * BO_ST, i1 = i0 + BO_ST;
+    const int ntiles = (r1 - r0 + a.st - 1) / a.st;
+    const int i0 = r0 + tile * a.st, i1 = i0 + a.st;
     const bool active = lane < row4;
     int key = -1, last = tile;
     bool own = false;
@@ -496,7 +530,7 @@ __global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const
     if (own) {                                                               // uniform in the wave
         for (int base = tile + 1; base < ntiles; base += WAVE) {
             const int u = base + lane;
-            const bool in = u < ntiles && (int)ks[r0 + (size_t)u * BO_ST] == key;
+            const bool in = u < ntiles && (int)ks[r0 + (size_t)u * a.st] == key;
             const unsigned long long b = __ballot(in);
             const int reach = b == ~0ull ? WAVE : __builtin_ctzll(~b);
             last = base + reach - 1;
@@ -526,7 +560,7 @@ __global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const
     for (int q = 0; q < NWAVE; ++q) {                                        // long runs: uniform in the workgroup
         const int lkey = s_long[q][0];
         if (lkey < 0) continue;
-        const int ltile = blockIdx.x * NWAVE + q, llast = s_long[q][1];
+        const int ltile = vblock * NWAVE + q, llast = s_long[q][1];
         float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
         if (w == 0 && active) sum = *reinterpret_cast<const float4 *>(part + ((size_t)ltile * 2 + 1) * 256 + 4 * lane);
         for (int u0 = ltile + 1 + w; u0 <= llast; u0 += NB * NWAVE) {
@@ -554,13 +588,25 @@ __global__ __launch_bounds__(WG) void bo_seg_fix_kernel(int row4, int klo, const
     }
 }
 
-__global__ __launch_bounds__(WG) void bo_copy_kernel(const float4 *__restrict__ a, float4 *__restrict__ b, int64_t n4,
-                                                     const float4 *__restrict__ a2, float4 *__restrict__ b2, int64_t n42)
+// What follows the tile kernel, in two launches instead of seven (the parts are independent of each other, so they
+// fill the chip together): first the sums of the slice parts of the second core and the segmented sums of the first
+// and of the third core, then the runs of those two that cross tile borders.  Block ranges: [0, nseg) third core (the
+// longest part first), [nseg, 2 nseg) first core, [2 nseg, 2 nseg + nfin) slice parts of the second core.
+template <typename C>
+__global__ __launch_bounds__(WG) void bo_post_kernel(BoFinishArgs fin, int nfin, BoSegArgs s1, BoSegArgs s3, int nseg, BoRowP p1,
+                                                     BoRowT0<C> p3, int L, const uint64_t *__restrict__ ks,
+                                                     const int4 *__restrict__ info, const float *__restrict__ alpha, float mul)
 {
-    for (int64_t i = (int64_t)blockIdx.x * WG + threadIdx.x; i < n4 + n42; i += (int64_t)gridDim.x * WG) {
-        if (i < n4) b[i] = a[i];
-        else b2[i - n4] = a2[i - n4];
-    }
+    const int b = blockIdx.x;
+    if (b < nseg) bo_seg_body<(C::N1 * C::N2 > 4 ? 4 : 8)>(b, p3, s3, L, ks, info, alpha, mul);
+    else if (b < 2 * nseg) bo_seg_body<8>(b - nseg, p1, s1, L, ks, info, alpha, mul);
+    else bo_g2_finish_body(b - 2 * nseg, fin, mul);
+}
+
+__global__ __launch_bounds__(WG) void bo_fix_kernel(BoSegArgs s1, BoSegArgs s3, int nseg, const uint64_t *__restrict__ ks, float mul)
+{
+    if ((int)blockIdx.x < nseg) bo_seg_fix_body(blockIdx.x, s1, ks, mul);
+    else bo_seg_fix_body(blockIdx.x - nseg, s3, ks, mul);
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -586,7 +632,7 @@ static inline bool bwd_owner_supported(const Params &p)
 struct BoWs {
     float *part2;        // [tiles][sB]
     float *pbuf;         // [L][sA]
-    float *seg1, *seg3;  // [L / 64 + 1][2][256] each
+    float *seg1, *seg3;  // [L / bo_seg_st(L) + 2][2][256] each
     size_t bytes;
 };
 
@@ -601,7 +647,7 @@ static inline BoWs bo_ws_layout(void *ws, const Params &p, int64_t L)
     const int64_t Lp = L > 0 ? L : 1;
     b.part2 = (float *)take((size_t)bo_tiles(p, Lp) * p.sB * 4);
     b.pbuf = (float *)take((size_t)Lp * p.sA * 4);
-    const size_t seg = (size_t)(Lp / BO_ST + 2) * 2 * 256 * 4;
+    const size_t seg = (size_t)(Lp / bo_seg_st(Lp) + 2) * 2 * 256 * 4;
     b.seg1 = (float *)take(seg);
     b.seg3 = (float *)take(seg);
     b.bytes = off;
@@ -632,25 +678,18 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
     int nwg = BoCfg<C>::WGS_PER_CU * bo_compute_units();
     if ((ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK > nwg) nwg = (ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK;
     hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nwg), dim3(WG), lds, st, p, G1, G2, G3, (int)L, n_bags, alpha, go, g.info, g.tiles,
-                       ntiles, g.tile_base, b.part2, b.pbuf);
+                       ntiles, g.tile_base, b.part2, b.pbuf, (float4 *)(fused ? o1 : nullptr), (float4 *)(fused ? o3 : nullptr));
     const int slice4 = C::sB / 4, per = (slice4 + WAVE - 1) / WAVE;
-    hipLaunchKernelGGL(bo_g2_finish_kernel, dim3(p.m2 * per), dim3(WG), 0, st, p.m2, slice4, ntiles, nwg, g.tile_base,
-                       (const float4 *)b.part2, (const float4 *)(fused ? G2 : dG2), (float4 *)(fused ? o2 : dG2), mul);
-    if (fused) {
-        hipLaunchKernelGGL(bo_copy_kernel, dim3(256), dim3(WG), 0, st, (const float4 *)G1, (float4 *)o1, (int64_t)p.m1 * C::sA / 4,
-                           (const float4 *)G3, (float4 *)o3, (int64_t)p.m3 * C::sC / 4);
-    }
-    const int seg_tiles = (int)(L / BO_ST + 1), seg_grid = (seg_tiles + NWAVE - 1) / NWAVE;
-    // first core: items [crange[4], crange[5]) = [0, number of items of the first core)
-    hipLaunchKernelGGL((bo_seg_kernel<8, BoRowP>), dim3(seg_grid), dim3(WG), 0, st, BoRowP{b.pbuf, C::sA}, C::sA / 4, 0, (int)L,
-                       ks, g.info, g.crange + 4, alpha, fused ? G1 : dG1, fused ? o1 : dG1, mul, b.seg1);
-    hipLaunchKernelGGL(bo_seg_fix_kernel, dim3(seg_grid), dim3(WG), 0, st, C::sA / 4, 0, ks, g.crange + 4, fused ? G1 : dG1,
-                       fused ? o1 : dG1, mul, b.seg1);
-    hipLaunchKernelGGL((bo_seg_kernel<(C::N1 * C::N2 > 4 ? 4 : 8), BoRowT0<C>>), dim3(seg_grid), dim3(WG), 0, st,
-                       BoRowT0<C>{t0, go}, C::sC / 4, p.m1 + p.m2, (int)L, ks, g.info, g.crange + 2, alpha,
-                       fused ? G3 : dG3, fused ? o3 : dG3, mul, b.seg3);
-    hipLaunchKernelGGL(bo_seg_fix_kernel, dim3(seg_grid), dim3(WG), 0, st, C::sC / 4, p.m1 + p.m2, ks, g.crange + 2,
-                       fused ? G3 : dG3, fused ? o3 : dG3, mul, b.seg3);
+    const int sst = bo_seg_st(L);
+    const int seg_tiles = (int)(L / sst + 1), nseg = (seg_tiles + NWAVE - 1) / NWAVE, nfin = p.m2 * per;
+    const BoFinishArgs fin{p.m2, slice4, ntiles, nwg, g.tile_base, (const float4 *)b.part2, (const float4 *)(fused ? G2 : dG2),
+                           (float4 *)(fused ? o2 : dG2)};
+    // first core: items [crange[4], crange[5]) = [0, number of items of the first core); third core: [crange[2], crange[3])
+    const BoSegArgs s1{C::sA / 4, 0, sst, g.crange + 4, fused ? G1 : dG1, fused ? o1 : dG1, b.seg1};
+    const BoSegArgs s3{C::sC / 4, p.m1 + p.m2, sst, g.crange + 2, fused ? G3 : dG3, fused ? o3 : dG3, b.seg3};
+    hipLaunchKernelGGL((bo_post_kernel<C>), dim3(nfin + 2 * nseg), dim3(WG), 0, st, fin, nfin, s1, s3, nseg, BoRowP{b.pbuf, C::sA},
+                       BoRowT0<C>{t0, go}, (int)L, ks, g.info, alpha, mul);
+    hipLaunchKernelGGL(bo_fix_kernel, dim3(2 * nseg), dim3(WG), 0, st, s1, s3, nseg, ks, mul);
     return hipGetLastError();
 }
 

@@ -179,7 +179,7 @@ size_t fwd_bwd_ws_bytes(const Params &p, int64_t L, int64_t K)
 
 // what the specialised backward kernel needs beyond the lists: partial slice gradients of the roles it splits over
 // several workgroups and, for the (4,4,4) shapes, the per-row G1 gradients
-size_t split_ws_bytes(const Params &p, int64_t L, bool grouped);
+size_t split_ws_bytes(const Params &p, int64_t L, bool grouped, bool tiles_possible = true);
 
 // enough for either way of running the backward
 size_t split_ws_bytes_max(const Params &p, int64_t L)
@@ -188,11 +188,12 @@ size_t split_ws_bytes_max(const Params &p, int64_t L)
     return a > b ? a : b;
 }
 
-size_t split_ws_bytes(const Params &p, int64_t L, bool grouped)
+// tiles_possible: false for a call that brings no kept T0 (the tiled backward needs one)
+size_t split_ws_bytes(const Params &p, int64_t L, bool grouped, bool tiles_possible)
 {
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
     size_t bytes = n ? align256(n * sizeof(float)) : 0;
-    if (grouped && bwd_tiles_wanted(p, L)) {                            // the tiled backward's buffers instead
+    if (grouped && tiles_possible && bwd_tiles_wanted(p, L)) {          // the tiled backward's buffers instead
         const size_t b = align256(bo_ws_layout(nullptr, p, L).bytes);
         bytes = b > bytes ? b : bytes;
     }
@@ -402,7 +403,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
         for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
     // long streams with a kept T0: the products of Eq. 4 over tiles of positions, on the matrix cores (tt_bwd_owner.h)
     const bool tiled = grouped && t0 && bwd_tiles_wanted(p, L);
-    const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped) : 0;
+    const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped, t0 != nullptr) : 0;
     const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
     const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
     if (wants_ws && (!workspace || workspace_bytes < need))
