@@ -387,9 +387,17 @@ __device__ __forceinline__ void bo_g2_finish_body(int vblock, const BoFinishArgs
 // left in part[tile][1], the part of a run that began in an earlier tile in part[tile][0] (a tile that is one run
 // throughout: [0]); bo_seg_fix_kernel finishes the runs that cross tile borders.
 // Items per wave: fewer for shorter streams, so that there are thousands of waves and each one's chain of dependent
-// loads (a round trip per batch of items) stays short.
+// loads (a round trip per batch of items) stays short.  The host sizes the partial sums for bo_seg_st(L) items per
+// wave; the kernels take the smallest power of two from 8 on with which the items in the range (known on the device
+// only: cached positions have no items) still fit that many waves.
 // (measured: 8,192 positions of the (4,4,4) shape at rank 64, 64 -> 8 items: 77 -> 27 us; 204,800 positions: 64 is best)
 static inline int bo_seg_st(int64_t L) { return L >= 131072 ? 64 : (L >= 65536 ? 32 : (L >= 32768 ? 16 : 8)); }
+__device__ __forceinline__ int bo_seg_st_dev(int n, int cap)
+{
+    int st = 8;
+    while (st < 64 && (n + st - 1) / st > cap) st <<= 1;
+    return st;
+}
 
 // row of an item of the first core: the G1 gradient of its position, from pbuf
 struct BoRowP {
@@ -423,7 +431,7 @@ struct BoRowT0 {
 };
 
 struct BoSegArgs {
-    int row4, klo, st;                                                       // st: items per wave, a power of two up to 64
+    int row4, klo, cap;                                                      // cap: waves (tiles of items) that the partial sums have room for
     const int *range;
     const float *src;
     float *dst, *part;
@@ -440,9 +448,10 @@ __device__ __forceinline__ void bo_seg_body(int vblock, const Producer &prod, co
     const int lane = threadIdx.x & 63;
     const int tile = vblock * NWAVE + (threadIdx.x >> 6);
     const int r0 = range[0], r1 = range[1];
-    const int i0 = r0 + tile * a.st;
-    if (i0 >= r1) return;
-    const int cnt = min(a.st, r1 - i0);
+    const int st = bo_seg_st_dev(r1 - r0, a.cap);
+    const int i0 = r0 + tile * st;
+    if (i0 >= r1 || tile >= a.cap) return;
+    const int cnt = min(st, r1 - i0);
     const bool active = lane < row4;
     int my_key = -1, my_k = 0, my_bag = 0;
     float my_w = 0.f;
@@ -517,8 +526,9 @@ __device__ __forceinline__ void bo_seg_fix_body(int vblock, const BoSegArgs &a, 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int tile = vblock * NWAVE + w;
     const int r0 = range[0], r1 = range[1];
-    const int ntiles = (r1 - r0 + a.st - 1) / a.st;
-    const int i0 = r0 + tile * a.st, i1 = i0 + a.st;
+    const int st = bo_seg_st_dev(r1 - r0, a.cap);
+    const int ntiles = (r1 - r0 + st - 1) / st;
+    const int i0 = r0 + tile * st, i1 = i0 + st;
     const bool active = lane < row4;
     int key = -1, last = tile;
     bool own = false;
@@ -530,7 +540,7 @@ __device__ __forceinline__ void bo_seg_fix_body(int vblock, const BoSegArgs &a, 
     if (own) {                                                               // uniform in the wave
         for (int base = tile + 1; base < ntiles; base += WAVE) {
             const int u = base + lane;
-            const bool in = u < ntiles && (int)ks[r0 + (size_t)u * a.st] == key;
+            const bool in = u < ntiles && (int)ks[r0 + (size_t)u * st] == key;
             const unsigned long long b = __ballot(in);
             const int reach = b == ~0ull ? WAVE : __builtin_ctzll(~b);
             last = base + reach - 1;
@@ -685,8 +695,8 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
     const BoFinishArgs fin{p.m2, slice4, ntiles, nwg, g.tile_base, (const float4 *)b.part2, (const float4 *)(fused ? G2 : dG2),
                            (float4 *)(fused ? o2 : dG2)};
     // first core: items [crange[4], crange[5]) = [0, number of items of the first core); third core: [crange[2], crange[3])
-    const BoSegArgs s1{C::sA / 4, 0, sst, g.crange + 4, fused ? G1 : dG1, fused ? o1 : dG1, b.seg1};
-    const BoSegArgs s3{C::sC / 4, p.m1 + p.m2, sst, g.crange + 2, fused ? G3 : dG3, fused ? o3 : dG3, b.seg3};
+    const BoSegArgs s1{C::sA / 4, 0, seg_tiles, g.crange + 4, fused ? G1 : dG1, fused ? o1 : dG1, b.seg1};
+    const BoSegArgs s3{C::sC / 4, p.m1 + p.m2, seg_tiles, g.crange + 2, fused ? G3 : dG3, fused ? o3 : dG3, b.seg3};
     hipLaunchKernelGGL((bo_post_kernel<C>), dim3(nfin + 2 * nseg), dim3(WG), 0, st, fin, nfin, s1, s3, nseg, BoRowP{b.pbuf, C::sA},
                        BoRowT0<C>{t0, go}, (int)L, ks, g.info, alpha, mul);
     hipLaunchKernelGGL(bo_fix_kernel, dim3(2 * nseg), dim3(WG), 0, st, s1, s3, nseg, ks, mul);

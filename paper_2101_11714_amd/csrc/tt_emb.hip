@@ -39,21 +39,25 @@ thread_local char g_err[512] = "";
 // Kernel selection of the calling thread (tests only; no other thread's calls change with it):
 // 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
 thread_local int g_fast_path = 1;
-thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h wherever they apply
-// Without that switch the tile kernels run where they were measured faster than the list owners: the (2,2,4) shape at
-// rank 64 from 65,536 positions on (P = 100, 2048 bags: 357 against 429 us; at rank 32 and for the (4,4,4) shapes the
-// two are level or the list owners ahead).
-constexpr int64_t TILES_MIN_L = 65536;
-
+thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h even under selection 2
+// The grouped backward with a kept T0 runs on tiles of positions (tt_bwd_owner.h) wherever that path covers the
+// shape: measured ahead of the list owners for every shape it covers (rank 64, 204,800 positions: 276 against 444 us;
+// Terabyte-shaped, 8,192 positions: 83 against 101 us).  Selection 2 (tests) keeps the list owners.
 bool bwd_tiles_wanted(const Params &p, int64_t L)
 {
-    if (!bwd_owner_supported(p)) return false;
-    if (g_bwd_tiles) return true;
-    return g_fast_path == 1 && p.n1 == 2 && p.n2 == 2 && p.n3 == 4 && p.R1 == 64 && L >= TILES_MIN_L;
+    (void)L;
+    return bwd_owner_supported(p) && (g_bwd_tiles || g_fast_path == 1);
 }
 // from this many positions on the backward groups them first (tt_group.h)
 constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
 constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
+constexpr int64_t GROUP_MIN_L_TILES_444 = 8192; // the (4,4,4) shapes with a kept T0 and no cache: the tiles are ahead of the scanning owners from here on
+
+int64_t group_min_l(const Params &p, int64_t K, bool kept_t0)
+{
+    if (kept_t0 && !K && g_fast_path == 1 && p.n1 == 4 && p.n2 == 4 && p.n3 == 4 && bwd_owner_supported(p)) return GROUP_MIN_L_TILES_444;
+    return K ? GROUP_MIN_L_CACHE : GROUP_MIN_L;
+}
 
 int fail(int code, const char *fmt, ...)
 {
@@ -188,7 +192,7 @@ size_t split_ws_bytes_max(const Params &p, int64_t L)
     return a > b ? a : b;
 }
 
-// tiles_possible: false for a call that brings no kept T0 (the tiled backward needs one)
+// tiles_possible: false for a call that brings no kept T0 (the tiled backward needs one) or that has a cache
 size_t split_ws_bytes(const Params &p, int64_t L, bool grouped, bool tiles_possible)
 {
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
@@ -303,13 +307,15 @@ int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
 static bool bwd_groups(const Params &p, int64_t L, int64_t K, bool kept_t0)
 {
     const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
-    return fast && (g_fast_path == 2 || L >= (K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+    return fast && (g_fast_path == 2 || L >= group_min_l(p, K, kept_t0));
 }
 
 // does tt_emb_fwd_prepared work from the pre-pass's lists for such a call?
 static bool fwd_from_lists(const Params &p, int64_t L, int64_t K, bool kept_t0)
 {
-    return L > 0 && fwd_lists_pay(p, K) && bwd_groups(p, L, K, kept_t0) && 3 * L < (1ll << 31);
+    // (only for the long streams: at 8,192 positions, where the (4,4,4) backward already groups, the wave per bag is ahead: 31 against 36 us)
+    return L > 0 && fwd_lists_pay(p, K) && bwd_groups(p, L, K, kept_t0) && (g_fast_path == 2 || L >= (K ? GROUP_MIN_L_CACHE : GROUP_MIN_L)) &&
+           3 * L < (1ll << 31);
 }
 
 int tt_emb_fwd_uses_lists(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0)
@@ -391,7 +397,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                        : misaligned({grad_cores[0], grad_cores[1], grad_cores[2], grad_cache}))))
         return fail(TT_ERR_BAD_ARG, "cores, gradients, t0, cache rows and workspace must be 16-byte aligned");
     const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
-    const bool grouped = fast && (g_fast_path == 2 || L >= (cd.K ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cd.K, t0 != nullptr));
     if (grouped && 3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
     const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
     const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
@@ -402,8 +408,9 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     if (fused && !fast)
         for (int k = 0; k < 3; ++k) g_bytes[k] = align256((size_t)core_floats[k] * 4);
     // long streams with a kept T0: the products of Eq. 4 over tiles of positions, on the matrix cores (tt_bwd_owner.h)
-    const bool tiled = grouped && t0 && bwd_tiles_wanted(p, L);
-    const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped, t0 != nullptr) : 0;
+    // (with a cache the list owners stay: the cached rows' sums ride along in their launches, multi-hot table 0: 113 against 140 us)
+    const bool tiled = grouped && t0 && (!cd.K || g_bwd_tiles) && bwd_tiles_wanted(p, L);
+    const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped, t0 != nullptr && (!cd.K || g_bwd_tiles)) : 0;
     const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
     const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
     if (wants_ws && (!workspace || workspace_bytes < need))
@@ -824,7 +831,7 @@ int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_row
     Params p;
     if (check_shape(shape, &p) != TT_OK || L <= 0 || cache_rows < 0) return 0;
     const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
-    const bool grouped = fast && (g_fast_path == 2 || L >= (cache_rows ? GROUP_MIN_L_CACHE : GROUP_MIN_L));
+    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cache_rows, kept_t0 != 0));
     return cache_rows > 0 || grouped;
 }
 

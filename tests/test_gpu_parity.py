@@ -619,9 +619,11 @@ def test_backward_with_kept_t0(name, path):
     new = d.bwd_sgd(wl.lr, t0=t0)
     for k in range(3):
         assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], wl.lr), "%s fused core %d with kept T0" % (name, k + 1))
-    # only the third core's owners use T0: the other two gradients are the recomputing kernel's, bit for bit
-    # (a kept T0 always takes the specialised kernel, so the comparison needs it on the other side too)
-    if path != 0:
+    # where both calls run the slice owners, only the third core's owners use T0: the other two gradients are the
+    # recomputing kernel's, bit for bit (a kept T0 always takes the specialised kernel, so the comparison needs it on
+    # the other side too; where the call with T0 groups the positions and works on tiles, the sums have another order)
+    same_kernels = B.bwd_has_prepass(d.shape, d.L, 0, kept_t0=True) == B.bwd_has_prepass(d.shape, d.L, 0, kept_t0=False)
+    if path != 0 and same_kernels:
         plain, _ = d.bwd()
         assert torch.equal(dg[0], plain[0]) and torch.equal(dg[1], plain[1])
 
