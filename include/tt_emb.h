@@ -322,7 +322,10 @@ size_t tt_emb_static_scratch_bytes(void);
  * for long index lists, the grouping of the positions by the core slices they touch.
  * tt_emb_bwd_prepare runs that part into the workspace; tt_emb_bwd_sgd_prepared then
  * does the rest and gives the result of tt_emb_bwd_sgd (t0 == NULL) or
- * tt_emb_bwd_sgd_t0 (t0 != NULL), bit for bit.  A caller can enqueue the first call on
+ * tt_emb_bwd_sgd_t0 (t0 != NULL): bit for bit, except where tt_emb_bwd_two_calls_group_earlier
+ * says that the pair groups the positions at a length at which the one call does not yet
+ * (the pre-pass can be hidden behind other work here, so it pays earlier); the two results
+ * then differ in the order of their sums only.  A caller can enqueue the first call on
  * another stream next to the forward pass of the same batch (it reads neither the cores
  * nor the cache rows) and make the second wait for it.
  * Both calls take the same shape, indices, L, offsets, n_bags, cache and workspace;
@@ -335,6 +338,9 @@ int tt_emb_bwd_prepare(const tt_shape_t *shape, const int64_t *indices, int64_t 
                        void *workspace, size_t workspace_bytes, void *stream);
 /* 1 if tt_emb_bwd_prepare enqueues work for such a call (worth a stream of its own), else 0. */
 int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0);
+/* 1 if the pair tt_emb_bwd_prepare + tt_emb_bwd_sgd_prepared groups the positions of such a call
+ * (Alg. 2's "+=" as sums over sorted lists) where the one call does not, else 0. */
+int tt_emb_bwd_two_calls_group_earlier(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0);
 
 /*
  * The forward pass of a call whose index-only pre-pass has run: tt_emb_fwd / tt_emb_fwd_keep_t0

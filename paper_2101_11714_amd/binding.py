@@ -26,7 +26,7 @@ EXPORTS = ("tt_last_error", "tt_cache_table_capacity", "tt_emb_workspace_bytes",
            "tt_cache_build_workspace_bytes", "tt_emb_dedup_workspace_bytes",
            "tt_emb_bwd_sgd_workspace_bytes", "tt_cache_refill_workspace_bytes", "tt_cache_refill",
            "tt_emb_mean_weights", "tt_init_sampled_gaussian", "tt_embd_fwd", "tt_embd_bwd", "tt_embd_sgd_update", "tt_freq_reset", "tt_freq_update", "tt_freq_export", "tt_dense_bag_fwd", "tt_dense_bag_bwd_sgd", "tt_dense_bag_bwd_sgd_merged", "tt_dense_bag_bwd_workspace_bytes",
-           "tt_emb_validate", "tt_emb_debug_launch_probe", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_fwd_prepared", "tt_emb_fwd_uses_lists", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass",
+           "tt_emb_validate", "tt_emb_debug_launch_probe", "tt_emb_kept_bytes", "tt_emb_kept_has_lists", "tt_emb_kept_prepare", "tt_emb_fwd_keep", "tt_emb_bwd_kept", "tt_emb_bwd_sgd_kept", "tt_emb_debug_kept_lists", "tt_emb_bwd_sgd_static", "tt_emb_static_scratch_bytes", "tt_emb_fwd_keep_t0", "tt_emb_bwd_t0", "tt_emb_bwd_sgd_t0", "tt_emb_bwd_prepare", "tt_emb_fwd_prepared", "tt_emb_fwd_uses_lists", "tt_emb_bwd_sgd_prepared", "tt_emb_bwd_has_prepass", "tt_emb_bwd_two_calls_group_earlier",
            "tt_emb_fwd", "tt_emb_bwd", "tt_emb_bwd_sgd", "tt_emb_sgd_update", "tt_cache_build", "tt_cache_lookup",
            "tt_emb_debug_decode", "tt_emb_debug_decode_as", "tt_emb_debug_dedup", "tt_emb_debug_set_fast_path")
 
@@ -91,6 +91,7 @@ def lib():
         l.tt_emb_fwd_uses_lists.argtypes = [vp, i64, i64, C.c_int]
         l.tt_emb_fwd_prepared.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, C.c_size_t, vp]
         l.tt_emb_bwd_has_prepass.argtypes = [vp, i64, i64, C.c_int]
+        l.tt_emb_bwd_two_calls_group_earlier.argtypes = [vp, i64, i64, C.c_int]
         l.tt_emb_bwd_sgd_prepared.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, f32, vp, C.c_size_t, vp]
         l.tt_emb_sgd_update.argtypes = [vp, vp, vp, f32, vp, vp, C.c_int, vp]
         l.tt_cache_build.argtypes = [vp, vp, vp, vp, i64, vp, vp, C.c_size_t, vp]
@@ -303,6 +304,10 @@ def tt_emb_bwd(shape: TTShape, cores: Sequence[torch.Tensor], indices: torch.Ten
 
 def bwd_has_prepass(shape: TTShape, L: int, cache_rows: int = 0, kept_t0: bool = False) -> bool:
     return bool(lib().tt_emb_bwd_has_prepass(C.byref(shape), L, cache_rows, int(kept_t0)))
+
+
+def bwd_two_calls_group_earlier(shape: TTShape, L: int, cache_rows: int = 0, kept_t0: bool = False) -> bool:
+    return bool(lib().tt_emb_bwd_two_calls_group_earlier(C.byref(shape), L, cache_rows, int(kept_t0)))
 
 
 def tt_emb_bwd_prepare(shape: TTShape, indices: torch.Tensor, offsets: Optional[torch.Tensor], n_bags: int,

@@ -51,11 +51,16 @@ bool bwd_tiles_wanted(const Params &p, int64_t L)
 // from this many positions on the backward groups them first (tt_group.h)
 constexpr int64_t GROUP_MIN_L = 32768;          // without a cache
 constexpr int64_t GROUP_MIN_L_CACHE = 16384;    // with a cache (the grouped path also has the faster cached-row reduction)
-constexpr int64_t GROUP_MIN_L_TILES_444 = 8192; // the (4,4,4) shapes with a kept T0 and no cache: the tiles are ahead of the scanning owners from here on
+// With a kept T0 and no cache the grouped backward runs on tiles (tt_bwd_owner.h), which are ahead of the scanning
+// owners much earlier, but only if the pre-pass (about 30 us of small kernels) does not count: so these limits hold
+// for the two-call form, whose first call can run beside other work (Terabyte-shaped, 8,192 positions: 84 against
+// 101 us; (2,2,4) at rank 32 / 64, 20,480 positions: 38 against 59 / 64 against 90 us).
+constexpr int64_t GROUP_MIN_L_TILES_444 = 8192, GROUP_MIN_L_TILES_224 = 16384;
 
-int64_t group_min_l(const Params &p, int64_t K, bool kept_t0)
+int64_t group_min_l(const Params &p, int64_t K, bool kept_t0, bool two_calls)
 {
-    if (kept_t0 && !K && g_fast_path == 1 && p.n1 == 4 && p.n2 == 4 && p.n3 == 4 && bwd_owner_supported(p)) return GROUP_MIN_L_TILES_444;
+    if (two_calls && kept_t0 && !K && g_fast_path == 1 && bwd_owner_supported(p))
+        return p.n1 == 4 ? GROUP_MIN_L_TILES_444 : GROUP_MIN_L_TILES_224;
     return K ? GROUP_MIN_L_CACHE : GROUP_MIN_L;
 }
 
@@ -307,7 +312,7 @@ int tt_emb_fwd_keep_t0(const tt_shape_t *shape, const float *const cores[3],
 static bool bwd_groups(const Params &p, int64_t L, int64_t K, bool kept_t0)
 {
     const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
-    return fast && (g_fast_path == 2 || L >= group_min_l(p, K, kept_t0));
+    return fast && (g_fast_path == 2 || L >= group_min_l(p, K, kept_t0, false));
 }
 
 // does tt_emb_fwd_prepared work from the pre-pass's lists for such a call?
@@ -397,7 +402,7 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                        : misaligned({grad_cores[0], grad_cores[1], grad_cores[2], grad_cache}))))
         return fail(TT_ERR_BAD_ARG, "cores, gradients, t0, cache rows and workspace must be 16-byte aligned");
     const bool fast = (g_fast_path || t0) && fast_bwd_supported(p);
-    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cd.K, t0 != nullptr));
+    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cd.K, t0 != nullptr, phase != BWD_ALL));
     if (grouped && 3 * L >= (1ll << 31)) return fail(TT_ERR_UNSUPPORTED, "3 L >= 2^31");
     const size_t need_bwd = grouped ? fwd_bwd_ws_bytes(p, L, cd.K) : 256 + slot_ws_bytes(L, cd.K != 0);
     const int64_t core_floats[3] = {(int64_t)p.m1 * p.sA, (int64_t)p.m2 * p.sB, (int64_t)p.m3 * p.sC};
@@ -831,8 +836,17 @@ int tt_emb_bwd_has_prepass(const tt_shape_t *shape, int64_t L, int64_t cache_row
     Params p;
     if (check_shape(shape, &p) != TT_OK || L <= 0 || cache_rows < 0) return 0;
     const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
-    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cache_rows, kept_t0 != 0));
+    const bool grouped = fast && (g_fast_path == 2 || L >= group_min_l(p, cache_rows, kept_t0 != 0, true));
     return cache_rows > 0 || grouped;
+}
+
+int tt_emb_bwd_two_calls_group_earlier(const tt_shape_t *shape, int64_t L, int64_t cache_rows, int kept_t0)
+{
+    Params p;
+    if (check_shape(shape, &p) != TT_OK || L <= 0 || cache_rows < 0) return 0;
+    const bool fast = (g_fast_path || kept_t0) && fast_bwd_supported(p);
+    if (!fast || g_fast_path == 2) return 0;
+    return L >= group_min_l(p, cache_rows, kept_t0 != 0, true) && L < group_min_l(p, cache_rows, kept_t0 != 0, false);
 }
 
 int tt_emb_bwd_sgd_prepared(const tt_shape_t *shape, const float *const cores[3], float *const cores_out[3],
