@@ -30,26 +30,31 @@ namespace tt {
 
 constexpr int BO_MAX_CHUNK = 64;                    // tiles that one workgroup takes at most (their descriptors sit in LDS)
 
-template <typename C>
+template <typename C, int ROWS_ = 128>
 struct BoCfg {
-    static constexpr int ROWS = 128, TP = ROWS / C::N1;
+    static constexpr int ROWS = ROWS_, TP = ROWS / C::N1;      // stacked rows / positions of a tile
     static constexpr int RB = C::R / 32;                       // 32-wide blocks of a rank index
     static constexpr int NB = RB * RB;                         // 32 x 32 blocks of the R x R slice gradient of one j2
     static constexpr int KS = NWAVE / NB;                      // waves that share a block: each takes ROWS / KS of the stacked rows
+    static constexpr int RBK = ROWS / 32;                      // 32-row blocks of P
+    static constexpr int WPR = NWAVE / RBK;                    // waves that share a row block of P: each takes RB / WPR of its 32-wide column blocks
+    static constexpr int ABW = RB / WPR;
     static constexpr int LDA = C::R + 1, LDT = C::R + 2, LDB = C::R + 1;
     static constexpr int NBQ = WG / TP, BQ = C::R / NBQ;       // threads per position / values of b per thread in dT0'
     static constexpr int DY_FLOATS = TP * C::N;
     static constexpr int LDS_FLOATS = DY_FLOATS + ROWS * LDA + ROWS * LDT + C::R * LDB;
     static constexpr int NDY = TP * C::N / 4 / WG;             // float4 of dY per thread and tile
     static constexpr int NA4 = ROWS * C::R / 4 / WG;           // float4 of the stacked G1 rows per thread and tile
-    static constexpr int WGS_PER_CU = C::R >= 64 ? 1 : 2;      // what the LDS of a tile leaves room for
-    static_assert(C::R % 32 == 0 && NB <= NWAVE && NWAVE % NB == 0 && WG % TP == 0 && NBQ <= 8, "tile layout");
+    static constexpr int WGS_PER_CU = C::R >= 64 ? 1 : 2;      // what the LDS and the registers of a tile leave room for
+    static_assert(C::R % 32 == 0 && NB <= NWAVE && NWAVE % NB == 0 && WG % TP == 0 && NBQ <= 16 && BQ >= 1, "tile layout");
+    static_assert(ROWS % 32 == 0 && RBK <= NWAVE && NWAVE % RBK == 0 && RB % WPR == 0 && ABW >= 1, "the waves share out the blocks of P");
     static_assert(TP * C::N % (4 * WG) == 0 && ROWS * C::R % (4 * WG) == 0, "whole float4 per thread");
-    static_assert(NWAVE * 1024 <= ROWS * LDT, "the partial blocks of a slice gradient fit the dT0' area");
+    static_assert(KS == 1 || NWAVE * 1024 <= ROWS * LDT, "the partial blocks of a slice gradient fit the dT0' area");
+    static_assert((ROWS / KS) % 2 == 0, "pairs of rows per product step");
 };
 
-template <typename C>
-static inline size_t bo_lds_bytes() { return (size_t)BoCfg<C>::LDS_FLOATS * sizeof(float); }
+template <typename C, int ROWS_>
+static inline size_t bo_lds_bytes() { return (size_t)BoCfg<C, ROWS_>::LDS_FLOATS * sizeof(float); }
 
 // tiles per workgroup: the tiles in use (the first `used` of the table) shared out evenly among the workgroups
 __host__ __device__ static inline int bo_chunk(int used, int nwg) { return used > 0 ? (used + nwg - 1) / nwg : 1; }
@@ -68,14 +73,14 @@ __host__ __device__ static inline int bo_chunk(int used, int nwg) { return used 
 // that the tile kernel stores to global memory is read again by it.
 __device__ __forceinline__ void bo_lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <typename C>
-__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WGS_PER_CU, BoCfg<C>::WGS_PER_CU))) void bo_tile_kernel(
+template <typename C, int ROWS_>
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C, ROWS_>::WGS_PER_CU, BoCfg<C, ROWS_>::WGS_PER_CU))) void bo_tile_kernel(
     Params p, const float *__restrict__ G1, const float *__restrict__ G2, const float *__restrict__ G3, int L, int n_bags,
     const float *__restrict__ alpha, const float *__restrict__ grad_out, const int4 *__restrict__ info,
     const int4 *__restrict__ tiles, int ntiles, const int *__restrict__ tile_base, float *__restrict__ part2,
     float *__restrict__ pbuf, float4 *__restrict__ o1, float4 *__restrict__ o3)
 {
-    using F = BoCfg<C>;
+    using F = BoCfg<C, ROWS_>;
     if (o1) {
         // the fused step: the first and the third core are copied to the second set here, all workgroups together; the
         // kernels that follow overwrite the slices that the batch touches
@@ -99,6 +104,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WG
     const int ln = lane & 31, kh = lane >> 5;
     const int blk = w % F::NB, ks = w / F::NB;        // this wave adds rows [ks ROWS / KS, (ks + 1) ROWS / KS) into block blk
     const int ab1 = blk / F::RB, bb1 = blk % F::RB;
+    const int rb = w % F::RBK, ab0 = (w / F::RBK) * F::ABW;   // this wave's block of P: rows 32 rb .., column blocks ab0 .. ab0 + ABW - 1
 
     const int used = min(ntiles, tile_base[p.m2]);
     const int ch = bo_chunk(used, gridDim.x);
@@ -258,9 +264,9 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WG
             if (tile + 2 < tend) load_records(s_tlo[tile + 2 - tbeg]);
         }
 
-        mfma16_t accp[F::RB];                                              // P: rows 32 w .. 32 w + 31, all a
+        mfma16_t accp[F::ABW];                                             // P: rows 32 rb .. 32 rb + 31, this wave's column blocks
 #pragma unroll
-        for (int ab = 0; ab < F::RB; ++ab)
+        for (int ab = 0; ab < F::ABW; ++ab)
 #pragma unroll
             for (int r = 0; r < 16; ++r) accp[ab][r] = 0.f;
 
@@ -299,20 +305,20 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C>::WG
             // P += dT0' Bm^T over the columns of this j2
 #pragma unroll
             for (int s = 0; s < R / 2; ++s) {
-                const float av = dT[(32 * w + ln) * LDT + kh * (R / 2) + s];
+                const float av = dT[(32 * rb + ln) * LDT + kh * (R / 2) + s];
 #pragma unroll
-                for (int ab = 0; ab < F::RB; ++ab)
-                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * ab + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
+                for (int ab = 0; ab < F::ABW; ++ab)
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * (ab0 + ab) + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
             }
             bo_lds_barrier();                                               // dT0' and Bm are rewritten for the next j2
         }
         // the rows P of the positions: pbuf[k][j1][a]
 #pragma unroll
-        for (int ab = 0; ab < F::RB; ++ab)
+        for (int ab = 0; ab < F::ABW; ++ab)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = 32 * w + 8 * (r / 4) + 4 * kh + r % 4, e = row / N1, j1 = row % N1;
-                if (e < n) pbuf[((size_t)s_k[sc][e] * N1 + j1) * R + 32 * ab + ln] = accp[ab][r];
+                const int row = 32 * rb + 8 * (r / 4) + 4 * kh + r % 4, e = row / N1, j1 = row % N1;
+                if (e < n) pbuf[((size_t)s_k[sc][e] * N1 + j1) * R + 32 * (ab0 + ab) + ln] = accp[ab][r];
             }
         if (has_next) commit_operands(nn);
         bo_lds_barrier();                                                   // the next tile's operands are in place; this tile's records are free
@@ -646,16 +652,17 @@ struct BoWs {
     size_t bytes;
 };
 
-static inline int bo_tiles(const Params &p, int64_t L) { return (int)((L + 128 / p.n1 - 1) / (128 / p.n1)) + p.m2; }
+// tp: positions per tile (128 / n1, or 64 / n1 for short streams of the (4,4,4) shape at rank 64: see launch_bwd_owner)
+static inline int bo_tiles(const Params &p, int64_t L, int tp) { return (int)((L + tp - 1) / tp) + p.m2; }
 
-static inline BoWs bo_ws_layout(void *ws, const Params &p, int64_t L)
+static inline BoWs bo_ws_layout(void *ws, const Params &p, int64_t L, int tp)
 {
     BoWs b;
     char *base = (char *)ws;
     size_t off = 0;
     auto take = [&](size_t bytes) { char *q = base ? base + off : nullptr; off += (bytes + 255) & ~(size_t)255; return q; };
     const int64_t Lp = L > 0 ? L : 1;
-    b.part2 = (float *)take((size_t)bo_tiles(p, Lp) * p.sB * 4);
+    b.part2 = (float *)take((size_t)bo_tiles(p, Lp, tp) * p.sB * 4);
     b.pbuf = (float *)take((size_t)Lp * p.sA * 4);
     const size_t seg = (size_t)(Lp / bo_seg_st(Lp) + 2) * 2 * 256 * 4;
     b.seg1 = (float *)take(seg);
@@ -666,29 +673,60 @@ static inline BoWs bo_ws_layout(void *ws, const Params &p, int64_t L)
 
 // dst (o1..o3, or the gradient arrays if they are null) as described at the top.  crange[2..3]: the sorted range of
 // the third core's items; the first core's items start the sorted arrays.
+// Positions per tile.  Tiles of 128 stacked rows, except for short streams of the (4,4,4) shape at rank 64 (the
+// Terabyte-shaped table: 8,192 positions over 200 slices are 328 tiles of 32 positions, two rounds on 256 compute
+// units and a fifth of the rows empty): there tiles of 64 rows, two workgroups to a compute unit.  `small_ok` is
+// false where the forward pass shares the tile table (it works on tiles of 128 rows).
+static inline int bo_tp(const Params &p, int64_t L, bool small_ok)
+{
+    const bool small = small_ok && fast_config(p) == 5 && L < 32768;
+    return (small ? 64 : 128) / p.n1;
+}
+
+template <typename C, int ROWS_>
+static inline hipError_t launch_bo_tiles(const Params &p, const float *G1, const float *G2, const float *G3, int64_t L, int n_bags,
+                                         const float *alpha, const float *go, float *o1, float *o3, const GroupWs &g, const BoWs &b,
+                                         int ntiles, int *nwg_out, hipStream_t st)
+{
+    const size_t lds = bo_lds_bytes<C, ROWS_>();
+    static bool allowed = false;                                             // (one device per process)
+    if (!allowed) {
+        hipError_t e = hipFuncSetAttribute((const void *)bo_tile_kernel<C, ROWS_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        allowed = true;
+    }
+    // one or two workgroups per compute unit (what the tile's LDS and registers allow), more only where a workgroup would
+    // get more tiles than it can hold descriptors of (the table's size is an upper bound of the tiles in use)
+    int nwg = BoCfg<C, ROWS_>::WGS_PER_CU * bo_compute_units();
+    if ((ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK > nwg) nwg = (ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK;
+    hipLaunchKernelGGL((bo_tile_kernel<C, ROWS_>), dim3(nwg), dim3(WG), lds, st, p, G1, G2, G3, (int)L, n_bags, alpha, go, g.info,
+                       g.tiles, ntiles, g.tile_base, b.part2, b.pbuf, (float4 *)o1, (float4 *)o3);
+    *nwg_out = nwg;
+    return hipSuccess;
+}
+
 template <typename C>
 static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                                           int64_t L, const int64_t *off, int n_bags, const float *alpha, const float *go,
                                           const float *t0, float *dG1, float *dG2, float *dG3, float lr, float *o1, float *o2,
-                                          float *o3, const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b,
+                                          float *o3, const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b, int tp,
                                           hipStream_t st)
 {
-    const size_t lds = bo_lds_bytes<C>();
-    static bool allowed = false;                                             // (one device per process)
-    if (!allowed) {
-        hipError_t e = hipFuncSetAttribute((const void *)bo_tile_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        allowed = true;
-    }
     const bool fused = o1 != nullptr;
     const float mul = fused ? -lr : 1.f;
-    const int ntiles = bo_tiles(p, L);
-    // one or two workgroups per compute unit (what the tile's LDS allows), more only where a workgroup would get more
-    // tiles than it can hold descriptors of (the table's size is an upper bound of the tiles in use)
-    int nwg = BoCfg<C>::WGS_PER_CU * bo_compute_units();
-    if ((ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK > nwg) nwg = (ntiles + BO_MAX_CHUNK - 1) / BO_MAX_CHUNK;
-    hipLaunchKernelGGL((bo_tile_kernel<C>), dim3(nwg), dim3(WG), lds, st, p, G1, G2, G3, (int)L, n_bags, alpha, go, g.info, g.tiles,
-                       ntiles, g.tile_base, b.part2, b.pbuf, (float4 *)(fused ? o1 : nullptr), (float4 *)(fused ? o3 : nullptr));
+    const int ntiles = bo_tiles(p, L, tp);
+    int nwg = 0;
+    hipError_t et;
+    if constexpr (C::N1 == 4 && C::R == 64) {
+        if (tp * C::N1 == 64)
+            et = launch_bo_tiles<C, 64>(p, G1, G2, G3, L, n_bags, alpha, go, fused ? o1 : nullptr, fused ? o3 : nullptr, g, b, ntiles, &nwg, st);
+        else
+            et = launch_bo_tiles<C, 128>(p, G1, G2, G3, L, n_bags, alpha, go, fused ? o1 : nullptr, fused ? o3 : nullptr, g, b, ntiles, &nwg, st);
+    } else {
+        if (tp * C::N1 != 128) return hipErrorInvalidValue;
+        et = launch_bo_tiles<C, 128>(p, G1, G2, G3, L, n_bags, alpha, go, fused ? o1 : nullptr, fused ? o3 : nullptr, g, b, ntiles, &nwg, st);
+    }
+    if (et != hipSuccess) return et;
     const int slice4 = C::sB / 4, per = (slice4 + WAVE - 1) / WAVE;
     const int sst = bo_seg_st(L);
     const int seg_tiles = (int)(L / sst + 1), nseg = (seg_tiles + NWAVE - 1) / NWAVE, nfin = p.m2 * per;
@@ -706,13 +744,13 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
 static inline hipError_t bwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                                    int64_t L, const int64_t *off, int n_bags, const float *alpha, const float *go, const float *t0,
                                    float *dG1, float *dG2, float *dG3, float lr, float *o1, float *o2, float *o3,
-                                   const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b, hipStream_t st)
+                                   const uint64_t *ks, const uint32_t *vs, const GroupWs &g, const BoWs &b, int tp, hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 2: return launch_bwd_owner<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
-    case 3: return launch_bwd_owner<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
-    case 4: return launch_bwd_owner<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
-    case 5: return launch_bwd_owner<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, st);
+    case 2: return launch_bwd_owner<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, tp, st);
+    case 3: return launch_bwd_owner<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, tp, st);
+    case 4: return launch_bwd_owner<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, tp, st);
+    case 5: return launch_bwd_owner<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, go, t0, dG1, dG2, dG3, lr, o1, o2, o3, ks, vs, g, b, tp, st);
     default: return hipErrorInvalidValue;
     }
 }

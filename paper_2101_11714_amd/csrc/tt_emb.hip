@@ -203,7 +203,9 @@ size_t split_ws_bytes(const Params &p, int64_t L, bool grouped, bool tiles_possi
     const size_t n = fast_bwd_supported(p) ? fast_bwd_extra_floats(p, (int)L, grouped) : 0;
     size_t bytes = n ? align256(n * sizeof(float)) : 0;
     if (grouped && tiles_possible && bwd_tiles_wanted(p, L)) {          // the tiled backward's buffers instead
-        const size_t b = align256(bo_ws_layout(nullptr, p, L).bytes);
+        // (room for either size of tile)
+        const size_t b1 = align256(bo_ws_layout(nullptr, p, L, bo_tp(p, L, false)).bytes), b2 = align256(bo_ws_layout(nullptr, p, L, bo_tp(p, L, true)).bytes);
+        const size_t b = b1 > b2 ? b1 : b2;
         bytes = b > bytes ? b : bytes;
     }
     return bytes;
@@ -415,6 +417,10 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
     // long streams with a kept T0: the products of Eq. 4 over tiles of positions, on the matrix cores (tt_bwd_owner.h)
     // (with a cache the list owners stay: the cached rows' sums ride along in their launches, multi-hot table 0: 113 against 140 us)
     const bool tiled = grouped && t0 && (!cd.K || g_bwd_tiles) && bwd_tiles_wanted(p, L);
+    // positions per tile of the tile table: 128 / n1 where the forward pass works from it too; the smaller tiles of the
+    // tiled backward only where the table has room for them (tt_group.h: L / 32 + slices + 1 entries)
+    int tile_tp = bo_tp(p, L, tiled && !fwd_from_lists(p, L, cd.K, t0 != nullptr));
+    if (bo_tiles(p, L, tile_tp) > L / 32 + p.m1 + p.m2 + p.m3 + cd.K + 1) tile_tp = 128 / p.n1;
     const size_t sp_bytes = fast ? split_ws_bytes(p, L, grouped, t0 != nullptr && (!cd.K || g_bwd_tiles)) : 0;
     const size_t need = need_bwd + gc_bytes + g_bytes[0] + g_bytes[1] + g_bytes[2] + sp_bytes;
     const bool wants_ws = cd.K || grouped || (fused && !fast) || sp_bytes;
@@ -494,8 +500,8 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                 hipLaunchKernelGGL(grp_info_kernel, dim3(cdiv(n, WG)), dim3(WG), 0, st, p, indices, (int)L, offsets, (int)n_bags, ks, vs,
                                    nb3, g.info);
             if (fwd_from_lists(p, L, cd.K, t0 != nullptr) || tiled) {       // for tt_emb_fwd_prepared and the tiled backward
-                const int ntiles = fwd_owner_tiles(p, L);
-                hipLaunchKernelGGL(grp_tiles_kernel, dim3(cdiv(ntiles, WG)), dim3(WG), 0, st, p.m1, p.m2, (int)L, fwd_owner_tp(p),
+                const int ntiles = bo_tiles(p, L, tile_tp);
+                hipLaunchKernelGGL(grp_tiles_kernel, dim3(cdiv(ntiles, WG)), dim3(WG), 0, st, p.m1, p.m2, (int)L, tile_tp,
                                    g.off, g.end, g.tiles, ntiles, g.tile_base);
             }
         }
@@ -512,9 +518,9 @@ static int bwd_common(const tt_shape_t *shape, const float *const cores[3],
                                grad_cache);
         }
         if (tiled) {
-            const BoWs bw = bo_ws_layout(split_ws, p, L);
+            const BoWs bw = bo_ws_layout(split_ws, p, L, tile_tp);
             hipError_t eb = bwd_owner(p, cores[0], cores[1], cores[2], indices, L, offsets, (int)n_bags, alpha, grad_output, t0,
-                                      d1, d2, d3, lr, o1, o2, o3, ks, vs, g, bw, st);
+                                      d1, d2, d3, lr, o1, o2, o3, ks, vs, g, bw, tile_tp, st);
             if (eb != hipSuccess) return hip_fail(eb, "backward launch");
         } else
         fast_bwd(p, cores[0], cores[1], cores[2], indices, (int)L, offsets, (int)n_bags, alpha, slot, grad_output,

@@ -1,6 +1,6 @@
-"""The backward pass that works on tiles of positions on the matrix cores (long index streams after the grouping
-pre-pass, with the kept T0; selected by tt_emb_debug_set_fast_path(3), not the default): against the oracle, against
-the list owners, and for bit-identical repeats."""
+"""The backward pass that works on tiles of positions on the matrix cores (the grouped backward with a kept T0 and no
+cache; tt_emb_debug_set_fast_path(3) forces it for every length and with a cache): against the oracle, against the
+list owners, and for bit-identical repeats."""
 import dataclasses
 
 import numpy as np
@@ -115,3 +115,25 @@ def _full_size(name):
     new = d.bwd_sgd(wl.lr, t0=t0)
     for k in range(3):
         assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], wl.lr), "%s P = 100 fused core %d" % (name, k + 1))
+
+
+@pytest.mark.parametrize("name,n_bags,longest", [("terabyte_r64", 800, 24), ("sweep_r32", 1800, 24), ("sweep_r64", 1800, 24)])
+def test_two_call_form_groups_earlier_and_matches_oracle(name, n_bags, longest):
+    """The default kernel selection: with a kept T0 and no cache the pair tt_emb_bwd_prepare + tt_emb_bwd_sgd_prepared
+    works on tiles from lengths on at which the one call still runs the slice owners (for the Terabyte-shaped table
+    on tiles of 64 stacked rows).  Ragged, weighted bags with a hot row; both forms against the oracle, the pair twice."""
+    wl = W.WORKLOADS[name]
+    t = wl.tables[0]
+    d = DeviceTable(wl, batch=_ragged(t, 7, n_bags=n_bags, longest=longest))
+    assert B.bwd_two_calls_group_earlier(d.shape, d.L, 0, kept_t0=True), "the test's length no longer falls between the two limits"
+    assert not B.bwd_two_calls_group_earlier(d.shape, d.L, 0, kept_t0=False)
+    _, t0 = d.fwd_keep_t0()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    one = d.bwd_sgd(0.05, t0=t0)
+    two = d.bwd_sgd(0.05, t0=t0, two_calls=True)
+    again = d.bwd_sgd(0.05, t0=t0, two_calls=True)
+    for k in range(3):
+        want = ora.sgd(d.cores[k], ref[k], 0.05)
+        assert_close(one[k].cpu().numpy(), want, "%s fused core %d in one call" % (name, k + 1))
+        assert_close(two[k].cpu().numpy(), want, "%s fused core %d in two calls" % (name, k + 1))
+        assert torch.equal(two[k], again[k]), "core %d differs between two runs of the pair" % (k + 1)
