@@ -369,21 +369,32 @@ def main():
 
     # per-kernel durations: each stage alone, launched back to back on the stream the step runs on
     reps = max(POOL * 16, min(steps, 4096))
-    if fwd_lists:
-        # the forward pass of the step works from the lists of the pre-pass: one prepared workspace per batch of the pool
+    ws_stage, ms_prepass = None, None
+    if two_calls:
+        # the step runs the fused backward in its two-call form: the stages are timed in that form too, the index-only
+        # pre-pass on its own (in the step it runs beside other work) and the rest on one prepared workspace per batch
+        ms_prepass = timed_ms(lambda i: B.tt_emb_bwd_prepare(shape, idx[i % POOL], off[i % POOL], n_bags, cache=cache, workspace=ws,
+                                                             kept_t0=keep_t0), reps)[0]
         ws_stage = [torch.empty_like(ws) for _ in range(POOL)]
         for j in range(POOL):
             B.tt_emb_bwd_prepare(shape, idx[j], off[j], n_bags, cache=cache, workspace=ws_stage[j], kept_t0=keep_t0)
+    if fwd_lists:
+        # the forward pass of the step works from the lists of the pre-pass
         ms_fwd = timed_ms(lambda i: B.tt_emb_fwd_prepared(shape, cores, idx[i % POOL], off[i % POOL], n_bags, out, ws_stage[i % POOL],
                                                           t0=t0_pool[i % POOL] if keep_t0 else None, alpha=alpha[i % POOL],
                                                           cache=cache), reps)[0]
-        del ws_stage
     else:
         ms_fwd = timed_ms(lambda i: fwd_call(cores, i % POOL), reps)[0]
     if args.step == "fused":
         # (the forward timing above has left the T0 of every batch of the pool in t0_pool)
-        ms_bs = timed_ms(lambda i: bwd_sgd_call(cores, cores2, i % POOL, (i + 1) % POOL), reps)[0]
+        if two_calls:
+            ms_bs = timed_ms(lambda i: B.tt_emb_bwd_sgd(shape, cores, cores2, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], lr,
+                                                        alpha=alpha[i % POOL], cache=cache, workspace=ws_stage[i % POOL],
+                                                        t0=t0_pool[i % POOL] if keep_t0 else None, prepared=True), reps)[0]
+        else:
+            ms_bs = timed_ms(lambda i: bwd_sgd_call(cores, cores2, i % POOL, (i + 1) % POOL), reps)[0]
         stage_ms = {"fwd": ms_fwd, "bwd_sgd": ms_bs}
+        del ws_stage
     else:
         ms_bwd = timed_ms(lambda i: B.tt_emb_bwd(shape, cores, idx[i % POOL], off[i % POOL], n_bags, go[i % POOL], grads,
                                                  alpha=alpha[i % POOL], cache=cache, grad_cache=grad_cache, workspace=ws), reps)[0]
@@ -432,7 +443,7 @@ def main():
     kept_bytes = (Ls[0] - n_cached) * 4 * B.t0_floats(shape) if keep_t0 else 0
     list_bytes = 3 * Ls[0] * 16 if use_lists else 0      # one 16-byte list entry per position and core
     dominant = max(stage_ms, key=stage_ms.get)
-    variant = "lists" if use_lists else ("keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate"))
+    variant = "lists" if use_lists else ("two_calls" if two_calls else ("keep_t0" if keep_t0 else ("recompute" if args.step == "fused" else "separate")))
     achieved = ab[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -441,6 +452,7 @@ def main():
                 "algorithmic_bytes": ab[dominant], "kept_intermediate_bytes": kept_bytes, "kept_list_bytes": list_bytes,
                 "avg_us": round(stage_ms[dominant] * 1e3, 3),
                 "stages_us": {k: round(v * 1e3, 3) for k, v in stage_ms.items()},
+                "prepass_us": None if ms_prepass is None else round(ms_prepass * 1e3, 3),
                 "launch_floor_us": launch_floor,
                 "stages_frac": {k: round(ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k in stage_ms},
                 "fp32_tflops": round(af[dominant] / (stage_ms[dominant] * 1e-3) / 1e12, 3),
