@@ -546,10 +546,11 @@ int tt_emb_debug_dedup(const tt_shape_t *shape, const int64_t *indices, int64_t 
 /* Kernel selection for the library calls that the CALLING THREAD makes from now on, meant for
  * tests: the value is per thread, every thread starts at 1, and no other thread's calls are
  * affected.  1: shapes with a specialised kernel use it, and the backward groups long index
- * streams first.  0: every call takes the shape-generic kernels.  2: as 1, but the backward
- * always groups first.  3: as 2, and the grouped backward with a kept T0 takes the kernels
- * that work on tiles of positions on the matrix cores (built and tested; not the default: slower than
- * the list owners so far).  Returns the thread's old value.  Workspace queries, tt_emb_bwd_prepare
+ * streams first; with a kept T0 and no cache the grouped backward works on tiles of positions on
+ * the matrix cores, else a workgroup per slice works through the slice's list.  0: every call
+ * takes the shape-generic kernels.  2: as 1, but the backward always groups first and always
+ * takes the list owners.  3: as 2, but the grouped backward with a kept T0 takes the tile kernels,
+ * also with a cache.  Returns the thread's old value.  Workspace queries, tt_emb_bwd_prepare
  * and the backward call that follows must be made under the same value. */
 int tt_emb_debug_set_fast_path(int mode);
 

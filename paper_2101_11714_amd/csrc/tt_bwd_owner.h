@@ -327,10 +327,13 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C, ROW
 }
 
 // dst[i2] = src[i2] + mul * (sum of the parts of slice i2, in the order of their tiles); a slice without tiles is copied
-// if dst is another array.  A workgroup takes 64 float4 of a slice; wave q adds the q-th quarter of the slice's parts,
-// 16 in flight, and the four sums are added in wave order.  tile_base[i2] .. tile_base[i2 + 1] are the slice's tiles;
-// only those that begin a stretch hold a part (the slice's first tile and every ch-th tile of the table, ch being the
-// tiles per workgroup of bo_tile_kernel, which ran with nwg workgroups).
+// if dst is another array.  A workgroup takes BO_FIN float4 of a slice, two per thread, and every thread adds the parts
+// of its float4 one after the other, eight in flight (a workgroup of the tile kernel adds consecutive tiles of a slice
+// in registers, so a slice has few parts: a twentieth of its tiles at 100 positions per bag).  tile_base[i2] ..
+// tile_base[i2 + 1] are the slice's tiles; only those that begin a stretch hold a part (the slice's first tile and
+// every ch-th tile of the table, ch being the tiles per workgroup of bo_tile_kernel, which ran with nwg workgroups).
+constexpr int BO_FIN = 2 * WG;
+
 struct BoFinishArgs {
     int m2, slice4, ntiles, nwg;
     const int *tile_base;
@@ -340,49 +343,56 @@ struct BoFinishArgs {
 
 __device__ __forceinline__ void bo_g2_finish_body(int vblock, const BoFinishArgs &a, float mul)
 {
+    constexpr int NF = BO_FIN / WG, NP = 8;
     const int m2 = a.m2, slice4 = a.slice4;
     const int *__restrict__ tile_base = a.tile_base;
     const float4 *__restrict__ part2 = a.part2, *__restrict__ src = a.src;
     float4 *__restrict__ dst = a.dst;
     const int ch = bo_chunk(min(a.ntiles, tile_base[m2]), a.nwg);            // as in bo_tile_kernel
-    __shared__ float4 s_red[NWAVE][WAVE];
-    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int per = (slice4 + WAVE - 1) / WAVE;                             // workgroups per slice
-    const int i2 = vblock / per, e = (vblock % per) * WAVE + lane;
+    const int per = (slice4 + BO_FIN - 1) / BO_FIN;                          // workgroups per slice
+    const int i2 = vblock / per, e0 = (vblock % per) * BO_FIN + threadIdx.x;
     if (i2 >= m2) return;
-    const bool on = e < slice4;
     const int t0 = tile_base[i2], t1 = tile_base[i2 + 1];
-    const size_t at = (size_t)i2 * slice4 + e;
+    const size_t base = (size_t)i2 * slice4;
     if (t1 <= t0) {                                                          // uniform
-        if (dst != src && on && q == 0) dst[at] = src[at];
+        if (dst != src) {
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                if (e0 + f * WG < slice4) dst[base + e0 + f * WG] = src[base + e0 + f * WG];
+        }
         return;
     }
     // the parts: the stretch that begins with the slice, then those that begin at multiples of ch
     const int first_u = (t0 / ch + 1) * ch;
     const int nparts = first_u < t1 ? (t1 - first_u + ch - 1) / ch : 0;      // beyond the first one
-    const int pq = (nparts + NWAVE - 1) / NWAVE, j0 = q * pq, j1 = min(nparts, j0 + pq);
-    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (q == 0 && on) sum = part2[(size_t)t0 * slice4 + e];
-    for (int jb = j0; jb < j1; jb += 16) {
-        float4 x[16];
+    int e[NF];
+    float4 sum[NF], old[NF];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int u = first_u + min(jb + j, j1 - 1) * ch;
-            x[j] = on ? part2[(size_t)u * slice4 + e] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int f = 0; f < NF; ++f) {
+        e[f] = min(e0 + f * WG, slice4 - 1);                                 // (clamped: no load is conditional)
+        sum[f] = part2[(size_t)t0 * slice4 + e[f]];
+        old[f] = src[base + e[f]];
+    }
+    for (int jb = 0; jb < nparts; jb += NP) {                                // uniform
+        float4 x[NF][NP];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int u = first_u + min(jb + j, nparts - 1) * ch;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) x[f][j] = part2[(size_t)u * slice4 + e[f]];
         }
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (jb + j < j1) { sum.x += x[j].x; sum.y += x[j].y; sum.z += x[j].z; sum.w += x[j].w; }
-    }
-    s_red[q][lane] = sum;
-    __syncthreads();
-    if (q == 0 && on) {
-        float4 tot = s_red[0][lane];
+        for (int j = 0; j < NP; ++j)
+            if (jb + j < nparts) {
 #pragma unroll
-        for (int ww = 1; ww < NWAVE; ++ww) { tot.x += s_red[ww][lane].x; tot.y += s_red[ww][lane].y; tot.z += s_red[ww][lane].z; tot.w += s_red[ww][lane].w; }
-        const float4 old = src[at];
-        dst[at] = make_float4(fmaf(mul, tot.x, old.x), fmaf(mul, tot.y, old.y), fmaf(mul, tot.z, old.z), fmaf(mul, tot.w, old.w));
+                for (int f = 0; f < NF; ++f) { sum[f].x += x[f][j].x; sum[f].y += x[f][j].y; sum[f].z += x[f][j].z; sum[f].w += x[f][j].w; }
+            }
     }
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+        if (e0 + f * WG < slice4)
+            dst[base + e[f]] = make_float4(fmaf(mul, sum[f].x, old[f].x), fmaf(mul, sum[f].y, old[f].y), fmaf(mul, sum[f].z, old[f].z),
+                                           fmaf(mul, sum[f].w, old[f].w));
 }
 
 // ---- segmented sums over the sorted items of the first and of the third core ----------------------
@@ -727,7 +737,7 @@ static inline hipError_t launch_bwd_owner(const Params &p, const float *G1, cons
         et = launch_bo_tiles<C, 128>(p, G1, G2, G3, L, n_bags, alpha, go, fused ? o1 : nullptr, fused ? o3 : nullptr, g, b, ntiles, &nwg, st);
     }
     if (et != hipSuccess) return et;
-    const int slice4 = C::sB / 4, per = (slice4 + WAVE - 1) / WAVE;
+    const int slice4 = C::sB / 4, per = (slice4 + BO_FIN - 1) / BO_FIN;
     const int sst = bo_seg_st(L);
     const int seg_tiles = (int)(L / sst + 1), nseg = (seg_tiles + NWAVE - 1) / NWAVE, nfin = p.m2 * per;
     const BoFinishArgs fin{p.m2, slice4, ntiles, nwg, g.tile_base, (const float4 *)b.part2, (const float4 *)(fused ? G2 : dG2),
