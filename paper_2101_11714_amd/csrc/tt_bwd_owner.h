@@ -415,32 +415,52 @@ __device__ __forceinline__ int bo_seg_st_dev(int n, int cap)
     return st;
 }
 
+// The row of an item comes from a producer in two steps, so that a wave can have the loads of a whole batch of items
+// in flight before it uses any of them (a producer that loads and computes in one go, under a test of the lane, makes
+// every item a round trip of its own: 8 dependent trips per batch): issue() only loads, for every lane (a lane past
+// the row loads what the row's last lane loads), finish() only computes.
+//
 // row of an item of the first core: the G1 gradient of its position, from pbuf
 struct BoRowP {
     const float *pbuf;
     int row_floats;
-    __device__ __forceinline__ float4 operator()(int k, int /*bag*/, float /*w*/, int lane, bool active) const
+    struct Raw { float v[4]; };
+    __device__ __forceinline__ Raw issue(int k, int /*bag*/, int lane_c) const
     {
-        return active ? *reinterpret_cast<const float4 *>(pbuf + (size_t)k * row_floats + 4 * lane) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 x = *reinterpret_cast<const float4 *>(pbuf + (size_t)k * row_floats + 4 * lane_c);
+        return Raw{{x.x, x.y, x.z, x.w}};
     }
+    __device__ __forceinline__ float4 finish(const Raw &r, float /*w*/) const { return make_float4(r.v[0], r.v[1], r.v[2], r.v[3]); }
 };
 
-// row of an item of the third core: lane b holds sum_(j1,j2) T0_k[(j1,j2)][b] w dY[bag][(j1,j2)][0..3]
+// row of an item of the third core: lane b holds sum_(j1,j2) T0_k[(j1,j2)][b] w dY[bag][(j1,j2)][0..3].  The
+// upstream gradient row (N <= 64 values) is loaded one value per lane and handed round with readlane.
 template <typename C>
 struct BoRowT0 {
     const float *t0, *grad_out;
-    __device__ __forceinline__ float4 operator()(int k, int bag, float w, int lane, bool active) const
+    static constexpr int NJ = C::N1 * C::N2;
+    static_assert(C::N <= WAVE && (C::N & (C::N - 1)) == 0, "the upstream gradient row fits the lanes of a wave");
+    struct Raw { float tv[NJ]; float dy; };
+    __device__ __forceinline__ Raw issue(int k, int bag, int lane_c) const
     {
-        constexpr int NJ = C::N1 * C::N2;
+        Raw r;
+        const float *T = t0 + (size_t)k * NJ * C::R + lane_c;
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) r.tv[jj] = T[jj * C::R];
+        r.dy = grad_out[(size_t)bag * C::N + (threadIdx.x & (C::N - 1))];
+        return r;
+    }
+    __device__ __forceinline__ float4 finish(const Raw &r, float w) const
+    {
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!active) return o;
-        const float *T = t0 + (size_t)k * NJ * C::R + lane;
-        const float4 *dy = reinterpret_cast<const float4 *>(grad_out + (size_t)bag * C::N);
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj) {
-            const float tv = w * T[jj * C::R];
-            const float4 d = dy[jj];
-            o.x = fmaf(tv, d.x, o.x); o.y = fmaf(tv, d.y, o.y); o.z = fmaf(tv, d.z, o.z); o.w = fmaf(tv, d.w, o.w);
+            const float tv = w * r.tv[jj];
+            const float dx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r.dy), 4 * jj + 0));
+            const float dy = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r.dy), 4 * jj + 1));
+            const float dz = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r.dy), 4 * jj + 2));
+            const float dw = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r.dy), 4 * jj + 3));
+            o.x = fmaf(tv, dx, o.x); o.y = fmaf(tv, dy, o.y); o.z = fmaf(tv, dz, o.z); o.w = fmaf(tv, dw, o.w);
         }
         return o;
     }
@@ -497,27 +517,31 @@ __device__ __forceinline__ void bo_seg_body(int vblock, const Producer &prod, co
         first = false;
         sum = make_float4(0.f, 0.f, 0.f, 0.f);
     };
+    const int lane_c = min(lane, row4 - 1);                                  // (a lane past the row repeats the row's last lane: no load is conditional)
     for (int e0 = 0; e0 < cnt; e0 += NBATCH) {
-        float4 g[NBATCH], old[NBATCH];
+        typename Producer::Raw raw[NBATCH];
+        float old[NBATCH][4];
+        // all loads of the batch first: the items' rows and the old values of their slices (needed where a run ends; the
+        // few slices stay in the caches)
 #pragma unroll
         for (int q = 0; q < NBATCH; ++q) {
             const int e = min(e0 + q, cnt - 1);
             const int key = __builtin_amdgcn_readlane(my_key, e), k = __builtin_amdgcn_readlane(my_k, e);
             const int bag = __builtin_amdgcn_readlane(my_bag, e);
-            const float wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), e));
-            g[q] = prod(k, bag, wgt, lane, active);
-            old[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (__builtin_amdgcn_readlane(my_end, e) && active)                // (uniform but for `active`)
-                old[q] = *reinterpret_cast<const float4 *>(src + (size_t)(key - klo) * (4 * row4) + 4 * lane);
+            raw[q] = prod.issue(k, bag, lane_c);
+            const float4 o4 = *reinterpret_cast<const float4 *>(src + (size_t)(key - klo) * (4 * row4) + 4 * lane_c);
+            old[q][0] = o4.x; old[q][1] = o4.y; old[q][2] = o4.z; old[q][3] = o4.w;
         }
 #pragma unroll
         for (int q = 0; q < NBATCH; ++q) {
             const int e = e0 + q;
             if (e < cnt) {                                                   // uniform
                 const int key = __builtin_amdgcn_readlane(my_key, e);
+                const float wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), e));
+                const float4 g = prod.finish(raw[q], wgt);
                 if (key != cur) { flush(cur, false); cur = key; }
-                sum.x += g[q].x; sum.y += g[q].y; sum.z += g[q].z; sum.w += g[q].w;
-                if (__builtin_amdgcn_readlane(my_end, e)) old_last = old[q];
+                sum.x += g.x; sum.y += g.y; sum.z += g.z; sum.w += g.w;
+                if (__builtin_amdgcn_readlane(my_end, e)) old_last = make_float4(old[q][0], old[q][1], old[q][2], old[q][3]);
             }
         }
     }

@@ -16,7 +16,7 @@ of tt_dense_bag_bwd_sgd (one float atomic per position and column) and tt_dense_
 (positions sorted by row, duplicates added up first, one write per distinct row), both reported.
 Every step sequence is captured in a HIP graph, so the figures are GPU times.  Prints a markdown table.
 
-    python -m paper_2101_11714_amd.microbench [pooling] [hitrate] [tables]
+    python -m paper_2101_11714_amd.microbench [pooling] [hitrate] [tables] [pooling:P:R]
 """
 
 from __future__ import annotations
@@ -63,7 +63,7 @@ class _Table:
         self.cores2 = [torch.empty_like(x) for x in self.cores]
         self.dense = torch.empty((shape.num_rows, shape.dim), dtype=torch.float32, device=dev).normal_(0, 0.01)
 
-    def time(self, batches, cache=None, lr=1e-6):
+    def time(self, batches, cache=None, lr=1e-6, dense=True):
         dev, n_bags = self.dev, batches[0].offsets.size - 1
         idx = [torch.from_numpy(b.indices).to(dev) for b in batches]
         off = [torch.from_numpy(b.offsets).to(dev) for b in batches]
@@ -127,20 +127,27 @@ class _Table:
             B.tt_dense_bag_fwd(self.dense, idx[j], off[j], n_bags, out)
             B.tt_dense_bag_bwd_sgd_merged(self.dense, idx[j], off[j], n_bags, go[j], lr, workspace=wsd)
 
+        if not dense:                                       # (the TT side alone: for a kernel trace)
+            return _graph_us(tt_step), float("nan"), float("nan")
         return _graph_us(tt_step), _graph_us(dense_step_atomic), _graph_us(dense_step_merged)
 
 
-def pooling(dev):
+def pooling(dev, only=None):
+    """only = (P, R): that configuration alone, TT side only (for a kernel trace of it)."""
     print("## Pooling factor x TT rank (Kaggle-shaped table, %d samples per step, no cache)\n" % N_BAGS)
     print("| P | lookups/step | R | TT step us | dense us, atomics | dense us, merged | TT / faster dense | TT us per sample | TT M lookups/s |")
     print("|---|---|---|---|---|---|---|---|---|")
     for R in (8, 16, 32, 64):
+        if only and R != only[1]:
+            continue
         base = W.WORKLOADS["sweep_r%d" % R]
         tab = _Table(base.tables[0], base.init, base.seed, dev)
         for P in (1, 10, 100):
+            if only and P != only[0]:
+                continue
             wl = dataclasses.replace(base, n_bags=N_BAGS, bag_len=(P, P))
             batches = [W.make_batch(wl, 0, j) for j in range(STEPS)]
-            tt, da, dm = tab.time(batches)
+            tt, da, dm = tab.time(batches, dense=not only)
             L = N_BAGS * P
             print("| %d | %d | %d | %.1f | %.1f | %.1f | %.1f | %.4f | %.1f |"
                   % (P, L, R, tt, da, dm, tt / min(da, dm), tt / N_BAGS, L / tt), flush=True)
@@ -251,6 +258,9 @@ def main():
     print("# TT-EmbeddingBag against an uncompressed EmbeddingBag on one MI355X (forward + backward + SGD per step)\n")
     if "pooling" in which:
         pooling(dev)
+    for w in which:
+        if w.startswith("pooling:"):                          # pooling:P:R, e.g. pooling:100:64
+            pooling(dev, only=tuple(int(x) for x in w.split(":")[1:3]))
     if "hitrate" in which:
         hitrate(dev)
     if "tables" in which:
