@@ -360,7 +360,9 @@ int tt_emb_fwd_prepared(const tt_shape_t *shape, const float *const cores[3],
     while ((1 << bits) <= nbins) ++bits;
     uint64_t *ks; uint32_t *vs;
     radix_sort_result(g.sort, bits, &ks, &vs);
-    hipError_t e = fwd_owner(p, cores[0], cores[1], cores[2], indices, L, offsets, (int)n_bags, alpha, cd, vs, g.tiles,
+    // the pre-pass wrote the items' records if the backward that follows runs on tiles (the same test as there)
+    const bool have_info = t0 != nullptr && (!cd.K || g_bwd_tiles) && bwd_tiles_wanted(p, L);
+    hipError_t e = fwd_owner(p, cores[0], cores[1], cores[2], indices, L, offsets, (int)n_bags, alpha, cd, vs, have_info ? g.info : nullptr, g.tiles,
                              g.rows, output, t0, (hipStream_t)stream);
     return e == hipSuccess ? TT_OK : hip_fail(e, "forward launch");
 }

@@ -39,13 +39,16 @@ template <typename C>
 static inline size_t fo_lds_bytes() { return (size_t)FoCfg<C>::LDS_FLOATS * sizeof(float); }
 
 // Workgroup n2 * tile + j2 computes, for the tile's positions, the columns (j2, .) of T0 and the outputs (., j2, .).
-// vs / tiles: the sorted payloads (r L + k) and the tile table of the grouping pre-pass.
+// vs / tiles: the sorted payloads (r L + k) and the tile table of the grouping pre-pass; info: the records (position,
+// first digit, third digit, bag) of the sorted items if the pre-pass wrote them (it does for the backward on tiles),
+// else null: then the positions' rows are read and decoded here, one dependent round trip more.
 template <typename C>
 __global__ __launch_bounds__(WG) void fwd_owner_kernel(Params p, const float *__restrict__ G1, const float *__restrict__ G2,
                                                        const float *__restrict__ G3, const int64_t *__restrict__ indices,
                                                        int L, const float *__restrict__ alpha,
-                                                       const uint32_t *__restrict__ vs, const int4 *__restrict__ tiles,
-                                                       int ntiles, float *__restrict__ rows_out, float *__restrict__ t0_out)
+                                                       const uint32_t *__restrict__ vs, const int4 *__restrict__ info,
+                                                       const int4 *__restrict__ tiles, int ntiles,
+                                                       float *__restrict__ rows_out, float *__restrict__ t0_out)
 {
     using F = FoCfg<C>;
     constexpr int N1 = C::N1, N2 = C::N2, R = C::R, COLS = C::COLS, TP = F::TP, LDT = F::LDT;
@@ -81,10 +84,17 @@ __global__ __launch_bounds__(WG) void fwd_owner_kernel(Params p, const float *__
     const bool have = e < n;
     int k = 0, i1 = 0, i3 = 0;
     if (have) {
-        k = (int)(vs[lo + e] - (uint32_t)L);                               // item 1 of position k carries L + k
-        k = (unsigned)k < (unsigned)L ? k : 0;
-        int i2x;
-        decode(p, (uint32_t)indices[k], i1, i2x, i3);
+        if (info) {
+            const int4 pi = info[lo + e];
+            k = (unsigned)pi.x < (unsigned)L ? pi.x : 0;
+            i1 = min(max(pi.y, 0), p.m1 - 1);
+            i3 = min(max(pi.z, 0), p.m3 - 1);
+        } else {
+            k = (int)(vs[lo + e] - (uint32_t)L);                           // item 1 of position k carries L + k
+            k = (unsigned)k < (unsigned)L ? k : 0;
+            int i2x;
+            decode(p, (uint32_t)indices[k], i1, i2x, i3);
+        }
     }
     if (j1 == 0 && kh == 0 && have) { s_k[e] = k; s_w[e] = alpha ? alpha[k] : 1.f; }
     // ... and thread (position ee, bq) of the second product fetches its part of G3[i3] now, to have it when the
@@ -96,9 +106,13 @@ __global__ __launch_bounds__(WG) void fwd_owner_kernel(Params p, const float *__
     {
         int k2 = 0, i1x, i2x, i3x = 0;
         if (on) {
-            k2 = (int)(vs[lo + ee] - (uint32_t)L);
-            k2 = (unsigned)k2 < (unsigned)L ? k2 : 0;
-            decode(p, (uint32_t)indices[k2], i1x, i2x, i3x);
+            if (info) {
+                i3x = min(max(info[lo + ee].z, 0), p.m3 - 1);
+            } else {
+                k2 = (int)(vs[lo + ee] - (uint32_t)L);
+                k2 = (unsigned)k2 < (unsigned)L ? k2 : 0;
+                decode(p, (uint32_t)indices[k2], i1x, i2x, i3x);
+            }
         }
         // (the NBQ lanes of a position read neighbouring rows of the slice: b = NBQ i + bq)
         Cp = reinterpret_cast<const float4 *>(G3 + (size_t)i3x * C::sC) + bq;
@@ -258,7 +272,7 @@ static inline int fwd_owner_tiles(const Params &p, int64_t L) { return (int)((L 
 template <typename C>
 static inline hipError_t launch_fwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                                           int64_t L, const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd,
-                                          const uint32_t *vs, const int4 *tiles, float *rows, float *out,
+                                          const uint32_t *vs, const int4 *info, const int4 *tiles, float *rows, float *out,
                                           float *t0_out, hipStream_t st)
 {
     const size_t lds = fo_lds_bytes<C>();
@@ -273,7 +287,7 @@ static inline hipError_t launch_fwd_owner(const Params &p, const float *G1, cons
     const int ntiles = fwd_owner_tiles(p, L);
     const int grid_tiles = ntiles < FO_GRID_TILES ? ntiles : FO_GRID_TILES;
     hipLaunchKernelGGL((fwd_owner_kernel<C>), dim3(grid_tiles * C::N2), dim3(WG), lds, st, p, G1, G2, G3, idx, (int)L, alpha, vs,
-                       tiles, ntiles, rows, t0_out);
+                       info, tiles, ntiles, rows, t0_out);
     hipLaunchKernelGGL(fwd_pool_kernel, dim3((unsigned)((n_bags + NWAVE - 1) / NWAVE)), dim3(WG), 0, st, C::N, rows, idx, off, n_bags,
                        alpha, cd, out);
     return hipGetLastError();
@@ -281,14 +295,14 @@ static inline hipError_t launch_fwd_owner(const Params &p, const float *G1, cons
 
 static inline hipError_t fwd_owner(const Params &p, const float *G1, const float *G2, const float *G3, const int64_t *idx,
                                    int64_t L, const int64_t *off, int n_bags, const float *alpha, const CacheDev &cd,
-                                   const uint32_t *vs, const int4 *tiles, float *rows, float *out, float *t0_out,
+                                   const uint32_t *vs, const int4 *info, const int4 *tiles, float *rows, float *out, float *t0_out,
                                    hipStream_t st)
 {
     switch (fast_config(p)) {
-    case 2: return launch_fwd_owner<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, tiles, rows, out, t0_out, st);
-    case 3: return launch_fwd_owner<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, tiles, rows, out, t0_out, st);
-    case 4: return launch_fwd_owner<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, tiles, rows, out, t0_out, st);
-    case 5: return launch_fwd_owner<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, tiles, rows, out, t0_out, st);
+    case 2: return launch_fwd_owner<Cfg224R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, info, tiles, rows, out, t0_out, st);
+    case 3: return launch_fwd_owner<Cfg224R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, info, tiles, rows, out, t0_out, st);
+    case 4: return launch_fwd_owner<Cfg444R32>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, info, tiles, rows, out, t0_out, st);
+    case 5: return launch_fwd_owner<Cfg444R64>(p, G1, G2, G3, idx, L, off, n_bags, alpha, cd, vs, info, tiles, rows, out, t0_out, st);
     default: return hipErrorInvalidValue;
     }
 }
