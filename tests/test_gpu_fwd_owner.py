@@ -139,3 +139,31 @@ def test_short_streams_and_other_shapes_fall_back():
     B.tt_emb_fwd_prepared(d.shape, d.g, d.idx, d.off, d.n_bags, out, ws)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), d.fwd())
+
+
+@pytest.mark.parametrize("name,table,with_cache", [("sweep_r32", 0, False), ("terabyte_r64", 0, False), ("sweep_r64", 0, True)])
+def test_ragged_weighted_bags_with_item_records(name, table, with_cache):
+    """Where the backward that follows runs on tiles, the pre-pass also writes a record per sorted item (position, digits,
+    bag) and the forward takes its tiles' positions and digits from those instead of reading and decoding the rows:
+    ragged, weighted bags with a hot row, with and without a cache, the kept T0 as well."""
+    old = B.set_fast_path(3)                       # groups whatever the number of positions; the backward on tiles, also with a cache
+    try:
+        wl = W.WORKLOADS[name]
+        t = wl.tables[table]
+        d = DeviceTable(wl, table=table, batch=_ragged(t, 53 + table))
+        cache, keys, crow = None, None, None
+        if with_cache:
+            rows, counts = np.unique(d.batch.indices, return_counts=True)
+            cache, _, _ = d.build_cache(40, rows.astype(np.int64), counts.astype(np.int64))
+            keys = ora.cache_select(rows, counts, 40)
+            crow = cache.rows.cpu().numpy()[:40].copy()
+        out, t0, _ = _prepared_forward(d, cache=cache, keep=True)
+        ref = ora.fwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, alpha=d.batch.alpha, cache_keys=keys, cache_rows=crow)
+        assert_close(out, ref, "%s forward from lists and item records" % name)
+        got = t0.cpu().numpy()
+        cached = ora.cache_lookup(d.oshape, keys, d.batch.indices) >= 0 if with_cache else np.zeros(d.L, dtype=bool)
+        pick = np.random.default_rng(3).choice(np.flatnonzero(~cached), 48, replace=False)
+        want = np.stack([ora.t0(d.oshape, d.cores, int(d.batch.indices[k])).reshape(-1) for k in pick])
+        assert_close(got[pick], want, "%s T0 from lists and item records" % name)
+    finally:
+        B.set_fast_path(old)
