@@ -137,3 +137,22 @@ def test_two_call_form_groups_earlier_and_matches_oracle(name, n_bags, longest):
         assert_close(one[k].cpu().numpy(), want, "%s fused core %d in one call" % (name, k + 1))
         assert_close(two[k].cpu().numpy(), want, "%s fused core %d in two calls" % (name, k + 1))
         assert torch.equal(two[k], again[k]), "core %d differs between two runs of the pair" % (k + 1)
+
+
+@pytest.mark.parametrize("name,table,n_bags,longest", [("multihot_cache", 0, 3600, 24), ("sweep_r64", 0, 7000, 24)])
+def test_medium_streams_in_one_call(name, table, n_bags, longest):
+    """Between 32,768 and 131,072 positions, default kernel selection, no cache, one call: the backward groups the
+    positions and works on tiles, and the segmented sums take 16 or 32 items per wave (worked out on the device).
+    Ragged, weighted bags with a hot row; gradients and the fused step against the oracle."""
+    wl = W.WORKLOADS[name]
+    t = wl.tables[table]
+    d = DeviceTable(wl, table=table, batch=_ragged(t, 19 + table, n_bags=n_bags, longest=longest))
+    assert 32768 <= d.L < 131072
+    _, t0 = d.fwd_keep_t0()
+    ref, _ = ora.bwd(d.oshape, d.cores, d.batch.indices, d.batch.offsets, d.batch.grad_output, alpha=d.batch.alpha)
+    dg, _ = d.bwd(t0=t0)
+    for k in range(3):
+        assert_close(dg[k].cpu().numpy(), ref[k], "%s dG%d, %d positions" % (name, k + 1, d.L))
+    new = d.bwd_sgd(0.05, t0=t0)
+    for k in range(3):
+        assert_close(new[k].cpu().numpy(), ora.sgd(d.cores[k], ref[k], 0.05), "%s fused core %d, %d positions" % (name, k + 1, d.L))
