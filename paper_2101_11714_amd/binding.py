@@ -569,7 +569,8 @@ def tt_emb_debug_dedup(shape: TTShape, indices: torch.Tensor, which: int, slot: 
 
 
 def set_fast_path(mode: int) -> int:
-    """0: generic kernels, 1: specialised (default), 2: specialised + grouping pre-pass always."""
+    """0: generic kernels, 1: specialised (default), 2: specialised + grouping pre-pass always + list owners always,
+    3: as 2 but the grouped backward with a kept T0 on tiles of positions, also with a cache.  Per thread; returns the old value."""
     return int(lib().tt_emb_debug_set_fast_path(int(mode)))
 
 

@@ -7,13 +7,15 @@
 // positions stacked: 128 rows):
 //     dG2[i2][a][(j2,b)] += sum_rows A[(e,j1)][a] dT0'[(e,j1)][(j2,b)]        (A = stacked rows of G1)
 //     P[(e,j1)][a]        = sum_(j2,b) dT0'[(e,j1)][(j2,b)] Bm[a][(j2,b)]     (the G1 gradient of position e)
-// both as fp32 MFMA 32x32x2 products with operands in LDS, one j2 at a time.  A tile leaves
-// its part of the slice gradient in part2[tile] and the rows P in pbuf[k]; three small kernels
-// finish the cores in a fixed order of summation (no atomics):
-//   * the parts of every G2 slice are added tile after tile,
+// both as fp32 MFMA 32x32x2 products with operands in LDS, one j2 at a time.  A workgroup works
+// through consecutive tiles, leaves the part of a slice gradient that it has added up in
+// part2[first tile of the stretch] and the rows P in pbuf[k]; two more launches finish the
+// cores in a fixed order of summation (no atomics):
+//   * the parts of every G2 slice are added in tile order,
 //   * the G1 gradient is a segmented sum of the rows P over the sorted items of the first
-//     core (one wave per 64 items; runs over tile borders are finished by the wave where the
-//     run begins, as in the cached-row reduction of tt_group.h),
+//     core (one wave per 8 to 64 items; runs over the borders of such pieces are finished, in
+//     the second of the two launches, by the wave where the run begins, as in the cached-row
+//     reduction of tt_group.h),
 //   * the G3 gradient dG3[i3][b][j3] += sum_(j1,j2) T0_k[(j1,j2)][b] dY_k[(j1,j2)][j3] is the same
 //     kind of segmented sum over the sorted items of the third core, the row of an item being
 //     computed from the kept T0 on the way.

@@ -37,7 +37,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 // Kernel selection of the calling thread (tests only; no other thread's calls change with it):
-// 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always
+// 0: generic kernels, 1: specialised, 2: specialised + grouping pre-pass always + list owners always
 thread_local int g_fast_path = 1;
 thread_local int g_bwd_tiles = 0;          // 1: the grouped backward with a kept T0 runs the tile kernels of tt_bwd_owner.h even under selection 2
 // The grouped backward with a kept T0 runs on tiles of positions (tt_bwd_owner.h) wherever that path covers the
