@@ -41,7 +41,9 @@ struct BoCfg {
     static constexpr int RBK = ROWS / 32;                      // 32-row blocks of P
     static constexpr int WPR = NWAVE / RBK;                    // waves that share a row block of P: each takes RB / WPR of its 32-wide column blocks
     static constexpr int ABW = RB / WPR;
-    static constexpr int LDA = C::R + 1, LDT = C::R + 2, LDB = C::R + 1;
+    // row strides in LDS: As and Bm rows are written and (Bm) read as float4 (stride a multiple of 4; four K-steps of the
+    // second product per read), dT0' is read in pairs (even stride)
+    static constexpr int LDA = C::R + 4, LDT = C::R + 2, LDB = C::R + 4;
     static constexpr int NBQ = WG / TP, BQ = C::R / NBQ;       // threads per position / values of b per thread in dT0'
     static constexpr int DY_FLOATS = TP * C::N;
     static constexpr int LDS_FLOATS = DY_FLOATS + ROWS * LDA + ROWS * LDT + C::R * LDB;
@@ -186,9 +188,8 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C, ROW
         for (int q = 0; q < F::NA4; ++q) {
             const int i = q * WG + t, row = i / (R / 4), a4 = 4 * (i % (R / 4)), e = row / N1;
             const bool on = e < n;
-            float *d = As + row * LDA + a4;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) d[x] = on ? nxt_a[q][x] : 0.f;
+            *reinterpret_cast<float4 *>(As + row * LDA + a4) =
+                make_float4(on ? nxt_a[q][0] : 0.f, on ? nxt_a[q][1] : 0.f, on ? nxt_a[q][2] : 0.f, on ? nxt_a[q][3] : 0.f);
         }
 #pragma unroll
         for (int i = 0; i < F::BQ; ++i)
@@ -279,8 +280,7 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C, ROW
 #pragma unroll
             for (int q = 0; q < NB4; ++q) {
                 const int i = q * WG + t, a = i / (R / 4), b4 = 4 * (i % (R / 4));
-                float *d = Bl + a * LDB + b4;
-                d[0] = bm[q][0]; d[1] = bm[q][1]; d[2] = bm[q][2]; d[3] = bm[q][3];
+                *reinterpret_cast<float4 *>(Bl + a * LDB + b4) = make_float4(bm[q][0], bm[q][1], bm[q][2], bm[q][3]);
             }
             if (j2 + 1 < N2) fetch_bm(i2, j2 + 1);
             else if (i2n >= 0) fetch_bm(i2n, 0);
@@ -306,11 +306,17 @@ __global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(BoCfg<C, ROW
             }
             // P += dT0' Bm^T over the columns of this j2
 #pragma unroll
-            for (int s = 0; s < R / 2; ++s) {
-                const float av = dT[(32 * rb + ln) * LDT + kh * (R / 2) + s];
+            for (int s = 0; s < R / 2; s += 4) {
+                const float2 av0 = *reinterpret_cast<const float2 *>(&dT[(32 * rb + ln) * LDT + kh * (R / 2) + s]);
+                const float2 av1 = *reinterpret_cast<const float2 *>(&dT[(32 * rb + ln) * LDT + kh * (R / 2) + s + 2]);
 #pragma unroll
-                for (int ab = 0; ab < F::ABW; ++ab)
-                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, Bl[(32 * (ab0 + ab) + ln) * LDB + kh * (R / 2) + s], accp[ab], 0, 0, 0);
+                for (int ab = 0; ab < F::ABW; ++ab) {
+                    const float4 bv = *reinterpret_cast<const float4 *>(&Bl[(32 * (ab0 + ab) + ln) * LDB + kh * (R / 2) + s]);
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0.x, bv.x, accp[ab], 0, 0, 0);
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0.y, bv.y, accp[ab], 0, 0, 0);
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1.x, bv.z, accp[ab], 0, 0, 0);
+                    accp[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1.y, bv.w, accp[ab], 0, 0, 0);
+                }
             }
             bo_lds_barrier();                                               // dT0' and Bm are rewritten for the next j2
         }
